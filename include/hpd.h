@@ -1,0 +1,215 @@
+/*
+ * hpd.h - C ABI of the MI355X (gfx950) library for Hyper-Parallel Decoding (HPD)
+ * masked decode attention.
+ *
+ * One decode step of HPD (paper Section 4.3.3) feeds only the newest token of every
+ * unfinished attribute value ("branch").  Each of those queries is RoPE-rotated at a
+ * manipulated position ID (Section 4.3.1, Appendix A.1), attends to the shared
+ * instruction/attribute header, to its own document and to its own earlier value
+ * tokens (Section 4.3.2, with the per-document restriction that makes Eq. 3's
+ * conditional independence exact), and its new K/V is appended to the cache
+ * (Section 4.3.2: the cache only grows at its end).  Documents are stacked in one
+ * prompt (Section 4.3.5), prompts are batched (Section 4.3.6), finished values are
+ * pruned (Section 4.3.4).
+ *
+ * Conventions
+ *   - "host" / "device" on every pointer says where the memory lives.  Device memory
+ *     is caller-owned (e.g. a torch tensor's data_ptr); the library allocates only the
+ *     small tables inside hpd_layout.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Per-step
+ *     calls only enqueue work; they never synchronise or allocate.
+ *   - Every function returns HPD_OK (0) or a negative HPD_E_* code; on error no output
+ *     is written.  No exception or abort crosses this boundary.
+ *   - Global ids: prompts p in [0,P); documents d in CSR order (p, j); branches b in
+ *     CSR order (p, j, n), which is Algorithm 1's d[jN+i] order.
+ *   - Steps are 0-based decode steps t in [0, max_new); the paper's step t = 1 (the
+ *     prefill) is outside this library.
+ *   - Live rows: at step t the rows of q / k_new / v_new / out / pos_out / slot_out
+ *     are the branches {b : branch_len[b] > t} in ascending b (the pruned input of
+ *     Section 4.3.4).
+ *
+ * KV pool layouts (element type = cfg.dtype; Hkv = n_kv_heads, D = head_dim,
+ * T = max_new, B = number of branches):
+ *   k_prefix : [Hkv][NP][D]          NP = HPD_Q_COUNTS.n_prefix_slots.  A segment
+ *                                    (header of a prompt, or a document) occupies slots
+ *                                    [seg_off, seg_off + seg_len); seg_off is a multiple
+ *                                    of HPD_KEY_BLOCK.  K is stored already rotated.
+ *   v_prefix : [Hkv][NP/8][D][8]     same slots; 8 consecutive keys are interleaved so
+ *                                    that the P.V contraction reads 8 keys of one
+ *                                    channel with one 16-byte load.
+ *   k_tail   : [B][Hkv][T][D]        slot b*T + t holds the rotated key of branch b's
+ *   v_tail   : [B][Hkv][T][D]        t-th value token (Algorithm 1's values[j,i,t]).
+ *   Padding slots of the prefix pools may hold anything (including NaN patterns).
+ */
+#ifndef HPD_H
+#define HPD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HPD_KEY_BLOCK 32 /* alignment (in key slots) of every prefix segment */
+
+enum hpd_status {
+  HPD_OK = 0,
+  HPD_E_INVALID = -1,     /* bad shapes, non-monotone CSR, lengths out of range, null pointers */
+  HPD_E_OVERFLOW = -2,    /* a position or an offset does not fit its integer type */
+  HPD_E_UNSUPPORTED = -3, /* dtype / head_dim / mode the kernels do not cover */
+  HPD_E_HIP = -4,         /* HIP runtime error; hpd_status_string(HPD_E_HIP) gives the text */
+  HPD_E_NOMEM = -5
+};
+
+enum hpd_dtype { HPD_F32 = 0, HPD_BF16 = 1 };
+enum hpd_pos_mode {
+  HPD_POS_CONTIG = 0,   /* every document restarts right after the header; a branch
+                           continues from the end of its own document */
+  HPD_POS_PAPER_GAP = 1 /* Algorithm 2: ordinary positions over header + documents,
+                           then a gap of max_new after every attribute */
+};
+enum hpd_mask_mode { HPD_MASK_BLOCK = 0 /* header + own document + own branch */ };
+enum hpd_flags {
+  HPD_FLAG_HOST_ONLY = 1 /* build host tables only (no HIP call); only hpd_layout_query
+                            and hpd_layout_free may then be used on the layout */
+};
+
+typedef struct hpd_config {
+  int32_t n_q_heads;  /* Hq */
+  int32_t n_kv_heads; /* Hkv, divides Hq; query head h uses kv head h / (Hq/Hkv) */
+  int32_t head_dim;   /* D: multiple of 8, <= 256; the MFMA path needs D = 128 */
+  int32_t dtype;      /* hpd_dtype of q, k, v, out and of the pools */
+  double rope_base;   /* rotate-half RoPE, theta_i = base^(-2i/D), no scaling */
+  int32_t max_new;    /* T = K_max (Section 4.3.1): tail capacity and number of steps */
+  int32_t pos_mode;   /* hpd_pos_mode */
+  int32_t mask_mode;  /* hpd_mask_mode */
+  int32_t flags;      /* hpd_flags */
+} hpd_config;
+
+typedef struct hpd_layout hpd_layout; /* opaque; created and destroyed by the library */
+
+/* hpd_layout_query selectors.  All outputs are host arrays. */
+enum hpd_query {
+  HPD_Q_COUNTS = 0,      /* int64[HPD_N_COUNTS], see hpd_count */
+  HPD_Q_POOL_BYTES = 1,  /* int64[4]: bytes of k_prefix, v_prefix, k_tail, v_tail */
+  HPD_Q_N_LIVE = 2,      /* int32[T]: live branches per step */
+  HPD_Q_LIVE_BRANCH = 3, /* int32[total_live]: live lists of steps 0..T-1 back to back */
+  HPD_Q_BRANCH_BASE_POS = 4, /* int32[B]: position of the token a branch continues from */
+  HPD_Q_BRANCH_DOC = 5,  /* int32[B] */
+  HPD_Q_SEG_OFF = 6,     /* int32[P + n_docs]: first pool slot; headers first, then documents */
+  HPD_Q_SEG_LEN = 7,     /* int32[P + n_docs] */
+  HPD_Q_SEG_POS0 = 8,    /* int32[P + n_docs]: position ID of the segment's first token */
+  HPD_Q_SEG_RAW_OFF = 9, /* int32[P + n_docs]: first token in hpd_prefix_fill's input order */
+  HPD_Q_N_UNITS = 10     /* int32[T]: documents with at least one live branch per step */
+};
+enum hpd_count {
+  HPD_C_N_PROMPTS = 0,
+  HPD_C_N_DOCS = 1,
+  HPD_C_N_BRANCHES = 2,
+  HPD_C_N_PREFIX_TOKENS = 3, /* header + document tokens, unpadded */
+  HPD_C_N_PREFIX_SLOTS = 4,  /* NP */
+  HPD_C_N_TAIL_SLOTS = 5,    /* B * T */
+  HPD_C_MAX_POS = 6,         /* largest position ID any token can take */
+  HPD_C_TOTAL_LIVE = 7,      /* sum over steps of live branches = sum of branch_len */
+  HPD_N_COUNTS = 8
+};
+
+/*
+ * hpd_build_layout - Sections 4.3.1, 4.3.4-4.3.6, Appendix A.1.
+ * Validates the batch description, builds the CSR tables (segments, branches, per-step
+ * live lists, per-step work lists, RoPE table) and, unless HPD_FLAG_HOST_ONLY, uploads
+ * them (synchronises `stream` once).  All input arrays are host memory and are copied.
+ *   header_len [P]        H_p >= 0
+ *   doc_ptr    [P+1]      CSR prompts -> documents, doc_ptr[0] = 0, non-decreasing
+ *   doc_len    [n_docs]   L_d >= 1
+ *   branch_ptr [n_docs+1] CSR documents -> branches, non-decreasing
+ *   branch_len [B] or NULL  number of steps branch b is decoded, in [1, T]; NULL = all T
+ *   attr_len   [B] or NULL  A_b >= 1, skeleton attribute lengths; required for
+ *                           HPD_POS_PAPER_GAP, ignored otherwise
+ * On success *out owns the layout (release with hpd_layout_free).
+ */
+int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* header_len,
+                     const int32_t* doc_ptr, const int32_t* doc_len, const int32_t* branch_ptr,
+                     const int32_t* branch_len, const int32_t* attr_len, void* stream,
+                     hpd_layout** out);
+
+void hpd_layout_free(hpd_layout* layout);
+
+/* Copies one table to host memory.  `bytes` must be at least the table's size. */
+int hpd_layout_query(const hpd_layout* layout, int32_t what, void* host_out, size_t bytes);
+
+/*
+ * hpd_prefix_fill - batched form of the append for the tokens that exist before
+ * decoding starts (header and documents; the paper's prefill writes them).
+ *   k_raw, v_raw : device [n_prefix_tokens][Hkv][D], un-rotated, token order = prompts in
+ *                  order, each as [header | doc_0 | doc_1 | ...]
+ *   k_prefix, v_prefix : device pools (layouts above).  K is rotated at the token's
+ *                  position ID (HPD_Q_SEG_POS0 + index in segment) and stored.
+ */
+int hpd_prefix_fill(const hpd_layout* layout, const void* k_raw, const void* v_raw,
+                    void* k_prefix, void* v_prefix, void* stream);
+
+/*
+ * hpd_rope_positions - Appendix A.1 ("value token k of attribute n gets
+ * pos_id[end(a_n)] + k") and Section 4.3.3 (previous position + 1):
+ *   pos_out[r] = base_pos[b_r] + 1 + step   for the r-th live branch b_r.
+ *   pos_out    : device int32 [n_live(step)]
+ *   n_live_out : host int32*, may be NULL
+ */
+int hpd_rope_positions(const hpd_layout* layout, int32_t step, int32_t* pos_out,
+                       int32_t* n_live_out, void* stream);
+
+/*
+ * hpd_kv_append - Section 4.3.2 (new tokens are appended at the end of the cache).
+ * Rotates the new key of every live branch at its position ID and stores key and value
+ * at tail slot b*T + step.
+ *   k_new, v_new : device [n_live(step)][Hkv][D], K un-rotated
+ *   k_tail, v_tail : device tail pools
+ *   slot_out : device int64 [n_live(step)] or NULL; receives b*T + step
+ */
+int hpd_kv_append(const hpd_layout* layout, int32_t step, const void* k_new, const void* v_new,
+                  void* k_tail, void* v_tail, int64_t* slot_out, void* stream);
+
+/*
+ * hpd_decode_attention - Sections 4.3.2-4.3.3.  For every live branch b and query head h:
+ *   out = softmax( RoPE(q, pos) . K^T / sqrt(D) ) V  over the keys
+ *   header(prompt of b)  ++  document(b)  ++  tail slots 0..step of b
+ * (the block form of the position-ordered causal mask).  Call after hpd_kv_append of the
+ * same step: a query attends to its own token.
+ *   q   : device [n_live(step)][Hq][D], un-rotated
+ *   out : device [n_live(step)][Hq][D]
+ */
+int hpd_decode_attention(const hpd_layout* layout, int32_t step, const void* q,
+                         const void* k_prefix, const void* v_prefix, const void* k_tail,
+                         const void* v_tail, void* out, void* stream);
+
+/*
+ * hpd_decode_step - hpd_kv_append followed by hpd_decode_attention of the same step with
+ * fewer launches; results equal the two-call sequence.
+ */
+int hpd_decode_step(const hpd_layout* layout, int32_t step, const void* q, const void* k_new,
+                    const void* v_new, const void* k_prefix, const void* v_prefix, void* k_tail,
+                    void* v_tail, void* out, void* stream);
+
+/*
+ * hpd_expand_mask - debugging export of the mask of Section 4.3.2 as the library
+ * understands it.  Memory order of prompt `prompt` after step `step_hi`:
+ *   [header | doc_0 | ... | step-0 live branches | step-1 live branches | ... ].
+ *   mask_out : device uint8 [S][S] row-major (query row, key column), S = *s_out
+ *   s_out    : host int32*, receives S; if mask_out is NULL only S is reported.
+ * Allocates and frees a small descriptor table and synchronises: test use only.
+ */
+int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, uint8_t* mask_out,
+                    int32_t* s_out, void* stream);
+
+/* Selects the attention kernel: 0 = automatic, 1 = generic wave-reduction kernel for
+ * everything, 2 = MFMA shared-prefix kernel (error if the shape does not allow it). */
+int hpd_set_kernel_mode(hpd_layout* layout, int32_t mode);
+
+const char* hpd_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HPD_H */

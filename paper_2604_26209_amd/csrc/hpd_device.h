@@ -1,0 +1,54 @@
+// Small device helpers: bf16 <-> fp32 conversion and vector loads.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hpd {
+
+struct bf16_t {
+  uint16_t bits;
+};
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t bits) {
+  return __uint_as_float(bits << 16);
+}
+
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ uint32_t float_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return bf16_bits_to_float(x.bits); }
+
+template <typename T>
+__device__ __forceinline__ T from_float(float f);
+template <>
+__device__ __forceinline__ float from_float<float>(float f) { return f; }
+template <>
+__device__ __forceinline__ bf16_t from_float<bf16_t>(float f) {
+  bf16_t r;
+  r.bits = (uint16_t)float_to_bf16_bits(f);
+  return r;
+}
+
+// 8 consecutive elements (16-byte aligned for bf16, 32-byte for fp32) to fp32
+__device__ __forceinline__ void load8(const float* p, float out[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p);
+  const float4 b = *reinterpret_cast<const float4*>(p + 4);
+  out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+  out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t* p, float out[8]) {
+  const uint4 a = *reinterpret_cast<const uint4*>(p);
+  out[0] = bf16_bits_to_float(a.x & 0xffffu); out[1] = bf16_bits_to_float(a.x >> 16);
+  out[2] = bf16_bits_to_float(a.y & 0xffffu); out[3] = bf16_bits_to_float(a.y >> 16);
+  out[4] = bf16_bits_to_float(a.z & 0xffffu); out[5] = bf16_bits_to_float(a.z >> 16);
+  out[6] = bf16_bits_to_float(a.w & 0xffffu); out[7] = bf16_bits_to_float(a.w >> 16);
+}
+
+}  // namespace hpd

@@ -1,0 +1,458 @@
+// Host side of the HPD library: validation, layout tables and the C ABI.
+// The layout follows the paper's problem statement: a shared header per prompt,
+// J stacked documents (Section 4.3.5), N attribute branches per document decoded for at
+// most K_max steps (Sections 4.3.1, 4.3.4), prompts batched (Section 4.3.6).
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <numeric>
+#include <string>
+
+#include "hpd_internal.h"
+
+namespace {
+
+thread_local std::string g_hip_text = "no HIP error recorded";
+
+int hip_fail(hipError_t e) {
+  g_hip_text = std::string("HIP error: ") + hipGetErrorString(e);
+  return HPD_E_HIP;
+}
+
+#define HPD_HIP(expr)                        \
+  do {                                       \
+    hipError_t e_ = (expr);                  \
+    if (e_ != hipSuccess) return hip_fail(e_); \
+  } while (0)
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+size_t elem_bytes(const hpd_config& c) { return c.dtype == HPD_F32 ? 4 : 2; }
+
+int validate_config(const hpd_config* c) {
+  if (!c) return HPD_E_INVALID;
+  if (c->n_q_heads < 1 || c->n_kv_heads < 1 || c->n_q_heads % c->n_kv_heads != 0) return HPD_E_INVALID;
+  if (c->head_dim < 2 || (c->head_dim & 1)) return HPD_E_INVALID;
+  if (c->max_new < 1) return HPD_E_INVALID;
+  if (!(c->rope_base > 1.0) || !std::isfinite(c->rope_base)) return HPD_E_INVALID;
+  if (c->dtype != HPD_F32 && c->dtype != HPD_BF16) return HPD_E_UNSUPPORTED;
+  if (c->head_dim % 8 != 0 || c->head_dim > 256) return HPD_E_UNSUPPORTED;
+  if (c->pos_mode != HPD_POS_CONTIG && c->pos_mode != HPD_POS_PAPER_GAP) return HPD_E_UNSUPPORTED;
+  if (c->mask_mode != HPD_MASK_BLOCK) return HPD_E_UNSUPPORTED;
+  if (c->flags & ~HPD_FLAG_HOST_ONLY) return HPD_E_INVALID;
+  return HPD_OK;
+}
+
+// Copies a host vector into the device int arena and returns its device address.
+struct IntArena {
+  std::vector<int32_t> host;
+  std::vector<size_t> offs;
+  size_t add(const std::vector<int32_t>& v) {
+    size_t o = host.size();
+    host.insert(host.end(), v.begin(), v.end());
+    // keep every table 16-byte aligned
+    while (host.size() % 4) host.push_back(0);
+    if (v.empty()) { host.insert(host.end(), 4, 0); }
+    return o;
+  }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char* hpd_status_string(int status) {
+  switch (status) {
+    case HPD_OK: return "ok";
+    case HPD_E_INVALID: return "invalid argument";
+    case HPD_E_OVERFLOW: return "integer overflow in positions or offsets";
+    case HPD_E_UNSUPPORTED: return "unsupported dtype, head_dim or mode";
+    case HPD_E_HIP: return g_hip_text.c_str();
+    case HPD_E_NOMEM: return "out of host memory";
+    default: return "unknown status";
+  }
+}
+
+int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* header_len,
+                     const int32_t* doc_ptr, const int32_t* doc_len, const int32_t* branch_ptr,
+                     const int32_t* branch_len, const int32_t* attr_len, void* stream,
+                     hpd_layout** out) {
+  if (!out) return HPD_E_INVALID;
+  int rc = validate_config(cfg);
+  if (rc != HPD_OK) return rc;
+  if (n_prompts < 1 || !header_len || !doc_ptr || !doc_len || !branch_ptr) return HPD_E_INVALID;
+  if (cfg->pos_mode == HPD_POS_PAPER_GAP && !attr_len) return HPD_E_INVALID;
+  const int32_t P = n_prompts;
+  const int32_t T = cfg->max_new;
+  if (doc_ptr[0] != 0) return HPD_E_INVALID;
+  for (int32_t p = 0; p < P; ++p) {
+    if (header_len[p] < 0) return HPD_E_INVALID;
+    if (doc_ptr[p + 1] < doc_ptr[p]) return HPD_E_INVALID;
+  }
+  const int32_t n_docs = doc_ptr[P];
+  if (branch_ptr[0] != 0) return HPD_E_INVALID;
+  for (int32_t d = 0; d < n_docs; ++d) {
+    if (doc_len[d] < 1) return HPD_E_INVALID;
+    if (branch_ptr[d + 1] < branch_ptr[d]) return HPD_E_INVALID;
+  }
+  const int32_t B = branch_ptr[n_docs];
+  for (int32_t b = 0; b < B; ++b) {
+    if (branch_len && (branch_len[b] < 1 || branch_len[b] > T)) return HPD_E_INVALID;
+    if (cfg->pos_mode == HPD_POS_PAPER_GAP && attr_len[b] < 1) return HPD_E_INVALID;
+  }
+  if ((int64_t)B * T > (int64_t)1 << 40) return HPD_E_OVERFLOW;
+
+  hpd_layout* L = new (std::nothrow) hpd_layout();
+  if (!L) return HPD_E_NOMEM;
+  try {
+    L->cfg = *cfg;
+    L->P = P; L->n_docs = n_docs; L->B = B; L->T = T; L->n_seg = P + n_docs;
+    const int32_t n_seg = L->n_seg;
+    L->seg_off.assign(n_seg, 0); L->seg_len.assign(n_seg, 0); L->seg_pos0.assign(n_seg, 0);
+    L->seg_raw_off.assign(n_seg + 1, 0); L->raw_seg.assign(n_seg, 0);
+    L->doc_prompt.assign(n_docs, 0);
+    L->branch_doc.assign(B, 0); L->branch_base_pos.assign(B, 0); L->branch_len.assign(B, T);
+    if (branch_len) std::copy(branch_len, branch_len + B, L->branch_len.begin());
+
+    // ---- segments: pool slots (each segment starts on a HPD_KEY_BLOCK boundary), raw
+    //      token order [header | doc_0 | doc_1 ...] per prompt, position of first token
+    int64_t slot = 0, raw = 0, max_pos = 0;
+    int32_t ri = 0;
+    for (int32_t p = 0; p < P; ++p) {
+      const int64_t H = header_len[p];
+      L->seg_off[p] = (int32_t)slot; L->seg_len[p] = (int32_t)H; L->seg_pos0[p] = 0;
+      L->seg_raw_off[ri] = (int32_t)raw; L->raw_seg[ri] = p; ++ri;
+      slot += round_up(H, HPD_KEY_BLOCK); raw += H;
+      int64_t run_pos = H;  // paper-gap mode: ordinary increasing positions across documents
+      for (int32_t d = doc_ptr[p]; d < doc_ptr[p + 1]; ++d) {
+        const int64_t Ld = doc_len[d];
+        const int32_t sid = P + d;
+        L->doc_prompt[d] = p;
+        L->seg_off[sid] = (int32_t)slot; L->seg_len[sid] = (int32_t)Ld;
+        const int64_t pos0 = (cfg->pos_mode == HPD_POS_CONTIG) ? H : run_pos;
+        L->seg_pos0[sid] = (int32_t)pos0;
+        L->seg_raw_off[ri] = (int32_t)raw; L->raw_seg[ri] = sid; ++ri;
+        slot += round_up(Ld, HPD_KEY_BLOCK); raw += Ld; run_pos += Ld;
+        max_pos = std::max(max_pos, pos0 + Ld - 1);
+        if (slot > std::numeric_limits<int32_t>::max() - 4096 || run_pos > (1 << 30)) {
+          delete L; return HPD_E_OVERFLOW;
+        }
+      }
+      // ---- branches of this prompt: base position = position of the token they continue from
+      if (cfg->pos_mode == HPD_POS_CONTIG) {
+        for (int32_t d = doc_ptr[p]; d < doc_ptr[p + 1]; ++d)
+          for (int32_t b = branch_ptr[d]; b < branch_ptr[d + 1]; ++b) {
+            L->branch_doc[b] = d;
+            L->branch_base_pos[b] = (int32_t)(H + doc_len[d] - 1);
+          }
+      } else {
+        // Algorithm 2 over s = cat(prompt, a_1..a_N): attribute n keeps its ordinary
+        // position plus n*K_max; a branch continues from its attribute's last token.
+        int64_t idx = run_pos;  // index in s of the next skeleton token
+        int64_t offset = 0;
+        for (int32_t d = doc_ptr[p]; d < doc_ptr[p + 1]; ++d)
+          for (int32_t b = branch_ptr[d]; b < branch_ptr[d + 1]; ++b) {
+            L->branch_doc[b] = d;
+            const int64_t end = idx + attr_len[b] - 1;
+            const int64_t bp = end + offset;
+            if (bp + T > (1 << 30)) { delete L; return HPD_E_OVERFLOW; }
+            L->branch_base_pos[b] = (int32_t)bp;
+            idx = end + 1;
+            offset += T;
+          }
+      }
+    }
+    L->seg_raw_off[n_seg] = (int32_t)raw;
+    L->n_prefix_tokens = raw;
+    // slack of 128 slots so that a kernel tile that starts inside the last segment never
+    // leaves the pool
+    L->NP = round_up(slot, HPD_KEY_BLOCK) + 128;
+    for (int32_t b = 0; b < B; ++b)
+      max_pos = std::max<int64_t>(max_pos, (int64_t)L->branch_base_pos[b] + L->branch_len[b]);
+    if (max_pos > (1 << 30)) { delete L; return HPD_E_OVERFLOW; }
+    L->max_pos = (int32_t)max_pos;
+
+    // ---- per-step live lists (Section 4.3.4: a finished value is no longer fed)
+    L->live_ptr.assign(T + 1, 0);
+    for (int32_t t = 0; t < T; ++t) {
+      int32_t n = 0;
+      for (int32_t b = 0; b < B; ++b) n += L->branch_len[b] > t;
+      L->live_ptr[t + 1] = L->live_ptr[t] + n;
+    }
+    L->total_live = L->live_ptr[T];
+    L->live_branch.assign((size_t)L->total_live, 0);
+    L->doc_live_ptr.assign((size_t)T * (n_docs + 1), 0);
+    L->unit_ptr.assign(T + 1, 0);
+    L->max_rows.assign(T, 0);
+    for (int32_t t = 0; t < T; ++t) {
+      int32_t w = L->live_ptr[t];
+      int32_t* dlp = &L->doc_live_ptr[(size_t)t * (n_docs + 1)];
+      std::vector<int32_t> units;
+      for (int32_t d = 0; d < n_docs; ++d) {
+        dlp[d] = w - L->live_ptr[t];
+        for (int32_t b = branch_ptr[d]; b < branch_ptr[d + 1]; ++b)
+          if (L->branch_len[b] > t) L->live_branch[w++] = b;
+        const int32_t nb = w - L->live_ptr[t] - dlp[d];
+        if (nb > 0) units.push_back(d);
+        L->max_rows[t] = std::max(L->max_rows[t], nb);
+      }
+      dlp[n_docs] = w - L->live_ptr[t];
+      // heaviest documents first: cost ~ keys streamed
+      std::stable_sort(units.begin(), units.end(), [&](int32_t a, int32_t b) {
+        const int64_t ca = (int64_t)header_len[L->doc_prompt[a]] + doc_len[a];
+        const int64_t cb = (int64_t)header_len[L->doc_prompt[b]] + doc_len[b];
+        return ca > cb;
+      });
+      L->unit_doc.insert(L->unit_doc.end(), units.begin(), units.end());
+      L->unit_ptr[t + 1] = (int32_t)L->unit_doc.size();
+    }
+    L->total_units = (int64_t)L->unit_doc.size();
+
+    // ---- RoPE table: angles in double, stored as float (cos, sin)
+    const int32_t half = cfg->head_dim / 2;
+    L->rope.resize((size_t)(L->max_pos + 1) * half * 2);
+    std::vector<double> theta(half);
+    for (int32_t i = 0; i < half; ++i)
+      theta[i] = std::pow(cfg->rope_base, -2.0 * (double)i / (double)cfg->head_dim);
+    for (int64_t pos = 0; pos <= L->max_pos; ++pos)
+      for (int32_t i = 0; i < half; ++i) {
+        const double a = (double)pos * theta[i];
+        L->rope[((size_t)pos * half + i) * 2 + 0] = (float)std::cos(a);
+        L->rope[((size_t)pos * half + i) * 2 + 1] = (float)std::sin(a);
+      }
+  } catch (const std::bad_alloc&) {
+    delete L;
+    return HPD_E_NOMEM;
+  }
+
+  if (!(cfg->flags & HPD_FLAG_HOST_ONLY)) {
+    // ---- upload
+    IntArena A;
+    const size_t o_seg_off = A.add(L->seg_off), o_seg_len = A.add(L->seg_len),
+                 o_seg_pos0 = A.add(L->seg_pos0), o_raw_off = A.add(L->seg_raw_off),
+                 o_raw_seg = A.add(L->raw_seg), o_doc_prompt = A.add(L->doc_prompt),
+                 o_branch_doc = A.add(L->branch_doc), o_base = A.add(L->branch_base_pos),
+                 o_live_ptr = A.add(L->live_ptr), o_live_branch = A.add(L->live_branch),
+                 o_dlp = A.add(L->doc_live_ptr), o_unit_ptr = A.add(L->unit_ptr),
+                 o_unit_doc = A.add(L->unit_doc);
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipGetDevice(&L->device);
+    if (e == hipSuccess) e = hipMalloc(&L->d_ints, A.host.size() * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(&L->d_rope, L->rope.size() * sizeof(float));
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(L->d_ints, A.host.data(), A.host.size() * sizeof(int32_t),
+                         hipMemcpyHostToDevice, s);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(L->d_rope, L->rope.data(), L->rope.size() * sizeof(float),
+                         hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+      if (L->d_ints) (void)hipFree(L->d_ints);
+      if (L->d_rope) (void)hipFree(L->d_rope);
+      delete L;
+      return hip_fail(e);
+    }
+    const int32_t* base = (const int32_t*)L->d_ints;
+    L->dev.seg_off = base + o_seg_off; L->dev.seg_len = base + o_seg_len;
+    L->dev.seg_pos0 = base + o_seg_pos0; L->dev.seg_raw_off = base + o_raw_off;
+    L->dev.raw_seg = base + o_raw_seg; L->dev.doc_prompt = base + o_doc_prompt;
+    L->dev.branch_doc = base + o_branch_doc; L->dev.branch_base_pos = base + o_base;
+    L->dev.live_ptr = base + o_live_ptr; L->dev.live_branch = base + o_live_branch;
+    L->dev.doc_live_ptr = base + o_dlp; L->dev.unit_ptr = base + o_unit_ptr;
+    L->dev.unit_doc = base + o_unit_doc;
+    L->dev.rope = (const float2*)L->d_rope;
+    L->on_device = true;
+  }
+  *out = L;
+  return HPD_OK;
+}
+
+void hpd_layout_free(hpd_layout* L) {
+  if (!L) return;
+  if (L->d_ints) (void)hipFree(L->d_ints);
+  if (L->d_rope) (void)hipFree(L->d_rope);
+  delete L;
+}
+
+int hpd_layout_query(const hpd_layout* L, int32_t what, void* host_out, size_t bytes) {
+  if (!L || !host_out) return HPD_E_INVALID;
+  auto copy32 = [&](const std::vector<int32_t>& v, size_t n) -> int {
+    if (bytes < n * sizeof(int32_t)) return HPD_E_INVALID;
+    if (n) std::memcpy(host_out, v.data(), n * sizeof(int32_t));
+    return HPD_OK;
+  };
+  const size_t eb = elem_bytes(L->cfg);
+  switch (what) {
+    case HPD_Q_COUNTS: {
+      if (bytes < HPD_N_COUNTS * sizeof(int64_t)) return HPD_E_INVALID;
+      int64_t c[HPD_N_COUNTS];
+      c[HPD_C_N_PROMPTS] = L->P; c[HPD_C_N_DOCS] = L->n_docs; c[HPD_C_N_BRANCHES] = L->B;
+      c[HPD_C_N_PREFIX_TOKENS] = L->n_prefix_tokens; c[HPD_C_N_PREFIX_SLOTS] = L->NP;
+      c[HPD_C_N_TAIL_SLOTS] = (int64_t)L->B * L->T; c[HPD_C_MAX_POS] = L->max_pos;
+      c[HPD_C_TOTAL_LIVE] = L->total_live;
+      std::memcpy(host_out, c, sizeof(c));
+      return HPD_OK;
+    }
+    case HPD_Q_POOL_BYTES: {
+      if (bytes < 4 * sizeof(int64_t)) return HPD_E_INVALID;
+      const int64_t per_slot = (int64_t)L->cfg.n_kv_heads * L->cfg.head_dim * (int64_t)eb;
+      int64_t c[4] = {L->NP * per_slot, L->NP * per_slot, (int64_t)L->B * L->T * per_slot,
+                      (int64_t)L->B * L->T * per_slot};
+      std::memcpy(host_out, c, sizeof(c));
+      return HPD_OK;
+    }
+    case HPD_Q_N_LIVE: {
+      if (bytes < (size_t)L->T * sizeof(int32_t)) return HPD_E_INVALID;
+      int32_t* o = (int32_t*)host_out;
+      for (int32_t t = 0; t < L->T; ++t) o[t] = L->live_ptr[t + 1] - L->live_ptr[t];
+      return HPD_OK;
+    }
+    case HPD_Q_N_UNITS: {
+      if (bytes < (size_t)L->T * sizeof(int32_t)) return HPD_E_INVALID;
+      int32_t* o = (int32_t*)host_out;
+      for (int32_t t = 0; t < L->T; ++t) o[t] = L->unit_ptr[t + 1] - L->unit_ptr[t];
+      return HPD_OK;
+    }
+    case HPD_Q_LIVE_BRANCH: return copy32(L->live_branch, (size_t)L->total_live);
+    case HPD_Q_BRANCH_BASE_POS: return copy32(L->branch_base_pos, (size_t)L->B);
+    case HPD_Q_BRANCH_DOC: return copy32(L->branch_doc, (size_t)L->B);
+    case HPD_Q_SEG_OFF: return copy32(L->seg_off, (size_t)L->n_seg);
+    case HPD_Q_SEG_LEN: return copy32(L->seg_len, (size_t)L->n_seg);
+    case HPD_Q_SEG_POS0: return copy32(L->seg_pos0, (size_t)L->n_seg);
+    case HPD_Q_SEG_RAW_OFF: {
+      if (bytes < (size_t)L->n_seg * sizeof(int32_t)) return HPD_E_INVALID;
+      int32_t* o = (int32_t*)host_out;
+      for (int32_t i = 0; i < L->n_seg; ++i) o[L->raw_seg[i]] = L->seg_raw_off[i];
+      return HPD_OK;
+    }
+    default: return HPD_E_INVALID;
+  }
+}
+
+int hpd_set_kernel_mode(hpd_layout* L, int32_t mode) {
+  if (!L || mode < 0 || mode > 2) return HPD_E_INVALID;
+  if (mode == 2 && !hpd_mfma_supported(L)) return HPD_E_UNSUPPORTED;
+  L->kernel_mode = mode;
+  return HPD_OK;
+}
+
+static int check_step(const hpd_layout* L, int32_t step) {
+  if (!L) return HPD_E_INVALID;
+  if (!L->on_device) return HPD_E_INVALID;
+  if (step < 0 || step >= L->T) return HPD_E_INVALID;
+  return HPD_OK;
+}
+
+int hpd_prefix_fill(const hpd_layout* L, const void* k_raw, const void* v_raw, void* k_prefix,
+                    void* v_prefix, void* stream) {
+  if (!L || !L->on_device || !k_prefix || !v_prefix) return HPD_E_INVALID;
+  if (L->n_prefix_tokens == 0) return HPD_OK;
+  if (!k_raw || !v_raw) return HPD_E_INVALID;
+  HPD_HIP(hpd_launch_prefix_fill(L, k_raw, v_raw, k_prefix, v_prefix, (hipStream_t)stream));
+  return HPD_OK;
+}
+
+int hpd_rope_positions(const hpd_layout* L, int32_t step, int32_t* pos_out, int32_t* n_live_out,
+                       void* stream) {
+  int rc = check_step(L, step);
+  if (rc != HPD_OK) return rc;
+  const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
+  if (n_live > 0 && !pos_out) return HPD_E_INVALID;
+  if (n_live > 0) HPD_HIP(hpd_launch_positions(L, step, pos_out, (hipStream_t)stream));
+  if (n_live_out) *n_live_out = n_live;
+  return HPD_OK;
+}
+
+int hpd_kv_append(const hpd_layout* L, int32_t step, const void* k_new, const void* v_new,
+                  void* k_tail, void* v_tail, int64_t* slot_out, void* stream) {
+  int rc = check_step(L, step);
+  if (rc != HPD_OK) return rc;
+  const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
+  if (n_live == 0) return HPD_OK;
+  if (!k_new || !v_new || !k_tail || !v_tail) return HPD_E_INVALID;
+  HPD_HIP(hpd_launch_append(L, step, k_new, v_new, k_tail, v_tail, slot_out, (hipStream_t)stream));
+  return HPD_OK;
+}
+
+int hpd_decode_attention(const hpd_layout* L, int32_t step, const void* q, const void* k_prefix,
+                         const void* v_prefix, const void* k_tail, const void* v_tail, void* out,
+                         void* stream) {
+  int rc = check_step(L, step);
+  if (rc != HPD_OK) return rc;
+  const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
+  if (n_live == 0) return HPD_OK;
+  if (!q || !k_prefix || !v_prefix || !k_tail || !v_tail || !out) return HPD_E_INVALID;
+  bool use_mfma = false;
+  if (L->kernel_mode == 2) use_mfma = true;
+  else if (L->kernel_mode == 0) use_mfma = hpd_mfma_supported(L);
+  if (use_mfma) {
+    HPD_HIP(hpd_launch_attention_mfma(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out,
+                                      (hipStream_t)stream));
+  } else {
+    // the generic kernel keeps one score per key in LDS
+    int64_t max_keys = 0;
+    for (int32_t u = L->unit_ptr[step]; u < L->unit_ptr[step + 1]; ++u) {
+      const int32_t d = L->unit_doc[u];
+      max_keys = std::max<int64_t>(max_keys, (int64_t)L->seg_len[L->doc_prompt[d]] +
+                                                 L->seg_len[L->P + d] + step + 1);
+    }
+    if (max_keys > 15000) return HPD_E_UNSUPPORTED;
+    HPD_HIP(hpd_launch_attention_generic(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out,
+                                         (hipStream_t)stream));
+  }
+  return HPD_OK;
+}
+
+int hpd_decode_step(const hpd_layout* L, int32_t step, const void* q, const void* k_new,
+                    const void* v_new, const void* k_prefix, const void* v_prefix, void* k_tail,
+                    void* v_tail, void* out, void* stream) {
+  int rc = check_step(L, step);
+  if (rc != HPD_OK) return rc;
+  const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
+  if (n_live == 0) return HPD_OK;
+  if (!q || !k_new || !v_new || !k_prefix || !v_prefix || !k_tail || !v_tail || !out)
+    return HPD_E_INVALID;
+  rc = hpd_kv_append(L, step, k_new, v_new, k_tail, v_tail, nullptr, stream);
+  if (rc != HPD_OK) return rc;
+  return hpd_decode_attention(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, stream);
+}
+
+int hpd_expand_mask(const hpd_layout* L, int32_t prompt, int32_t step_hi, uint8_t* mask_out,
+                    int32_t* s_out, void* stream) {
+  if (!L || !L->on_device || !s_out) return HPD_E_INVALID;
+  if (prompt < 0 || prompt >= L->P || step_hi < -1 || step_hi >= L->T) return HPD_E_INVALID;
+  // token descriptors in memory order: (kind, document, branch, step)
+  //   kind 0 header, 1 document, 2 branch token
+  std::vector<int32_t> desc;
+  const int32_t H = L->seg_len[prompt];
+  for (int32_t i = 0; i < H; ++i) { desc.insert(desc.end(), {0, -1, -1, -1}); }
+  int32_t d0 = -1, d1 = -1;
+  for (int32_t d = 0; d < L->n_docs; ++d)
+    if (L->doc_prompt[d] == prompt) { if (d0 < 0) d0 = d; d1 = d + 1; }
+  for (int32_t d = d0; d >= 0 && d < d1; ++d)
+    for (int32_t i = 0; i < L->seg_len[L->P + d]; ++i) desc.insert(desc.end(), {1, d, -1, -1});
+  for (int32_t t = 0; t <= step_hi; ++t)
+    for (int32_t r = L->live_ptr[t]; r < L->live_ptr[t + 1]; ++r) {
+      const int32_t b = L->live_branch[r];
+      const int32_t d = L->branch_doc[b];
+      if (L->doc_prompt[d] == prompt) desc.insert(desc.end(), {2, d, b, t});
+    }
+  const int64_t S = (int64_t)desc.size() / 4;
+  if (S > 46000) return HPD_E_OVERFLOW;
+  *s_out = (int32_t)S;
+  if (!mask_out || S == 0) return HPD_OK;
+  int32_t* d_desc = nullptr;
+  hipStream_t s = (hipStream_t)stream;
+  HPD_HIP(hipMalloc((void**)&d_desc, desc.size() * sizeof(int32_t)));
+  hipError_t e = hipMemcpyAsync(d_desc, desc.data(), desc.size() * sizeof(int32_t),
+                                hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hpd_launch_expand_mask(d_desc, (int32_t)S, mask_out, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipFree(d_desc);
+  if (e != hipSuccess) return hip_fail(e);
+  return HPD_OK;
+}
+
+}  // extern "C"

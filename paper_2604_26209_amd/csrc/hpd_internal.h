@@ -1,0 +1,71 @@
+// Internal declarations shared by the host side (layout builder, C ABI) and the
+// kernel launchers.  Not part of the public interface.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "hpd.h"
+
+// Device-resident tables of one layout.  All int32 tables live in one allocation.
+struct hpd_dev_tables {
+  const int32_t* seg_off;       // [n_seg] first pool slot of header p (index p) / document d (index P+d)
+  const int32_t* seg_len;       // [n_seg]
+  const int32_t* seg_pos0;      // [n_seg] position ID of the first token
+  const int32_t* seg_raw_off;   // [n_seg+1] first token in prefix_fill input order (sorted by raw order, see raw_seg)
+  const int32_t* raw_seg;       // [n_seg] segment ids in raw (prompt-major) order
+  const int32_t* doc_prompt;    // [n_docs]
+  const int32_t* branch_doc;    // [B]
+  const int32_t* branch_base_pos;  // [B]
+  const int32_t* live_ptr;      // [T+1]
+  const int32_t* live_branch;   // [total_live]
+  const int32_t* doc_live_ptr;  // [T][n_docs+1] first live row (within the step's list) of each document
+  const int32_t* unit_ptr;      // [T+1]
+  const int32_t* unit_doc;      // [total_units] documents with live branches, heaviest first
+  const float2* rope;           // [max_pos+1][D/2] (cos, sin)
+};
+
+struct hpd_layout {
+  hpd_config cfg;
+  int32_t P = 0, n_docs = 0, B = 0, T = 0, n_seg = 0;
+  int64_t n_prefix_tokens = 0, NP = 0, total_live = 0, total_units = 0;
+  int32_t max_pos = 0;
+  int32_t kernel_mode = 0;
+  int32_t mfma_waves = 0;  // 0 = heuristic
+
+  std::vector<int32_t> seg_off, seg_len, seg_pos0, seg_raw_off, raw_seg;
+  std::vector<int32_t> doc_prompt, branch_doc, branch_base_pos, branch_len;
+  std::vector<int32_t> live_ptr, live_branch, doc_live_ptr, unit_ptr, unit_doc;
+  std::vector<int32_t> max_rows;  // [T] largest number of live branches of any document at step t
+  std::vector<float> rope;        // host copy of the (cos, sin) table
+
+  bool on_device = false;
+  int device = -1;
+  void* d_ints = nullptr;
+  void* d_rope = nullptr;
+  hpd_dev_tables dev{};
+};
+
+struct hpd_shape {
+  int32_t Hq, Hkv, D, T, P, n_docs;
+  int64_t NP;
+};
+
+// Launchers (hpd_kernels.hip).  Each returns a hipError_t from the launch.
+hipError_t hpd_launch_prefix_fill(const hpd_layout* L, const void* k_raw, const void* v_raw,
+                                  void* k_prefix, void* v_prefix, hipStream_t s);
+hipError_t hpd_launch_positions(const hpd_layout* L, int32_t step, int32_t* pos_out, hipStream_t s);
+hipError_t hpd_launch_append(const hpd_layout* L, int32_t step, const void* k_new, const void* v_new,
+                             void* k_tail, void* v_tail, int64_t* slot_out, hipStream_t s);
+hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const void* q,
+                                        const void* k_prefix, const void* v_prefix,
+                                        const void* k_tail, const void* v_tail, void* out,
+                                        hipStream_t s);
+hipError_t hpd_launch_attention_mfma(const hpd_layout* L, int32_t step, const void* q,
+                                     const void* k_prefix, const void* v_prefix, const void* k_tail,
+                                     const void* v_tail, void* out, hipStream_t s);
+hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, uint8_t* mask_out, hipStream_t s);
+
+bool hpd_mfma_supported(const hpd_layout* L);

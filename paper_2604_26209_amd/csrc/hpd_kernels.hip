@@ -1,0 +1,289 @@
+// HIP kernels (gfx950) for HPD masked decode attention: helper kernels (prefix fill,
+// positions, append, mask export) and the generic wave-reduction attention kernel that
+// covers fp32, odd shapes and serves as the fallback.  The MFMA shared-prefix kernel is
+// in hpd_attn_mfma.hip.
+#include "hpd_internal.h"
+#include "hpd_device.h"
+
+namespace {
+
+// ---------------------------------------------------------------------------------------
+// Prefix fill: RoPE(K) at the token's position ID, store K row-major and V with 8 keys
+// interleaved.  One thread per (raw token, kv head, rotation pair).
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void prefix_fill_kernel(hpd_dev_tables tb, int32_t n_seg, int64_t n_tok, int32_t Hkv,
+                                   int32_t D, int64_t NP, const T* __restrict__ k_raw,
+                                   const T* __restrict__ v_raw, T* __restrict__ k_prefix,
+                                   T* __restrict__ v_prefix) {
+  const int32_t half = D / 2;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t total = n_tok * Hkv * half;
+  if (gid >= total) return;
+  const int32_t i = (int32_t)(gid % half);
+  const int32_t h = (int32_t)((gid / half) % Hkv);
+  const int64_t tok = gid / ((int64_t)half * Hkv);
+  // segment that holds raw token `tok`: last entry of the sorted start table <= tok
+  int32_t lo = 0, hi = n_seg;  // invariant: start[lo] <= tok < start[hi]
+  while (hi - lo > 1) {
+    const int32_t mid = (lo + hi) >> 1;
+    if (tb.seg_raw_off[mid] <= tok) lo = mid; else hi = mid;
+  }
+  // skip empty segments that share the same start
+  while (lo + 1 < n_seg && tb.seg_raw_off[lo + 1] <= tok) ++lo;
+  const int32_t sid = tb.raw_seg[lo];
+  const int32_t idx = (int32_t)(tok - tb.seg_raw_off[lo]);
+  const int32_t pos = tb.seg_pos0[sid] + idx;
+  const int64_t slot = (int64_t)tb.seg_off[sid] + idx;
+  const float2 cs = tb.rope[(int64_t)pos * half + i];
+  const int64_t src = (tok * Hkv + h) * D;
+  const float a = hpd::to_float(k_raw[src + i]);
+  const float b = hpd::to_float(k_raw[src + i + half]);
+  const int64_t kdst = ((int64_t)h * NP + slot) * D;
+  k_prefix[kdst + i] = hpd::from_float<T>(a * cs.x - b * cs.y);
+  k_prefix[kdst + i + half] = hpd::from_float<T>(b * cs.x + a * cs.y);
+  const int64_t vblk = ((int64_t)h * (NP / 8) + slot / 8) * D;
+  v_prefix[(vblk + i) * 8 + (slot & 7)] = v_raw[src + i];
+  v_prefix[(vblk + i + half) * 8 + (slot & 7)] = v_raw[src + i + half];
+}
+
+// ---------------------------------------------------------------------------------------
+// Position IDs of the live branches of one step.
+// ---------------------------------------------------------------------------------------
+__global__ void positions_kernel(hpd_dev_tables tb, int32_t step, int32_t n_live,
+                                 int32_t* __restrict__ pos_out) {
+  const int32_t r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_live) return;
+  const int32_t b = tb.live_branch[tb.live_ptr[step] + r];
+  pos_out[r] = tb.branch_base_pos[b] + 1 + step;
+}
+
+// ---------------------------------------------------------------------------------------
+// Append: RoPE(K) + store K, V of every live branch at tail slot b*T + step.
+// ---------------------------------------------------------------------------------------
+template <typename T>
+__global__ void append_kernel(hpd_dev_tables tb, int32_t step, int32_t n_live, int32_t Hkv,
+                              int32_t D, int32_t Tcap, const T* __restrict__ k_new,
+                              const T* __restrict__ v_new, T* __restrict__ k_tail,
+                              T* __restrict__ v_tail, int64_t* __restrict__ slot_out) {
+  const int32_t half = D / 2;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t total = (int64_t)n_live * Hkv * half;
+  if (gid >= total) return;
+  const int32_t i = (int32_t)(gid % half);
+  const int32_t h = (int32_t)((gid / half) % Hkv);
+  const int32_t r = (int32_t)(gid / ((int64_t)half * Hkv));
+  const int32_t b = tb.live_branch[tb.live_ptr[step] + r];
+  const int32_t pos = tb.branch_base_pos[b] + 1 + step;
+  const int64_t slot = (int64_t)b * Tcap + step;
+  const float2 cs = tb.rope[(int64_t)pos * half + i];
+  const int64_t src = ((int64_t)r * Hkv + h) * D;
+  const float a = hpd::to_float(k_new[src + i]);
+  const float bb = hpd::to_float(k_new[src + i + half]);
+  const int64_t dst = (((int64_t)b * Hkv + h) * Tcap + step) * D;
+  k_tail[dst + i] = hpd::from_float<T>(a * cs.x - bb * cs.y);
+  k_tail[dst + i + half] = hpd::from_float<T>(bb * cs.x + a * cs.y);
+  v_tail[dst + i] = v_new[src + i];
+  v_tail[dst + i + half] = v_new[src + i + half];
+  if (slot_out && h == 0 && i == 0) slot_out[r] = slot;
+}
+
+// ---------------------------------------------------------------------------------------
+// Dense mask export (debugging aid).  desc[S][4] = (kind, document, branch, step).
+// ---------------------------------------------------------------------------------------
+__global__ void expand_mask_kernel(const int32_t* __restrict__ desc, int32_t S,
+                                   uint8_t* __restrict__ mask) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (int64_t)S * S) return;
+  const int32_t qi = (int32_t)(gid / S), ki = (int32_t)(gid % S);
+  const int32_t qk = desc[qi * 4], qd = desc[qi * 4 + 1], qb = desc[qi * 4 + 2], qs = desc[qi * 4 + 3];
+  const int32_t kk = desc[ki * 4], kd = desc[ki * 4 + 1], kb = desc[ki * 4 + 2], ks = desc[ki * 4 + 3];
+  bool ok;
+  if (kk == 0) ok = (qk != 0) || (ki <= qi);                         // header key
+  else if (kk == 1) ok = (qk == 1 && qd == kd && ki <= qi) || (qk == 2 && qd == kd);  // doc key
+  else ok = (qk == 2 && qb == kb && ks <= qs);                        // branch key
+  mask[gid] = ok ? 1 : 0;
+}
+
+// ---------------------------------------------------------------------------------------
+// Generic attention: one 256-thread block per (live row, query head).
+//   phase 1  one key per thread: full dot product with the rotated query (kept in LDS),
+//            scores to LDS, block max
+//   phase 2  p = exp(s - max), block sum
+//   phase 3  one channel per thread, keys split over 256/D thread groups, reduce in LDS
+// ---------------------------------------------------------------------------------------
+constexpr int GEN_THREADS = 256;
+
+__device__ inline float block_reduce(float v, bool is_max, float* red) {
+  for (int o = 32; o > 0; o >>= 1) {
+    const float w = __shfl_xor(v, o);
+    v = is_max ? fmaxf(v, w) : v + w;
+  }
+  const int wave = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  float r = red[0];
+  for (int w = 1; w < GEN_THREADS / 64; ++w) r = is_max ? fmaxf(r, red[w]) : r + red[w];
+  return r;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(GEN_THREADS)
+attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hkv, int32_t D,
+                         int32_t Tcap, int32_t P, int64_t NP, const T* __restrict__ q,
+                         const T* __restrict__ k_prefix, const T* __restrict__ v_prefix,
+                         const T* __restrict__ k_tail, const T* __restrict__ v_tail,
+                         T* __restrict__ out) {
+  extern __shared__ float smem[];
+  float* q_rot = smem;             // [D]
+  float* red = smem + D;           // [8]
+  float* part = red + 8;           // [256] partial outputs
+  float* scores = part + GEN_THREADS;  // [n_keys]
+
+  const int32_t r = blockIdx.x / Hq;
+  const int32_t h = blockIdx.x % Hq;
+  const int32_t hk = h / (Hq / Hkv);
+  const int32_t b = tb.live_branch[tb.live_ptr[step] + r];
+  const int32_t d = tb.branch_doc[b];
+  const int32_t p = tb.doc_prompt[d];
+  const int32_t pos = tb.branch_base_pos[b] + 1 + step;
+  const int32_t Hlen = tb.seg_len[p], Llen = tb.seg_len[P + d];
+  const int64_t hoff = tb.seg_off[p], doff = tb.seg_off[P + d];
+  const int32_t n_keys = Hlen + Llen + step + 1;
+  const int32_t half = D / 2;
+  const int tid = threadIdx.x;
+
+  if (tid < half) {
+    const float2 cs = tb.rope[(int64_t)pos * half + tid];
+    const int64_t src = ((int64_t)r * Hq + h) * D;
+    const float a = hpd::to_float(q[src + tid]), bb = hpd::to_float(q[src + tid + half]);
+    q_rot[tid] = a * cs.x - bb * cs.y;
+    q_rot[tid + half] = bb * cs.x + a * cs.y;
+  }
+  __syncthreads();
+
+  const float scale = 1.0f / sqrtf((float)D);
+  const int64_t tail_base = (((int64_t)b * Hkv + hk) * Tcap) * D;
+  float lmax = -INFINITY;
+  for (int32_t kk = tid; kk < n_keys; kk += GEN_THREADS) {
+    const T* kp;
+    if (kk < Hlen) kp = k_prefix + ((int64_t)hk * NP + hoff + kk) * D;
+    else if (kk < Hlen + Llen) kp = k_prefix + ((int64_t)hk * NP + doff + (kk - Hlen)) * D;
+    else kp = k_tail + tail_base + (int64_t)(kk - Hlen - Llen) * D;
+    float acc = 0.f;
+    for (int32_t c = 0; c < D; c += 8) {
+      float kv[8];
+      hpd::load8(kp + c, kv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc = fmaf(kv[e], q_rot[c + e], acc);
+    }
+    acc *= scale;
+    scores[kk] = acc;
+    lmax = fmaxf(lmax, acc);
+  }
+  const float m = block_reduce(lmax, true, red);
+  float lsum = 0.f;
+  for (int32_t kk = tid; kk < n_keys; kk += GEN_THREADS) {
+    const float pr = expf(scores[kk] - m);
+    scores[kk] = pr;
+    lsum += pr;
+  }
+  const float l = block_reduce(lsum, false, red);  // contains the barrier that publishes scores
+
+  const int32_t groups = GEN_THREADS / D > 0 ? GEN_THREADS / D : 1;
+  const int32_t c = tid % D, g = tid / D;
+  float acc = 0.f;
+  if (g < groups && tid < groups * D) {
+    const int64_t vhead = (int64_t)hk * (NP / 8);
+    for (int32_t kk = g; kk < n_keys; kk += groups) {
+      float vv;
+      if (kk < Hlen + Llen) {
+        const int64_t slot = (kk < Hlen) ? hoff + kk : doff + (kk - Hlen);
+        vv = hpd::to_float(v_prefix[((vhead + slot / 8) * D + c) * 8 + (slot & 7)]);
+      } else {
+        vv = hpd::to_float(v_tail[tail_base + (int64_t)(kk - Hlen - Llen) * D + c]);
+      }
+      acc = fmaf(scores[kk], vv, acc);
+    }
+  }
+  part[tid] = acc;
+  __syncthreads();
+  if (tid < D) {
+    float o = 0.f;
+    for (int32_t gg = 0; gg < groups; ++gg) o += part[gg * D + tid];
+    out[((int64_t)r * Hq + h) * D + tid] = hpd::from_float<T>(o / l);
+  }
+}
+
+inline dim3 grid1d(int64_t n, int block) { return dim3((unsigned)((n + block - 1) / block)); }
+
+}  // namespace
+
+hipError_t hpd_launch_prefix_fill(const hpd_layout* L, const void* k_raw, const void* v_raw,
+                                  void* k_prefix, void* v_prefix, hipStream_t s) {
+  const int64_t total = L->n_prefix_tokens * L->cfg.n_kv_heads * (L->cfg.head_dim / 2);
+  if (total == 0) return hipSuccess;
+  if (L->cfg.dtype == HPD_F32)
+    prefix_fill_kernel<float><<<grid1d(total, 256), 256, 0, s>>>(
+        L->dev, L->n_seg, L->n_prefix_tokens, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP,
+        (const float*)k_raw, (const float*)v_raw, (float*)k_prefix, (float*)v_prefix);
+  else
+    prefix_fill_kernel<hpd::bf16_t><<<grid1d(total, 256), 256, 0, s>>>(
+        L->dev, L->n_seg, L->n_prefix_tokens, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP,
+        (const hpd::bf16_t*)k_raw, (const hpd::bf16_t*)v_raw, (hpd::bf16_t*)k_prefix,
+        (hpd::bf16_t*)v_prefix);
+  return hipGetLastError();
+}
+
+hipError_t hpd_launch_positions(const hpd_layout* L, int32_t step, int32_t* pos_out, hipStream_t s) {
+  const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
+  positions_kernel<<<grid1d(n_live, 256), 256, 0, s>>>(L->dev, step, n_live, pos_out);
+  return hipGetLastError();
+}
+
+hipError_t hpd_launch_append(const hpd_layout* L, int32_t step, const void* k_new, const void* v_new,
+                             void* k_tail, void* v_tail, int64_t* slot_out, hipStream_t s) {
+  const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
+  const int64_t total = (int64_t)n_live * L->cfg.n_kv_heads * (L->cfg.head_dim / 2);
+  if (L->cfg.dtype == HPD_F32)
+    append_kernel<float><<<grid1d(total, 256), 256, 0, s>>>(
+        L->dev, step, n_live, L->cfg.n_kv_heads, L->cfg.head_dim, L->T, (const float*)k_new,
+        (const float*)v_new, (float*)k_tail, (float*)v_tail, slot_out);
+  else
+    append_kernel<hpd::bf16_t><<<grid1d(total, 256), 256, 0, s>>>(
+        L->dev, step, n_live, L->cfg.n_kv_heads, L->cfg.head_dim, L->T, (const hpd::bf16_t*)k_new,
+        (const hpd::bf16_t*)v_new, (hpd::bf16_t*)k_tail, (hpd::bf16_t*)v_tail, slot_out);
+  return hipGetLastError();
+}
+
+hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const void* q,
+                                        const void* k_prefix, const void* v_prefix,
+                                        const void* k_tail, const void* v_tail, void* out,
+                                        hipStream_t s) {
+  const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
+  int64_t max_keys = 0;
+  for (int32_t u = L->unit_ptr[step]; u < L->unit_ptr[step + 1]; ++u) {
+    const int32_t d = L->unit_doc[u];
+    max_keys = std::max<int64_t>(max_keys, (int64_t)L->seg_len[L->doc_prompt[d]] +
+                                               L->seg_len[L->P + d] + step + 1);
+  }
+  const size_t smem = (size_t)(L->cfg.head_dim + 8 + GEN_THREADS + max_keys) * sizeof(float);
+  const dim3 grid((unsigned)((int64_t)n_live * L->cfg.n_q_heads));
+  if (L->cfg.dtype == HPD_F32)
+    attention_generic_kernel<float><<<grid, GEN_THREADS, smem, s>>>(
+        L->dev, step, L->cfg.n_q_heads, L->cfg.n_kv_heads, L->cfg.head_dim, L->T, L->P, L->NP,
+        (const float*)q, (const float*)k_prefix, (const float*)v_prefix, (const float*)k_tail,
+        (const float*)v_tail, (float*)out);
+  else
+    attention_generic_kernel<hpd::bf16_t><<<grid, GEN_THREADS, smem, s>>>(
+        L->dev, step, L->cfg.n_q_heads, L->cfg.n_kv_heads, L->cfg.head_dim, L->T, L->P, L->NP,
+        (const hpd::bf16_t*)q, (const hpd::bf16_t*)k_prefix, (const hpd::bf16_t*)v_prefix,
+        (const hpd::bf16_t*)k_tail, (const hpd::bf16_t*)v_tail, (hpd::bf16_t*)out);
+  return hipGetLastError();
+}
+
+hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, uint8_t* mask_out, hipStream_t s) {
+  expand_mask_kernel<<<grid1d((int64_t)S * S, 256), 256, 0, s>>>(d_desc, S, mask_out);
+  return hipGetLastError();
+}

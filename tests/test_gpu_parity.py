@@ -1,0 +1,146 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integers (positions, slots, masks) bit-exact; outputs within 1e-4 max-abs
+(fp32) or 2e-2 x RMS (bf16)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_26209_amd import workloads as W
+
+import hpd_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def test_cfg1_fp32_all_steps_two_call_and_fused():
+    wl = W.config(1)
+    _say("cfg1 two-call")
+    hip = H.run_hip(wl)
+    err = H.check_all(wl, hip, label="cfg1")
+    _say(f"cfg1 max-abs {err:.2e}")
+    _say("cfg1 fused")
+    hip2 = H.run_hip(wl, inputs=hip["inputs"], fused=True)
+    for a, b in zip(hip["out"], hip2["out"]):
+        assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_ragged_fp32(seed):
+    _say(f"random fp32 seed {seed}")
+    wl = W.random_workload(seed, dtype="f32", hq=4, hkv=2, d=64, t=6, p=3)
+    hip = H.run_hip(wl)
+    H.check_all(wl, hip, label=f"rand_f32_{seed}")
+
+
+def test_fp32_other_head_dims_and_empty_header():
+    for d, hq, hkv in [(32, 2, 1), (128, 4, 4), (96, 3, 1)]:
+        _say(f"fp32 D={d}")
+        wl = W.random_workload(40 + d, dtype="f32", hq=hq, hkv=hkv, d=d, t=3, p=2, h_range=(0, 0),
+                               l_range=(1, 40))
+        H.check_all(wl, H.run_hip(wl), label=f"f32_D{d}")
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("seed", [11, 12])
+def test_random_ragged_bf16_both_kernels(seed, mode):
+    """mode 1 = generic wave-reduction kernel, mode 2 = MFMA shared-prefix kernel."""
+    _say(f"random bf16 seed {seed} mode {mode}")
+    wl = W.random_workload(seed, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=5, p=3,
+                           h_range=(0, 70), l_range=(1, 150), n_range=(1, 12))
+    hip = H.run_hip(wl, kernel_mode=mode)
+    rel = H.check_all(wl, hip, label=f"rand_bf16_{seed}_m{mode}")
+    _say(f"  worst err/rms {rel:.2e}")
+
+
+def test_mfma_edge_shapes():
+    cases = {
+        "single_branch_h0_l1": W.make_workload("e1", "bf16", 4, 1, 128, 500000.0, 3, [0], [1], [1], [1]),
+        "mha_g1": W.make_workload("e2", "bf16", 2, 2, 128, 500000.0, 2, [5], [1], [33], [3]),
+        "many_rows_two_row_groups": W.make_workload("e3", "bf16", 16, 2, 128, 500000.0, 2, [40], [1],
+                                                    [100], [40]),  # 8*40 = 320 rows -> 10 blocks
+        "exact_blocks": W.make_workload("e4", "bf16", 8, 2, 128, 500000.0, 4, [64], [2], [128, 96], [8, 16]),
+        "t1": W.make_workload("e5", "bf16", 8, 8, 128, 500000.0, 1, [7], [1], [9], [5]),
+    }
+    for name, wl in cases.items():
+        _say(f"mfma edge {name}")
+        hip = H.run_hip(wl, kernel_mode=2)
+        H.check_all(wl, hip, label=name)
+
+
+def test_paper_gap_positions_mode():
+    _say("paper-gap mode")
+    wl = W.random_workload(21, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=4, p=2)
+    attr = np.random.default_rng(3).integers(1, 6, size=wl.n_branches).astype(np.int32)
+    hip = H.run_hip(wl, pos_mode=1, attr_len=attr)
+    H.check_all(wl, hip, pos_mode="paper_gap", attr_len=attr, label="gap")
+    wl = W.random_workload(22, dtype="f32", t=4, p=2)
+    attr = np.random.default_rng(4).integers(1, 6, size=wl.n_branches).astype(np.int32)
+    hip = H.run_hip(wl, pos_mode=1, attr_len=attr)
+    H.check_all(wl, hip, pos_mode="paper_gap", attr_len=attr, label="gap_f32")
+
+
+def test_mask_export_bit_exact():
+    from paper_2604_26209_amd import binding as B
+    _say("mask export")
+    wl = W.random_workload(31, dtype="f32", t=4, p=3, l_range=(1, 30), h_range=(0, 12))
+    hip = H.run_hip(wl)
+    orc, _ = H.run_oracle(wl, hip["inputs"])
+    for p, po in orc.prompts.items():
+        s = B.hpd_expand_mask(hip["layout"], p, wl.max_new - 1)
+        assert s == len(po.kind)
+        m = torch.full((s, s), 7, dtype=torch.uint8, device="cuda")
+        B.hpd_expand_mask(hip["layout"], p, wl.max_new - 1, m)
+        assert np.array_equal(m.cpu().numpy(), po.dense_mask())
+
+
+def test_kv_pools_hold_rotated_keys_at_reported_slots():
+    """K tail and prefix pools against the oracle's cache (rotated K), through the
+    documented pool layouts."""
+    from paper_2604_26209_amd import binding as B
+    _say("pool contents")
+    wl = W.random_workload(51, dtype="f32", hq=4, hkv=2, d=64, t=4, p=2)
+    hip = H.run_hip(wl, poison_pools=False)
+    orc, res = H.run_oracle(wl, hip["inputs"])
+    kp, vp, kt, vt = [x.cpu().numpy() for x in hip["pools"]]
+    lay = hip["layout"]
+    c = lay.counts()
+    NP, T, Hkv, D = int(c[B.HPD_C_N_PREFIX_SLOTS]), wl.max_new, wl.n_kv_heads, wl.head_dim
+    kp = kp.reshape(Hkv, NP, D)
+    vp = vp.reshape(Hkv, NP // 8, D, 8)
+    kt = kt.reshape(wl.n_branches, Hkv, T, D)
+    vt = vt.reshape(wl.n_branches, Hkv, T, D)
+    seg_off = B.hpd_layout_query(lay, B.HPD_Q_SEG_OFF)
+    for p, po in orc.prompts.items():
+        segs = [(p, 0, po.h)]
+        run = po.h
+        for j, d in enumerate(range(wl.doc_ptr[p], wl.doc_ptr[p + 1])):
+            segs.append((wl.n_prompts + d, run, po.doc_lens[j]))
+            run += po.doc_lens[j]
+        for sid, first, n in segs:
+            for i in range(n):
+                slot = seg_off[sid] + i
+                assert np.abs(kp[:, slot, :] - po.k[first + i]).max() < 1e-5
+                assert np.array_equal(vp[:, slot // 8, :, slot % 8], po.v[first + i])
+        b0, _ = orc.branch_range[p]
+        for idx in range(po.n_prefix, len(po.kind)):
+            b, t = b0 + po.branch[idx], po.step_of[idx]
+            assert np.abs(kt[b, :, t, :] - po.k[idx]).max() < 1e-5
+            assert np.array_equal(vt[b, :, t, :], po.v[idx])
+
+
+def test_error_paths_on_device_layout():
+    from paper_2604_26209_amd import binding as B
+    wl = W.config(1)
+    lay = B.layout_from_workload(wl)
+    with pytest.raises(B.HpdError):
+        B.hpd_rope_positions(lay, wl.max_new, torch.zeros(4, dtype=torch.int32, device="cuda"))
+    with pytest.raises(B.HpdError):
+        B.hpd_rope_positions(lay, -1, torch.zeros(4, dtype=torch.int32, device="cuda"))
+    with pytest.raises(B.HpdError):
+        B.hpd_kv_append(lay, 0, None, None, None, None)
+    with pytest.raises(B.HpdError):
+        B.hpd_set_kernel_mode(lay, 2)  # fp32 / D=64 has no MFMA path
