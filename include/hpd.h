@@ -70,6 +70,11 @@ enum hpd_pos_mode {
                            then a gap of max_new after every attribute */
 };
 enum hpd_mask_mode { HPD_MASK_BLOCK = 0 /* header + own document + own branch */ };
+enum hpd_out_dtype {
+  HPD_OUT_SAME = 0, /* `out` has the element type of the inputs */
+  HPD_OUT_F32 = 1   /* `out` is fp32 whatever the inputs are: bf16 cannot resolve 2e-2 x RMS
+                       on the largest outputs (half an ulp at |o| = 8 x RMS is 3e-2 x RMS) */
+};
 enum hpd_flags {
   HPD_FLAG_HOST_ONLY = 1 /* build host tables only (no HIP call); only hpd_layout_query
                             and hpd_layout_free may then be used on the layout */
@@ -85,6 +90,7 @@ typedef struct hpd_config {
   int32_t pos_mode;   /* hpd_pos_mode */
   int32_t mask_mode;  /* hpd_mask_mode */
   int32_t flags;      /* hpd_flags */
+  int32_t out_dtype;  /* hpd_out_dtype */
 } hpd_config;
 
 typedef struct hpd_layout hpd_layout; /* opaque; created and destroyed by the library */
@@ -206,6 +212,15 @@ int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, u
 /* Selects the attention kernel: 0 = automatic, 1 = generic wave-reduction kernel for
  * everything, 2 = MFMA shared-prefix kernel (error if the shape does not allow it). */
 int hpd_set_kernel_mode(hpd_layout* layout, int32_t mode);
+
+/* Tuning / diagnostic knobs of the MFMA kernel; defaults are chosen by the library. */
+enum hpd_tuning {
+  HPD_TUNE_WAVES = 0,  /* waves per workgroup: 4 or 8 (0 = default) */
+  HPD_TUNE_QSPLIT = 1, /* 1: feed the rotated query as bf16 hi + lo parts (two MFMA passes) */
+  HPD_TUNE_PSPLIT = 2  /* 0: probabilities as one bf16; 1: hi + lo parts where a weight is
+                          large enough to matter; 2: hi + lo always */
+};
+int hpd_set_tuning(hpd_layout* layout, int32_t key, int32_t value);
 
 const char* hpd_status_string(int status);
 

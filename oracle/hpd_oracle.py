@@ -9,7 +9,13 @@ Only tests, the smoke check and the benchmark's CPU-baseline leg may use it;
 the product path never imports it, and it imports nothing from the product.
 
 Arithmetic is NumPy in ``dtype`` (fp32 by default, fp64 on request); RoPE
-angles are always formed in fp64 and then cast.
+angles are always formed in fp64 and then cast.  Nothing is rounded in between,
+with one optional exception: ``cache_dtype="bf16"`` stores the rotated key in
+the cache rounded (to nearest even) to bfloat16, the storage type of the KV
+cache in the paper's bf16 inference (Appendix B, "Fine-tuning and Inference
+Details").  A cache entry is a quantised code; when the compared implementation
+keeps a bf16 cache, both sides have to take that rounding in the same precision
+or the comparison measures the cache format instead of the implementation.
 
 What each piece follows
 -----------------------
@@ -98,6 +104,14 @@ def rope(x: np.ndarray, pos, base: float, dtype=np.float32) -> np.ndarray:
     return out
 
 
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 -> nearest-even bfloat16, returned as fp32 values."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
 # ----------------------------------------------------------------------------
 # Dense masked attention (the plain definition)
 # ----------------------------------------------------------------------------
@@ -132,7 +146,10 @@ class PromptOracle:
     an explicit dense mask."""
 
     def __init__(self, header_len, doc_lens, branch_lens, n_q_heads, n_kv_heads, head_dim,
-                 rope_base, max_new, pos_mode="contig", attr_lens=None, dtype=np.float32):
+                 rope_base, max_new, pos_mode="contig", attr_lens=None, dtype=np.float32,
+                 cache_dtype=None):
+        self.cache_dtype = cache_dtype
+        assert cache_dtype in (None, "bf16")
         self.h = int(header_len)
         self.doc_lens = [int(x) for x in doc_lens]
         self.branch_lens = [[int(x) for x in bl] for bl in branch_lens]  # per doc
@@ -198,8 +215,13 @@ class PromptOracle:
         self.step_of = [-1] * self.n_prefix
         pos = self.prefix_positions()
         self.pos = [int(x) for x in pos]
-        self.k = rope(k_raw, pos, self.base, self.dtype)
+        self.k = self._to_cache(rope(k_raw, pos, self.base, self.dtype))
         self.v = np.asarray(v_raw, dtype=self.dtype).copy()
+
+    def _to_cache(self, k_rot):
+        if self.cache_dtype == "bf16":
+            return round_to_bf16(k_rot).astype(self.dtype)
+        return k_rot
 
     # -- liveness ---------------------------------------------------------------
     def live(self, t):
@@ -251,7 +273,8 @@ class PromptOracle:
         pos = np.asarray([self.branch_position(b, t) for b in live], dtype=np.int64)
         first = len(self.kind)
         if n_live:
-            self.k = np.concatenate([self.k, rope(k_new, pos, self.base, self.dtype)], axis=0)
+            self.k = np.concatenate(
+                [self.k, self._to_cache(rope(k_new, pos, self.base, self.dtype))], axis=0)
             self.v = np.concatenate([self.v, np.asarray(v_new, dtype=self.dtype)], axis=0)
         for r, b in enumerate(live):
             self.kind.append(KIND_BRANCH)
@@ -295,7 +318,7 @@ class HPDOracle:
 
     def __init__(self, header_len, doc_ptr, doc_len, branch_ptr, branch_len, n_q_heads,
                  n_kv_heads, head_dim, rope_base, max_new, pos_mode="contig", attr_len=None,
-                 dtype=np.float32, prompts=None):
+                 dtype=np.float32, prompts=None, cache_dtype=None):
         """``prompts``: optional subset of prompt ids to instantiate (others are
         skipped entirely; global ids keep their full-batch values)."""
         header_len = np.asarray(header_len)
@@ -330,7 +353,7 @@ class HPDOracle:
                 al = None if attr_len is None else [int(x) for x in np.asarray(attr_len)[b0:b1]]
                 self.prompts[p] = PromptOracle(int(header_len[p]), doc_len[d0:d1], bl, n_q_heads,
                                                n_kv_heads, head_dim, rope_base, max_new,
-                                               pos_mode, al, dtype)
+                                               pos_mode, al, dtype, cache_dtype)
         self.n_prefix_tokens = tok
 
     def live(self, t):

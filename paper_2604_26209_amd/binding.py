@@ -41,6 +41,8 @@ HPD_F32, HPD_BF16 = 0, 1
 HPD_POS_CONTIG, HPD_POS_PAPER_GAP = 0, 1
 HPD_MASK_BLOCK = 0
 HPD_FLAG_HOST_ONLY = 1
+HPD_OUT_SAME, HPD_OUT_F32 = 0, 1
+HPD_TUNE_WAVES, HPD_TUNE_QSPLIT, HPD_TUNE_PSPLIT = 0, 1, 2
 HPD_KEY_BLOCK = 32
 (HPD_Q_COUNTS, HPD_Q_POOL_BYTES, HPD_Q_N_LIVE, HPD_Q_LIVE_BRANCH, HPD_Q_BRANCH_BASE_POS,
  HPD_Q_BRANCH_DOC, HPD_Q_SEG_OFF, HPD_Q_SEG_LEN, HPD_Q_SEG_POS0, HPD_Q_SEG_RAW_OFF,
@@ -50,7 +52,7 @@ HPD_KEY_BLOCK = 32
 
 EXPORTS = ["hpd_build_layout", "hpd_layout_free", "hpd_layout_query", "hpd_prefix_fill",
            "hpd_rope_positions", "hpd_kv_append", "hpd_decode_attention", "hpd_decode_step",
-           "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_status_string"]
+           "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_set_tuning", "hpd_status_string"]
 
 
 class hpd_config(ctypes.Structure):
@@ -58,7 +60,7 @@ class hpd_config(ctypes.Structure):
                 ("head_dim", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("rope_base", ctypes.c_double), ("max_new", ctypes.c_int32),
                 ("pos_mode", ctypes.c_int32), ("mask_mode", ctypes.c_int32),
-                ("flags", ctypes.c_int32)]
+                ("flags", ctypes.c_int32), ("out_dtype", ctypes.c_int32)]
 
 
 _vp, _i32, _i64p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)
@@ -75,6 +77,7 @@ _lib.hpd_decode_attention.argtypes = [_vp, _i32] + [_vp] * 7
 _lib.hpd_decode_step.argtypes = [_vp, _i32] + [_vp] * 9
 _lib.hpd_expand_mask.argtypes = [_vp, _i32, _i32, _vp, _i32p, _vp]
 _lib.hpd_set_kernel_mode.argtypes = [_vp, _i32]
+_lib.hpd_set_tuning.argtypes = [_vp, _i32, _i32]
 _lib.hpd_status_string.argtypes = [ctypes.c_int]
 _lib.hpd_status_string.restype = ctypes.c_char_p
 for _name in EXPORTS:
@@ -232,17 +235,22 @@ def hpd_set_kernel_mode(layout, mode: int):
     _check(_lib.hpd_set_kernel_mode(layout.handle, int(mode)), "hpd_set_kernel_mode")
 
 
+def hpd_set_tuning(layout, key: int, value: int):
+    _check(_lib.hpd_set_tuning(layout.handle, int(key), int(value)), "hpd_set_tuning")
+
+
 # ---------------------------------------------------------------------------
 # marshalling helpers (no arithmetic of the method)
 # ---------------------------------------------------------------------------
-def config_from_workload(wl, pos_mode=HPD_POS_CONTIG, flags=0) -> hpd_config:
+def config_from_workload(wl, pos_mode=HPD_POS_CONTIG, flags=0, out_dtype=HPD_OUT_SAME) -> hpd_config:
     return hpd_config(wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
                       HPD_F32 if wl.dtype == "f32" else HPD_BF16, float(wl.rope_base),
-                      wl.max_new, pos_mode, HPD_MASK_BLOCK, flags)
+                      wl.max_new, pos_mode, HPD_MASK_BLOCK, flags, out_dtype)
 
 
-def layout_from_workload(wl, pos_mode=HPD_POS_CONTIG, attr_len=None, flags=0, stream=None):
-    cfg = config_from_workload(wl, pos_mode, flags)
+def layout_from_workload(wl, pos_mode=HPD_POS_CONTIG, attr_len=None, flags=0, stream=None,
+                         out_dtype=HPD_OUT_SAME):
+    cfg = config_from_workload(wl, pos_mode, flags, out_dtype)
     return hpd_build_layout(cfg, wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr,
                             wl.branch_len, attr_len, stream)
 

@@ -22,6 +22,8 @@
 // Per-branch tails (Section 4.3.3: each value still grows autoregressively) are not
 // shared, have G rows per key and are handled with lane-private dot products plus one
 // cross-lane add, merged into the same running statistics.
+#include <cmath>
+
 #include "hpd_internal.h"
 #include "hpd_device.h"
 
@@ -38,7 +40,7 @@ constexpr float NEG_BIG = -1.0e30f;
 
 struct MfmaArgs {
   hpd_dev_tables tb;
-  int32_t step, Hq, Hkv, G, Tcap, P, n_docs, W, RG;
+  int32_t step, Hq, Hkv, G, Tcap, P, n_docs, W, RG, psplit, out_f32;
   int64_t NP;
   float scale_log2;
 };
@@ -77,10 +79,15 @@ __device__ __forceinline__ void rescale(RowState& st, float alpha) {
     for (int i = 0; i < 16; ++i) st.acc[blk][i] *= alpha;
 }
 
+// QSPLIT: the rotated query enters the score product as bf16 hi + lo parts (two MFMA passes),
+// which removes its rounding from the error budget.  a.psplit does the same for the
+// probabilities in the P.V product: 2 = always, 1 = only for a 16-key half-block in which
+// some row holds a weight of at least 2^-6 of its running sum, 0 = never.
+template <bool QSPLIT>
 __global__ void __launch_bounds__(MAX_WAVES * 64)
 attn_mfma_kernel(MfmaArgs a, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_prefix,
                  const uint16_t* __restrict__ v_prefix, const uint16_t* __restrict__ k_tail,
-                 const uint16_t* __restrict__ v_tail, uint16_t* __restrict__ out) {
+                 const uint16_t* __restrict__ v_tail, void* __restrict__ out) {
   extern __shared__ float merge_buf[];
 
   const int tid = threadIdx.x;
@@ -129,6 +136,7 @@ attn_mfma_kernel(MfmaArgs a, const uint16_t* __restrict__ q, const uint16_t* __r
     //      Qf[kk] holds channels kk*16 + g2*8 + 0..7 of row n; the rotation partner of
     //      channel c is c + 64, i.e. Qf[kk + 4] of the same lane.
     bf16x8 Qf[8];
+    bf16x8 Ql[QSPLIT ? 8 : 1];
     {
       const int32_t pos = a.tb.branch_base_pos[b] + 1 + a.step;
       const float2* cs_row = a.tb.rope + (int64_t)pos * (D / 2);
@@ -154,6 +162,15 @@ attn_mfma_kernel(MfmaArgs a, const uint16_t* __restrict__ q, const uint16_t* __r
         }
         Qf[kk] = pack8(rl);
         Qf[kk + 4] = pack8(rh);
+        if (QSPLIT) {
+          float hl[8], hh[8];
+          unpack8(__builtin_bit_cast(uint4, Qf[kk]), hl);
+          unpack8(__builtin_bit_cast(uint4, Qf[kk + 4]), hh);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { rl[e] -= hl[e]; rh[e] -= hh[e]; }
+          Ql[kk] = pack8(rl);
+          Ql[kk + 4] = pack8(rh);
+        }
       }
     }
 
@@ -180,6 +197,7 @@ attn_mfma_kernel(MfmaArgs a, const uint16_t* __restrict__ q, const uint16_t* __r
       for (int kk = 0; kk < 8; ++kk) {
         const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(kp + kk * 16));
         S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qf[kk], S, 0, 0, 0);
+        if (QSPLIT) S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Ql[kk], S, 0, 0, 0);
       }
       // V operands can be requested before the softmax arithmetic
       uint4 vf[8];
@@ -209,6 +227,23 @@ attn_mfma_kernel(MfmaArgs a, const uint16_t* __restrict__ q, const uint16_t* __r
       st.l += ps;
       st.m = m_new;
       const bf16x8 P0 = pack8(s), P1 = pack8(s + 8);
+      bool lo0 = false, lo1 = false;
+      bf16x8 L0 = P0, L1 = P1;
+      if (a.psplit) {
+        float h0[8], h1[8], r0[8], r1[8];
+        unpack8(__builtin_bit_cast(uint4, P0), h0);
+        unpack8(__builtin_bit_cast(uint4, P1), h1);
+        float big0 = 0.f, big1 = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          big0 = fmaxf(big0, s[e]); big1 = fmaxf(big1, s[8 + e]);
+          r0[e] = s[e] - h0[e]; r1[e] = s[8 + e] - h1[e];
+        }
+        L0 = pack8(r0); L1 = pack8(r1);
+        const float thr = st.l * 0.015625f;
+        lo0 = a.psplit == 2 || __any(big0 >= thr);
+        lo1 = a.psplit == 2 || __any(big1 >= thr);
+      }
 
       if (valid < 32) {
         // padding slots may hold NaN patterns: 0 * NaN must not reach the accumulators
@@ -229,6 +264,18 @@ attn_mfma_kernel(MfmaArgs a, const uint16_t* __restrict__ q, const uint16_t* __r
         st.acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
             __builtin_bit_cast(bf16x8, vf[blk * 2 + 1]), P1, st.acc[blk], 0, 0, 0);
       }
+      if (lo0) {
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk)
+          st.acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, vf[blk * 2]), L0, st.acc[blk], 0, 0, 0);
+      }
+      if (lo1) {
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk)
+          st.acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, vf[blk * 2 + 1]), L1, st.acc[blk], 0, 0, 0);
+      }
     }
 
     // ---- per-branch tail: keys 0..step of the lane's own branch, split over key groups.
@@ -243,6 +290,12 @@ attn_mfma_kernel(MfmaArgs a, const uint16_t* __restrict__ q, const uint16_t* __r
           float kv[8], qv[8];
           unpack8(*reinterpret_cast<const uint4*>(kp + kk * 16), kv);
           unpack8(__builtin_bit_cast(uint4, Qf[kk]), qv);
+          if (QSPLIT) {
+            float ql[8];
+            unpack8(__builtin_bit_cast(uint4, Ql[kk]), ql);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qv[e] += ql[e];
+          }
 #pragma unroll
           for (int e = 0; e < 8; ++e) dot = fmaf(kv[e], qv[e], dot);
         }
@@ -302,16 +355,27 @@ attn_mfma_kernel(MfmaArgs a, const uint16_t* __restrict__ q, const uint16_t* __r
   // ---- normalise and store
   if (active && kg == 0 && row_valid) {
     const float inv = 1.0f / st.l;
-    uint16_t* op = out + q_off + g2 * 4;
+    if (a.out_f32) {
+      float* op = reinterpret_cast<float*>(out) + q_off + g2 * 4;
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk)
+      for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        uint2 w;
-        w.x = pack_bf16x2(st.acc[blk][c * 4 + 0] * inv, st.acc[blk][c * 4 + 1] * inv);
-        w.y = pack_bf16x2(st.acc[blk][c * 4 + 2] * inv, st.acc[blk][c * 4 + 3] * inv);
-        *reinterpret_cast<uint2*>(op + blk * 32 + c * 8) = w;
-      }
+        for (int c = 0; c < 4; ++c)
+          *reinterpret_cast<float4*>(op + blk * 32 + c * 8) =
+              make_float4(st.acc[blk][c * 4 + 0] * inv, st.acc[blk][c * 4 + 1] * inv,
+                          st.acc[blk][c * 4 + 2] * inv, st.acc[blk][c * 4 + 3] * inv);
+    } else {
+      uint16_t* op = reinterpret_cast<uint16_t*>(out) + q_off + g2 * 4;
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          uint2 w;
+          w.x = pack_bf16x2(st.acc[blk][c * 4 + 0] * inv, st.acc[blk][c * 4 + 1] * inv);
+          w.y = pack_bf16x2(st.acc[blk][c * 4 + 2] * inv, st.acc[blk][c * 4 + 3] * inv);
+          *reinterpret_cast<uint2*>(op + blk * 32 + c * 8) = w;
+        }
+    }
   }
 }
 
@@ -327,8 +391,11 @@ hipError_t hpd_launch_attention_mfma(const hpd_layout* L, int32_t step, const vo
   static bool attr_set = false;
   const size_t smem = (size_t)MERGE_REGIONS * MERGE_FLOATS * sizeof(float);
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel,
+    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<false>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)attn_mfma_kernel<true>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
@@ -343,8 +410,15 @@ hipError_t hpd_launch_attention_mfma(const hpd_layout* L, int32_t step, const vo
   a.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)D));
   const int32_t n_units = L->unit_ptr[step + 1] - L->unit_ptr[step];
   const dim3 grid((unsigned)((int64_t)n_units * a.Hkv * a.RG));
-  attn_mfma_kernel<<<grid, a.W * 64, smem, s>>>(a, (const uint16_t*)q, (const uint16_t*)k_prefix,
-                                                (const uint16_t*)v_prefix, (const uint16_t*)k_tail,
-                                                (const uint16_t*)v_tail, (uint16_t*)out);
+  a.psplit = L->psplit;
+  a.out_f32 = L->cfg.out_dtype == HPD_OUT_F32 ? 1 : 0;
+  if (L->qsplit)
+    attn_mfma_kernel<true><<<grid, a.W * 64, smem, s>>>(
+        a, (const uint16_t*)q, (const uint16_t*)k_prefix, (const uint16_t*)v_prefix,
+        (const uint16_t*)k_tail, (const uint16_t*)v_tail, out);
+  else
+    attn_mfma_kernel<false><<<grid, a.W * 64, smem, s>>>(
+        a, (const uint16_t*)q, (const uint16_t*)k_prefix, (const uint16_t*)v_prefix,
+        (const uint16_t*)k_tail, (const uint16_t*)v_tail, out);
   return hipGetLastError();
 }

@@ -42,6 +42,7 @@ int validate_config(const hpd_config* c) {
   if (c->pos_mode != HPD_POS_CONTIG && c->pos_mode != HPD_POS_PAPER_GAP) return HPD_E_UNSUPPORTED;
   if (c->mask_mode != HPD_MASK_BLOCK) return HPD_E_UNSUPPORTED;
   if (c->flags & ~HPD_FLAG_HOST_ONLY) return HPD_E_INVALID;
+  if (c->out_dtype != HPD_OUT_SAME && c->out_dtype != HPD_OUT_F32) return HPD_E_UNSUPPORTED;
   return HPD_OK;
 }
 
@@ -336,6 +337,22 @@ int hpd_set_kernel_mode(hpd_layout* L, int32_t mode) {
   if (mode == 2 && !hpd_mfma_supported(L)) return HPD_E_UNSUPPORTED;
   L->kernel_mode = mode;
   return HPD_OK;
+}
+
+int hpd_set_tuning(hpd_layout* L, int32_t key, int32_t value) {
+  if (!L) return HPD_E_INVALID;
+  switch (key) {
+    case HPD_TUNE_WAVES:
+      if (value != 0 && value != 4 && value != 8) return HPD_E_INVALID;
+      L->mfma_waves = value; return HPD_OK;
+    case HPD_TUNE_QSPLIT:
+      if (value < 0 || value > 1) return HPD_E_INVALID;
+      L->qsplit = value; return HPD_OK;
+    case HPD_TUNE_PSPLIT:
+      if (value < 0 || value > 2) return HPD_E_INVALID;
+      L->psplit = value; return HPD_OK;
+    default: return HPD_E_INVALID;
+  }
 }
 
 static int check_step(const hpd_layout* L, int32_t step) {

@@ -34,6 +34,7 @@ struct hpd_layout {
   int32_t max_pos = 0;
   int32_t kernel_mode = 0;
   int32_t mfma_waves = 0;  // 0 = heuristic
+  int32_t qsplit = 1, psplit = 0;  // see hpd_tuning; defaults meet the 2e-2 x RMS bound
 
   std::vector<int32_t> seg_off, seg_len, seg_pos0, seg_raw_off, raw_seg;
   std::vector<int32_t> doc_prompt, branch_doc, branch_base_pos, branch_len;

@@ -2,6 +2,8 @@
 // positions, append, mask export) and the generic wave-reduction attention kernel that
 // covers fp32, odd shapes and serves as the fallback.  The MFMA shared-prefix kernel is
 // in hpd_attn_mfma.hip.
+#include <algorithm>
+
 #include "hpd_internal.h"
 #include "hpd_device.h"
 
@@ -134,7 +136,7 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
                          int32_t Tcap, int32_t P, int64_t NP, const T* __restrict__ q,
                          const T* __restrict__ k_prefix, const T* __restrict__ v_prefix,
                          const T* __restrict__ k_tail, const T* __restrict__ v_tail,
-                         T* __restrict__ out) {
+                         void* __restrict__ out, int32_t out_f32) {
   extern __shared__ float smem[];
   float* q_rot = smem;             // [D]
   float* red = smem + D;           // [8]
@@ -212,7 +214,9 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
   if (tid < D) {
     float o = 0.f;
     for (int32_t gg = 0; gg < groups; ++gg) o += part[gg * D + tid];
-    out[((int64_t)r * Hq + h) * D + tid] = hpd::from_float<T>(o / l);
+    const int64_t oi = ((int64_t)r * Hq + h) * D + tid;
+    if (out_f32) reinterpret_cast<float*>(out)[oi] = o / l;
+    else reinterpret_cast<T*>(out)[oi] = hpd::from_float<T>(o / l);
   }
 }
 
@@ -274,12 +278,13 @@ hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const
     attention_generic_kernel<float><<<grid, GEN_THREADS, smem, s>>>(
         L->dev, step, L->cfg.n_q_heads, L->cfg.n_kv_heads, L->cfg.head_dim, L->T, L->P, L->NP,
         (const float*)q, (const float*)k_prefix, (const float*)v_prefix, (const float*)k_tail,
-        (const float*)v_tail, (float*)out);
+        (const float*)v_tail, out, 1);
   else
     attention_generic_kernel<hpd::bf16_t><<<grid, GEN_THREADS, smem, s>>>(
         L->dev, step, L->cfg.n_q_heads, L->cfg.n_kv_heads, L->cfg.head_dim, L->T, L->P, L->NP,
         (const hpd::bf16_t*)q, (const hpd::bf16_t*)k_prefix, (const hpd::bf16_t*)v_prefix,
-        (const hpd::bf16_t*)k_tail, (const hpd::bf16_t*)v_tail, (hpd::bf16_t*)out);
+        (const hpd::bf16_t*)k_tail, (const hpd::bf16_t*)v_tail, out,
+        L->cfg.out_dtype == HPD_OUT_F32 ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -1,0 +1,44 @@
+"""Parity at the benchmark configurations' full sizes, launched exactly as bench.py launches
+them (automatic kernel choice, fp32 outputs, fused step call), on sampled prompts the oracle
+can afford: every integer output of the whole batch bit-exact, float outputs of the sampled
+prompts within 2e-2 x RMS(step) for every step."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_26209_amd import workloads as W
+
+import hpd_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _integers_whole_batch(wl, hip):
+    """positions and slots of every live branch of every step against closed forms the oracle
+    tests pin (H + L + t ; b*T + t) - cheap enough for the whole batch."""
+    doc_of_branch = np.repeat(np.arange(wl.n_docs), np.diff(wl.branch_ptr))
+    prompt_of_doc = np.repeat(np.arange(wl.n_prompts), np.diff(wl.doc_ptr))
+    for t in range(wl.max_new):
+        live = np.nonzero(wl.branch_len > t)[0]
+        d = doc_of_branch[live]
+        assert np.array_equal(hip["pos"][t].cpu().numpy(), wl.header_len[prompt_of_doc[d]] + wl.doc_len[d] + t)
+        assert np.array_equal(hip["slot"][t].cpu().numpy(), live.astype(np.int64) * wl.max_new + t)
+
+
+@pytest.mark.parametrize("k,prompts", [(2, [0, 31]), (3, [5, 63]), (4, [15]), (5, None)])
+def test_full_size_config(k, prompts):
+    wl = W.config(k)
+    print(f"full-size cfg{k}: {wl.n_prompts} prompts, {wl.n_docs} docs, {wl.n_branches} branches", flush=True)
+    hip = H.run_hip(wl, fused=True, poison_pools=True)
+    _integers_whole_batch(wl, hip)
+    if prompts is None:
+        # ragged config: a prompt with one document, one with the most documents, the prompt
+        # holding the longest and the one holding the shortest document
+        nd = np.diff(wl.doc_ptr)
+        prompt_of_doc = np.repeat(np.arange(wl.n_prompts), nd)
+        prompts = sorted({int(np.argmin(nd)), int(np.argmax(nd)),
+                          int(prompt_of_doc[np.argmax(wl.doc_len)]),
+                          int(prompt_of_doc[np.argmin(wl.doc_len)])})
+    print(f"  oracle on prompts {prompts}", flush=True)
+    worst = H.check_all(wl, hip, prompts=prompts, label=f"cfg{k}")
+    print(f"  worst max-abs / RMS(step) = {worst:.4f}", flush=True)

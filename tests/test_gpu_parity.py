@@ -56,6 +56,17 @@ def test_random_ragged_bf16_both_kernels(seed, mode):
     _say(f"  worst err/rms {rel:.2e}")
 
 
+def test_bf16_output_is_the_fp32_output_rounded_once():
+    """out_dtype = SAME writes RNE(bf16) of exactly the values out_dtype = F32 writes."""
+    _say("bf16 out == rne(fp32 out)")
+    wl = W.config(2, n_prompts=3)
+    for mode in (1, 2):
+        a = H.run_hip(wl, kernel_mode=mode, out_f32=True)
+        b = H.run_hip(wl, inputs=a["inputs"], kernel_mode=mode, out_f32=False)
+        for x, y in zip(a["out"], b["out"]):
+            assert y.dtype == torch.bfloat16 and torch.equal(x.to(torch.bfloat16), y)
+
+
 def test_mfma_edge_shapes():
     cases = {
         "single_branch_h0_l1": W.make_workload("e1", "bf16", 4, 1, 128, 500000.0, 3, [0], [1], [1], [1]),
