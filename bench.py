@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of HPD masked decode attention on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input: for every
+decode step t = 0..T-1 of the workload, RoPE(K) + KV append and RoPE(Q) + masked attention
+(shared header + own document + own tail) + output, for one attention layer.  Inputs and KV
+pools are resident in HBM before the timed region.  Metric: branch-tokens/s =
+sum_t n_live(t) / time.
+
+Cold-cache protocol: R independent replicas of the KV pools (R x footprint >= ~2 GB, far
+above the 256 MB Infinity Cache) are cycled, one per pass, as the other layers' KV would be
+in a real model.
+
+Prints ONE JSON line.  `roofline` is measured live with events around every attention launch
+in a second, identical timed region; `cpu_baseline` times the CPU oracle on a bounded sample
+of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
+
+
+def algorithmic_bytes(wl, n_live_lists, eb):
+    """Bytes the method has to move per decode step: each shared prefix K/V once per
+    (prompt | document, kv head), each tail once per (branch, kv head), Q in, O out, new K/V
+    in and out.  Returns (attention_bytes[t], append_bytes[t], flops[t])."""
+    import numpy as np
+
+    tok_b = 2 * wl.n_kv_heads * wl.head_dim * eb
+    doc_of_branch = np.repeat(np.arange(wl.n_docs), np.diff(wl.branch_ptr))
+    prompt_of_doc = np.repeat(np.arange(wl.n_prompts), np.diff(wl.doc_ptr))
+    attn, app, flops = [], [], []
+    for t, live in enumerate(n_live_lists):
+        docs = np.unique(doc_of_branch[live])
+        prompts = np.unique(prompt_of_doc[docs])
+        prefix = int(wl.header_len[prompts].sum() + wl.doc_len[docs].sum()) * tok_b
+        n = len(live)
+        tail = n * (t + 1) * tok_b
+        qo = n * 2 * wl.n_q_heads * wl.head_dim * eb
+        attn.append(prefix + tail + qo)
+        app.append(n * 2 * tok_b)
+        keys = wl.header_len[prompt_of_doc[doc_of_branch[live]]] + wl.doc_len[doc_of_branch[live]] + t + 1
+        flops.append(int(4 * wl.head_dim * wl.n_q_heads * keys.sum()))
+    return attn, app, flops
+
+
+def cpu_baseline(wl, budget_s=15.0):
+    """Times the dense CPU oracle on as many prompts of the workload as fit the budget."""
+    import numpy as np
+    import torch
+
+    from oracle import hpd_oracle as O
+    from paper_2604_26209_amd import workloads as W
+
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    cores = len(os.sched_getaffinity(0))
+    done_tokens, spent, used = 0, 0.0, []
+    p = 0
+    while p < wl.n_prompts and (spent < budget_s or not used):
+        d0, d1 = int(wl.doc_ptr[p]), int(wl.doc_ptr[p + 1])
+        b0, b1 = int(wl.branch_ptr[d0]), int(wl.branch_ptr[d1])
+        n_tok = int(wl.header_len[p] + wl.doc_len[d0:d1].sum())
+        g = np.random.default_rng(1000 + p)
+        kr = g.standard_normal((n_tok, wl.n_kv_heads, wl.head_dim), dtype=np.float32)
+        vr = g.standard_normal((n_tok, wl.n_kv_heads, wl.head_dim), dtype=np.float32)
+        bl = wl.branch_len[b0:b1]
+        ins = []
+        for t in range(wl.max_new):
+            n = int((bl > t).sum())
+            ins.append((g.standard_normal((n, wl.n_q_heads, wl.head_dim), dtype=np.float32),
+                        g.standard_normal((n, wl.n_kv_heads, wl.head_dim), dtype=np.float32),
+                        g.standard_normal((n, wl.n_kv_heads, wl.head_dim), dtype=np.float32)))
+        t0 = time.perf_counter()
+        po = O.PromptOracle(int(wl.header_len[p]), wl.doc_len[d0:d1],
+                            [[int(x) for x in wl.branch_len[int(wl.branch_ptr[d]):int(wl.branch_ptr[d + 1])]]
+                             for d in range(d0, d1)],
+                            wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new,
+                            cache_dtype="bf16" if wl.dtype == "bf16" else None)
+        po.prefill(kr, vr)
+        for t in range(wl.max_new):
+            po.step(t, *ins[t])
+        spent += time.perf_counter() - t0
+        done_tokens += int(bl.sum())
+        used.append(p)
+        p += 1
+    return {"value": done_tokens / spent, "unit": "branch-tokens/s", "cores": int(min(threads, cores)),
+            "kind": "oracle",
+            "sample": f"prompts 0..{used[-1]} of {wl.n_prompts}, all {wl.max_new} steps incl. prefix "
+                      f"RoPE, {done_tokens} branch-tokens in {spent:.1f} s; host affinity {cores} cores"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5")
+    ap.add_argument("--replicas", type=int, default=0, help="KV replicas (0 = enough for 2 GB)")
+    ap.add_argument("--out", default="f32", choices=["f32", "same"], help="output element type")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--waves", type=int, default=0)
+    ap.add_argument("--two-call", action="store_true", help="hpd_kv_append + hpd_decode_attention")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2604_26209_amd import binding as B
+    from paper_2604_26209_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda"
+    wl = W.config(args.config)
+    eb = 4 if wl.dtype == "f32" else 2
+    out_f32 = args.out == "f32" or wl.dtype == "f32"
+    layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME)
+    if args.waves:
+        B.hpd_set_tuning(layout, B.HPD_TUNE_WAVES, args.waves)
+    n_live = layout.n_live()
+    live_flat = B.hpd_layout_query(layout, B.HPD_Q_LIVE_BRANCH)
+    live_lists, off = [], 0
+    for t in range(wl.max_new):
+        live_lists.append(live_flat[off:off + n_live[t]])
+        off += n_live[t]
+    total_tokens = int(sum(n_live))
+    attn_b, app_b, flops = algorithmic_bytes(wl, live_lists, eb)
+
+    pool_bytes = B.hpd_layout_query(layout, B.HPD_Q_POOL_BYTES)
+    footprint = int(pool_bytes.sum())
+    R = args.replicas or max(2, -(-(2 << 30) // footprint))
+    tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+
+    # ---- inputs (seeded), resident in HBM
+    base = wl.value_seed * 1000
+    k_raw = W.normal_values((wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim), base + 1, dev, wl.dtype)
+    v_raw = W.normal_values((wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim), base + 2, dev, wl.dtype)
+    q, kn, vn, outs = [], [], [], []
+    for t in range(wl.max_new):
+        n = int(n_live[t])
+        q.append(W.normal_values((n, wl.n_q_heads, wl.head_dim), base + 10 + 3 * t, dev, wl.dtype))
+        kn.append(W.normal_values((n, wl.n_kv_heads, wl.head_dim), base + 11 + 3 * t, dev, wl.dtype))
+        vn.append(W.normal_values((n, wl.n_kv_heads, wl.head_dim), base + 12 + 3 * t, dev, wl.dtype))
+        outs.append(torch.empty((n, wl.n_q_heads, wl.head_dim), dtype=torch.float32 if out_f32 else tdt, device=dev))
+    pools = []
+    for _ in range(R):
+        ps = B.alloc_pools(layout, dev)
+        B.hpd_prefix_fill(layout, k_raw, v_raw, ps[0], ps[1])
+        ps[2].zero_(), ps[3].zero_()
+        pools.append(ps)
+    del k_raw, v_raw
+    torch.cuda.synchronize()
+
+    def one_pass(i, events=None):
+        kp, vp, kt, vt = pools[i % R]
+        for t in range(wl.max_new):
+            if int(n_live[t]) == 0:
+                continue
+            if events is None and not args.two_call:
+                B.hpd_decode_step(layout, t, q[t], kn[t], vn[t], kp, vp, kt, vt, outs[t])
+            else:
+                B.hpd_kv_append(layout, t, kn[t], vn[t], kt, vt)
+                if events is not None:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                B.hpd_decode_attention(layout, t, q[t], kp, vp, kt, vt, outs[t])
+                if events is not None:
+                    e1.record()
+                    events.append((t, e0, e1))
+
+    for i in range(args.warmup):
+        one_pass(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_pass(args.warmup + i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = total_tokens * args.steps / elapsed
+
+    # ---- roofline of the dominant kernel (attention), per launch, live
+    events = []
+    for i in range(args.steps):
+        one_pass(args.warmup + args.steps + i, events)
+    torch.cuda.synchronize()
+    dur_s = sum(e0.elapsed_time(e1) for _, e0, e1 in events) * 1e-3
+    alg = sum(attn_b[t] for t, _, _ in events)
+    achieved = alg / dur_s / 1e9
+    mfma_tflops = sum(flops[t] for t, _, _ in events) / dur_s / 1e12
+    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel": "attn_mfma_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attention_generic_kernel",
+                "launches": len(events), "avg_launch_us": round(dur_s / len(events) * 1e6, 2),
+                "algorithmic_bytes_per_launch": int(alg / len(events)),
+                "useful_tflops": round(mfma_tflops, 1)}
+
+    rec = {
+        "metric": "branch tokens/s of HPD masked decode attention; achieved HBM GB/s vs peak",
+        "value": round(value, 1), "unit": "branch-tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}] {wl.name}: {wl.note}",
+                   "prompts": wl.n_prompts, "documents": wl.n_docs, "branches": wl.n_branches,
+                   "decode_steps_per_pass": wl.max_new, "branch_tokens_per_pass": total_tokens,
+                   "heads": f"{wl.n_q_heads}/{wl.n_kv_heads}x{wl.head_dim}", "kv_replicas": R,
+                   "kv_footprint_mb": round(footprint / 1e6, 1), "out_dtype": "f32" if out_f32 else wl.dtype,
+                   "call": "hpd_kv_append+hpd_decode_attention" if args.two_call else "hpd_decode_step"},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        rec["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

@@ -210,7 +210,8 @@ int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, u
                     int32_t* s_out, void* stream);
 
 /* Selects the attention kernel: 0 = automatic, 1 = generic wave-reduction kernel for
- * everything, 2 = MFMA shared-prefix kernel (error if the shape does not allow it). */
+ * everything, 2 = register-fed MFMA kernel, 3 = LDS-streaming MFMA kernel (2 and 3 return
+ * HPD_E_UNSUPPORTED if the shape does not allow them). */
 int hpd_set_kernel_mode(hpd_layout* layout, int32_t mode);
 
 /* Tuning / diagnostic knobs of the MFMA kernel; defaults are chosen by the library. */

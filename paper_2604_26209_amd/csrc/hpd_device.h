@@ -36,6 +36,13 @@ __device__ __forceinline__ bf16_t from_float<bf16_t>(float f) {
   return r;
 }
 
+// Rotation of one (first-half, second-half) channel pair.  Every kernel that rotates a key
+// or a query uses this exact sequence so that all of them round identically.
+__device__ __forceinline__ void rope_pair(float x1, float x2, float c, float s, float& r1, float& r2) {
+  r1 = __fmaf_rn(x1, c, -__fmul_rn(x2, s));
+  r2 = __fmaf_rn(x2, c, __fmul_rn(x1, s));
+}
+
 // 8 consecutive elements (16-byte aligned for bf16, 32-byte for fp32) to fp32
 __device__ __forceinline__ void load8(const float* p, float out[8]) {
   const float4 a = *reinterpret_cast<const float4*>(p);

@@ -208,6 +208,15 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
       });
       L->unit_doc.insert(L->unit_doc.end(), units.begin(), units.end());
       L->unit_ptr[t + 1] = (int32_t)L->unit_doc.size();
+      for (int32_t d : units) {
+        const int32_t p = L->doc_prompt[d];
+        // all live branches of a document share one position in the contiguous mode
+        int32_t pos = -1;
+        if (cfg->pos_mode == HPD_POS_CONTIG) pos = L->seg_len[p] + L->seg_len[P + d] + t;
+        const int32_t desc[8] = {L->seg_off[p], L->seg_len[p], L->seg_off[P + d], L->seg_len[P + d],
+                                 dlp[d], dlp[d + 1] - dlp[d], pos, d};
+        L->unit_desc.insert(L->unit_desc.end(), desc, desc + 8);
+      }
     }
     L->total_units = (int64_t)L->unit_doc.size();
 
@@ -237,7 +246,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
                  o_branch_doc = A.add(L->branch_doc), o_base = A.add(L->branch_base_pos),
                  o_live_ptr = A.add(L->live_ptr), o_live_branch = A.add(L->live_branch),
                  o_dlp = A.add(L->doc_live_ptr), o_unit_ptr = A.add(L->unit_ptr),
-                 o_unit_doc = A.add(L->unit_doc);
+                 o_unit_doc = A.add(L->unit_doc), o_unit_desc = A.add(L->unit_desc);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipGetDevice(&L->device);
     if (e == hipSuccess) e = hipMalloc(&L->d_ints, A.host.size() * sizeof(int32_t));
@@ -262,7 +271,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     L->dev.branch_doc = base + o_branch_doc; L->dev.branch_base_pos = base + o_base;
     L->dev.live_ptr = base + o_live_ptr; L->dev.live_branch = base + o_live_branch;
     L->dev.doc_live_ptr = base + o_dlp; L->dev.unit_ptr = base + o_unit_ptr;
-    L->dev.unit_doc = base + o_unit_doc;
+    L->dev.unit_doc = base + o_unit_doc; L->dev.unit_desc = base + o_unit_desc;
     L->dev.rope = (const float2*)L->d_rope;
     L->on_device = true;
   }
@@ -333,8 +342,9 @@ int hpd_layout_query(const hpd_layout* L, int32_t what, void* host_out, size_t b
 }
 
 int hpd_set_kernel_mode(hpd_layout* L, int32_t mode) {
-  if (!L || mode < 0 || mode > 2) return HPD_E_INVALID;
+  if (!L || mode < 0 || mode > 3) return HPD_E_INVALID;
   if (mode == 2 && !hpd_mfma_supported(L)) return HPD_E_UNSUPPORTED;
+  if (mode == 3 && !hpd_stream_supported(L)) return HPD_E_UNSUPPORTED;
   L->kernel_mode = mode;
   return HPD_OK;
 }
@@ -401,10 +411,13 @@ int hpd_decode_attention(const hpd_layout* L, int32_t step, const void* q, const
   const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
   if (n_live == 0) return HPD_OK;
   if (!q || !k_prefix || !v_prefix || !k_tail || !v_tail || !out) return HPD_E_INVALID;
-  bool use_mfma = false;
-  if (L->kernel_mode == 2) use_mfma = true;
-  else if (L->kernel_mode == 0) use_mfma = hpd_mfma_supported(L);
-  if (use_mfma) {
+  const bool use_stream = L->kernel_mode == 3 || (L->kernel_mode == 0 && hpd_stream_supported(L));
+  const bool use_mfma = L->kernel_mode == 2;
+  if (use_stream) {
+    HPD_HIP(hpd_launch_attention_stream(L, step, q, k_prefix, v_prefix, const_cast<void*>(k_tail),
+                                        const_cast<void*>(v_tail), nullptr, nullptr, out,
+                                        (hipStream_t)stream));
+  } else if (use_mfma) {
     HPD_HIP(hpd_launch_attention_mfma(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out,
                                       (hipStream_t)stream));
   } else {
@@ -431,6 +444,12 @@ int hpd_decode_step(const hpd_layout* L, int32_t step, const void* q, const void
   if (n_live == 0) return HPD_OK;
   if (!q || !k_new || !v_new || !k_prefix || !v_prefix || !k_tail || !v_tail || !out)
     return HPD_E_INVALID;
+  if (L->kernel_mode == 3 || (L->kernel_mode == 0 && hpd_stream_supported(L))) {
+    // one launch: the attention kernel rotates, stores and uses the new keys itself
+    HPD_HIP(hpd_launch_attention_stream(L, step, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new,
+                                        out, (hipStream_t)stream));
+    return HPD_OK;
+  }
   rc = hpd_kv_append(L, step, k_new, v_new, k_tail, v_tail, nullptr, stream);
   if (rc != HPD_OK) return rc;
   return hpd_decode_attention(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, stream);

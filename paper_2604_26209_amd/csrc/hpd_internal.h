@@ -24,6 +24,7 @@ struct hpd_dev_tables {
   const int32_t* doc_live_ptr;  // [T][n_docs+1] first live row (within the step's list) of each document
   const int32_t* unit_ptr;      // [T+1]
   const int32_t* unit_doc;      // [total_units] documents with live branches, heaviest first
+  const int32_t* unit_desc;     // [total_units][8] {hoff, Hlen, doff, Llen, first live row, live branches, position or -1, doc}
   const float2* rope;           // [max_pos+1][D/2] (cos, sin)
 };
 
@@ -38,7 +39,7 @@ struct hpd_layout {
 
   std::vector<int32_t> seg_off, seg_len, seg_pos0, seg_raw_off, raw_seg;
   std::vector<int32_t> doc_prompt, branch_doc, branch_base_pos, branch_len;
-  std::vector<int32_t> live_ptr, live_branch, doc_live_ptr, unit_ptr, unit_doc;
+  std::vector<int32_t> live_ptr, live_branch, doc_live_ptr, unit_ptr, unit_doc, unit_desc;
   std::vector<int32_t> max_rows;  // [T] largest number of live branches of any document at step t
   std::vector<float> rope;        // host copy of the (cos, sin) table
 
@@ -70,3 +71,9 @@ hipError_t hpd_launch_attention_mfma(const hpd_layout* L, int32_t step, const vo
 hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, uint8_t* mask_out, hipStream_t s);
 
 bool hpd_mfma_supported(const hpd_layout* L);
+bool hpd_stream_supported(const hpd_layout* L);
+// k_new / v_new may be null: then the newest token is read from the tail pool like the others
+hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const void* q,
+                                       const void* k_prefix, const void* v_prefix, void* k_tail,
+                                       void* v_tail, const void* k_new, const void* v_new, void* out,
+                                       hipStream_t s);

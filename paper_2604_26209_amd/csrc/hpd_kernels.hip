@@ -42,8 +42,10 @@ __global__ void prefix_fill_kernel(hpd_dev_tables tb, int32_t n_seg, int64_t n_t
   const float a = hpd::to_float(k_raw[src + i]);
   const float b = hpd::to_float(k_raw[src + i + half]);
   const int64_t kdst = ((int64_t)h * NP + slot) * D;
-  k_prefix[kdst + i] = hpd::from_float<T>(a * cs.x - b * cs.y);
-  k_prefix[kdst + i + half] = hpd::from_float<T>(b * cs.x + a * cs.y);
+  float r1, r2;
+  hpd::rope_pair(a, b, cs.x, cs.y, r1, r2);
+  k_prefix[kdst + i] = hpd::from_float<T>(r1);
+  k_prefix[kdst + i + half] = hpd::from_float<T>(r2);
   const int64_t vblk = ((int64_t)h * (NP / 8) + slot / 8) * D;
   v_prefix[(vblk + i) * 8 + (slot & 7)] = v_raw[src + i];
   v_prefix[(vblk + i + half) * 8 + (slot & 7)] = v_raw[src + i + half];
@@ -83,8 +85,10 @@ __global__ void append_kernel(hpd_dev_tables tb, int32_t step, int32_t n_live, i
   const float a = hpd::to_float(k_new[src + i]);
   const float bb = hpd::to_float(k_new[src + i + half]);
   const int64_t dst = (((int64_t)b * Hkv + h) * Tcap + step) * D;
-  k_tail[dst + i] = hpd::from_float<T>(a * cs.x - bb * cs.y);
-  k_tail[dst + i + half] = hpd::from_float<T>(bb * cs.x + a * cs.y);
+  float r1, r2;
+  hpd::rope_pair(a, bb, cs.x, cs.y, r1, r2);
+  k_tail[dst + i] = hpd::from_float<T>(r1);
+  k_tail[dst + i + half] = hpd::from_float<T>(r2);
   v_tail[dst + i] = v_new[src + i];
   v_tail[dst + i + half] = v_new[src + i + half];
   if (slot_out && h == 0 && i == 0) slot_out[r] = slot;
@@ -160,8 +164,7 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
     const float2 cs = tb.rope[(int64_t)pos * half + tid];
     const int64_t src = ((int64_t)r * Hq + h) * D;
     const float a = hpd::to_float(q[src + tid]), bb = hpd::to_float(q[src + tid + half]);
-    q_rot[tid] = a * cs.x - bb * cs.y;
-    q_rot[tid + half] = bb * cs.x + a * cs.y;
+    hpd::rope_pair(a, bb, cs.x, cs.y, q_rot[tid], q_rot[tid + half]);
   }
   __syncthreads();
 

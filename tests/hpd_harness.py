@@ -52,7 +52,10 @@ def run_hip(wl, inputs=None, kernel_mode=0, fused=False, pos_mode=0, attr_len=No
     if inputs is None:
         inputs = Inputs(wl, n_live, "cuda")
     kp, vp, kt, vt = B.alloc_pools(layout)
-    if poison_pools:  # padding slots and unwritten tail slots must never matter
+    if poison_pools == "zero":
+        for x in (kp, vp, kt, vt):
+            x.zero_()
+    elif poison_pools:  # padding slots and unwritten tail slots must never matter
         for x in (kp, vp, kt, vt):
             x.fill_(float("nan"))
     B.hpd_prefix_fill(layout, inputs.k_raw, inputs.v_raw, kp, vp)
