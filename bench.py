@@ -29,6 +29,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# of this same command, each scaled by what the counter reads for a 1 GiB copy
+# (profiles/attn_stream_<workload>.txt).  None where no counter run has been made.
+MEASURED_TRAFFIC_BYTES = {2: 117.4e6}
+
 
 def algorithmic_bytes(wl, n_live_lists, eb):
     """Bytes the method has to move per decode step: each shared prefix K/V once per
@@ -70,7 +75,8 @@ def cpu_baseline(wl, budget_s=15.0):
     cores = len(os.sched_getaffinity(0))
     done_tokens, spent, used = 0, 0.0, []
     p = 0
-    while p < wl.n_prompts and (spent < budget_s or not used):
+    while p < 64 * wl.n_prompts and (spent < budget_s or not used):
+        pid, p = p, p % wl.n_prompts  # small workloads are repeated until the budget is used
         d0, d1 = int(wl.doc_ptr[p]), int(wl.doc_ptr[p + 1])
         b0, b1 = int(wl.branch_ptr[d0]), int(wl.branch_ptr[d1])
         n_tok = int(wl.header_len[p] + wl.doc_len[d0:d1].sum())
@@ -95,12 +101,13 @@ def cpu_baseline(wl, budget_s=15.0):
             po.step(t, *ins[t])
         spent += time.perf_counter() - t0
         done_tokens += int(bl.sum())
-        used.append(p)
-        p += 1
+        used.append(pid)
+        p = pid + 1
     return {"value": done_tokens / spent, "unit": "branch-tokens/s", "cores": int(min(threads, cores)),
             "kind": "oracle",
-            "sample": f"prompts 0..{used[-1]} of {wl.n_prompts}, all {wl.max_new} steps incl. prefix "
-                      f"RoPE, {done_tokens} branch-tokens in {spent:.1f} s; host affinity {cores} cores"}
+            "sample": f"{len(used)} prompt decodes (prompts 0..{min(used[-1], wl.n_prompts - 1)} of "
+                      f"{wl.n_prompts}, repeated if needed), all {wl.max_new} steps incl. prefix RoPE, "
+                      f"{done_tokens} branch-tokens in {spent:.1f} s; host affinity {cores} cores"}
 
 
 def main():
@@ -114,6 +121,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--two-call", action="store_true", help="hpd_kv_append + hpd_decode_attention")
+    ap.add_argument("--copy-calibration", type=int, default=0,
+                    help="after the timed regions, run this many 1 GiB device copies (reference "
+                         "dispatches for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
@@ -171,21 +181,24 @@ def main():
     torch.cuda.synchronize()
 
     def one_pass(i, events=None):
+        """All decode steps of the workload on KV replica i.  With `events`, every launch of
+        the dominant (attention) kernel is bracketed by a pair of events on the same stream."""
         kp, vp, kt, vt = pools[i % R]
         for t in range(wl.max_new):
             if int(n_live[t]) == 0:
                 continue
-            if events is None and not args.two_call:
-                B.hpd_decode_step(layout, t, q[t], kn[t], vn[t], kp, vp, kt, vt, outs[t])
-            else:
+            if args.two_call:
                 B.hpd_kv_append(layout, t, kn[t], vn[t], kt, vt)
-                if events is not None:
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record()
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+            if args.two_call:
                 B.hpd_decode_attention(layout, t, q[t], kp, vp, kt, vt, outs[t])
-                if events is not None:
-                    e1.record()
-                    events.append((t, e0, e1))
+            else:
+                B.hpd_decode_step(layout, t, q[t], kn[t], vn[t], kp, vp, kt, vt, outs[t])
+            if events is not None:
+                e1.record()
+                events.append((t, e0, e1))
 
     for i in range(args.warmup):
         one_pass(i)
@@ -204,12 +217,14 @@ def main():
         one_pass(args.warmup + args.steps + i, events)
     torch.cuda.synchronize()
     dur_s = sum(e0.elapsed_time(e1) for _, e0, e1 in events) * 1e-3
-    alg = sum(attn_b[t] for t, _, _ in events)
+    # the fused step kernel also does the append (new K/V in, rotated K/V out)
+    alg = sum(attn_b[t] + (0 if args.two_call else app_b[t]) for t, _, _ in events)
     achieved = alg / dur_s / 1e9
     mfma_tflops = sum(flops[t] for t, _, _ in events) / dur_s / 1e12
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel": "attn_mfma_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attention_generic_kernel",
+                "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not args.two_call and out_f32 else None,
+                "kernel": "attn_stream_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attention_generic_kernel",
                 "launches": len(events), "avg_launch_us": round(dur_s / len(events) * 1e6, 2),
                 "algorithmic_bytes_per_launch": int(alg / len(events)),
                 "useful_tflops": round(mfma_tflops, 1)}
@@ -227,6 +242,12 @@ def main():
                    "call": "hpd_kv_append+hpd_decode_attention" if args.two_call else "hpd_decode_step"},
         "roofline": roofline,
     }
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_calibration):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         rec["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(rec))

@@ -31,12 +31,17 @@
 //    down to a power of two; the key groups split each stage's four blocks and are merged
 //    through LDS at the end (identical lane layout on both sides).
 //  * Tails (Section 4.3.3: every value still grows token by token) are private to a branch:
-//    G rows per key, no reuse, so no MFMA.  After the prefix partials have been parked in LDS
-//    (row-major, XOR-swizzled), each wave takes branches round-robin and does
-//    wavefront-reduction dot products: 16 lanes cover one 256-byte key row, 4 keys per load
-//    instruction, coalesced.  The same lanes merge tail and prefix statistics and write the
-//    output rows with full-line stores.  In fused mode (hpd_decode_step) the newest key is
-//    rotated, rounded, stored to the tail pool and used in the same pass.
+//    G rows per key, no reuse, so no MFMA.  Each wave takes branches round-robin and does
+//    wavefront-reduction dot products: 16 lanes cover one 256-byte key row (DPP row
+//    reductions), 4 keys per load instruction, coalesced; the next branch's loads are issued
+//    before the current branch is computed.  In fused mode (hpd_decode_step) the newest key
+//    is rotated, rounded, stored to the tail pool and used in the same pass.
+//  * Order.  With at most 128 rows the tails are done FIRST, while the first stage's DMA is
+//    in flight: their (max, sum, O) are parked row-major (XOR-swizzled) in the idle second
+//    stage and become the initial online-softmax state of the MFMA waves; at the end the
+//    finished rows are parked again and written with full-line stores.  With more rows the
+//    second stage is too small: the prefix partials are parked at the end and the tail pass
+//    merges into them.
 #include <cmath>
 
 #include "hpd_internal.h"
@@ -60,7 +65,7 @@ constexpr float NEG_BIG = -1.0e30f;
 
 struct StreamArgs {
   hpd_dev_tables tb;
-  int32_t step, Hq, Hkv, Tcap, P, n_docs, RG, out_f32, fused;
+  int32_t step, Hq, Hkv, Tcap, P, n_docs, RG, out_f32, fused, live_base;
   int64_t NP;
   float scale_log2;
 };
@@ -86,6 +91,15 @@ __device__ __forceinline__ void unpack8(uint4 a, float out[8]) {
   out[6] = __uint_as_float(a.w << 16); out[7] = __uint_as_float(a.w & 0xffff0000u);
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// sum over the 16 lanes of a DPP row; every lane of the row gets the total
+__device__ __forceinline__ float row16_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
+  return v;
+}
 
 // XOR-swizzled row-major park buffer: element (row, 4-float chunk c4) of a 128-float row.
 __device__ __forceinline__ int park_off(int row, int c4) { return row * 128 + ((c4 ^ (row & 31)) << 2); }
@@ -153,6 +167,271 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 
   issue_round(0, ringA);
 
+  const int32_t rows_here = min(R - first_blk * 32, nblk_here * 32);
+  const bool tails_first = nblk_here <= 4;  // the idle second stage can park 128 rows
+  float* const parkA = reinterpret_cast<float*>(ringA);
+  float* const parkB = reinterpret_cast<float*>(ringB);
+
+  // =====================================================================================
+  // Tail pass.  lane = (ks, c): the 16 lanes c of a DPP row cover one key row (8 channels
+  // each), ks = key within a group of 4.
+  //   merge_prefix = false: park (max, sum, O) of every row in `park`/ml_buf
+  //   merge_prefix = true : combine with the prefix partials parked there and store `out`
+  // =====================================================================================
+  const int32_t ks = lane >> 4, c = lane & 15;
+  const int32_t br0 = first_blk * 32 / G;
+  const int32_t nbr_here = min(nb - br0, nblk_here * 32 / G);
+  const int32_t nkeys_pool = a.step;  // older keys; the newest one is handled separately
+
+  // A branch with G = 8 is handled as two half-branches of GH = 4 rows (same keys).
+  constexpr int GH = G < 4 ? G : 4;
+  constexpr int NH = G / GH;
+  struct TailLoads {  // what is prefetched one (half-)branch ahead
+    uint4 kraw[4], vraw[4], qa[GH], qb[GH];
+    int64_t tbase;
+    int32_t live_row;
+  };
+  auto tail_issue = [&](int32_t vb, TailLoads& t) {
+    const int32_t bl = vb / NH, g0 = (vb % NH) * GH;
+    t.live_row = row0_live + br0 + bl;
+    const int32_t b = a.tb.live_branch[a.live_base + t.live_row];
+    t.tbase = (((int64_t)b * a.Hkv + hk) * a.Tcap) * D;
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      const uint16_t* qp = q + ((int64_t)t.live_row * a.Hq + hk * G + g0 + g) * D;
+      t.qa[g] = *reinterpret_cast<const uint4*>(qp + c * 8);
+      t.qb[g] = *reinterpret_cast<const uint4*>(qp + (c ^ 8) * 8);
+    }
+#pragma unroll
+    for (int uu = 0; uu < 4; ++uu) {
+      const int32_t tt = uu * 4 + ks;
+      t.kraw[uu] = make_uint4(0, 0, 0, 0);
+      t.vraw[uu] = make_uint4(0, 0, 0, 0);
+      if (tt < nkeys_pool) {
+        t.kraw[uu] = *reinterpret_cast<const uint4*>(k_tail + t.tbase + (int64_t)tt * D + c * 8);
+        t.vraw[uu] = *reinterpret_cast<const uint4*>(v_tail + t.tbase + (int64_t)tt * D + c * 8);
+      }
+    }
+  };
+
+  auto tail_compute = [&](int32_t vb, TailLoads& t, bool merge_prefix, float* park_lo, float* park_hi) {
+    const int32_t bl = vb / NH, g0 = (vb % NH) * GH;
+    // the newest token's inputs are requested now and used at the very end
+    uint4 kna = make_uint4(0, 0, 0, 0), knb = kna, vn = kna;
+    if (a.fused) {
+      const uint16_t* kp = k_new + ((int64_t)t.live_row * a.Hkv + hk) * D;
+      kna = *reinterpret_cast<const uint4*>(kp + c * 8);
+      knb = *reinterpret_cast<const uint4*>(kp + (c ^ 8) * 8);
+      vn = *reinterpret_cast<const uint4*>(v_new + ((int64_t)t.live_row * a.Hkv + hk) * D + c * 8);
+    } else {  // already appended by hpd_kv_append: rotated and rounded
+      kna = *reinterpret_cast<const uint4*>(k_tail + t.tbase + (int64_t)a.step * D + c * 8);
+      vn = *reinterpret_cast<const uint4*>(v_tail + t.tbase + (int64_t)a.step * D + c * 8);
+    }
+    int32_t pos = upos;
+    if (upos < 0) {
+      const int32_t b = a.tb.live_branch[a.live_base + t.live_row];
+      pos = a.tb.branch_base_pos[b] + 1 + a.step;
+    }
+    const float4* csp = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)pos * (D / 2) + (c & 7) * 8);
+    // rotated query rows in fp32, pre-multiplied by scale * log2(e)
+    float qf[GH][8];
+    {
+      float cs_c[8], cs_s[8];
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        const float4 cs = csp[e2];
+        cs_c[2 * e2] = cs.x; cs_s[2 * e2] = cs.y; cs_c[2 * e2 + 1] = cs.z; cs_s[2 * e2 + 1] = cs.w;
+      }
+#pragma unroll
+      for (int g = 0; g < GH; ++g) {
+        float x[8], y[8];
+        unpack8(t.qa[g], x);
+        unpack8(t.qb[g], y);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float r1, r2;
+          if (c < 8) hpd::rope_pair(x[e], y[e], cs_c[e], cs_s[e], r1, r2);  // x = first half
+          else { hpd::rope_pair(y[e], x[e], cs_c[e], cs_s[e], r2, r1); }    // x = second half
+          qf[g][e] = r1 * a.scale_log2;
+        }
+      }
+    }
+    float tm[GH], tl[GH], ta[GH][8];
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      tm[g] = NEG_BIG; tl[g] = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ta[g][e] = 0.f;
+    }
+    // ---- keys already in the pool, 16 per batch (the first batch was loaded by tail_issue)
+    for (int32_t base = 0; base < nkeys_pool; base += 16) {
+      if (base > 0) {
+#pragma unroll
+        for (int uu = 0; uu < 4; ++uu) {
+          const int32_t tt = base + uu * 4 + ks;
+          t.kraw[uu] = make_uint4(0, 0, 0, 0);
+          t.vraw[uu] = make_uint4(0, 0, 0, 0);
+          if (tt < nkeys_pool) {
+            t.kraw[uu] = *reinterpret_cast<const uint4*>(k_tail + t.tbase + (int64_t)tt * D + c * 8);
+            t.vraw[uu] = *reinterpret_cast<const uint4*>(v_tail + t.tbase + (int64_t)tt * D + c * 8);
+          }
+        }
+      }
+      float sc[GH][4];
+#pragma unroll
+      for (int uu = 0; uu < 4; ++uu) {
+        const bool ok = base + uu * 4 + ks < nkeys_pool;
+        float kv[8];
+        unpack8(t.kraw[uu], kv);
+#pragma unroll
+        for (int g = 0; g < GH; ++g) {
+          float dot = 0.f;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) dot = fmaf(kv[e], qf[g][e], dot);
+          dot = row16_sum(dot);
+          sc[g][uu] = ok ? dot : -INFINITY;
+        }
+      }
+#pragma unroll
+      for (int g = 0; g < GH; ++g) {
+        const float bmax = fmaxf(fmaxf(sc[g][0], sc[g][1]), fmaxf(sc[g][2], sc[g][3]));
+        const float m_new = fmaxf(tm[g], bmax);
+        const float alpha = fast_exp2(tm[g] - m_new);
+        tm[g] = m_new;
+        tl[g] *= alpha;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ta[g][e] *= alpha;
+#pragma unroll
+        for (int uu = 0; uu < 4; ++uu) sc[g][uu] = fast_exp2(sc[g][uu] - m_new);
+        tl[g] += (sc[g][0] + sc[g][1]) + (sc[g][2] + sc[g][3]);
+      }
+#pragma unroll
+      for (int uu = 0; uu < 4; ++uu) {
+        float vv[8];
+        unpack8(t.vraw[uu], vv);
+#pragma unroll
+        for (int g = 0; g < GH; ++g)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) ta[g][e] = fmaf(sc[g][uu], vv[e], ta[g][e]);
+      }
+    }
+    // ---- merge the 4 key lane-groups (lanes l, l^16, l^32, l^48)
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      float mm = fmaxf(tm[g], __shfl_xor(tm[g], 16));
+      mm = fmaxf(mm, __shfl_xor(mm, 32));
+      const float f = fast_exp2(tm[g] - mm);
+      tm[g] = mm;
+      tl[g] *= f;
+      tl[g] += __shfl_xor(tl[g], 16);
+      tl[g] += __shfl_xor(tl[g], 32);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float v = ta[g][e] * f;
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        ta[g][e] = v;
+      }
+    }
+    // ---- the newest token, after the older ones in both modes so that the fused and the
+    //      two-call sequence add up in the same order.  Fused: rotate, round once, store, use
+    //      the stored value.
+    {
+      float kv[8], vv[8];
+      uint4 kst = kna;
+      if (a.fused) {
+      float x[8], y[8], rr[8];
+      unpack8(kna, x);
+      unpack8(knb, y);
+      // the table row is read again (cache hit) rather than held in registers throughout:
+      // the empty asm hides the pointer's origin so the two reads are not merged
+      const float4* csp2 = csp;
+      asm volatile("" : "+v"(csp2));
+#pragma unroll
+      for (int e2 = 0; e2 < 4; ++e2) {
+        const float4 cs = csp2[e2];
+        float r1, r2;
+        if (c < 8) hpd::rope_pair(x[2 * e2], y[2 * e2], cs.x, cs.y, r1, r2);
+        else { hpd::rope_pair(y[2 * e2], x[2 * e2], cs.x, cs.y, r2, r1); }
+        rr[2 * e2] = r1;
+        if (c < 8) hpd::rope_pair(x[2 * e2 + 1], y[2 * e2 + 1], cs.z, cs.w, r1, r2);
+        else { hpd::rope_pair(y[2 * e2 + 1], x[2 * e2 + 1], cs.z, cs.w, r2, r1); }
+        rr[2 * e2 + 1] = r1;
+      }
+      kst = __builtin_bit_cast(uint4, pack8(rr));
+      if (ks == 0 && g0 == 0) {
+        *reinterpret_cast<uint4*>(k_tail + t.tbase + (int64_t)a.step * D + c * 8) = kst;
+        *reinterpret_cast<uint4*>(v_tail + t.tbase + (int64_t)a.step * D + c * 8) = vn;
+      }
+      }
+      unpack8(kst, kv);
+      unpack8(vn, vv);
+#pragma unroll
+      for (int g = 0; g < GH; ++g) {
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dot = fmaf(kv[e], qf[g][e], dot);
+        dot = row16_sum(dot);
+        const float m_new = fmaxf(tm[g], dot);
+        const float alpha = fast_exp2(tm[g] - m_new);
+        const float pr = fast_exp2(dot - m_new);
+        tm[g] = m_new;
+        tl[g] = tl[g] * alpha + pr;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ta[g][e] = fmaf(pr, vv[e], ta[g][e] * alpha);
+      }
+    }
+    // ---- lane group ks finishes row g0 + ks
+#pragma unroll
+    for (int g = 0; g < GH; ++g) {
+      if (g == ks) {
+        const int32_t lr = bl * G + g0 + g;
+        float* park = lr < 128 ? park_lo : park_hi;
+        const int32_t lrr = lr & 127;
+        if (!merge_prefix) {
+          *reinterpret_cast<float4*>(park + park_off(lrr, 2 * c)) =
+              make_float4(ta[g][0], ta[g][1], ta[g][2], ta[g][3]);
+          *reinterpret_cast<float4*>(park + park_off(lrr, 2 * c + 1)) =
+              make_float4(ta[g][4], ta[g][5], ta[g][6], ta[g][7]);
+          if (c == 0) { ml_buf[lr * 2] = tm[g]; ml_buf[lr * 2 + 1] = tl[g]; }
+        } else {
+          const float mp = ml_buf[lr * 2], lp = ml_buf[lr * 2 + 1];
+          const float4 p0 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c));
+          const float4 p1 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c + 1));
+          const float mx = fmaxf(mp, tm[g]);
+          const float ap = fast_exp2(mp - mx), at = fast_exp2(tm[g] - mx);
+          const float inv = 1.0f / (lp * ap + tl[g] * at);
+          float o[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = (o[e] * ap + ta[g][e] * at) * inv;
+          const int64_t o_off = ((int64_t)t.live_row * a.Hq + hk * G + g0 + g) * D + c * 8;
+          if (a.out_f32) {
+            float* op = reinterpret_cast<float*>(out) + o_off;
+            *reinterpret_cast<float4*>(op) = make_float4(o[0], o[1], o[2], o[3]);
+            *reinterpret_cast<float4*>(op + 4) = make_float4(o[4], o[5], o[6], o[7]);
+          } else {
+            *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(out) + o_off) =
+                __builtin_bit_cast(uint4, pack8(o));
+          }
+        }
+      }
+    }
+  };
+
+  auto tail_pass = [&](bool merge_prefix, float* park_lo, float* park_hi) {
+    const int32_t nvb = nbr_here * NH;
+    TailLoads cur, nxt;
+    if (wave < nvb) tail_issue(wave, cur);
+    for (int32_t vb = wave; vb < nvb; vb += WAVES) {
+      const bool more = vb + WAVES < nvb;
+      if (more) tail_issue(vb + WAVES, nxt);
+      tail_compute(vb, cur, merge_prefix, park_lo, park_hi);
+      if (more) cur = nxt;
+    }
+  };
+
+  if (tails_first) tail_pass(false, parkB, parkB);
+
   // ---- this lane's query row, rotated, as bf16 hi + lo MFMA B operands
   const int32_t r_row = (first_blk + rb) * 32 + n;
   const bool row_valid = active && r_row < R;
@@ -163,7 +442,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const int32_t live_row = row0_live + bi;
     int32_t pos = upos;
     if (upos < 0) {
-      const int32_t b = a.tb.live_branch[a.tb.live_ptr[a.step] + live_row];
+      const int32_t b = a.tb.live_branch[a.live_base + live_row];
       pos = a.tb.branch_base_pos[b] + 1 + a.step;
     }
     const int64_t q_off = ((int64_t)live_row * a.Hq + hk * G + gq) * D;
@@ -198,13 +477,32 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     }
   }
 
+  // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
   float m_used = NEG_BIG;  // running maximum (log2 units), equal in lanes n and n+32
-  float l_lane = 0.f;      // this lane's share of the row sum
+  float l_lane = 0.f;
   floatx16 acc[4];
 #pragma unroll
   for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[blk][i] = 0.f;
+
+  if (tails_first) {
+    __syncthreads();  // tail partials are parked in the second stage
+    if (active && kg == 0 && r_row < R) {
+      const int32_t lr = rb * 32 + n;
+      m_used = ml_buf[lr * 2];
+      l_lane = g2 == 0 ? ml_buf[lr * 2 + 1] : 0.f;
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+          const float4 v = *reinterpret_cast<const float4*>(parkB + park_off(lr, blk * 8 + cc * 2 + g2));
+          acc[blk][cc * 4 + 0] = v.x; acc[blk][cc * 4 + 1] = v.y;
+          acc[blk][cc * 4 + 2] = v.z; acc[blk][cc * 4 + 3] = v.w;
+        }
+    }
+    // the first round's barrier comes before any DMA into the second stage
+  }
 
   auto compute_block = [&](const uint4* slot, int32_t valid) {
     const uint4* fr = slot + lane;
@@ -300,8 +598,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const bool writer = active && (kg % (2 * s)) == s;
     const bool reader = active && (kg % (2 * s)) == 0 && kg + s < KG;
     const int32_t region = rb + nblk_here * (kg / (2 * s));  // < 4
-    float* buf = (region < 2 ? reinterpret_cast<float*>(ringA) + region * MERGE_FLOATS
-                             : reinterpret_cast<float*>(ringB) + (region - 2) * MERGE_FLOATS) + lane;
+    float* buf = (region < 2 ? parkA + region * MERGE_FLOATS : parkB + (region - 2) * MERGE_FLOATS) + lane;
     if (writer) {
 #pragma unroll
       for (int blk = 0; blk < 4; ++blk)
@@ -325,164 +622,39 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     __syncthreads();
   }
 
-  // ---- park the prefix partials row-major (rows 0..127 in ringA, 128..255 in ringB)
+  // ---- park the MFMA waves' state row-major (rows 0..127 in ringA, 128..255 in ringB)
   if (active && kg == 0) {
     const int32_t lr = rb * 32 + n;
-    float* park = lr < 128 ? reinterpret_cast<float*>(ringA) : reinterpret_cast<float*>(ringB);
+    float* park = lr < 128 ? parkA : parkB;
     const int32_t lrr = lr & 127;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
-        *reinterpret_cast<float4*>(park + park_off(lrr, blk * 8 + c * 2 + g2)) =
-            make_float4(acc[blk][c * 4 + 0], acc[blk][c * 4 + 1], acc[blk][c * 4 + 2], acc[blk][c * 4 + 3]);
+      for (int cc = 0; cc < 4; ++cc)
+        *reinterpret_cast<float4*>(park + park_off(lrr, blk * 8 + cc * 2 + g2)) =
+            make_float4(acc[blk][cc * 4 + 0], acc[blk][cc * 4 + 1], acc[blk][cc * 4 + 2], acc[blk][cc * 4 + 3]);
     const float l_row = l_lane + __shfl_xor(l_lane, 32);
     if (g2 == 0) { ml_buf[lr * 2] = m_used; ml_buf[lr * 2 + 1] = l_row; }
   }
   __syncthreads();
 
-  // ---- tails + final merge + output: branches of this row group, round-robin over waves.
-  //      lane = (ks, c): 16 lanes c cover one key row (8 channels each), ks = key in a group
-  //      of 4.
-  const int32_t ks = lane >> 4, c = lane & 15;
-  const int32_t br0 = first_blk * 32 / G;
-  const int32_t nbr_here = min(nb - br0, nblk_here * 32 / G);
-  for (int32_t bl = wave; bl < nbr_here; bl += WAVES) {
-    const int32_t live_row = row0_live + br0 + bl;
-    const int32_t b = a.tb.live_branch[a.tb.live_ptr[a.step] + live_row];
-    const int32_t pos = upos >= 0 ? upos : a.tb.branch_base_pos[b] + 1 + a.step;
-    const float2* cs_row = a.tb.rope + (int64_t)pos * (D / 2) + (c & 7) * 8;
-    float cs_c[8], cs_s[8];
-#pragma unroll
-    for (int e2 = 0; e2 < 4; ++e2) {
-      const float4 cs = reinterpret_cast<const float4*>(cs_row)[e2];
-      cs_c[2 * e2] = cs.x; cs_s[2 * e2] = cs.y; cs_c[2 * e2 + 1] = cs.z; cs_s[2 * e2 + 1] = cs.w;
-    }
-    // rotated query rows of this branch in fp32, pre-multiplied by scale * log2(e)
-    float qf[G][8];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const uint16_t* qp = q + ((int64_t)live_row * a.Hq + hk * G + g) * D;
-      float x[8], y[8];
-      unpack8(*reinterpret_cast<const uint4*>(qp + c * 8), x);
-      unpack8(*reinterpret_cast<const uint4*>(qp + (c ^ 8) * 8), y);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float r1, r2;
-        if (c < 8) hpd::rope_pair(x[e], y[e], cs_c[e], cs_s[e], r1, r2);  // x = first half
-        else { hpd::rope_pair(y[e], x[e], cs_c[e], cs_s[e], r2, r1); }    // x = second half
-        qf[g][e] = r1 * a.scale_log2;
-      }
-    }
-    float tm[G], tl[G], ta[G][8];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      tm[g] = NEG_BIG; tl[g] = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ta[g][e] = 0.f;
-    }
-    const int64_t tbase = (((int64_t)b * a.Hkv + hk) * a.Tcap) * D;
-    const int32_t nkeys = a.step + 1;
-    for (int32_t base = 0; base < nkeys; base += 16) {
-      uint4 kraw[4], vraw[4];
-#pragma unroll
-      for (int uu = 0; uu < 4; ++uu) {
-        const int32_t tt = base + uu * 4 + ks;
-        kraw[uu] = make_uint4(0, 0, 0, 0);
-        vraw[uu] = make_uint4(0, 0, 0, 0);
-        if (tt < nkeys) {
-          if (a.fused && tt == a.step) {
-            // newest token: rotate, round once, store to the tail pool, use the stored value
-            const uint16_t* kp = k_new + ((int64_t)live_row * a.Hkv + hk) * D;
-            float x[8], y[8], rr[8];
-            unpack8(*reinterpret_cast<const uint4*>(kp + c * 8), x);
-            unpack8(*reinterpret_cast<const uint4*>(kp + (c ^ 8) * 8), y);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-              float r1, r2;
-              if (c < 8) hpd::rope_pair(x[e], y[e], cs_c[e], cs_s[e], r1, r2);
-              else { hpd::rope_pair(y[e], x[e], cs_c[e], cs_s[e], r2, r1); }
-              rr[e] = r1;
-            }
-            kraw[uu] = __builtin_bit_cast(uint4, pack8(rr));
-            vraw[uu] = *reinterpret_cast<const uint4*>(v_new + ((int64_t)live_row * a.Hkv + hk) * D + c * 8);
-            *reinterpret_cast<uint4*>(k_tail + tbase + (int64_t)tt * D + c * 8) = kraw[uu];
-            *reinterpret_cast<uint4*>(v_tail + tbase + (int64_t)tt * D + c * 8) = vraw[uu];
-          } else {
-            kraw[uu] = *reinterpret_cast<const uint4*>(k_tail + tbase + (int64_t)tt * D + c * 8);
-            vraw[uu] = *reinterpret_cast<const uint4*>(v_tail + tbase + (int64_t)tt * D + c * 8);
-          }
-        }
-      }
-#pragma unroll
-      for (int uu = 0; uu < 4; ++uu) {
-        const bool ok = base + uu * 4 + ks < nkeys;
-        float kv[8], vv[8];
-        unpack8(kraw[uu], kv);
-        unpack8(vraw[uu], vv);
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          float dot = 0.f;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) dot = fmaf(kv[e], qf[g][e], dot);
-          dot += __shfl_xor(dot, 1);
-          dot += __shfl_xor(dot, 2);
-          dot += __shfl_xor(dot, 4);
-          dot += __shfl_xor(dot, 8);
-          const float sc = ok ? dot : -INFINITY;
-          const float m_new = fmaxf(tm[g], sc);
-          const float alpha = fast_exp2(tm[g] - m_new);
-          const float pr = fast_exp2(sc - m_new);
-          tm[g] = m_new;
-          tl[g] = tl[g] * alpha + pr;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) ta[g][e] = fmaf(pr, vv[e], ta[g][e] * alpha);
-        }
-      }
-    }
-    // merge the 4 key lanes-groups (lanes l, l^16, l^32, l^48)
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float mm = fmaxf(tm[g], __shfl_xor(tm[g], 16));
-      mm = fmaxf(mm, __shfl_xor(mm, 32));
-      const float sc = fast_exp2(tm[g] - mm);
-      tm[g] = mm;
-      tl[g] *= sc;
-      tl[g] += __shfl_xor(tl[g], 16);
-      tl[g] += __shfl_xor(tl[g], 32);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float v = ta[g][e] * sc;
-        v += __shfl_xor(v, 16);
-        v += __shfl_xor(v, 32);
-        ta[g][e] = v;
-      }
-    }
-    // lane group ks finishes rows g = ks, ks + 4, ...
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      if ((g & 3) == ks) {
-        const int32_t lr = bl * G + g;
-        const float* park = lr < 128 ? reinterpret_cast<const float*>(ringA) : reinterpret_cast<const float*>(ringB);
-        const int32_t lrr = lr & 127;
-        const float mp = ml_buf[lr * 2], lp = ml_buf[lr * 2 + 1];
-        const float4 p0 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c));
-        const float4 p1 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c + 1));
-        const float mx = fmaxf(mp, tm[g]);
-        const float ap = fast_exp2(mp - mx), at = fast_exp2(tm[g] - mx);
-        const float inv = 1.0f / (lp * ap + tl[g] * at);
-        float o[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (o[e] * ap + ta[g][e] * at) * inv;
-        const int64_t o_off = ((int64_t)live_row * a.Hq + hk * G + g) * D + c * 8;
-        if (a.out_f32) {
-          float* op = reinterpret_cast<float*>(out) + o_off;
-          *reinterpret_cast<float4*>(op) = make_float4(o[0], o[1], o[2], o[3]);
-          *reinterpret_cast<float4*>(op + 4) = make_float4(o[4], o[5], o[6], o[7]);
-        } else {
-          *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(out) + o_off) =
-              __builtin_bit_cast(uint4, pack8(o));
-        }
+  if (!tails_first) {
+    tail_pass(true, parkA, parkB);
+  } else {
+    // rows are complete: normalise and store, 4 rows per wave pass, 512 contiguous bytes each
+    for (int32_t lr = wave * 4 + ks; lr < rows_here; lr += WAVES * 4) {
+      const float inv = 1.0f / ml_buf[lr * 2 + 1];
+      const float4 p0 = *reinterpret_cast<const float4*>(parkA + park_off(lr, 2 * c));
+      const float4 p1 = *reinterpret_cast<const float4*>(parkA + park_off(lr, 2 * c + 1));
+      float o[8] = {p0.x * inv, p0.y * inv, p0.z * inv, p0.w * inv, p1.x * inv, p1.y * inv, p1.z * inv, p1.w * inv};
+      const int32_t live_row = row0_live + br0 + lr / G;
+      const int64_t o_off = ((int64_t)live_row * a.Hq + hk * G + lr % G) * D + c * 8;
+      if (a.out_f32) {
+        float* op = reinterpret_cast<float*>(out) + o_off;
+        *reinterpret_cast<float4*>(op) = make_float4(o[0], o[1], o[2], o[3]);
+        *reinterpret_cast<float4*>(op + 4) = make_float4(o[4], o[5], o[6], o[7]);
+      } else {
+        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(out) + o_off) = __builtin_bit_cast(uint4, pack8(o));
       }
     }
   }
@@ -519,6 +691,7 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   if (a.RG < 1) a.RG = 1;
   a.out_f32 = L->cfg.out_dtype == HPD_OUT_F32 ? 1 : 0;
   a.fused = (k_new != nullptr) ? 1 : 0;
+  a.live_base = L->live_ptr[step];
   a.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)D));
   a.tb.unit_desc = L->dev.unit_desc + (int64_t)L->unit_ptr[step] * 8;
   const int32_t n_units = L->unit_ptr[step + 1] - L->unit_ptr[step];
