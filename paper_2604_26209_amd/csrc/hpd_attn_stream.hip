@@ -16,32 +16,41 @@
 //    64 KB of stage B are in flight.  The two stages are distinct __shared__ arrays on
 //    purpose: the compiler then knows that reading one does not alias the DMA into the
 //    other and does not drain the DMA queue before every LDS read.
-//  * Contraction (transposed, see hpd_attn_mfma.hip for the derivation):
-//        S^T[key,row] = K.Q^T   (A = K fragment from LDS, B = rotated Q in registers, bf16
-//                                hi + lo parts: two MFMA passes, Q rounding drops out)
-//        O^T[d,row]  += V^T.P^T (A = V fragment from the 8-key interleaved pool, B = P)
-//    One query row lives in lanes n and n+32; softmax statistics never leave them.
+//  * Contraction (transposed):
+//        S^T[key,row] = K.Q^T   (A = K fragment, B = rotated Q in registers as bf16 hi + lo
+//                                parts: two MFMA passes, Q rounding drops out of the error)
+//        O^T[d,row]  += V^T.P^T (A = V fragment, B = P)
+//    with v_mfma_f32_32x32x16_bf16.  One query row lives in lanes n and n+32; softmax
+//    statistics never leave them, and the fp32 scores of the first product become, after
+//    exponentiation and bf16 packing, the B operand of the second without any cross-lane
+//    movement.  The key order inside a block is permuted on the K side (an address, free) so
+//    that the 8 probabilities a lane holds for one MFMA belong to 8 consecutive keys, which
+//    is what the 8-key interleaved V pool delivers in 16 bytes.
 //  * Softmax.  Online max/sum in registers.  The running maximum is exact (the accumulators
 //    are rescaled whenever some row of the wave sees a larger score; the rescale is skipped,
 //    wave-uniformly, when no row does).  Exactness matters for accuracy: the dominant key of a
 //    row then has probability exactly 1.0, which bf16 represents without error; with a stale
 //    maximum the largest weight would carry a 2^-9 rounding error into P.V (measured: 3x
 //    larger max-abs error).
-//  * Waves.  8 waves = (row block of 32 rows) x (key group).  KG = 8 / row blocks rounded
-//    down to a power of two; the key groups split each stage's four blocks and are merged
-//    through LDS at the end (identical lane layout on both sides).
-//  * Tails (Section 4.3.3: every value still grows token by token) are private to a branch:
-//    G rows per key, no reuse, so no MFMA.  Each wave takes branches round-robin and does
-//    wavefront-reduction dot products: 16 lanes cover one 256-byte key row (DPP row
-//    reductions), 4 keys per load instruction, coalesced; the next branch's loads are issued
-//    before the current branch is computed.  In fused mode (hpd_decode_step) the newest key
-//    is rotated, rounded, stored to the tail pool and used in the same pass.
-//  * Order.  With at most 128 rows the tails are done FIRST, while the first stage's DMA is
-//    in flight: their (max, sum, O) are parked row-major (XOR-swizzled) in the idle second
-//    stage and become the initial online-softmax state of the MFMA waves; at the end the
-//    finished rows are parked again and written with full-line stores.  With more rows the
-//    second stage is too small: the prefix partials are parked at the end and the tail pass
-//    merges into them.
+//  * Waves.  8 waves = (row block of 32 rows) x (key group), KG = 4 / 2 / 1 for <= 2 / <= 4 /
+//    <= 8 row blocks; the key groups split every stage's four blocks and the tail tiles, and
+//    are merged once through LDS at the end (identical lane layout on both sides).
+//  * Tails (Section 4.3.3: every value still grows token by token) are private to a branch.
+//    A first version used wavefront-reduction dot products (16 lanes per key row); measured
+//    on MI355X it needed ~1000 VALU instructions per branch and 5 us per branch per wave,
+//    more than the whole prefix.  The tails now go through the same MFMA code as masked
+//    "virtual key blocks": a tile holds G tail positions of each of the 32/G branches of the
+//    row block, the score tile is block-diagonal (a row keeps only its own branch's keys,
+//    the rest get -inf), K fragments are loaded straight from the row-major tail pool, and
+//    the V fragments - which need 8 keys of one channel - are transposed through a
+//    wave-private 8 KB LDS buffer (coalesced 16-byte writes, 2-byte reads, XOR-swizzled so
+//    that the two half-waves hit different banks).  The MFMA work wasted on the masked
+//    entries is irrelevant: the matrix pipe is idle while the first stage is in flight.
+//    Tail tiles are processed first and simply initialise the online-softmax state.
+//  * Fused mode (hpd_decode_step): the workgroup first rotates, rounds and stores the newest
+//    key/value of its own branches (the same arithmetic as hpd_kv_append), synchronises, and
+//    then reads them back like every other tail entry - bit-identical to the two-call
+//    sequence by construction.
 #include <cmath>
 
 #include "hpd_internal.h"
@@ -92,15 +101,6 @@ __device__ __forceinline__ void unpack8(uint4 a, float out[8]) {
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// sum over the 16 lanes of a DPP row; every lane of the row gets the total
-__device__ __forceinline__ float row16_sum(float v) {
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
-  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
-  return v;
-}
-
 // XOR-swizzled row-major park buffer: element (row, 4-float chunk c4) of a 128-float row.
 __device__ __forceinline__ int park_off(int row, int c4) { return row * 128 + ((c4 ^ (row & 31)) << 2); }
 
@@ -110,21 +110,25 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
                    const uint16_t* __restrict__ v_prefix, uint16_t* __restrict__ k_tail,
                    uint16_t* __restrict__ v_tail, const uint16_t* __restrict__ k_new,
                    const uint16_t* __restrict__ v_new, void* __restrict__ out) {
+  constexpr int BPB = 32 / G;  // branches per row block; a tail tile holds G positions of each
+
   __shared__ uint4 ringA[STAGE_U4];
   __shared__ uint4 ringB[STAGE_U4];
-  __shared__ float ml_buf[MAX_ROWS * 2];
+  __shared__ float l_buf[MAX_ROWS];
+  __shared__ int64_t tail_base[MAX_ROWS];  // per local branch: element offset of its tail
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int n = lane & 31, g2 = lane >> 5;
 
-  // ---- unit descriptor (one dependent load): {hoff, Hlen, doff, Llen, row0_live, nb, pos, doc}
+  // ---- unit descriptor (one dependent load):
+  //      {hoff, Hlen, doff, Llen, first live row, live branches, position | -1, first branch | -1}
   const int32_t rg = blockIdx.x % a.RG;
   const int32_t hk = (blockIdx.x / a.RG) % a.Hkv;
   const int32_t u = blockIdx.x / (a.RG * a.Hkv);
   const int32_t* desc = a.tb.unit_desc + (int64_t)u * 8;  // pre-offset to this step by the host
   const int32_t hoff = desc[0], Hlen = desc[1], doff = desc[2], Llen = desc[3];
-  const int32_t row0_live = desc[4], nb = desc[5], upos = desc[6];
+  const int32_t row0_live = desc[4], nb = desc[5], upos = desc[6], ub0 = desc[7];
 
   const int32_t R = nb * G;
   const int32_t nblk = (R + 31) >> 5;
@@ -144,6 +148,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // ---- loader role: wave w fills block slot w/2 of a stage, K fragments (even w) or V (odd w)
   const int32_t ld_slot = wave >> 1;
   const bool ld_v = wave & 1;
+  // MFMA row m of a score tile carries this key of the block (see the file header)
   const int32_t krow = ((n >> 4) << 4) | (((n >> 2) & 1) << 3) | (((n >> 3) & 1) << 2) | (n & 3);
   const uint16_t* kbase = k_prefix + (int64_t)hk * a.NP * D;
   const uint16_t* vbase = v_prefix + (int64_t)hk * (a.NP / 8) * D * 8;
@@ -167,270 +172,45 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 
   issue_round(0, ringA);
 
-  const int32_t rows_here = min(R - first_blk * 32, nblk_here * 32);
-  const bool tails_first = nblk_here <= 4;  // the idle second stage can park 128 rows
-  float* const parkA = reinterpret_cast<float*>(ringA);
-  float* const parkB = reinterpret_cast<float*>(ringB);
-
-  // =====================================================================================
-  // Tail pass.  lane = (ks, c): the 16 lanes c of a DPP row cover one key row (8 channels
-  // each), ks = key within a group of 4.
-  //   merge_prefix = false: park (max, sum, O) of every row in `park`/ml_buf
-  //   merge_prefix = true : combine with the prefix partials parked there and store `out`
-  // =====================================================================================
-  const int32_t ks = lane >> 4, c = lane & 15;
-  const int32_t br0 = first_blk * 32 / G;
-  const int32_t nbr_here = min(nb - br0, nblk_here * 32 / G);
-  const int32_t nkeys_pool = a.step;  // older keys; the newest one is handled separately
-
-  // A branch with G = 8 is handled as two half-branches of GH = 4 rows (same keys).
-  constexpr int GH = G < 4 ? G : 4;
-  constexpr int NH = G / GH;
-  struct TailLoads {  // what is prefetched one (half-)branch ahead
-    uint4 kraw[4], vraw[4], qa[GH], qb[GH];
-    int64_t tbase;
-    int32_t live_row;
+  // ---- branches of this row group: tail offsets (and, fused, the append itself)
+  const int32_t br0 = first_blk * BPB;
+  const int32_t nbr_here = min(nb - br0, nblk_here * BPB);
+  const int32_t rows_here = nbr_here * G;
+  auto branch_id = [&](int32_t lb) -> int32_t {
+    const int32_t live_row = row0_live + br0 + lb;
+    return ub0 >= 0 ? ub0 + br0 + lb : a.tb.live_branch[a.live_base + live_row];
   };
-  auto tail_issue = [&](int32_t vb, TailLoads& t) {
-    const int32_t bl = vb / NH, g0 = (vb % NH) * GH;
-    t.live_row = row0_live + br0 + bl;
-    const int32_t b = a.tb.live_branch[a.live_base + t.live_row];
-    t.tbase = (((int64_t)b * a.Hkv + hk) * a.Tcap) * D;
-#pragma unroll
-    for (int g = 0; g < GH; ++g) {
-      const uint16_t* qp = q + ((int64_t)t.live_row * a.Hq + hk * G + g0 + g) * D;
-      t.qa[g] = *reinterpret_cast<const uint4*>(qp + c * 8);
-      t.qb[g] = *reinterpret_cast<const uint4*>(qp + (c ^ 8) * 8);
-    }
-#pragma unroll
-    for (int uu = 0; uu < 4; ++uu) {
-      const int32_t tt = uu * 4 + ks;
-      t.kraw[uu] = make_uint4(0, 0, 0, 0);
-      t.vraw[uu] = make_uint4(0, 0, 0, 0);
-      if (tt < nkeys_pool) {
-        t.kraw[uu] = *reinterpret_cast<const uint4*>(k_tail + t.tbase + (int64_t)tt * D + c * 8);
-        t.vraw[uu] = *reinterpret_cast<const uint4*>(v_tail + t.tbase + (int64_t)tt * D + c * 8);
-      }
-    }
-  };
-
-  auto tail_compute = [&](int32_t vb, TailLoads& t, bool merge_prefix, float* park_lo, float* park_hi) {
-    const int32_t bl = vb / NH, g0 = (vb % NH) * GH;
-    // the newest token's inputs are requested now and used at the very end
-    uint4 kna = make_uint4(0, 0, 0, 0), knb = kna, vn = kna;
-    if (a.fused) {
-      const uint16_t* kp = k_new + ((int64_t)t.live_row * a.Hkv + hk) * D;
-      kna = *reinterpret_cast<const uint4*>(kp + c * 8);
-      knb = *reinterpret_cast<const uint4*>(kp + (c ^ 8) * 8);
-      vn = *reinterpret_cast<const uint4*>(v_new + ((int64_t)t.live_row * a.Hkv + hk) * D + c * 8);
-    } else {  // already appended by hpd_kv_append: rotated and rounded
-      kna = *reinterpret_cast<const uint4*>(k_tail + t.tbase + (int64_t)a.step * D + c * 8);
-      vn = *reinterpret_cast<const uint4*>(v_tail + t.tbase + (int64_t)a.step * D + c * 8);
-    }
-    int32_t pos = upos;
-    if (upos < 0) {
-      const int32_t b = a.tb.live_branch[a.live_base + t.live_row];
-      pos = a.tb.branch_base_pos[b] + 1 + a.step;
-    }
-    const float4* csp = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)pos * (D / 2) + (c & 7) * 8);
-    // rotated query rows in fp32, pre-multiplied by scale * log2(e)
-    float qf[GH][8];
-    {
-      float cs_c[8], cs_s[8];
+  if (tid < MAX_ROWS) {
+    const int32_t lb = min(tid, nbr_here - 1);  // entries past the last branch repeat it
+    tail_base[tid] = (((int64_t)branch_id(lb) * a.Hkv + hk) * a.Tcap) * D;
+  }
+  if (a.fused) {
+    // the same arithmetic as hpd_kv_append, for this kv head of this row group's branches:
+    // one thread per (branch, 8-channel chunk of the first half and its rotation partner)
+    for (int32_t item = tid; item < nbr_here * 8; item += WAVES * 64) {
+      const int32_t lb = item >> 3, c8 = item & 7;
+      const int32_t live_row = row0_live + br0 + lb;
+      const int32_t b = branch_id(lb);
+      const int32_t pos = upos >= 0 ? upos : a.tb.branch_base_pos[b] + 1 + a.step;
+      const int64_t src = ((int64_t)live_row * a.Hkv + hk) * D + c8 * 8;
+      const int64_t dst = (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D + c8 * 8;
+      float x[8], y[8], r1[8], r2[8];
+      unpack8(*reinterpret_cast<const uint4*>(k_new + src), x);
+      unpack8(*reinterpret_cast<const uint4*>(k_new + src + 64), y);
+      const float4* csp = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)pos * (D / 2) + c8 * 8);
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {
         const float4 cs = csp[e2];
-        cs_c[2 * e2] = cs.x; cs_s[2 * e2] = cs.y; cs_c[2 * e2 + 1] = cs.z; cs_s[2 * e2 + 1] = cs.w;
+        hpd::rope_pair(x[2 * e2], y[2 * e2], cs.x, cs.y, r1[2 * e2], r2[2 * e2]);
+        hpd::rope_pair(x[2 * e2 + 1], y[2 * e2 + 1], cs.z, cs.w, r1[2 * e2 + 1], r2[2 * e2 + 1]);
       }
-#pragma unroll
-      for (int g = 0; g < GH; ++g) {
-        float x[8], y[8];
-        unpack8(t.qa[g], x);
-        unpack8(t.qb[g], y);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          float r1, r2;
-          if (c < 8) hpd::rope_pair(x[e], y[e], cs_c[e], cs_s[e], r1, r2);  // x = first half
-          else { hpd::rope_pair(y[e], x[e], cs_c[e], cs_s[e], r2, r1); }    // x = second half
-          qf[g][e] = r1 * a.scale_log2;
-        }
-      }
+      *reinterpret_cast<uint4*>(k_tail + dst) = __builtin_bit_cast(uint4, pack8(r1));
+      *reinterpret_cast<uint4*>(k_tail + dst + 64) = __builtin_bit_cast(uint4, pack8(r2));
+      *reinterpret_cast<uint4*>(v_tail + dst) = *reinterpret_cast<const uint4*>(v_new + src);
+      *reinterpret_cast<uint4*>(v_tail + dst + 64) = *reinterpret_cast<const uint4*>(v_new + src + 64);
     }
-    float tm[GH], tl[GH], ta[GH][8];
-#pragma unroll
-    for (int g = 0; g < GH; ++g) {
-      tm[g] = NEG_BIG; tl[g] = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) ta[g][e] = 0.f;
-    }
-    // ---- keys already in the pool, 16 per batch (the first batch was loaded by tail_issue)
-    for (int32_t base = 0; base < nkeys_pool; base += 16) {
-      if (base > 0) {
-#pragma unroll
-        for (int uu = 0; uu < 4; ++uu) {
-          const int32_t tt = base + uu * 4 + ks;
-          t.kraw[uu] = make_uint4(0, 0, 0, 0);
-          t.vraw[uu] = make_uint4(0, 0, 0, 0);
-          if (tt < nkeys_pool) {
-            t.kraw[uu] = *reinterpret_cast<const uint4*>(k_tail + t.tbase + (int64_t)tt * D + c * 8);
-            t.vraw[uu] = *reinterpret_cast<const uint4*>(v_tail + t.tbase + (int64_t)tt * D + c * 8);
-          }
-        }
-      }
-      float sc[GH][4];
-#pragma unroll
-      for (int uu = 0; uu < 4; ++uu) {
-        const bool ok = base + uu * 4 + ks < nkeys_pool;
-        float kv[8];
-        unpack8(t.kraw[uu], kv);
-#pragma unroll
-        for (int g = 0; g < GH; ++g) {
-          float dot = 0.f;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) dot = fmaf(kv[e], qf[g][e], dot);
-          dot = row16_sum(dot);
-          sc[g][uu] = ok ? dot : -INFINITY;
-        }
-      }
-#pragma unroll
-      for (int g = 0; g < GH; ++g) {
-        const float bmax = fmaxf(fmaxf(sc[g][0], sc[g][1]), fmaxf(sc[g][2], sc[g][3]));
-        const float m_new = fmaxf(tm[g], bmax);
-        const float alpha = fast_exp2(tm[g] - m_new);
-        tm[g] = m_new;
-        tl[g] *= alpha;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ta[g][e] *= alpha;
-#pragma unroll
-        for (int uu = 0; uu < 4; ++uu) sc[g][uu] = fast_exp2(sc[g][uu] - m_new);
-        tl[g] += (sc[g][0] + sc[g][1]) + (sc[g][2] + sc[g][3]);
-      }
-#pragma unroll
-      for (int uu = 0; uu < 4; ++uu) {
-        float vv[8];
-        unpack8(t.vraw[uu], vv);
-#pragma unroll
-        for (int g = 0; g < GH; ++g)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) ta[g][e] = fmaf(sc[g][uu], vv[e], ta[g][e]);
-      }
-    }
-    // ---- merge the 4 key lane-groups (lanes l, l^16, l^32, l^48)
-#pragma unroll
-    for (int g = 0; g < GH; ++g) {
-      float mm = fmaxf(tm[g], __shfl_xor(tm[g], 16));
-      mm = fmaxf(mm, __shfl_xor(mm, 32));
-      const float f = fast_exp2(tm[g] - mm);
-      tm[g] = mm;
-      tl[g] *= f;
-      tl[g] += __shfl_xor(tl[g], 16);
-      tl[g] += __shfl_xor(tl[g], 32);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float v = ta[g][e] * f;
-        v += __shfl_xor(v, 16);
-        v += __shfl_xor(v, 32);
-        ta[g][e] = v;
-      }
-    }
-    // ---- the newest token, after the older ones in both modes so that the fused and the
-    //      two-call sequence add up in the same order.  Fused: rotate, round once, store, use
-    //      the stored value.
-    {
-      float kv[8], vv[8];
-      uint4 kst = kna;
-      if (a.fused) {
-      float x[8], y[8], rr[8];
-      unpack8(kna, x);
-      unpack8(knb, y);
-      // the table row is read again (cache hit) rather than held in registers throughout:
-      // the empty asm hides the pointer's origin so the two reads are not merged
-      const float4* csp2 = csp;
-      asm volatile("" : "+v"(csp2));
-#pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {
-        const float4 cs = csp2[e2];
-        float r1, r2;
-        if (c < 8) hpd::rope_pair(x[2 * e2], y[2 * e2], cs.x, cs.y, r1, r2);
-        else { hpd::rope_pair(y[2 * e2], x[2 * e2], cs.x, cs.y, r2, r1); }
-        rr[2 * e2] = r1;
-        if (c < 8) hpd::rope_pair(x[2 * e2 + 1], y[2 * e2 + 1], cs.z, cs.w, r1, r2);
-        else { hpd::rope_pair(y[2 * e2 + 1], x[2 * e2 + 1], cs.z, cs.w, r2, r1); }
-        rr[2 * e2 + 1] = r1;
-      }
-      kst = __builtin_bit_cast(uint4, pack8(rr));
-      if (ks == 0 && g0 == 0) {
-        *reinterpret_cast<uint4*>(k_tail + t.tbase + (int64_t)a.step * D + c * 8) = kst;
-        *reinterpret_cast<uint4*>(v_tail + t.tbase + (int64_t)a.step * D + c * 8) = vn;
-      }
-      }
-      unpack8(kst, kv);
-      unpack8(vn, vv);
-#pragma unroll
-      for (int g = 0; g < GH; ++g) {
-        float dot = 0.f;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) dot = fmaf(kv[e], qf[g][e], dot);
-        dot = row16_sum(dot);
-        const float m_new = fmaxf(tm[g], dot);
-        const float alpha = fast_exp2(tm[g] - m_new);
-        const float pr = fast_exp2(dot - m_new);
-        tm[g] = m_new;
-        tl[g] = tl[g] * alpha + pr;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ta[g][e] = fmaf(pr, vv[e], ta[g][e] * alpha);
-      }
-    }
-    // ---- lane group ks finishes row g0 + ks
-#pragma unroll
-    for (int g = 0; g < GH; ++g) {
-      if (g == ks) {
-        const int32_t lr = bl * G + g0 + g;
-        float* park = lr < 128 ? park_lo : park_hi;
-        const int32_t lrr = lr & 127;
-        if (!merge_prefix) {
-          *reinterpret_cast<float4*>(park + park_off(lrr, 2 * c)) =
-              make_float4(ta[g][0], ta[g][1], ta[g][2], ta[g][3]);
-          *reinterpret_cast<float4*>(park + park_off(lrr, 2 * c + 1)) =
-              make_float4(ta[g][4], ta[g][5], ta[g][6], ta[g][7]);
-          if (c == 0) { ml_buf[lr * 2] = tm[g]; ml_buf[lr * 2 + 1] = tl[g]; }
-        } else {
-          const float mp = ml_buf[lr * 2], lp = ml_buf[lr * 2 + 1];
-          const float4 p0 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c));
-          const float4 p1 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c + 1));
-          const float mx = fmaxf(mp, tm[g]);
-          const float ap = fast_exp2(mp - mx), at = fast_exp2(tm[g] - mx);
-          const float inv = 1.0f / (lp * ap + tl[g] * at);
-          float o[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-#pragma unroll
-          for (int e = 0; e < 8; ++e) o[e] = (o[e] * ap + ta[g][e] * at) * inv;
-          const int64_t o_off = ((int64_t)t.live_row * a.Hq + hk * G + g0 + g) * D + c * 8;
-          if (a.out_f32) {
-            float* op = reinterpret_cast<float*>(out) + o_off;
-            *reinterpret_cast<float4*>(op) = make_float4(o[0], o[1], o[2], o[3]);
-            *reinterpret_cast<float4*>(op + 4) = make_float4(o[4], o[5], o[6], o[7]);
-          } else {
-            *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(out) + o_off) =
-                __builtin_bit_cast(uint4, pack8(o));
-          }
-        }
-      }
-    }
-  };
-
-  auto tail_pass = [&](bool merge_prefix, float* park_lo, float* park_hi) {
-    const int32_t nvb = nbr_here * NH;
-    TailLoads cur, nxt;
-    if (wave < nvb) tail_issue(wave, cur);
-    for (int32_t vb = wave; vb < nvb; vb += WAVES) {
-      const bool more = vb + WAVES < nvb;
-      if (more) tail_issue(vb + WAVES, nxt);
-      tail_compute(vb, cur, merge_prefix, park_lo, park_hi);
-      if (more) cur = nxt;
-    }
-  };
-
-  if (tails_first) tail_pass(false, parkB, parkB);
+  }
+  __syncthreads();  // tail_base is published; appended rows are visible to the workgroup
 
   // ---- this lane's query row, rotated, as bf16 hi + lo MFMA B operands
   const int32_t r_row = (first_blk + rb) * 32 + n;
@@ -441,10 +221,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const int32_t gq = r_row % G;
     const int32_t live_row = row0_live + bi;
     int32_t pos = upos;
-    if (upos < 0) {
-      const int32_t b = a.tb.live_branch[a.live_base + live_row];
-      pos = a.tb.branch_base_pos[b] + 1 + a.step;
-    }
+    if (upos < 0) pos = a.tb.branch_base_pos[branch_id(bi - br0)] + 1 + a.step;
     const int64_t q_off = ((int64_t)live_row * a.Hq + hk * G + gq) * D;
     const float2* cs_row = a.tb.rope + (int64_t)pos * (D / 2);
 #pragma unroll
@@ -486,64 +263,16 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[blk][i] = 0.f;
 
-  if (tails_first) {
-    __syncthreads();  // tail partials are parked in the second stage
-    if (active && kg == 0 && r_row < R) {
-      const int32_t lr = rb * 32 + n;
-      m_used = ml_buf[lr * 2];
-      l_lane = g2 == 0 ? ml_buf[lr * 2 + 1] : 0.f;
-#pragma unroll
-      for (int blk = 0; blk < 4; ++blk)
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-          const float4 v = *reinterpret_cast<const float4*>(parkB + park_off(lr, blk * 8 + cc * 2 + g2));
-          acc[blk][cc * 4 + 0] = v.x; acc[blk][cc * 4 + 1] = v.y;
-          acc[blk][cc * 4 + 2] = v.z; acc[blk][cc * 4 + 3] = v.w;
-        }
-    }
-    // the first round's barrier comes before any DMA into the second stage
-  }
-
-  auto compute_block = [&](const uint4* slot, int32_t valid) {
-    const uint4* fr = slot + lane;
-    floatx16 S;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) S[i] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 kf = __builtin_bit_cast(bf16x8, fr[kk * 64]);
-      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qh[kk], S, 0, 0, 0);
-      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Ql[kk], S, 0, 0, 0);
-    }
-    uint4 vf[8];
-#pragma unroll
-    for (int f = 0; f < 8; ++f) vf[f] = fr[(8 + f) * 64];
-
+  // softmax update + P.V for one 32-key tile: S = raw scores (C layout: value i of lane
+  // (n, g2) is key (i>>3)*16 + g2*8 + (i&7)), ok = which of them exist for this row,
+  // vf = the 8 V fragments (d-block * 2 + key half).
+  auto softmax_pv = [&](const floatx16& S, uint32_t ok, const uint4* vf) {
     float s[16];
     float bm = NEG_BIG;
-    if (valid < 32) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int key = ((i >> 3) << 4) + g2 * 8 + (i & 7);
-        s[i] = key < valid ? S[i] * a.scale_log2 : -INFINITY;
-        bm = fmaxf(bm, s[i]);
-      }
-      // padding slots may hold NaN patterns: 0 * NaN must not reach the accumulators
-#pragma unroll
-      for (int f = 0; f < 8; ++f) {
-        const int key0 = (f & 1) * 16 + g2 * 8;
-        uint32_t w[4] = {vf[f].x, vf[f].y, vf[f].z, vf[f].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (key0 + e >= valid) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-        vf[f] = make_uint4(w[0], w[1], w[2], w[3]);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        s[i] = S[i] * a.scale_log2;
-        bm = fmaxf(bm, s[i]);
-      }
+    for (int i = 0; i < 16; ++i) {
+      s[i] = (ok >> i) & 1 ? S[i] * a.scale_log2 : -INFINITY;
+      bm = fmaxf(bm, s[i]);
     }
     if (__any(bm > m_used)) {
       bm = fmaxf(bm, __shfl_xor(bm, 32));
@@ -571,9 +300,110 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     }
   };
 
+  // =====================================================================================
+  // Tail tiles.  Virtual key k of tile ti = (position ti*G + k / BPB, branch k % BPB of this
+  // row block); a row may only see the keys of its own branch at positions <= step.
+  // =====================================================================================
+  if (active) {
+    uint16_t* const stage = reinterpret_cast<uint16_t*>(ringB) + wave * 4096;  // 8 KB, wave-private
+    const int32_t NT = (a.step + G) / G;  // ceil((step + 1) / G)
+    const int32_t lb0 = rb * BPB;
+    for (int32_t ti = kg; ti < NT; ti += KG) {
+      const int32_t tau0 = ti * G;
+      // K fragments straight from the row-major tail pool (clamped: always a written row)
+      uint4 kf[8];
+      {
+        const int32_t tau = min(tau0 + krow / BPB, a.step);
+        const uint16_t* kp = k_tail + tail_base[lb0 + krow % BPB] + (int64_t)tau * D + g2 * 8;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) kf[kk] = *reinterpret_cast<const uint4*>(kp + kk * 16);
+      }
+      // V rows -> LDS (row-major, the 16-byte chunk index XOR-swizzled by bit 3 of the key)
+      {
+        uint4 vr[8];
+        const int32_t r4 = lane >> 4, c16 = lane & 15;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int32_t k = j * 4 + r4;
+          const int32_t tau = min(tau0 + k / BPB, a.step);
+          vr[j] = *reinterpret_cast<const uint4*>(v_tail + tail_base[lb0 + k % BPB] + (int64_t)tau * D + c16 * 8);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int32_t k = j * 4 + r4;
+          *reinterpret_cast<uint4*>(stage + k * 128 + ((c16 ^ (((k >> 3) & 1) << 2)) << 3)) = vr[j];
+        }
+      }
+      floatx16 S;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const bf16x8 kfr = __builtin_bit_cast(bf16x8, kf[kk]);
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, Qh[kk], S, 0, 0, 0);
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, Ql[kk], S, 0, 0, 0);
+      }
+      // which of this lane's 16 virtual keys belong to its own branch and exist
+      uint32_t ok = 0;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int k = ((i >> 3) << 4) + g2 * 8 + (i & 7);
+        if (k % BPB == n / G && tau0 + k / BPB <= a.step) ok |= 1u << i;
+      }
+      // V^T fragments: 8 keys of one channel, gathered with 2-byte LDS reads
+      uint4 vf[8];
+#pragma unroll
+      for (int f = 0; f < 8; ++f) {
+        const int blk = f >> 1, hf = f & 1;
+        const int d = blk * 32 + n;
+        const uint16_t* col = stage + (hf * 16 + g2 * 8) * 128 + ((((d >> 3) ^ (g2 << 2)) << 3) | (d & 7));
+        uint32_t w[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2)
+          w[e2] = (uint32_t)col[(2 * e2) * 128] | ((uint32_t)col[(2 * e2 + 1) * 128] << 16);
+        vf[f] = make_uint4(w[0], w[1], w[2], w[3]);
+      }
+      softmax_pv(S, ok, vf);
+    }
+  }
+
+  auto compute_block = [&](const uint4* slot, int32_t valid) {
+    const uint4* fr = slot + lane;
+    floatx16 S;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 kf = __builtin_bit_cast(bf16x8, fr[kk * 64]);
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qh[kk], S, 0, 0, 0);
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Ql[kk], S, 0, 0, 0);
+    }
+    uint4 vf[8];
+#pragma unroll
+    for (int f = 0; f < 8; ++f) vf[f] = fr[(8 + f) * 64];
+    uint32_t ok = 0xffffu;
+    if (valid < 32) {
+      ok = 0;
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        if (((i >> 3) << 4) + g2 * 8 + (i & 7) < valid) ok |= 1u << i;
+      // padding slots may hold NaN patterns: 0 * NaN must not reach the accumulators
+#pragma unroll
+      for (int f = 0; f < 8; ++f) {
+        const int key0 = (f & 1) * 16 + g2 * 8;
+        uint32_t w[4] = {vf[f].x, vf[f].y, vf[f].z, vf[f].w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (key0 + e >= valid) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
+        vf[f] = make_uint4(w[0], w[1], w[2], w[3]);
+      }
+    }
+    softmax_pv(S, ok, vf);
+  };
+
   auto round_body = [&](int32_t r, const uint4* cur, uint4* nxt) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+    __syncthreads();  // round r has landed; everybody is done with the other stage
     if (r + 1 < NR) issue_round(r + 1, nxt);
     if (active) {
       for (int32_t j = kg; j < STAGE_BLOCKS; j += KG) {
@@ -586,6 +416,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     }
   };
 
+  // the first round's barrier also ends the use of the second stage as tail staging
   for (int32_t r = 0; r < NR; r += 2) {
     round_body(r, ringA, ringB);
     if (r + 1 < NR) round_body(r + 1, ringB, ringA);
@@ -593,13 +424,13 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();  // both stages are dead from here on and get reused
 
-  // ---- merge the key groups: regions 0,1 in ringA, 2,3 in ringB
-  for (int32_t s = 1; s < KG; s <<= 1) {
-    const bool writer = active && (kg % (2 * s)) == s;
-    const bool reader = active && (kg % (2 * s)) == 0 && kg + s < KG;
-    const int32_t region = rb + nblk_here * (kg / (2 * s));  // < 4
-    float* buf = (region < 2 ? parkA + region * MERGE_FLOATS : parkB + (region - 2) * MERGE_FLOATS) + lane;
-    if (writer) {
+  // ---- merge the key groups in one round: region r lives in stage (r & 1), slot r >> 1
+  float* const parkA = reinterpret_cast<float*>(ringA);
+  float* const parkB = reinterpret_cast<float*>(ringB);
+  if (KG > 1) {
+    auto region = [&](int32_t r) { return ((r & 1) ? parkB : parkA) + (r >> 1) * MERGE_FLOATS + lane; };
+    if (active && kg > 0) {
+      float* buf = region(rb * (KG - 1) + kg - 1);
 #pragma unroll
       for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
@@ -608,21 +439,24 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       buf[65 * 64] = l_lane;
     }
     __syncthreads();
-    if (reader) {
-      const float m2 = buf[64 * 64], l2 = buf[65 * 64];
-      const float m_new = fmaxf(m_used, m2);
-      const float a1 = fast_exp2(m_used - m_new), a2 = fast_exp2(m2 - m_new);
-      l_lane = l_lane * a1 + l2 * a2;
-      m_used = m_new;
+    if (active && kg == 0) {
+      for (int32_t o = 0; o < KG - 1; ++o) {
+        const float* buf = region(rb * (KG - 1) + o);
+        const float m2 = buf[64 * 64], l2 = buf[65 * 64];
+        const float m_new = fmaxf(m_used, m2);
+        const float a1 = fast_exp2(m_used - m_new), a2 = fast_exp2(m2 - m_new);
+        l_lane = l_lane * a1 + l2 * a2;
+        m_used = m_new;
 #pragma unroll
-      for (int blk = 0; blk < 4; ++blk)
+        for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[blk][i] = acc[blk][i] * a1 + buf[(blk * 16 + i) * 64] * a2;
+          for (int i = 0; i < 16; ++i) acc[blk][i] = acc[blk][i] * a1 + buf[(blk * 16 + i) * 64] * a2;
+      }
     }
     __syncthreads();
   }
 
-  // ---- park the MFMA waves' state row-major (rows 0..127 in ringA, 128..255 in ringB)
+  // ---- park the finished rows row-major (rows 0..127 in stage A, 128..255 in stage B) ...
   if (active && kg == 0) {
     const int32_t lr = rb * 32 + n;
     float* park = lr < 128 ? parkA : parkB;
@@ -634,18 +468,19 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         *reinterpret_cast<float4*>(park + park_off(lrr, blk * 8 + cc * 2 + g2)) =
             make_float4(acc[blk][cc * 4 + 0], acc[blk][cc * 4 + 1], acc[blk][cc * 4 + 2], acc[blk][cc * 4 + 3]);
     const float l_row = l_lane + __shfl_xor(l_lane, 32);
-    if (g2 == 0) { ml_buf[lr * 2] = m_used; ml_buf[lr * 2 + 1] = l_row; }
+    if (g2 == 0) l_buf[lr] = l_row;
   }
   __syncthreads();
 
-  if (!tails_first) {
-    tail_pass(true, parkA, parkB);
-  } else {
-    // rows are complete: normalise and store, 4 rows per wave pass, 512 contiguous bytes each
+  // ---- ... and write them normalised, 4 rows per wave pass, 512 contiguous bytes per row
+  {
+    const int32_t ks = lane >> 4, c = lane & 15;
     for (int32_t lr = wave * 4 + ks; lr < rows_here; lr += WAVES * 4) {
-      const float inv = 1.0f / ml_buf[lr * 2 + 1];
-      const float4 p0 = *reinterpret_cast<const float4*>(parkA + park_off(lr, 2 * c));
-      const float4 p1 = *reinterpret_cast<const float4*>(parkA + park_off(lr, 2 * c + 1));
+      const float inv = 1.0f / l_buf[lr];
+      const float* park = lr < 128 ? parkA : parkB;
+      const int32_t lrr = lr & 127;
+      const float4 p0 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c));
+      const float4 p1 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c + 1));
       float o[8] = {p0.x * inv, p0.y * inv, p0.z * inv, p0.w * inv, p1.x * inv, p1.y * inv, p1.z * inv, p1.w * inv};
       const int32_t live_row = row0_live + br0 + lr / G;
       const int64_t o_off = ((int64_t)live_row * a.Hq + hk * G + lr % G) * D + c * 8;

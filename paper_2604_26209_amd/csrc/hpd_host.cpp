@@ -213,8 +213,14 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
         // all live branches of a document share one position in the contiguous mode
         int32_t pos = -1;
         if (cfg->pos_mode == HPD_POS_CONTIG) pos = L->seg_len[p] + L->seg_len[P + d] + t;
+        // first branch id if the document's live branches are consecutive ids (no finished
+        // branch in between): the kernels then need no lookup in the live list
+        const int32_t nbl = dlp[d + 1] - dlp[d];
+        const int32_t bf = L->live_branch[L->live_ptr[t] + dlp[d]];
+        const int32_t bl = L->live_branch[L->live_ptr[t] + dlp[d + 1] - 1];
+        const int32_t b_first = (bl - bf == nbl - 1) ? bf : -1;
         const int32_t desc[8] = {L->seg_off[p], L->seg_len[p], L->seg_off[P + d], L->seg_len[P + d],
-                                 dlp[d], dlp[d + 1] - dlp[d], pos, d};
+                                 dlp[d], nbl, pos, b_first};
         L->unit_desc.insert(L->unit_desc.end(), desc, desc + 8);
       }
     }

@@ -24,7 +24,7 @@ struct hpd_dev_tables {
   const int32_t* doc_live_ptr;  // [T][n_docs+1] first live row (within the step's list) of each document
   const int32_t* unit_ptr;      // [T+1]
   const int32_t* unit_doc;      // [total_units] documents with live branches, heaviest first
-  const int32_t* unit_desc;     // [total_units][8] {hoff, Hlen, doff, Llen, first live row, live branches, position or -1, doc}
+  const int32_t* unit_desc;     // [total_units][8] {hoff, Hlen, doff, Llen, first live row, live branches, position or -1, first branch id or -1}
   const float2* rope;           // [max_pos+1][D/2] (cos, sin)
 };
 
