@@ -7,9 +7,11 @@ decode step t = 0..T-1 of the workload, RoPE(K) + KV append and RoPE(Q) + masked
 pools are resident in HBM before the timed region.  Metric: branch-tokens/s =
 sum_t n_live(t) / time.
 
-Cold-cache protocol: R independent replicas of the KV pools (R x footprint >= ~2 GB, far
-above the 256 MB Infinity Cache) are cycled, one per pass, as the other layers' KV would be
-in a real model.
+Cold-cache protocol: R independent replicas of the KV pools ("layers", R x footprint >= ~2 GB,
+far above the 256 MB Infinity Cache) are decoded interleaved - decode step t of layer 0, of
+layer 1, ... of layer R-1, then step t+1 of layer 0, ... - as the layers of a real model
+would be, so that every launch finds its KV evicted.  (Running all T steps of one replica
+back to back would serve steps 1..T-1 out of the Infinity Cache.)
 
 Prints ONE JSON line.  `roofline` is measured live with events around every attention launch
 in a second, identical timed region; `cpu_baseline` times the CPU oracle on a bounded sample
@@ -114,7 +116,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5")
     ap.add_argument("--replicas", type=int, default=0, help="KV replicas (0 = enough for 2 GB)")
     ap.add_argument("--out", default="f32", choices=["f32", "same"], help="output element type")
@@ -180,32 +182,39 @@ def main():
     del k_raw, v_raw
     torch.cuda.synchronize()
 
-    def one_pass(i, events=None):
-        """All decode steps of the workload on KV replica i.  With `events`, every launch of
-        the dominant (attention) kernel is bracketed by a pair of events on the same stream."""
-        kp, vp, kt, vt = pools[i % R]
+    def sweep(first, n_layers, events=None):
+        """n_layers passes (all decode steps of the workload, one KV replica each), interleaved
+        step by step.  With `events`, every launch of the dominant kernel is bracketed by a
+        pair of events on the same stream."""
         for t in range(wl.max_new):
             if int(n_live[t]) == 0:
                 continue
-            if args.two_call:
-                B.hpd_kv_append(layout, t, kn[t], vn[t], kt, vt)
-            if events is not None:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-            if args.two_call:
-                B.hpd_decode_attention(layout, t, q[t], kp, vp, kt, vt, outs[t])
-            else:
-                B.hpd_decode_step(layout, t, q[t], kn[t], vn[t], kp, vp, kt, vt, outs[t])
-            if events is not None:
-                e1.record()
-                events.append((t, e0, e1))
+            for j in range(n_layers):
+                kp, vp, kt, vt = pools[(first + j) % R]
+                if args.two_call:
+                    B.hpd_kv_append(layout, t, kn[t], vn[t], kt, vt)
+                if events is not None:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                if args.two_call:
+                    B.hpd_decode_attention(layout, t, q[t], kp, vp, kt, vt, outs[t])
+                else:
+                    B.hpd_decode_step(layout, t, q[t], kn[t], vn[t], kp, vp, kt, vt, outs[t])
+                if events is not None:
+                    e1.record()
+                    events.append((t, e0, e1))
 
-    for i in range(args.warmup):
-        one_pass(i)
+    def run(n_passes, events=None):
+        done = 0
+        while done < n_passes:
+            n = min(R, n_passes - done)
+            sweep(done, n, events)
+            done += n
+
+    run(args.warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        one_pass(args.warmup + i)
+    run(args.steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
@@ -213,8 +222,7 @@ def main():
 
     # ---- roofline of the dominant kernel (attention), per launch, live
     events = []
-    for i in range(args.steps):
-        one_pass(args.warmup + args.steps + i, events)
+    run(args.steps, events)
     torch.cuda.synchronize()
     dur_s = sum(e0.elapsed_time(e1) for _, e0, e1 in events) * 1e-3
     # the fused step kernel also does the append (new K/V in, rotated K/V out)

@@ -12,10 +12,12 @@
 //    (global_load_lds_dwordx4): no VGPRs are held by data in flight.  A lane fetches exactly
 //    the 16 bytes that the same lane will later feed to an MFMA, so LDS is a pure delay line:
 //    fragment f of a block sits at lds[f][lane], reads are lane-linear and conflict-free.
-//    Two 64 KB stages of four blocks are used alternately: while stage A is consumed, the
-//    64 KB of stage B are in flight.  The two stages are distinct __shared__ arrays on
-//    purpose: the compiler then knows that reading one does not alias the DMA into the
-//    other and does not drain the DMA queue before every LDS read.
+//    Four 32 KB stages of two blocks form a ring: while one stage is consumed up to three
+//    are in flight, and a round only waits (s_waitcnt vmcnt(N)) for its own stage.  The
+//    stages are distinct __shared__ arrays on purpose: the compiler then knows that reading
+//    one does not alias the DMA into the others and does not drain the DMA queue before
+//    every LDS read.  Measured with two 64 KB stages drained every round: 3.4 TB/s in the
+//    steady state, because HBM idled between the bursts.
 //  * Contraction (transposed):
 //        S^T[key,row] = K.Q^T   (A = K fragment, B = rotated Q in registers as bf16 hi + lo
 //                                parts: two MFMA passes, Q rounding drops out of the error)
@@ -33,8 +35,10 @@
 //    maximum the largest weight would carry a 2^-9 rounding error into P.V (measured: 3x
 //    larger max-abs error).
 //  * Waves.  8 waves = (row block of 32 rows) x (key group), KG = 4 / 2 / 1 for <= 2 / <= 4 /
-//    <= 8 row blocks; the key groups split every stage's four blocks and the tail tiles, and
-//    are merged once through LDS at the end (identical lane layout on both sides).
+//    <= 8 row blocks; key group kg takes the key blocks gb with gb % KG == kg and every
+//    KG-th tail tile.  At the end the groups are merged through LDS in one exchange in which
+//    every wave of a row block reduces its own 32-channel slice (identical lane layout on
+//    both sides, so the exchange is lane-private).
 //  * Tails (Section 4.3.3: every value still grows token by token) are private to a branch.
 //    A first version used wavefront-reduction dot products (16 lanes per key row); measured
 //    on MI355X it needed ~1000 VALU instructions per branch and 5 us per branch per wave,
@@ -47,10 +51,10 @@
 //    that the two half-waves hit different banks).  The MFMA work wasted on the masked
 //    entries is irrelevant: the matrix pipe is idle while the first stage is in flight.
 //    Tail tiles are processed first and simply initialise the online-softmax state.
-//  * Fused mode (hpd_decode_step): the workgroup first rotates, rounds and stores the newest
-//    key/value of its own branches (the same arithmetic as hpd_kv_append), synchronises, and
-//    then reads them back like every other tail entry - bit-identical to the two-call
-//    sequence by construction.
+//  * Fused mode (hpd_decode_step): the lanes whose tail-tile entry is the newest token take
+//    it from k_new / v_new instead of the pool, rotate and round it with the same arithmetic
+//    as hpd_kv_append, store it, and use the rounded registers - bit-identical to the
+//    two-call sequence, with no read-back and no extra synchronisation.
 #include <cmath>
 
 #include "hpd_internal.h"
@@ -66,8 +70,9 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int D = 128;
 constexpr int WAVES = 8;
 constexpr int SLOT_U4 = 16 * 64;       // one 32-key block: 8 K + 8 V fragments of 64 x 16 bytes
-constexpr int STAGE_BLOCKS = 4;
-constexpr int STAGE_U4 = STAGE_BLOCKS * SLOT_U4;  // 64 KB
+constexpr int STAGE_BLOCKS = 2;
+constexpr int STAGE_U4 = STAGE_BLOCKS * SLOT_U4;  // 32 KB
+constexpr int LOADS_PER_ROUND = STAGE_BLOCKS * 16 / WAVES;  // DMA instructions per wave per round
 constexpr int MERGE_FLOATS = 66 * 64;  // 64 accumulators + max + sum per lane
 constexpr int MAX_ROWS = 256;          // rows per workgroup (8 row blocks)
 constexpr float NEG_BIG = -1.0e30f;
@@ -112,13 +117,15 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
                    const uint16_t* __restrict__ v_new, void* __restrict__ out) {
   constexpr int BPB = 32 / G;  // branches per row block; a tail tile holds G positions of each
 
-  __shared__ uint4 ringA[STAGE_U4];
-  __shared__ uint4 ringB[STAGE_U4];
+  __shared__ uint4 ring0[STAGE_U4];
+  __shared__ uint4 ring1[STAGE_U4];
+  __shared__ uint4 ring2[STAGE_U4];
+  __shared__ uint4 ring3[STAGE_U4];
   __shared__ float l_buf[MAX_ROWS];
-  __shared__ int64_t tail_base[MAX_ROWS];  // per local branch: element offset of its tail
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
+  const int lane = tid & 63;
   const int n = lane & 31, g2 = lane >> 5;
 
   // ---- unit descriptor (one dependent load):
@@ -145,96 +152,83 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t NB = NBh + NBd;
   const int32_t NR = (NB + STAGE_BLOCKS - 1) / STAGE_BLOCKS;
 
-  // ---- loader role: wave w fills block slot w/2 of a stage, K fragments (even w) or V (odd w)
-  const int32_t ld_slot = wave >> 1;
-  const bool ld_v = wave & 1;
+  // ---- loader role: wave w fills a quarter of block slot w/4 of a stage (K fragments for
+  //      quarters 0 and 1, V fragments for 2 and 3): LOADS_PER_ROUND instructions per round,
+  //      always the same number, so that vmcnt(N) means the same thing in every wave
+  const int32_t ld_slot = wave >> 2;
+  const int32_t ld_part = wave & 3;
   // MFMA row m of a score tile carries this key of the block (see the file header)
   const int32_t krow = ((n >> 4) << 4) | (((n >> 2) & 1) << 3) | (((n >> 3) & 1) << 2) | (n & 3);
   const uint16_t* kbase = k_prefix + (int64_t)hk * a.NP * D;
   const uint16_t* vbase = v_prefix + (int64_t)hk * (a.NP / 8) * D * 8;
 
+  // one 32-bit per-lane element offset; everything else in the load addresses is wave-uniform
+  const int32_t ld_off = ld_part < 2 ? krow * D + g2 * 8 + ld_part * 64
+                                     : (g2 * D + (ld_part - 2) * 64 + n) * 8;
   auto issue_round = [&](int32_t r, uint4* stage) {
-    const int32_t gb = r * STAGE_BLOCKS + ld_slot;
-    if (gb >= NB) return;  // uniform per wave
+    // a slot past the last block re-loads the last block (never read): the count stays fixed
+    const int32_t gb = min(r * STAGE_BLOCKS + ld_slot, NB - 1);
     const int32_t slot0 = gb < NBh ? hoff + gb * 32 : doff + (gb - NBh) * 32;
-    uint4* dst = stage + ld_slot * SLOT_U4 + (ld_v ? 8 * 64 : 0);
-    if (!ld_v) {
-      const uint16_t* src = kbase + (int64_t)(slot0 + krow) * D + g2 * 8;
+    uint4* dst = stage + ld_slot * SLOT_U4 + ld_part * 4 * 64;
+    if (ld_part < 2) {
+      const uint16_t* src = kbase + (int64_t)slot0 * D;
 #pragma unroll
-      for (int f = 0; f < 8; ++f) HPD_GLL(src + f * 16, dst + f * 64);
+      for (int f = 0; f < 4; ++f) HPD_GLL(src + (ld_off + f * 16), dst + f * 64);
     } else {
-      const uint16_t* src = vbase + ((int64_t)(slot0 / 8 + g2) * D + n) * 8;
+      // V fragment f = d-block * 2 + key half; this wave loads d-blocks 2*(part-2), +1
+      const uint16_t* src = vbase + (int64_t)(slot0 / 8) * D * 8;
 #pragma unroll
-      for (int f = 0; f < 8; ++f)  // f = d-block * 2 + key half
-        HPD_GLL(src + ((int64_t)(f & 1) * 2 * D + (f >> 1) * 32) * 8, dst + f * 64);
+      for (int f = 0; f < 4; ++f)
+        HPD_GLL(src + (ld_off + ((f & 1) * 2 * D + (f >> 1) * 32) * 8), dst + f * 64);
     }
   };
 
-  issue_round(0, ringA);
-
-  // ---- branches of this row group: tail offsets (and, fused, the append itself)
+  // ---- branches of this row group
   const int32_t br0 = first_blk * BPB;
   const int32_t nbr_here = min(nb - br0, nblk_here * BPB);
   const int32_t rows_here = nbr_here * G;
   auto branch_id = [&](int32_t lb) -> int32_t {
-    const int32_t live_row = row0_live + br0 + lb;
-    return ub0 >= 0 ? ub0 + br0 + lb : a.tb.live_branch[a.live_base + live_row];
+    return ub0 >= 0 ? ub0 + br0 + lb : a.tb.live_branch[a.live_base + row0_live + br0 + lb];
   };
-  if (tid < MAX_ROWS) {
-    const int32_t lb = min(tid, nbr_here - 1);  // entries past the last branch repeat it
-    tail_base[tid] = (((int64_t)branch_id(lb) * a.Hkv + hk) * a.Tcap) * D;
-  }
-  if (a.fused) {
-    // the same arithmetic as hpd_kv_append, for this kv head of this row group's branches:
-    // one thread per (branch, 8-channel chunk of the first half and its rotation partner)
-    for (int32_t item = tid; item < nbr_here * 8; item += WAVES * 64) {
-      const int32_t lb = item >> 3, c8 = item & 7;
-      const int32_t live_row = row0_live + br0 + lb;
-      const int32_t b = branch_id(lb);
-      const int32_t pos = upos >= 0 ? upos : a.tb.branch_base_pos[b] + 1 + a.step;
-      const int64_t src = ((int64_t)live_row * a.Hkv + hk) * D + c8 * 8;
-      const int64_t dst = (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D + c8 * 8;
-      float x[8], y[8], r1[8], r2[8];
-      unpack8(*reinterpret_cast<const uint4*>(k_new + src), x);
-      unpack8(*reinterpret_cast<const uint4*>(k_new + src + 64), y);
-      const float4* csp = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)pos * (D / 2) + c8 * 8);
-#pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {
-        const float4 cs = csp[e2];
-        hpd::rope_pair(x[2 * e2], y[2 * e2], cs.x, cs.y, r1[2 * e2], r2[2 * e2]);
-        hpd::rope_pair(x[2 * e2 + 1], y[2 * e2 + 1], cs.z, cs.w, r1[2 * e2 + 1], r2[2 * e2 + 1]);
-      }
-      *reinterpret_cast<uint4*>(k_tail + dst) = __builtin_bit_cast(uint4, pack8(r1));
-      *reinterpret_cast<uint4*>(k_tail + dst + 64) = __builtin_bit_cast(uint4, pack8(r2));
-      *reinterpret_cast<uint4*>(v_tail + dst) = *reinterpret_cast<const uint4*>(v_new + src);
-      *reinterpret_cast<uint4*>(v_tail + dst + 64) = *reinterpret_cast<const uint4*>(v_new + src + 64);
-    }
-  }
-  __syncthreads();  // tail_base is published; appended rows are visible to the workgroup
+  auto tail_offset = [&](int32_t b) -> int64_t { return (((int64_t)b * a.Hkv + hk) * a.Tcap) * D; };
 
-  // ---- this lane's query row, rotated, as bf16 hi + lo MFMA B operands
+  // ---- first request, ahead of the DMA in the memory queue: this lane's query row
   const int32_t r_row = (first_blk + rb) * 32 + n;
   const bool row_valid = active && r_row < R;
+  const int32_t q_bi = min(r_row / G, nb - 1);
+  const int64_t q_off = ((int64_t)(row0_live + q_bi) * a.Hq + hk * G + r_row % G) * D;
+  int32_t q_pos = upos;
+  if (upos < 0) q_pos = a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
+  uint4 qraw[8];
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    qraw[kk] = make_uint4(0, 0, 0, 0);
+    if (row_valid) qraw[kk] = *reinterpret_cast<const uint4*>(q + q_off + kk * 16 + g2 * 8);
+  }
+
+  // ---- tail tiles
+  // Virtual key k of pool tile ti = (position ti*G + k / BPB, branch k % BPB of this row
+  // block), positions 0 .. step-1; the newest token (position step) gets a tile of its own
+  // with one key per branch, in both modes, so that the fused and the two-call sequence add
+  // up in the same order.  A row may only see the keys of its own branch.
+  const int32_t NT = (a.step + G - 1) / G;  // pool tiles: ceil(step / G)
+  const int32_t lb0 = rb * BPB;
+  const int32_t r4 = lane >> 4, c16 = lane & 15;
+
+  // ---- start the DMA ring: rounds 0 and 1 now; stages 2 and 3 serve as tail staging first
+  issue_round(0, ring0);
+  if (NR > 1) issue_round(1, ring1);
+
+  // ---- rotate the query: bf16 hi + lo MFMA B operands
   bf16x8 Qh[8], Ql[8];
   {
-    const int32_t bi = min(r_row / G, nb - 1);
-    const int32_t gq = r_row % G;
-    const int32_t live_row = row0_live + bi;
-    int32_t pos = upos;
-    if (upos < 0) pos = a.tb.branch_base_pos[branch_id(bi - br0)] + 1 + a.step;
-    const int64_t q_off = ((int64_t)live_row * a.Hq + hk * G + gq) * D;
-    const float2* cs_row = a.tb.rope + (int64_t)pos * (D / 2);
+    const float2* cs_row = a.tb.rope + (int64_t)q_pos * (D / 2);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       const int c0 = kk * 16 + g2 * 8;
       float lo[8], hi[8], rl[8], rh[8];
-      if (row_valid) {
-        unpack8(*reinterpret_cast<const uint4*>(q + q_off + c0), lo);
-        unpack8(*reinterpret_cast<const uint4*>(q + q_off + c0 + 64), hi);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) lo[e] = hi[e] = 0.f;
-      }
+      unpack8(qraw[kk], lo);
+      unpack8(qraw[kk + 4], hi);
       const float4* csp = reinterpret_cast<const float4*>(cs_row + c0);
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {
@@ -301,39 +295,15 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   };
 
   // =====================================================================================
-  // Tail tiles.  Virtual key k of tile ti = (position ti*G + k / BPB, branch k % BPB of this
-  // row block); a row may only see the keys of its own branch at positions <= step.
+  // Tail tiles
   // =====================================================================================
   if (active) {
-    uint16_t* const stage = reinterpret_cast<uint16_t*>(ringB) + wave * 4096;  // 8 KB, wave-private
-    const int32_t NT = (a.step + G) / G;  // ceil((step + 1) / G)
-    const int32_t lb0 = rb * BPB;
-    for (int32_t ti = kg; ti < NT; ti += KG) {
-      const int32_t tau0 = ti * G;
-      // K fragments straight from the row-major tail pool (clamped: always a written row)
-      uint4 kf[8];
-      {
-        const int32_t tau = min(tau0 + krow / BPB, a.step);
-        const uint16_t* kp = k_tail + tail_base[lb0 + krow % BPB] + (int64_t)tau * D + g2 * 8;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) kf[kk] = *reinterpret_cast<const uint4*>(kp + kk * 16);
-      }
-      // V rows -> LDS (row-major, the 16-byte chunk index XOR-swizzled by bit 3 of the key)
-      {
-        uint4 vr[8];
-        const int32_t r4 = lane >> 4, c16 = lane & 15;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int32_t k = j * 4 + r4;
-          const int32_t tau = min(tau0 + k / BPB, a.step);
-          vr[j] = *reinterpret_cast<const uint4*>(v_tail + tail_base[lb0 + k % BPB] + (int64_t)tau * D + c16 * 8);
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int32_t k = j * 4 + r4;
-          *reinterpret_cast<uint4*>(stage + k * 128 + ((c16 ^ (((k >> 3) & 1) << 2)) << 3)) = vr[j];
-        }
-      }
+    // 8 KB of wave-private staging in the two stages the DMA has not been pointed at yet
+    uint16_t* const stage = reinterpret_cast<uint16_t*>(wave < 4 ? ring2 : ring3) + (wave & 3) * 4096;
+
+    // scores from K fragments in registers, V^T fragments out of the staging area (row-major
+    // rows, 16-byte chunk index XOR-swizzled by bit 3 of the key), softmax, P.V
+    auto tile_core = [&](const uint4* kf, uint32_t ok) {
       floatx16 S;
 #pragma unroll
       for (int i = 0; i < 16; ++i) S[i] = 0.f;
@@ -343,14 +313,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, Qh[kk], S, 0, 0, 0);
         S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, Ql[kk], S, 0, 0, 0);
       }
-      // which of this lane's 16 virtual keys belong to its own branch and exist
-      uint32_t ok = 0;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int k = ((i >> 3) << 4) + g2 * 8 + (i & 7);
-        if (k % BPB == n / G && tau0 + k / BPB <= a.step) ok |= 1u << i;
-      }
-      // V^T fragments: 8 keys of one channel, gathered with 2-byte LDS reads
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the V rows have landed in LDS
       uint4 vf[8];
 #pragma unroll
       for (int f = 0; f < 8; ++f) {
@@ -364,6 +327,103 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         vf[f] = make_uint4(w[0], w[1], w[2], w[3]);
       }
       softmax_pv(S, ok, vf);
+    };
+
+    // ---- positions 0 .. step-1 from the pool
+    for (int32_t ti = kg; ti < NT; ti += KG) {
+      const int32_t tau0 = ti * G;
+      const int32_t last = a.step - 1;  // clamp: always a written row of a live branch
+      uint4 kf[8];
+      {
+        const int32_t lb = min(lb0 + krow % BPB, nbr_here - 1);
+        const uint16_t* kp = k_tail + tail_offset(branch_id(lb)) + (int64_t)min(tau0 + krow / BPB, last) * D + g2 * 8;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) kf[kk] = *reinterpret_cast<const uint4*>(kp + kk * 16);
+      }
+      // V rows by DMA: lane (r4, c16) of instruction j = chunk c16 of virtual key 4j + r4
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int32_t k = j * 4 + r4;
+        const int32_t lb = min(lb0 + k % BPB, nbr_here - 1);
+        const uint16_t* vp = v_tail + tail_offset(branch_id(lb)) + (int64_t)min(tau0 + k / BPB, last) * D;
+        HPD_GLL(vp + ((c16 ^ (((k >> 3) & 1) << 2)) << 3), stage + j * 4 * 128);
+      }
+      uint32_t ok = 0;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int k = ((i >> 3) << 4) + g2 * 8 + (i & 7);
+        if (k % BPB == n / G && tau0 + k / BPB < a.step) ok |= 1u << i;
+      }
+      tile_core(kf, ok);
+    }
+
+    // ---- the newest token: virtual key k < BPB = branch k (larger k repeat valid rows and
+    //      are masked).  Fused mode: take it from k_new / v_new, rotate and round with the
+    //      arithmetic of hpd_kv_append, store, and use the rounded registers.
+    if (kg == NT % KG) {
+      const int32_t lbu = lb0 + krow % BPB;
+      const int32_t lb = min(lbu, nbr_here - 1);
+      const int32_t b = branch_id(lb);
+      const int64_t toff = tail_offset(b) + (int64_t)a.step * D;
+      const int64_t noff = ((int64_t)(row0_live + br0 + lb) * a.Hkv + hk) * D;
+      uint4 kf[8];
+      {
+        const uint16_t* kp = (a.fused ? k_new + noff : k_tail + toff) + g2 * 8;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) kf[kk] = *reinterpret_cast<const uint4*>(kp + kk * 16);
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int32_t k = j * 4 + r4;
+        const int32_t lbv = min(lb0 + k % BPB, nbr_here - 1);
+        const uint16_t* vp = a.fused ? v_new + ((int64_t)(row0_live + br0 + lbv) * a.Hkv + hk) * D
+                                     : v_tail + tail_offset(branch_id(lbv)) + (int64_t)a.step * D;
+        HPD_GLL(vp + ((c16 ^ (((k >> 3) & 1) << 2)) << 3), stage + j * 4 * 128);
+      }
+      if (a.fused) {
+        const int32_t pos = upos >= 0 ? upos : a.tb.branch_base_pos[b] + 1 + a.step;
+        const float2* cs_row = a.tb.rope + (int64_t)pos * (D / 2);
+        const bool owner = lbu < nbr_here && krow < BPB;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          float lo[8], hi[8], rl[8], rh[8];
+          unpack8(kf[kk], lo);
+          unpack8(kf[kk + 4], hi);
+          const float4* csp = reinterpret_cast<const float4*>(cs_row + kk * 16 + g2 * 8);
+#pragma unroll
+          for (int e2 = 0; e2 < 4; ++e2) {
+            const float4 cs = csp[e2];
+            hpd::rope_pair(lo[2 * e2], hi[2 * e2], cs.x, cs.y, rl[2 * e2], rh[2 * e2]);
+            hpd::rope_pair(lo[2 * e2 + 1], hi[2 * e2 + 1], cs.z, cs.w, rl[2 * e2 + 1], rh[2 * e2 + 1]);
+          }
+          kf[kk] = __builtin_bit_cast(uint4, pack8(rl));
+          kf[kk + 4] = __builtin_bit_cast(uint4, pack8(rh));
+          if (owner) {
+            *reinterpret_cast<uint4*>(k_tail + toff + g2 * 8 + kk * 16) = kf[kk];
+            *reinterpret_cast<uint4*>(k_tail + toff + g2 * 8 + (kk + 4) * 16) = kf[kk + 4];
+          }
+        }
+      }
+      uint32_t ok = 0;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int k = ((i >> 3) << 4) + g2 * 8 + (i & 7);
+        if (k < BPB && k == n / G) ok |= 1u << i;
+      }
+      if (a.fused) {
+        // the value rows of the newest token: out of the staging area into the pool
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int j = 0; j < (BPB + 3) / 4; ++j) {
+          const int32_t k = j * 4 + r4;
+          if (k < BPB && lb0 + k < nbr_here) {
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + k * 128 + (c16 << 3));
+            *reinterpret_cast<uint4*>(v_tail + tail_offset(branch_id(lb0 + k)) + (int64_t)a.step * D +
+                                      ((c16 ^ (((k >> 3) & 1) << 2)) << 3)) = v;
+          }
+        }
+      }
+      tile_core(kf, ok);
     }
   }
 
@@ -401,14 +461,28 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     softmax_pv(S, ok, vf);
   };
 
-  auto round_body = [&](int32_t r, const uint4* cur, uint4* nxt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();  // round r has landed; everybody is done with the other stage
-    if (r + 1 < NR) issue_round(r + 1, nxt);
+  // Round r: wait until its stage has landed (newer rounds may stay in flight: the DMA
+  // instructions of a wave complete in order and every wave issues LOADS_PER_ROUND per
+  // round), meet, refill the stage that was consumed last round, compute.
+  auto round_body = [&](int32_t r, const uint4* cur, uint4* refill, uint4* refill0) {
+    const int32_t newer = r == 0 ? min(1, NR - 1) : min(2, NR - 1 - r);  // rounds issued after r
+    if (newer >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
+    else if (newer == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_ROUND) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS reads of the previous round are done
+    __builtin_amdgcn_s_barrier();
+    if (r == 0) {
+      // the tail staging is finished in every wave: point the DMA at stages 2 and 3
+      if (NR > 2) issue_round(2, refill0);
+      if (NR > 3) issue_round(3, refill);
+    } else if (r + 3 < NR) {
+      issue_round(r + 3, refill);
+    }
     if (active) {
-      for (int32_t j = kg; j < STAGE_BLOCKS; j += KG) {
+#pragma unroll
+      for (int32_t j = 0; j < STAGE_BLOCKS; ++j) {
         const int32_t gb = r * STAGE_BLOCKS + j;
-        if (gb < NB) {
+        if (gb < NB && gb % KG == kg) {
           const int32_t valid = gb < NBh ? min(32, Hlen - gb * 32) : min(32, Llen - (gb - NBh) * 32);
           compute_block(cur + j * SLOT_U4, valid);
         }
@@ -416,59 +490,97 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     }
   };
 
-  // the first round's barrier also ends the use of the second stage as tail staging
-  for (int32_t r = 0; r < NR; r += 2) {
-    round_body(r, ringA, ringB);
-    if (r + 1 < NR) round_body(r + 1, ringB, ringA);
+  // stage of round r is ring[r % 4]; round r refills ring[(r + 3) % 4] (consumed in round r-1)
+  for (int32_t r = 0; r < NR; r += 4) {
+    round_body(r, ring0, ring3, ring2);
+    if (r + 1 < NR) round_body(r + 1, ring1, ring0, nullptr);
+    if (r + 2 < NR) round_body(r + 2, ring2, ring1, nullptr);
+    if (r + 3 < NR) round_body(r + 3, ring3, ring2, nullptr);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();  // both stages are dead from here on and get reused
+  __syncthreads();  // all stages are dead from here on and get reused
 
-  // ---- merge the key groups in one round: region r lives in stage (r & 1), slot r >> 1
-  float* const parkA = reinterpret_cast<float*>(ringA);
-  float* const parkB = reinterpret_cast<float*>(ringB);
+  // ---- merge the key groups: every wave of a row block reduces its own d-blocks.
+  //      Wave w parks what the others need in region w: stage (w & 3), half (w >> 2).
+  float* const park0 = reinterpret_cast<float*>(ring0);
+  float* const park1 = reinterpret_cast<float*>(ring1);
+  float* const park2 = reinterpret_cast<float*>(ring2);
+  float* const park3 = reinterpret_cast<float*>(ring3);
+  auto region = [&](int32_t w) -> float* {
+    float* base = (w & 2) ? ((w & 1) ? park3 : park2) : ((w & 1) ? park1 : park0);
+    return base + (w >> 2) * (50 * 64) + lane;
+  };
+  const int32_t DB = 4 / KG;  // d-blocks reduced by one wave: blocks kg*DB .. kg*DB + DB - 1
   if (KG > 1) {
-    auto region = [&](int32_t r) { return ((r & 1) ? parkB : parkA) + (r >> 1) * MERGE_FLOATS + lane; };
-    if (active && kg > 0) {
-      float* buf = region(rb * (KG - 1) + kg - 1);
+    if (active) {
+      float* buf = region(wave);
+      int32_t sidx = 0;
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk) {
+        if (blk / DB != kg) {  // not mine: somebody else reduces it
+#pragma unroll
+          for (int i = 0; i < 16; ++i) buf[(sidx * 16 + i) * 64] = acc[blk][i];
+          ++sidx;
+        }
+      }
+      buf[48 * 64] = m_used;
+      buf[49 * 64] = l_lane;
+    }
+    __syncthreads();
+    if (active) {
+      float m_o[3], l_o[3];
+      float m_new = m_used;
+      for (int32_t o = 0; o < KG - 1; ++o) {
+        const int32_t okg = o < kg ? o : o + 1;  // the other key groups of this row block
+        const float* buf = region(rb * KG + okg);
+        m_o[o] = buf[48 * 64];
+        l_o[o] = buf[49 * 64];
+        m_new = fmaxf(m_new, m_o[o]);
+      }
+      const float a_own = fast_exp2(m_used - m_new);
+      l_lane *= a_own;
 #pragma unroll
       for (int blk = 0; blk < 4; ++blk)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) buf[(blk * 16 + i) * 64] = acc[blk][i];
-      buf[64 * 64] = m_used;
-      buf[65 * 64] = l_lane;
-    }
-    __syncthreads();
-    if (active && kg == 0) {
+        for (int i = 0; i < 16; ++i) acc[blk][i] *= a_own;
       for (int32_t o = 0; o < KG - 1; ++o) {
-        const float* buf = region(rb * (KG - 1) + o);
-        const float m2 = buf[64 * 64], l2 = buf[65 * 64];
-        const float m_new = fmaxf(m_used, m2);
-        const float a1 = fast_exp2(m_used - m_new), a2 = fast_exp2(m2 - m_new);
-        l_lane = l_lane * a1 + l2 * a2;
-        m_used = m_new;
+        const int32_t okg = o < kg ? o : o + 1;
+        const float* buf = region(rb * KG + okg);
+        const float a_o = fast_exp2(m_o[o] - m_new);
+        l_lane += l_o[o] * a_o;
+        // my blocks sit in the other wave's region at the index that skips ITS own blocks
 #pragma unroll
-        for (int blk = 0; blk < 4; ++blk)
+        for (int blk = 0; blk < 4; ++blk) {
+          if (blk / DB == kg) {
+            const int32_t sidx = blk - (blk / DB > okg ? DB : 0);
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc[blk][i] = acc[blk][i] * a1 + buf[(blk * 16 + i) * 64] * a2;
+            for (int i = 0; i < 16; ++i) acc[blk][i] += buf[(sidx * 16 + i) * 64] * a_o;
+          }
+        }
       }
+      m_used = m_new;
     }
     __syncthreads();
   }
 
-  // ---- park the finished rows row-major (rows 0..127 in stage A, 128..255 in stage B) ...
-  if (active && kg == 0) {
+  // ---- park the finished rows row-major (64 rows per stage): each wave its own d-blocks ...
+  if (active) {
     const int32_t lr = rb * 32 + n;
-    float* park = lr < 128 ? parkA : parkB;
-    const int32_t lrr = lr & 127;
+    float* park = (lr & 128) ? ((lr & 64) ? park3 : park2) : ((lr & 64) ? park1 : park0);
+    const int32_t lrr = lr & 63;
 #pragma unroll
-    for (int blk = 0; blk < 4; ++blk)
+    for (int blk = 0; blk < 4; ++blk) {
+      if (blk / DB == kg) {
 #pragma unroll
-      for (int cc = 0; cc < 4; ++cc)
-        *reinterpret_cast<float4*>(park + park_off(lrr, blk * 8 + cc * 2 + g2)) =
-            make_float4(acc[blk][cc * 4 + 0], acc[blk][cc * 4 + 1], acc[blk][cc * 4 + 2], acc[blk][cc * 4 + 3]);
-    const float l_row = l_lane + __shfl_xor(l_lane, 32);
-    if (g2 == 0) l_buf[lr] = l_row;
+        for (int cc = 0; cc < 4; ++cc)
+          *reinterpret_cast<float4*>(park + park_off(lrr, blk * 8 + cc * 2 + g2)) =
+              make_float4(acc[blk][cc * 4 + 0], acc[blk][cc * 4 + 1], acc[blk][cc * 4 + 2], acc[blk][cc * 4 + 3]);
+      }
+    }
+    if (kg == 0) {
+      const float l_row = l_lane + __shfl_xor(l_lane, 32);
+      if (g2 == 0) l_buf[lr] = l_row;
+    }
   }
   __syncthreads();
 
@@ -477,8 +589,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const int32_t ks = lane >> 4, c = lane & 15;
     for (int32_t lr = wave * 4 + ks; lr < rows_here; lr += WAVES * 4) {
       const float inv = 1.0f / l_buf[lr];
-      const float* park = lr < 128 ? parkA : parkB;
-      const int32_t lrr = lr & 127;
+      const float* park = (lr & 128) ? ((lr & 64) ? park3 : park2) : ((lr & 64) ? park1 : park0);
+      const int32_t lrr = lr & 63;
       const float4 p0 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c));
       const float4 p1 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c + 1));
       float o[8] = {p0.x * inv, p0.y * inv, p0.z * inv, p0.w * inv, p1.x * inv, p1.y * inv, p1.z * inv, p1.w * inv};
