@@ -121,7 +121,6 @@ def main():
     ap.add_argument("--replicas", type=int, default=0, help="KV replicas (0 = enough for 2 GB)")
     ap.add_argument("--out", default="f32", choices=["f32", "same"], help="output element type")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--two-call", action="store_true", help="hpd_kv_append + hpd_decode_attention")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="after the timed regions, run this many 1 GiB device copies (reference "
@@ -146,8 +145,6 @@ def main():
     eb = 4 if wl.dtype == "f32" else 2
     out_f32 = args.out == "f32" or wl.dtype == "f32"
     layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME)
-    if args.waves:
-        B.hpd_set_tuning(layout, B.HPD_TUNE_WAVES, args.waves)
     n_live = layout.n_live()
     live_flat = B.hpd_layout_query(layout, B.HPD_Q_LIVE_BRANCH)
     live_lists, off = [], 0

@@ -39,7 +39,9 @@
  *                                    channel with one 16-byte load.
  *   k_tail   : [B][Hkv][T][D]        slot b*T + t holds the rotated key of branch b's
  *   v_tail   : [B][Hkv][T][D]        t-th value token (Algorithm 1's values[j,i,t]).
- *   Padding slots of the prefix pools may hold anything (including NaN patterns).
+ *   hpd_prefix_fill zeroes the V padding slots between a segment's end and the next
+ *   multiple of HPD_KEY_BLOCK; K padding and unwritten tail slots may hold anything
+ *   (including NaN patterns).  HPD_Q_POOL_BYTES reports the four sizes.
  */
 #ifndef HPD_H
 #define HPD_H
@@ -210,18 +212,9 @@ int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, u
                     int32_t* s_out, void* stream);
 
 /* Selects the attention kernel: 0 = automatic, 1 = generic wave-reduction kernel for
- * everything, 2 = register-fed MFMA kernel, 3 = LDS-streaming MFMA kernel (2 and 3 return
- * HPD_E_UNSUPPORTED if the shape does not allow them). */
+ * everything, 2 = LDS-streaming MFMA kernel (HPD_E_UNSUPPORTED if the shape does not
+ * allow it: it needs bf16, head_dim 128 and a group size of 1, 2, 4 or 8). */
 int hpd_set_kernel_mode(hpd_layout* layout, int32_t mode);
-
-/* Tuning / diagnostic knobs of the MFMA kernel; defaults are chosen by the library. */
-enum hpd_tuning {
-  HPD_TUNE_WAVES = 0,  /* waves per workgroup: 4 or 8 (0 = default) */
-  HPD_TUNE_QSPLIT = 1, /* 1: feed the rotated query as bf16 hi + lo parts (two MFMA passes) */
-  HPD_TUNE_PSPLIT = 2  /* 0: probabilities as one bf16; 1: hi + lo parts where a weight is
-                          large enough to matter; 2: hi + lo always */
-};
-int hpd_set_tuning(hpd_layout* layout, int32_t key, int32_t value);
 
 const char* hpd_status_string(int status);
 

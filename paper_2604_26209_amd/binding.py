@@ -42,7 +42,6 @@ HPD_POS_CONTIG, HPD_POS_PAPER_GAP = 0, 1
 HPD_MASK_BLOCK = 0
 HPD_FLAG_HOST_ONLY = 1
 HPD_OUT_SAME, HPD_OUT_F32 = 0, 1
-HPD_TUNE_WAVES, HPD_TUNE_QSPLIT, HPD_TUNE_PSPLIT = 0, 1, 2
 HPD_KEY_BLOCK = 32
 (HPD_Q_COUNTS, HPD_Q_POOL_BYTES, HPD_Q_N_LIVE, HPD_Q_LIVE_BRANCH, HPD_Q_BRANCH_BASE_POS,
  HPD_Q_BRANCH_DOC, HPD_Q_SEG_OFF, HPD_Q_SEG_LEN, HPD_Q_SEG_POS0, HPD_Q_SEG_RAW_OFF,
@@ -52,7 +51,7 @@ HPD_KEY_BLOCK = 32
 
 EXPORTS = ["hpd_build_layout", "hpd_layout_free", "hpd_layout_query", "hpd_prefix_fill",
            "hpd_rope_positions", "hpd_kv_append", "hpd_decode_attention", "hpd_decode_step",
-           "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_set_tuning", "hpd_status_string"]
+           "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_status_string"]
 
 
 class hpd_config(ctypes.Structure):
@@ -77,7 +76,6 @@ _lib.hpd_decode_attention.argtypes = [_vp, _i32] + [_vp] * 7
 _lib.hpd_decode_step.argtypes = [_vp, _i32] + [_vp] * 9
 _lib.hpd_expand_mask.argtypes = [_vp, _i32, _i32, _vp, _i32p, _vp]
 _lib.hpd_set_kernel_mode.argtypes = [_vp, _i32]
-_lib.hpd_set_tuning.argtypes = [_vp, _i32, _i32]
 _lib.hpd_status_string.argtypes = [ctypes.c_int]
 _lib.hpd_status_string.restype = ctypes.c_char_p
 for _name in EXPORTS:
@@ -234,9 +232,6 @@ def hpd_expand_mask(layout, prompt, step_hi, mask_out=None, stream=None) -> int:
 def hpd_set_kernel_mode(layout, mode: int):
     _check(_lib.hpd_set_kernel_mode(layout.handle, int(mode)), "hpd_set_kernel_mode")
 
-
-def hpd_set_tuning(layout, key: int, value: int):
-    _check(_lib.hpd_set_tuning(layout.handle, int(key), int(value)), "hpd_set_tuning")
 
 
 # ---------------------------------------------------------------------------

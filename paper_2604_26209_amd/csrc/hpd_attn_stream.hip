@@ -8,26 +8,41 @@
 // pulls header ++ document K/V from HBM exactly once, through LDS, and every query row
 // consumes it from there.
 //
-//  * Loading.  Key blocks of 32 keys travel HBM -> LDS with direct-to-LDS 16-byte loads
-//    (global_load_lds_dwordx4): no VGPRs are held by data in flight.  A lane fetches exactly
-//    the 16 bytes that the same lane will later feed to an MFMA, so LDS is a pure delay line:
-//    fragment f of a block sits at lds[f][lane], reads are lane-linear and conflict-free.
-//    Four 32 KB stages of two blocks form a ring: while one stage is consumed up to three
-//    are in flight, and a round only waits (s_waitcnt vmcnt(N)) for its own stage.  The
-//    stages are distinct __shared__ arrays on purpose: the compiler then knows that reading
-//    one does not alias the DMA into the others and does not drain the DMA queue before
-//    every LDS read.  Measured with two 64 KB stages drained every round: 3.4 TB/s in the
-//    steady state, because HBM idled between the bursts.
+//  * One stream of key blocks.  Everything a unit attends to is cut into blocks of 32 keys
+//    = 8 K fragments + 8 V fragments of 64 lanes x 16 bytes (16 KB): the header blocks, the
+//    document blocks, and then "tail tiles" that hold 8 positions of each of 4 branches
+//    (Section 4.3.3: every value still grows token by token; the tails are private to a
+//    branch, so a row keeps only the keys of its own branch in a tile and the rest get
+//    probability 0).  A tail tile is gathered by the same 16-byte loads as a prefix block
+//    from the row-major tail pools.  Its K half is in fragment order like a prefix block's;
+//    its V half arrives as 32 rows of 256 bytes (the pool order: an append then is one
+//    coalesced row, where an 8-position interleave would cost a 2-byte scatter per channel)
+//    and is transposed by the consumer's LDS reads (2-byte reads, 16-byte chunks
+//    XOR-swizzled at load time so that the two half-waves hit different banks).
+//  * Loading.  Blocks travel HBM -> LDS with direct-to-LDS 16-byte loads
+//    (global_load_lds_dwordx4): no VGPRs are held by data in flight.  The V half of a prefix
+//    block is fetched in fragment order (a lane fetches exactly the 16 bytes that the same
+//    lane of a consumer feeds to an MFMA; the interleaved pool makes that 512-byte runs); the
+//    K half is fetched as 32 whole rows, whose 16-byte chunks are XOR-permuted at fetch time so
+//    that the per-lane fragment reads are conflict-free.  Loads that gather 32 bytes per row
+//    instead were measured to stall the issuing wave: every distinct cache line of an
+//    instruction is a separate request.  Four 32 KB stages of two blocks form a ring: while one stage is consumed
+//    up to three are in flight, and a round only waits (s_waitcnt vmcnt(N)) for its own
+//    stage.  The stages are distinct __shared__ arrays on purpose: the compiler then knows
+//    that reading one does not alias the DMA into the others and does not drain the DMA
+//    queue before every LDS read.  Only waves 0-3 load (8 instructions per round each):
+//    vector memory operations of a wave complete in order, so a wave with a deep DMA queue
+//    cannot get a latency-critical load through; waves 4-7 stay free for those.
 //  * Contraction (transposed):
-//        S^T[key,row] = K.Q^T   (A = K fragment, B = rotated Q in registers as bf16 hi + lo
-//                                parts: two MFMA passes, Q rounding drops out of the error)
+//        S^T[key,row] = K.Q^T   (A = K fragment, B = rotated, pre-scaled Q in registers as
+//                                bf16 hi + lo parts: two MFMA passes, Q rounding drops out)
 //        O^T[d,row]  += V^T.P^T (A = V fragment, B = P)
 //    with v_mfma_f32_32x32x16_bf16.  One query row lives in lanes n and n+32; softmax
 //    statistics never leave them, and the fp32 scores of the first product become, after
 //    exponentiation and bf16 packing, the B operand of the second without any cross-lane
 //    movement.  The key order inside a block is permuted on the K side (an address, free) so
 //    that the 8 probabilities a lane holds for one MFMA belong to 8 consecutive keys, which
-//    is what the 8-key interleaved V pool delivers in 16 bytes.
+//    is what the 8-key interleaved V pools deliver in 16 bytes.
 //  * Softmax.  Online max/sum in registers.  The running maximum is exact (the accumulators
 //    are rescaled whenever some row of the wave sees a larger score; the rescale is skipped,
 //    wave-uniformly, when no row does).  Exactness matters for accuracy: the dominant key of a
@@ -35,26 +50,16 @@
 //    maximum the largest weight would carry a 2^-9 rounding error into P.V (measured: 3x
 //    larger max-abs error).
 //  * Waves.  8 waves = (row block of 32 rows) x (key group), KG = 4 / 2 / 1 for <= 2 / <= 4 /
-//    <= 8 row blocks; key group kg takes the key blocks gb with gb % KG == kg and every
-//    KG-th tail tile.  At the end the groups are merged through LDS in one exchange in which
-//    every wave of a row block reduces its own 32-channel slice (identical lane layout on
-//    both sides, so the exchange is lane-private).
-//  * Tails (Section 4.3.3: every value still grows token by token) are private to a branch.
-//    A first version used wavefront-reduction dot products (16 lanes per key row); measured
-//    on MI355X it needed ~1000 VALU instructions per branch and 5 us per branch per wave,
-//    more than the whole prefix.  The tails now go through the same MFMA code as masked
-//    "virtual key blocks": a tile holds G tail positions of each of the 32/G branches of the
-//    row block, the score tile is block-diagonal (a row keeps only its own branch's keys,
-//    the rest get -inf), K fragments are loaded straight from the row-major tail pool, and
-//    the V fragments - which need 8 keys of one channel - are transposed through a
-//    wave-private 8 KB LDS buffer (coalesced 16-byte writes, 2-byte reads, XOR-swizzled so
-//    that the two half-waves hit different banks).  The MFMA work wasted on the masked
-//    entries is irrelevant: the matrix pipe is idle while the first stage is in flight.
-//    Tail tiles are processed first and simply initialise the online-softmax state.
-//  * Fused mode (hpd_decode_step): the lanes whose tail-tile entry is the newest token take
-//    it from k_new / v_new instead of the pool, rotate and round it with the same arithmetic
-//    as hpd_kv_append, store it, and use the rounded registers - bit-identical to the
-//    two-call sequence, with no read-back and no extra synchronisation.
+//    <= 8 row blocks; key group kg takes the prefix blocks gb with gb % KG == kg, and the tail
+//    tiles of a row block go round its key groups.  At the end the groups are merged through
+//    LDS in one exchange in which every wave of a row block reduces its own 32-channel slices
+//    (identical lane layout on both sides, so the exchange is lane-private), normalises them
+//    and writes them out.
+//  * Fused mode (hpd_decode_step): waves 4-7 rotate, round and store the new keys and values
+//    of the unit's branches (the arithmetic of hpd_kv_append) while waves 0-3 start the
+//    stream; the first barrier of the ring publishes them, and the tail tiles - which are
+//    last in the stream - read them back like any other token.  Both modes therefore add up
+//    in the same order and give identical bits.
 #include <cmath>
 
 #include "hpd_internal.h"
@@ -69,12 +74,11 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int D = 128;
 constexpr int WAVES = 8;
+constexpr int LOADERS = 4;             // waves 0..3 issue the DMA
 constexpr int SLOT_U4 = 16 * 64;       // one 32-key block: 8 K + 8 V fragments of 64 x 16 bytes
 constexpr int STAGE_BLOCKS = 2;
 constexpr int STAGE_U4 = STAGE_BLOCKS * SLOT_U4;  // 32 KB
-constexpr int LOADS_PER_ROUND = STAGE_BLOCKS * 16 / WAVES;  // DMA instructions per wave per round
-constexpr int MERGE_FLOATS = 66 * 64;  // 64 accumulators + max + sum per lane
-constexpr int MAX_ROWS = 256;          // rows per workgroup (8 row blocks)
+constexpr int LOADS_PER_ROUND = STAGE_BLOCKS * 16 / LOADERS;  // DMA instructions per loader wave per round
 constexpr float NEG_BIG = -1.0e30f;
 
 struct StreamArgs {
@@ -106,8 +110,20 @@ __device__ __forceinline__ void unpack8(uint4 a, float out[8]) {
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// XOR-swizzled row-major park buffer: element (row, 4-float chunk c4) of a 128-float row.
-__device__ __forceinline__ int park_off(int row, int c4) { return row * 128 + ((c4 ^ (row & 31)) << 2); }
+// 8 channel pairs (c .. c+7, 64+c .. 64+c+7) of one row, rotated at the (cos, sin) row cs_row
+__device__ __forceinline__ void rotate16(uint4 raw_lo, uint4 raw_hi, const float2* cs_row, int c,
+                                         float rl[8], float rh[8]) {
+  float lo[8], hi[8];
+  unpack8(raw_lo, lo);
+  unpack8(raw_hi, hi);
+  const float4* csp = reinterpret_cast<const float4*>(cs_row + c);
+#pragma unroll
+  for (int e2 = 0; e2 < 4; ++e2) {
+    const float4 cs = csp[e2];
+    hpd::rope_pair(lo[2 * e2], hi[2 * e2], cs.x, cs.y, rl[2 * e2], rh[2 * e2]);
+    hpd::rope_pair(lo[2 * e2 + 1], hi[2 * e2 + 1], cs.z, cs.w, rl[2 * e2 + 1], rh[2 * e2 + 1]);
+  }
+}
 
 template <int G>
 __global__ void __launch_bounds__(WAVES * 64)
@@ -115,13 +131,14 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
                    const uint16_t* __restrict__ v_prefix, uint16_t* __restrict__ k_tail,
                    uint16_t* __restrict__ v_tail, const uint16_t* __restrict__ k_new,
                    const uint16_t* __restrict__ v_new, void* __restrict__ out) {
-  constexpr int BPB = 32 / G;  // branches per row block; a tail tile holds G positions of each
+  constexpr int BPB = 32 / G;              // branches per row block
+  constexpr int QPR = G >= 8 ? 1 : 8 / G;  // branch quads (tail tiles per 8 positions) per row block
 
   __shared__ uint4 ring0[STAGE_U4];
   __shared__ uint4 ring1[STAGE_U4];
   __shared__ uint4 ring2[STAGE_U4];
   __shared__ uint4 ring3[STAGE_U4];
-  __shared__ float l_buf[MAX_ROWS];
+  __shared__ float4 rope_q[32];  // (cos, sin) row of the unit's shared position
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
@@ -144,44 +161,11 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t nblk_here = min(per_group, nblk - first_blk);
   if (nblk_here <= 0) return;  // uniform over the workgroup
   const int32_t KG = nblk_here <= 2 ? 4 : (nblk_here <= 4 ? 2 : 1);
-  const int32_t kg = wave % KG;
-  const int32_t rb = wave / KG;
+  // waves of one key group sit on different SIMDs (wave w runs on SIMD w % 4)
+  const int32_t rb_shift = KG == 4 ? 1 : (KG == 2 ? 2 : 3);
+  const int32_t rb = wave & ((1 << rb_shift) - 1);
+  const int32_t kg = wave >> rb_shift;
   const bool active = rb < nblk_here;
-
-  const int32_t NBh = (Hlen + 31) >> 5, NBd = (Llen + 31) >> 5;
-  const int32_t NB = NBh + NBd;
-  const int32_t NR = (NB + STAGE_BLOCKS - 1) / STAGE_BLOCKS;
-
-  // ---- loader role: wave w fills a quarter of block slot w/4 of a stage (K fragments for
-  //      quarters 0 and 1, V fragments for 2 and 3): LOADS_PER_ROUND instructions per round,
-  //      always the same number, so that vmcnt(N) means the same thing in every wave
-  const int32_t ld_slot = wave >> 2;
-  const int32_t ld_part = wave & 3;
-  // MFMA row m of a score tile carries this key of the block (see the file header)
-  const int32_t krow = ((n >> 4) << 4) | (((n >> 2) & 1) << 3) | (((n >> 3) & 1) << 2) | (n & 3);
-  const uint16_t* kbase = k_prefix + (int64_t)hk * a.NP * D;
-  const uint16_t* vbase = v_prefix + (int64_t)hk * (a.NP / 8) * D * 8;
-
-  // one 32-bit per-lane element offset; everything else in the load addresses is wave-uniform
-  const int32_t ld_off = ld_part < 2 ? krow * D + g2 * 8 + ld_part * 64
-                                     : (g2 * D + (ld_part - 2) * 64 + n) * 8;
-  auto issue_round = [&](int32_t r, uint4* stage) {
-    // a slot past the last block re-loads the last block (never read): the count stays fixed
-    const int32_t gb = min(r * STAGE_BLOCKS + ld_slot, NB - 1);
-    const int32_t slot0 = gb < NBh ? hoff + gb * 32 : doff + (gb - NBh) * 32;
-    uint4* dst = stage + ld_slot * SLOT_U4 + ld_part * 4 * 64;
-    if (ld_part < 2) {
-      const uint16_t* src = kbase + (int64_t)slot0 * D;
-#pragma unroll
-      for (int f = 0; f < 4; ++f) HPD_GLL(src + (ld_off + f * 16), dst + f * 64);
-    } else {
-      // V fragment f = d-block * 2 + key half; this wave loads d-blocks 2*(part-2), +1
-      const uint16_t* src = vbase + (int64_t)(slot0 / 8) * D * 8;
-#pragma unroll
-      for (int f = 0; f < 4; ++f)
-        HPD_GLL(src + (ld_off + ((f & 1) * 2 * D + (f >> 1) * 32) * 8), dst + f * 64);
-    }
-  };
 
   // ---- branches of this row group
   const int32_t br0 = first_blk * BPB;
@@ -190,52 +174,189 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   auto branch_id = [&](int32_t lb) -> int32_t {
     return ub0 >= 0 ? ub0 + br0 + lb : a.tb.live_branch[a.live_base + row0_live + br0 + lb];
   };
-  auto tail_offset = [&](int32_t b) -> int64_t { return (((int64_t)b * a.Hkv + hk) * a.Tcap) * D; };
 
-  // ---- first request, ahead of the DMA in the memory queue: this lane's query row
-  const int32_t r_row = (first_blk + rb) * 32 + n;
-  const bool row_valid = active && r_row < R;
-  const int32_t q_bi = min(r_row / G, nb - 1);
-  const int64_t q_off = ((int64_t)(row0_live + q_bi) * a.Hq + hk * G + r_row % G) * D;
-  int32_t q_pos = upos;
-  if (upos < 0) q_pos = a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
-  uint4 qraw[8];
-#pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    qraw[kk] = make_uint4(0, 0, 0, 0);
-    if (row_valid) qraw[kk] = *reinterpret_cast<const uint4*>(q + q_off + kk * 16 + g2 * 8);
-  }
+  // ---- the stream: NB prefix blocks, then NQ * NC tail tiles (quad-major inside a chunk of 8
+  //      positions), two blocks per round
+  const int32_t NBh = (Hlen + 31) >> 5, NBd = (Llen + 31) >> 5;
+  const int32_t NB = NBh + NBd;
+  const int32_t NQ = (nbr_here + 3) >> 2;  // quads of 4 branches
+  const int32_t NC = (a.step >> 3) + 1;    // chunks of 8 positions that hold positions 0 .. step
+  const int32_t NBT = NB + NQ * NC;
+  const int32_t NR = (NBT + STAGE_BLOCKS - 1) / STAGE_BLOCKS;
 
-  // ---- tail tiles
-  // Virtual key k of pool tile ti = (position ti*G + k / BPB, branch k % BPB of this row
-  // block), positions 0 .. step-1; the newest token (position step) gets a tile of its own
-  // with one key per branch, in both modes, so that the fused and the two-call sequence add
-  // up in the same order.  A row may only see the keys of its own branch.
-  const int32_t NT = (a.step + G - 1) / G;  // pool tiles: ceil(step / G)
-  const int32_t lb0 = rb * BPB;
+  // ---- rows
+  const int32_t lr = rb * 32 + n;  // row within the row group
+  const int32_t r_row = first_blk * 32 + lr;
+  const bool row_valid = active && lr < rows_here;
   const int32_t r4 = lane >> 4, c16 = lane & 15;
 
-  // ---- start the DMA ring: rounds 0 and 1 now; stages 2 and 3 serve as tail staging first
-  issue_round(0, ring0);
-  if (NR > 1) issue_round(1, ring1);
+  // ---- loader role (waves 0..3): wave w fills quarter w of both block slots of a stage (the K
+  //      half for quarters 0 and 1, the V half for 2 and 3): LOADS_PER_ROUND instructions per
+  //      round, always the same number, so that vmcnt(N) means the same thing in every round.
+  //      Every instruction reads whole 256-byte rows or 512-byte runs: a load whose lanes touch
+  //      64 different cache lines costs the memory pipeline 8 times as much as one whose lanes
+  //      touch 8.
+  const bool loader = wave < LOADERS;
+  const int32_t ld_part = wave & 3;
+  const bool ld_is_k = ld_part < 2;
+  const int32_t ld_half = ld_part & 1;
+  // MFMA row m of a score tile carries this key of the block (see the file header)
+  const int32_t krow = ((n >> 4) << 4) | (((n >> 2) & 1) << 3) | (((n >> 3) & 1) << 2) | (n & 3);
+  const uint16_t* kbase = k_prefix + (int64_t)hk * a.NP * D;
+  const uint16_t* vbase = v_prefix + (int64_t)hk * (a.NP / 8) * D * 8;
+  // K half of a slot (prefix and tail): 32 rows of 256 bytes, row = key, the 16-byte chunk c of
+  // row k at position c ^ (k & 15) (conflict-free fragment reads).  Load f of quarter h brings
+  // rows k = h*16 + f*4 + lane/16: lane%16 is the position, so the chunk to fetch is
+  // (lane%16) ^ (f*4 + lane/16).
+  // V half of a prefix block: fragment order, straight out of the 8-key interleaved pool:
+  // key halves 0 / 1 (2*D*8 elements apart) of d-blocks 2*h, 2*h+1 (32 channels * 8 apart).
+  // V half of a tail tile: 32 rows of 256 bytes like K, chunk position c ^ 4*(bit 3 of k).
+  const int32_t ld_e0 = ld_is_k ? ((c16 ^ r4) << 3) : (c16 << 3);  // element offset of load 0 within a row
+  const int32_t ld_vfrag = (g2 * D + ld_half * 64 + n) * 8;      // V prefix: element offset of load 0
+  auto row_elem = [&](int f) -> int32_t {  // row-major loads: element offset within the row of load f
+    return ld_is_k ? (ld_e0 ^ (f << 5)) : (ld_e0 ^ ((f >> 1) << 5));
+  };
+  auto issue_block = [&](int32_t gb_raw, uint4* dst_slot) {
+    // a slot past the last block re-loads the last block (never read): the count stays fixed
+    const int32_t gb = min(gb_raw, NBT - 1);
+    uint4* dst = dst_slot + ld_part * 4 * 64;
+    const uint16_t *p0, *p1, *p2, *p3;
+    if (gb < NB) {
+      const int32_t slot0 = gb < NBh ? hoff + gb * 32 : doff + (gb - NBh) * 32;
+      if (ld_is_k) {
+        const uint16_t* rowp = kbase + (int64_t)(slot0 + ld_half * 16 + r4) * D;
+        p0 = rowp + row_elem(0);
+        p1 = rowp + 4 * D + row_elem(1);
+        p2 = rowp + 8 * D + row_elem(2);
+        p3 = rowp + 12 * D + row_elem(3);
+      } else {
+        p0 = vbase + (int64_t)(slot0 / 8) * D * 8 + ld_vfrag;
+        p1 = p0 + 2 * D * 8;
+        p2 = p0 + 32 * 8;
+        p3 = p1 + 32 * 8;
+      }
+    } else {
+      // tail tile: key k = position c*8 + k%8 of branch qd*4 + k/8; row k = h*16 + f*4 + lane/16
+      // is position (f&1)*4 + lane/16 of branch 2*h + f/2.  Branches and positions past the
+      // end repeat the last valid one (masked by the consumer).
+      const int32_t tt = gb - NB;
+      const int32_t c = tt / NQ, qd = tt - c * NQ;
+      const int32_t bA = branch_id(min(qd * 4 + ld_half * 2, nbr_here - 1));
+      const int32_t bB = branch_id(min(qd * 4 + ld_half * 2 + 1, nbr_here - 1));
+      const int32_t posA = min(c * 8 + r4, a.step), posB = min(c * 8 + 4 + r4, a.step);
+      const uint16_t* pool = ld_is_k ? k_tail : v_tail;
+      const uint16_t* rowA = pool + ((int64_t)bA * a.Hkv + hk) * a.Tcap * D;
+      const uint16_t* rowB = pool + ((int64_t)bB * a.Hkv + hk) * a.Tcap * D;
+      p0 = rowA + (int64_t)posA * D + row_elem(0);
+      p1 = rowA + (int64_t)posB * D + row_elem(1);
+      p2 = rowB + (int64_t)posA * D + row_elem(2);
+      p3 = rowB + (int64_t)posB * D + row_elem(3);
+    }
+    HPD_GLL(p0, dst);
+    HPD_GLL(p1, dst + 64);
+    HPD_GLL(p2, dst + 128);
+    HPD_GLL(p3, dst + 192);
+  };
+  auto issue_round = [&](int32_t r, uint4* stage) {
+    if (loader) {
+#pragma nounroll
+      for (int32_t j = 0; j < STAGE_BLOCKS; ++j) issue_block(r * STAGE_BLOCKS + j, stage + j * SLOT_U4);
+    }
+  };
 
-  // ---- rotate the query: bf16 hi + lo MFMA B operands
+  // ---- fused mode: waves 4..7 append the newest token of the unit's branches (the
+  //      arithmetic of hpd_kv_append), 8 lanes per branch
+  auto append_newest = [&]() {
+    const int32_t t = tid - LOADERS * 64;
+    const int32_t c = (t & 7) * 8;  // channels c .. c+7 and 64+c .. 64+c+7
+    for (int32_t lb = t >> 3; lb < nbr_here; lb += (WAVES - LOADERS) * 8) {
+      const int32_t b = branch_id(lb);
+      const int32_t pos = upos >= 0 ? upos : a.tb.branch_base_pos[b] + 1 + a.step;
+      const int64_t noff = ((int64_t)(row0_live + br0 + lb) * a.Hkv + hk) * D;
+      const uint4 klo = *reinterpret_cast<const uint4*>(k_new + noff + c);
+      const uint4 khi = *reinterpret_cast<const uint4*>(k_new + noff + 64 + c);
+      const uint4 vlo = *reinterpret_cast<const uint4*>(v_new + noff + c);
+      const uint4 vhi = *reinterpret_cast<const uint4*>(v_new + noff + 64 + c);
+      float rl[8], rh[8];
+      rotate16(klo, khi, a.tb.rope + (int64_t)pos * (D / 2), c, rl, rh);
+      uint16_t* kd = k_tail + (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
+      *reinterpret_cast<uint4*>(kd + c) = __builtin_bit_cast(uint4, pack8(rl));
+      *reinterpret_cast<uint4*>(kd + 64 + c) = __builtin_bit_cast(uint4, pack8(rh));
+      uint16_t* vd = v_tail + (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
+      *reinterpret_cast<uint4*>(vd + c) = vlo;
+      *reinterpret_cast<uint4*>(vd + 64 + c) = vhi;
+    }
+  };
+  // Round x >= 2 is requested right after the barrier of round max(x - 3, 0), and the first
+  // tail tile sits in round NB / 2: the appending waves make sure their stores are complete
+  // before they enter that barrier (r_pub); until then the append runs beside the stream.
+  // Rounds 0 and 1 are requested before any barrier: if they would already hold tail tiles
+  // (a prefix of fewer than 4 blocks), the append is completed before anything is loaded.
+  const bool append_first = a.fused && NB < 2 * STAGE_BLOCKS;
+  const int32_t r_pub = (a.fused && !append_first && !loader) ? max(NB / STAGE_BLOCKS - 3, 0) : -1;
+  if (append_first) {
+    if (!loader) append_newest();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+  }
+
+  // ---- waves 0..3 start the DMA ring at once.  Waves 4..7 - whose memory queues stay short,
+  //      so that their loads come back with one latency - fetch the raw query rows of the row
+  //      group for everybody, 4 whole rows per instruction, and park them in stage 3 (rows
+  //      0..127) and stage 2 (rows 128..255), chunk c of row r at position c ^ (r & 15); one of
+  //      them fetches the (cos, sin) row of the shared position; then they append.
+  if (loader) {
+    issue_round(0, ring0);
+    if (NR > 1) issue_round(1, ring1);
+  } else {
+    const int32_t w4 = wave - LOADERS;
+    for (int32_t i0 = w4; i0 * 4 < rows_here; i0 += 4 * (WAVES - LOADERS)) {
+      uint4 v[4];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        v[b] = make_uint4(0, 0, 0, 0);
+        const int32_t i = i0 + b * (WAVES - LOADERS);
+        const int32_t urow = first_blk * 32 + min(i * 4 + r4, rows_here - 1);  // row within the unit
+        const int64_t off = ((int64_t)(row0_live + urow / G) * a.Hq + hk * G + urow % G) * D;
+        if (i * 4 < rows_here) v[b] = *reinterpret_cast<const uint4*>(q + off + (c16 << 3));
+      }
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const int32_t i = i0 + b * (WAVES - LOADERS);
+        const int32_t row = i * 4 + r4;
+        if (i * 4 < rows_here) (row < 128 ? ring3 : ring2)[(row & 127) * 16 + (c16 ^ (row & 15))] = v[b];
+      }
+    }
+    if (upos >= 0 && w4 == 0 && lane < 32)
+      rope_q[lane] = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)upos * (D / 2))[lane];
+    if (a.fused && !append_first) append_newest();
+  }
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
+  __builtin_amdgcn_s_barrier();        // a bare barrier: __syncthreads() would drain the DMA queue
+
+  // ---- rotate the query: bf16 hi + lo MFMA B operands.  The softmax scale and the change to
+  //      base 2 ride on the query: scores come out of the MFMA ready for exp2.
   bf16x8 Qh[8], Ql[8];
-  {
-    const float2* cs_row = a.tb.rope + (int64_t)q_pos * (D / 2);
+  auto rotate_query = [&](const uint4* stage, auto cos_sin) {
+    const uint4* qrow = stage + (lr & 127) * 16;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      const int c0 = kk * 16 + g2 * 8;
+      uint4 rlo = make_uint4(0, 0, 0, 0), rhi = make_uint4(0, 0, 0, 0);
+      if (row_valid) {
+        rlo = qrow[(kk * 2 + g2) ^ (lr & 15)];
+        rhi = qrow[((kk + 4) * 2 + g2) ^ (lr & 15)];
+      }
       float lo[8], hi[8], rl[8], rh[8];
-      unpack8(qraw[kk], lo);
-      unpack8(qraw[kk + 4], hi);
-      const float4* csp = reinterpret_cast<const float4*>(cs_row + c0);
+      unpack8(rlo, lo);
+      unpack8(rhi, hi);
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {
-        const float4 cs = csp[e2];
+        const float4 cs = cos_sin(kk * 8 + g2 * 4 + e2);  // pairs kk*16 + g2*8 + 2*e2, +1
         hpd::rope_pair(lo[2 * e2], hi[2 * e2], cs.x, cs.y, rl[2 * e2], rh[2 * e2]);
         hpd::rope_pair(lo[2 * e2 + 1], hi[2 * e2 + 1], cs.z, cs.w, rl[2 * e2 + 1], rh[2 * e2 + 1]);
       }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { rl[e] *= a.scale_log2; rh[e] *= a.scale_log2; }
       Qh[kk] = pack8(rl);
       Qh[kk + 4] = pack8(rh);
       float hl[8], hh[8];
@@ -246,6 +367,20 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       Ql[kk] = pack8(rl);
       Ql[kk + 4] = pack8(rh);
     }
+  };
+  // (the stage is chosen by a wave-uniform branch, not by a pointer select: the compiler must
+  // see which array is read, or it drains the DMA queue first)
+  if (upos >= 0) {
+    if (rb < 4) rotate_query(ring3, [&](int i4) -> float4 { return rope_q[i4]; });
+    else rotate_query(ring2, [&](int i4) -> float4 { return rope_q[i4]; });
+  } else {
+    // per-branch positions: straight from the table (in a loader wave this load queues behind
+    // the DMA: the slow path)
+    const int32_t q_bi = min(r_row / G, nb - 1);
+    const int32_t q_pos = a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
+    const float4* cs_row = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)q_pos * (D / 2));
+    if (rb < 4) rotate_query(ring3, [&](int i4) -> float4 { return cs_row[i4]; });
+    else rotate_query(ring2, [&](int i4) -> float4 { return cs_row[i4]; });
   }
 
   // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
@@ -257,17 +392,52 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[blk][i] = 0.f;
 
-  // softmax update + P.V for one 32-key tile: S = raw scores (C layout: value i of lane
-  // (n, g2) is key (i>>3)*16 + g2*8 + (i&7)), ok = which of them exist for this row,
-  // vf = the 8 V fragments (d-block * 2 + key half).
-  auto softmax_pv = [&](const floatx16& S, uint32_t ok, const uint4* vf) {
+  // One block for this wave's 32 rows.  Score value i of lane (n, g2) belongs to key
+  // (i>>3)*16 + g2*8 + (i&7); bit i of `ok` says whether the row may see it (`masked` is
+  // wave-uniform: false means all 32 keys count for every row).
+  auto compute_block = [&](const uint4* slot, bool masked, uint32_t ok, bool tail) {
+    const uint4* fr = slot + lane;
+    const char* krows = reinterpret_cast<const char*>(slot) + krow * 256;
+    floatx16 S;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) S[i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 kf = __builtin_bit_cast(
+          bf16x8, *reinterpret_cast<const uint4*>(krows + (((kk * 2 + g2) ^ (krow & 15)) << 4)));
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qh[kk], S, 0, 0, 0);
+      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Ql[kk], S, 0, 0, 0);
+    }
+    uint4 vf[8];
+    if (!tail) {
+#pragma unroll
+      for (int f = 0; f < 8; ++f) vf[f] = fr[(8 + f) * 64];
+    } else {
+      // V half of a tail tile: row k at 256 * k bytes, chunk index swizzled by bit 3 of k.
+      // Fragment f = d-block * 2 + key half wants keys half*16 + g2*8 + 0..7 of channel
+      // d-block*32 + n: eight 2-byte reads, one per row.
+      const uint16_t* vrows = reinterpret_cast<const uint16_t*>(slot + 8 * 64);
+#pragma unroll
+      for (int f = 0; f < 8; ++f) {
+        const int d = (f >> 1) * 32 + n;
+        const uint16_t* col = vrows + ((f & 1) * 16 + g2 * 8) * 128 + ((((d >> 3) ^ (g2 << 2)) << 3) | (d & 7));
+        uint32_t w[4];
+#pragma unroll
+        for (int e2 = 0; e2 < 4; ++e2)
+          w[e2] = (uint32_t)col[(2 * e2) * 128] | ((uint32_t)col[(2 * e2 + 1) * 128] << 16);
+        vf[f] = make_uint4(w[0], w[1], w[2], w[3]);
+      }
+    }
     float s[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s[i] = S[i];
+    if (masked) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = (ok >> i) & 1 ? s[i] : -INFINITY;
+    }
     float bm = NEG_BIG;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      s[i] = (ok >> i) & 1 ? S[i] * a.scale_log2 : -INFINITY;
-      bm = fmaxf(bm, s[i]);
-    }
+    for (int i = 0; i < 16; ++i) bm = fmaxf(bm, s[i]);
     if (__any(bm > m_used)) {
       bm = fmaxf(bm, __shfl_xor(bm, 32));
       const float m_new = fmaxf(m_used, bm);
@@ -294,198 +464,48 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     }
   };
 
-  // =====================================================================================
-  // Tail tiles
-  // =====================================================================================
-  if (active) {
-    // 8 KB of wave-private staging in the two stages the DMA has not been pointed at yet
-    uint16_t* const stage = reinterpret_cast<uint16_t*>(wave < 4 ? ring2 : ring3) + (wave & 3) * 4096;
-
-    // scores from K fragments in registers, V^T fragments out of the staging area (row-major
-    // rows, 16-byte chunk index XOR-swizzled by bit 3 of the key), softmax, P.V
-    auto tile_core = [&](const uint4* kf, uint32_t ok) {
-      floatx16 S;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) S[i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const bf16x8 kfr = __builtin_bit_cast(bf16x8, kf[kk]);
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, Qh[kk], S, 0, 0, 0);
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr, Ql[kk], S, 0, 0, 0);
-      }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the V rows have landed in LDS
-      uint4 vf[8];
-#pragma unroll
-      for (int f = 0; f < 8; ++f) {
-        const int blk = f >> 1, hf = f & 1;
-        const int d = blk * 32 + n;
-        const uint16_t* col = stage + (hf * 16 + g2 * 8) * 128 + ((((d >> 3) ^ (g2 << 2)) << 3) | (d & 7));
-        uint32_t w[4];
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2)
-          w[e2] = (uint32_t)col[(2 * e2) * 128] | ((uint32_t)col[(2 * e2 + 1) * 128] << 16);
-        vf[f] = make_uint4(w[0], w[1], w[2], w[3]);
-      }
-      softmax_pv(S, ok, vf);
-    };
-
-    // ---- positions 0 .. step-1 from the pool
-    for (int32_t ti = kg; ti < NT; ti += KG) {
-      const int32_t tau0 = ti * G;
-      const int32_t last = a.step - 1;  // clamp: always a written row of a live branch
-      uint4 kf[8];
-      {
-        const int32_t lb = min(lb0 + krow % BPB, nbr_here - 1);
-        const uint16_t* kp = k_tail + tail_offset(branch_id(lb)) + (int64_t)min(tau0 + krow / BPB, last) * D + g2 * 8;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) kf[kk] = *reinterpret_cast<const uint4*>(kp + kk * 16);
-      }
-      // V rows by DMA: lane (r4, c16) of instruction j = chunk c16 of virtual key 4j + r4
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int32_t k = j * 4 + r4;
-        const int32_t lb = min(lb0 + k % BPB, nbr_here - 1);
-        const uint16_t* vp = v_tail + tail_offset(branch_id(lb)) + (int64_t)min(tau0 + k / BPB, last) * D;
-        HPD_GLL(vp + ((c16 ^ (((k >> 3) & 1) << 2)) << 3), stage + j * 4 * 128);
-      }
-      uint32_t ok = 0;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int k = ((i >> 3) << 4) + g2 * 8 + (i & 7);
-        if (k % BPB == n / G && tau0 + k / BPB < a.step) ok |= 1u << i;
-      }
-      tile_core(kf, ok);
-    }
-
-    // ---- the newest token: virtual key k < BPB = branch k (larger k repeat valid rows and
-    //      are masked).  Fused mode: take it from k_new / v_new, rotate and round with the
-    //      arithmetic of hpd_kv_append, store, and use the rounded registers.
-    if (kg == NT % KG) {
-      const int32_t lbu = lb0 + krow % BPB;
-      const int32_t lb = min(lbu, nbr_here - 1);
-      const int32_t b = branch_id(lb);
-      const int64_t toff = tail_offset(b) + (int64_t)a.step * D;
-      const int64_t noff = ((int64_t)(row0_live + br0 + lb) * a.Hkv + hk) * D;
-      uint4 kf[8];
-      {
-        const uint16_t* kp = (a.fused ? k_new + noff : k_tail + toff) + g2 * 8;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) kf[kk] = *reinterpret_cast<const uint4*>(kp + kk * 16);
-      }
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const int32_t k = j * 4 + r4;
-        const int32_t lbv = min(lb0 + k % BPB, nbr_here - 1);
-        const uint16_t* vp = a.fused ? v_new + ((int64_t)(row0_live + br0 + lbv) * a.Hkv + hk) * D
-                                     : v_tail + tail_offset(branch_id(lbv)) + (int64_t)a.step * D;
-        HPD_GLL(vp + ((c16 ^ (((k >> 3) & 1) << 2)) << 3), stage + j * 4 * 128);
-      }
-      if (a.fused) {
-        const int32_t pos = upos >= 0 ? upos : a.tb.branch_base_pos[b] + 1 + a.step;
-        const float2* cs_row = a.tb.rope + (int64_t)pos * (D / 2);
-        const bool owner = lbu < nbr_here && krow < BPB;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          float lo[8], hi[8], rl[8], rh[8];
-          unpack8(kf[kk], lo);
-          unpack8(kf[kk + 4], hi);
-          const float4* csp = reinterpret_cast<const float4*>(cs_row + kk * 16 + g2 * 8);
-#pragma unroll
-          for (int e2 = 0; e2 < 4; ++e2) {
-            const float4 cs = csp[e2];
-            hpd::rope_pair(lo[2 * e2], hi[2 * e2], cs.x, cs.y, rl[2 * e2], rh[2 * e2]);
-            hpd::rope_pair(lo[2 * e2 + 1], hi[2 * e2 + 1], cs.z, cs.w, rl[2 * e2 + 1], rh[2 * e2 + 1]);
-          }
-          kf[kk] = __builtin_bit_cast(uint4, pack8(rl));
-          kf[kk + 4] = __builtin_bit_cast(uint4, pack8(rh));
-          if (owner) {
-            *reinterpret_cast<uint4*>(k_tail + toff + g2 * 8 + kk * 16) = kf[kk];
-            *reinterpret_cast<uint4*>(k_tail + toff + g2 * 8 + (kk + 4) * 16) = kf[kk + 4];
-          }
-        }
-      }
-      uint32_t ok = 0;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int k = ((i >> 3) << 4) + g2 * 8 + (i & 7);
-        if (k < BPB && k == n / G) ok |= 1u << i;
-      }
-      if (a.fused) {
-        // the value rows of the newest token: out of the staging area into the pool
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-        for (int j = 0; j < (BPB + 3) / 4; ++j) {
-          const int32_t k = j * 4 + r4;
-          if (k < BPB && lb0 + k < nbr_here) {
-            const uint4 v = *reinterpret_cast<const uint4*>(stage + k * 128 + (c16 << 3));
-            *reinterpret_cast<uint4*>(v_tail + tail_offset(branch_id(lb0 + k)) + (int64_t)a.step * D +
-                                      ((c16 ^ (((k >> 3) & 1) << 2)) << 3)) = v;
-          }
-        }
-      }
-      tile_core(kf, ok);
-    }
-  }
-
-  auto compute_block = [&](const uint4* slot, int32_t valid) {
-    const uint4* fr = slot + lane;
-    floatx16 S;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) S[i] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 kf = __builtin_bit_cast(bf16x8, fr[kk * 64]);
-      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qh[kk], S, 0, 0, 0);
-      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Ql[kk], S, 0, 0, 0);
-    }
-    uint4 vf[8];
-#pragma unroll
-    for (int f = 0; f < 8; ++f) vf[f] = fr[(8 + f) * 64];
-    uint32_t ok = 0xffffu;
-    if (valid < 32) {
-      ok = 0;
-#pragma unroll
-      for (int i = 0; i < 16; ++i)
-        if (((i >> 3) << 4) + g2 * 8 + (i & 7) < valid) ok |= 1u << i;
-      // padding slots may hold NaN patterns: 0 * NaN must not reach the accumulators
-#pragma unroll
-      for (int f = 0; f < 8; ++f) {
-        const int key0 = (f & 1) * 16 + g2 * 8;
-        uint32_t w[4] = {vf[f].x, vf[f].y, vf[f].z, vf[f].w};
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (key0 + e >= valid) w[e >> 1] &= (e & 1) ? 0x0000ffffu : 0xffff0000u;
-        vf[f] = make_uint4(w[0], w[1], w[2], w[3]);
-      }
-    }
-    softmax_pv(S, ok, vf);
-  };
+  // bits 0..7 of a mask byte: the first `cnt` (clamped to 0..8) of 8 consecutive keys
+  auto first_bits = [](int32_t cnt) -> uint32_t { return (1u << min(max(cnt, 0), 8)) - 1u; };
+  const int32_t lb_row = rb * BPB + n / G;  // this row's branch within the row group
 
   // Round r: wait until its stage has landed (newer rounds may stay in flight: the DMA
-  // instructions of a wave complete in order and every wave issues LOADS_PER_ROUND per
+  // instructions of a wave complete in order and every loader issues LOADS_PER_ROUND per
   // round), meet, refill the stage that was consumed last round, compute.
   auto round_body = [&](int32_t r, const uint4* cur, uint4* refill, uint4* refill0) {
-    const int32_t newer = r == 0 ? min(1, NR - 1) : min(2, NR - 1 - r);  // rounds issued after r
-    if (newer >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
-    else if (newer == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_ROUND) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const int32_t newer = r == 0 ? min(1, NR - 1) : min(2, NR - 1 - r);  // rounds requested after r
+    if (newer >= 2 && r != r_pub) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
+    else if (newer == 1 && r != r_pub) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_ROUND) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // also: the stores of the append at r_pub
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS reads of the previous round are done
     __builtin_amdgcn_s_barrier();
     if (r == 0) {
-      // the tail staging is finished in every wave: point the DMA at stages 2 and 3
+      // the query staging in stages 2 and 3 has been consumed by every wave
       if (NR > 2) issue_round(2, refill0);
       if (NR > 3) issue_round(3, refill);
     } else if (r + 3 < NR) {
       issue_round(r + 3, refill);
     }
     if (active) {
-#pragma unroll
+#pragma nounroll
       for (int32_t j = 0; j < STAGE_BLOCKS; ++j) {
         const int32_t gb = r * STAGE_BLOCKS + j;
-        if (gb < NB && gb % KG == kg) {
+        bool mine = false, masked = false, tail = false;
+        uint32_t ok = 0xffffu;
+        if (gb < NB) {
+          mine = gb % KG == kg;
           const int32_t valid = gb < NBh ? min(32, Hlen - gb * 32) : min(32, Llen - (gb - NBh) * 32);
-          compute_block(cur + j * SLOT_U4, valid);
+          masked = valid < 32;
+          ok = first_bits(valid - g2 * 8) | (first_bits(valid - 16 - g2 * 8) << 8);
+        } else if (gb < NBT) {
+          const int32_t tt = gb - NB;
+          const int32_t c = tt / NQ, qd = tt - c * NQ;
+          mine = qd / QPR == rb && (c * QPR + qd % QPR) % KG == kg;
+          masked = true;
+          tail = true;
+          const uint32_t pm = first_bits(a.step + 1 - c * 8);
+          ok = (qd * 4 + g2 == lb_row ? pm : 0u) | (qd * 4 + 2 + g2 == lb_row ? pm << 8 : 0u);
         }
+        if (mine) compute_block(cur + j * SLOT_U4, masked, ok, tail);
       }
     }
   };
@@ -502,16 +522,16 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 
   // ---- merge the key groups: every wave of a row block reduces its own d-blocks.
   //      Wave w parks what the others need in region w: stage (w & 3), half (w >> 2).
-  float* const park0 = reinterpret_cast<float*>(ring0);
-  float* const park1 = reinterpret_cast<float*>(ring1);
-  float* const park2 = reinterpret_cast<float*>(ring2);
-  float* const park3 = reinterpret_cast<float*>(ring3);
-  auto region = [&](int32_t w) -> float* {
-    float* base = (w & 2) ? ((w & 1) ? park3 : park2) : ((w & 1) ? park1 : park0);
-    return base + (w >> 2) * (50 * 64) + lane;
-  };
   const int32_t DB = 4 / KG;  // d-blocks reduced by one wave: blocks kg*DB .. kg*DB + DB - 1
   if (KG > 1) {
+    float* const park0 = reinterpret_cast<float*>(ring0);
+    float* const park1 = reinterpret_cast<float*>(ring1);
+    float* const park2 = reinterpret_cast<float*>(ring2);
+    float* const park3 = reinterpret_cast<float*>(ring3);
+    auto region = [&](int32_t w) -> float* {
+      float* base = (w & 2) ? ((w & 1) ? park3 : park2) : ((w & 1) ? park1 : park0);
+      return base + (w >> 2) * (50 * 64) + lane;
+    };
     if (active) {
       float* buf = region(wave);
       int32_t sidx = 0;
@@ -532,7 +552,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       float m_new = m_used;
       for (int32_t o = 0; o < KG - 1; ++o) {
         const int32_t okg = o < kg ? o : o + 1;  // the other key groups of this row block
-        const float* buf = region(rb * KG + okg);
+        const float* buf = region((okg << rb_shift) + rb);
         m_o[o] = buf[48 * 64];
         l_o[o] = buf[49 * 64];
         m_new = fmaxf(m_new, m_o[o]);
@@ -545,7 +565,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         for (int i = 0; i < 16; ++i) acc[blk][i] *= a_own;
       for (int32_t o = 0; o < KG - 1; ++o) {
         const int32_t okg = o < kg ? o : o + 1;
-        const float* buf = region(rb * KG + okg);
+        const float* buf = region((okg << rb_shift) + rb);
         const float a_o = fast_exp2(m_o[o] - m_new);
         l_lane += l_o[o] * a_o;
         // my blocks sit in the other wave's region at the index that skips ITS own blocks
@@ -558,50 +578,30 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
           }
         }
       }
-      m_used = m_new;
     }
-    __syncthreads();
   }
 
-  // ---- park the finished rows row-major (64 rows per stage): each wave its own d-blocks ...
-  if (active) {
-    const int32_t lr = rb * 32 + n;
-    float* park = (lr & 128) ? ((lr & 64) ? park3 : park2) : ((lr & 64) ? park1 : park0);
-    const int32_t lrr = lr & 63;
+  // ---- normalise and write: accumulator value i of d-block blk is channel
+  //      blk*32 + (i/4)*8 + g2*4 + i%4 of row n, so a lane stores 4 consecutive channels at a time
+  if (row_valid) {
+    const float inv = 1.0f / (l_lane + __shfl_xor(l_lane, 32));
+    const int32_t live_row = row0_live + br0 + lr / G;
+    const int64_t o_off = ((int64_t)live_row * a.Hq + hk * G + lr % G) * D + g2 * 4;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
       if (blk / DB == kg) {
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc)
-          *reinterpret_cast<float4*>(park + park_off(lrr, blk * 8 + cc * 2 + g2)) =
-              make_float4(acc[blk][cc * 4 + 0], acc[blk][cc * 4 + 1], acc[blk][cc * 4 + 2], acc[blk][cc * 4 + 3]);
-      }
-    }
-    if (kg == 0) {
-      const float l_row = l_lane + __shfl_xor(l_lane, 32);
-      if (g2 == 0) l_buf[lr] = l_row;
-    }
-  }
-  __syncthreads();
-
-  // ---- ... and write them normalised, 4 rows per wave pass, 512 contiguous bytes per row
-  {
-    const int32_t ks = lane >> 4, c = lane & 15;
-    for (int32_t lr = wave * 4 + ks; lr < rows_here; lr += WAVES * 4) {
-      const float inv = 1.0f / l_buf[lr];
-      const float* park = (lr & 128) ? ((lr & 64) ? park3 : park2) : ((lr & 64) ? park1 : park0);
-      const int32_t lrr = lr & 63;
-      const float4 p0 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c));
-      const float4 p1 = *reinterpret_cast<const float4*>(park + park_off(lrr, 2 * c + 1));
-      float o[8] = {p0.x * inv, p0.y * inv, p0.z * inv, p0.w * inv, p1.x * inv, p1.y * inv, p1.z * inv, p1.w * inv};
-      const int32_t live_row = row0_live + br0 + lr / G;
-      const int64_t o_off = ((int64_t)live_row * a.Hq + hk * G + lr % G) * D + c * 8;
-      if (a.out_f32) {
-        float* op = reinterpret_cast<float*>(out) + o_off;
-        *reinterpret_cast<float4*>(op) = make_float4(o[0], o[1], o[2], o[3]);
-        *reinterpret_cast<float4*>(op + 4) = make_float4(o[4], o[5], o[6], o[7]);
-      } else {
-        *reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(out) + o_off) = __builtin_bit_cast(uint4, pack8(o));
+        for (int cc = 0; cc < 4; ++cc) {
+          const float o0 = acc[blk][cc * 4 + 0] * inv, o1 = acc[blk][cc * 4 + 1] * inv;
+          const float o2 = acc[blk][cc * 4 + 2] * inv, o3 = acc[blk][cc * 4 + 3] * inv;
+          const int64_t off = o_off + blk * 32 + cc * 8;
+          if (a.out_f32) {
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + off) = make_float4(o0, o1, o2, o3);
+          } else {
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(out) + off) =
+                make_uint2(cvt_pk_bf16(o0, o1), cvt_pk_bf16(o2, o3));
+          }
+        }
       }
     }
   }

@@ -348,27 +348,10 @@ int hpd_layout_query(const hpd_layout* L, int32_t what, void* host_out, size_t b
 }
 
 int hpd_set_kernel_mode(hpd_layout* L, int32_t mode) {
-  if (!L || mode < 0 || mode > 3) return HPD_E_INVALID;
-  if (mode == 2 && !hpd_mfma_supported(L)) return HPD_E_UNSUPPORTED;
-  if (mode == 3 && !hpd_stream_supported(L)) return HPD_E_UNSUPPORTED;
+  if (!L || mode < 0 || mode > 2) return HPD_E_INVALID;
+  if (mode == 2 && !hpd_stream_supported(L)) return HPD_E_UNSUPPORTED;
   L->kernel_mode = mode;
   return HPD_OK;
-}
-
-int hpd_set_tuning(hpd_layout* L, int32_t key, int32_t value) {
-  if (!L) return HPD_E_INVALID;
-  switch (key) {
-    case HPD_TUNE_WAVES:
-      if (value != 0 && value != 4 && value != 8) return HPD_E_INVALID;
-      L->mfma_waves = value; return HPD_OK;
-    case HPD_TUNE_QSPLIT:
-      if (value < 0 || value > 1) return HPD_E_INVALID;
-      L->qsplit = value; return HPD_OK;
-    case HPD_TUNE_PSPLIT:
-      if (value < 0 || value > 2) return HPD_E_INVALID;
-      L->psplit = value; return HPD_OK;
-    default: return HPD_E_INVALID;
-  }
 }
 
 static int check_step(const hpd_layout* L, int32_t step) {
@@ -417,15 +400,11 @@ int hpd_decode_attention(const hpd_layout* L, int32_t step, const void* q, const
   const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
   if (n_live == 0) return HPD_OK;
   if (!q || !k_prefix || !v_prefix || !k_tail || !v_tail || !out) return HPD_E_INVALID;
-  const bool use_stream = L->kernel_mode == 3 || (L->kernel_mode == 0 && hpd_stream_supported(L));
-  const bool use_mfma = L->kernel_mode == 2;
+  const bool use_stream = L->kernel_mode == 2 || (L->kernel_mode == 0 && hpd_stream_supported(L));
   if (use_stream) {
     HPD_HIP(hpd_launch_attention_stream(L, step, q, k_prefix, v_prefix, const_cast<void*>(k_tail),
                                         const_cast<void*>(v_tail), nullptr, nullptr, out,
                                         (hipStream_t)stream));
-  } else if (use_mfma) {
-    HPD_HIP(hpd_launch_attention_mfma(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out,
-                                      (hipStream_t)stream));
   } else {
     // the generic kernel keeps one score per key in LDS
     int64_t max_keys = 0;
@@ -450,7 +429,7 @@ int hpd_decode_step(const hpd_layout* L, int32_t step, const void* q, const void
   if (n_live == 0) return HPD_OK;
   if (!q || !k_new || !v_new || !k_prefix || !v_prefix || !k_tail || !v_tail || !out)
     return HPD_E_INVALID;
-  if (L->kernel_mode == 3 || (L->kernel_mode == 0 && hpd_stream_supported(L))) {
+  if (L->kernel_mode == 2 || (L->kernel_mode == 0 && hpd_stream_supported(L))) {
     // one launch: the attention kernel rotates, stores and uses the new keys itself
     HPD_HIP(hpd_launch_attention_stream(L, step, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new,
                                         out, (hipStream_t)stream));

@@ -34,8 +34,6 @@ struct hpd_layout {
   int64_t n_prefix_tokens = 0, NP = 0, total_live = 0, total_units = 0;
   int32_t max_pos = 0;
   int32_t kernel_mode = 0;
-  int32_t mfma_waves = 0;  // 0 = heuristic
-  int32_t qsplit = 1, psplit = 0;  // see hpd_tuning; defaults meet the 2e-2 x RMS bound
 
   std::vector<int32_t> seg_off, seg_len, seg_pos0, seg_raw_off, raw_seg;
   std::vector<int32_t> doc_prompt, branch_doc, branch_base_pos, branch_len;
@@ -65,12 +63,8 @@ hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const
                                         const void* k_prefix, const void* v_prefix,
                                         const void* k_tail, const void* v_tail, void* out,
                                         hipStream_t s);
-hipError_t hpd_launch_attention_mfma(const hpd_layout* L, int32_t step, const void* q,
-                                     const void* k_prefix, const void* v_prefix, const void* k_tail,
-                                     const void* v_tail, void* out, hipStream_t s);
 hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, uint8_t* mask_out, hipStream_t s);
 
-bool hpd_mfma_supported(const hpd_layout* L);
 bool hpd_stream_supported(const hpd_layout* L);
 // k_new / v_new may be null: then the newest token is read from the tail pool like the others
 hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const void* q,

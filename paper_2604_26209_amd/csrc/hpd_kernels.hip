@@ -1,7 +1,7 @@
 // HIP kernels (gfx950) for HPD masked decode attention: helper kernels (prefix fill,
 // positions, append, mask export) and the generic wave-reduction attention kernel that
 // covers fp32, odd shapes and serves as the fallback.  The MFMA shared-prefix kernel is
-// in hpd_attn_mfma.hip.
+// in hpd_attn_stream.hip.
 #include <algorithm>
 
 #include "hpd_internal.h"
@@ -49,6 +49,26 @@ __global__ void prefix_fill_kernel(hpd_dev_tables tb, int32_t n_seg, int64_t n_t
   const int64_t vblk = ((int64_t)h * (NP / 8) + slot / 8) * D;
   v_prefix[(vblk + i) * 8 + (slot & 7)] = v_raw[src + i];
   v_prefix[(vblk + i + half) * 8 + (slot & 7)] = v_raw[src + i + half];
+}
+
+// Zero values in the padding slots between a segment's end and the next multiple of the key
+// block: the attention kernels give those keys probability 0 and rely on 0 * V being 0.
+// One thread per (segment, kv head, padding slot, channel).
+template <typename T>
+__global__ void prefix_pad_kernel(hpd_dev_tables tb, int32_t n_seg, int32_t Hkv, int32_t D, int64_t NP,
+                                  T* __restrict__ v_prefix) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t total = (int64_t)n_seg * Hkv * (HPD_KEY_BLOCK - 1) * D;
+  if (gid >= total) return;
+  const int32_t c = (int32_t)(gid % D);
+  const int32_t j = (int32_t)((gid / D) % (HPD_KEY_BLOCK - 1));
+  const int32_t h = (int32_t)((gid / ((int64_t)D * (HPD_KEY_BLOCK - 1))) % Hkv);
+  const int32_t sid = (int32_t)(gid / ((int64_t)D * (HPD_KEY_BLOCK - 1) * Hkv));
+  const int32_t len = tb.seg_len[sid];
+  const int32_t pad = (HPD_KEY_BLOCK - len % HPD_KEY_BLOCK) % HPD_KEY_BLOCK;
+  if (j >= pad) return;
+  const int64_t slot = (int64_t)tb.seg_off[sid] + len + j;
+  v_prefix[(((int64_t)h * (NP / 8) + slot / 8) * D + c) * 8 + (slot & 7)] = hpd::from_float<T>(0.f);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -231,15 +251,21 @@ hipError_t hpd_launch_prefix_fill(const hpd_layout* L, const void* k_raw, const 
                                   void* k_prefix, void* v_prefix, hipStream_t s) {
   const int64_t total = L->n_prefix_tokens * L->cfg.n_kv_heads * (L->cfg.head_dim / 2);
   if (total == 0) return hipSuccess;
-  if (L->cfg.dtype == HPD_F32)
+  const int64_t pad_total = (int64_t)L->n_seg * L->cfg.n_kv_heads * (HPD_KEY_BLOCK - 1) * L->cfg.head_dim;
+  if (L->cfg.dtype == HPD_F32) {
     prefix_fill_kernel<float><<<grid1d(total, 256), 256, 0, s>>>(
         L->dev, L->n_seg, L->n_prefix_tokens, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP,
         (const float*)k_raw, (const float*)v_raw, (float*)k_prefix, (float*)v_prefix);
-  else
+    prefix_pad_kernel<float><<<grid1d(pad_total, 256), 256, 0, s>>>(
+        L->dev, L->n_seg, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP, (float*)v_prefix);
+  } else {
     prefix_fill_kernel<hpd::bf16_t><<<grid1d(total, 256), 256, 0, s>>>(
         L->dev, L->n_seg, L->n_prefix_tokens, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP,
         (const hpd::bf16_t*)k_raw, (const hpd::bf16_t*)v_raw, (hpd::bf16_t*)k_prefix,
         (hpd::bf16_t*)v_prefix);
+    prefix_pad_kernel<hpd::bf16_t><<<grid1d(pad_total, 256), 256, 0, s>>>(
+        L->dev, L->n_seg, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP, (hpd::bf16_t*)v_prefix);
+  }
   return hipGetLastError();
 }
 

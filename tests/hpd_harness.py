@@ -36,7 +36,7 @@ class Inputs:
 
 
 def run_hip(wl, inputs=None, kernel_mode=0, fused=False, pos_mode=0, attr_len=None,
-            poison_pools=True, steps=None, out_f32=None, tuning=None):
+            poison_pools=True, steps=None, out_f32=None):
     """Runs every step through the C ABI.  Returns dict(out, pos, slot per step, layout, inputs)."""
     from paper_2604_26209_amd import binding as B
 
@@ -46,8 +46,6 @@ def run_hip(wl, inputs=None, kernel_mode=0, fused=False, pos_mode=0, attr_len=No
                                     out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME)
     if kernel_mode:
         B.hpd_set_kernel_mode(layout, kernel_mode)
-    for key, value in (tuning or {}).items():
-        B.hpd_set_tuning(layout, key, value)
     n_live = layout.n_live()
     if inputs is None:
         inputs = Inputs(wl, n_live, "cuda")
