@@ -74,7 +74,9 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int D = 128;
 constexpr int WAVES = 8;
-constexpr int LOADERS = 4;             // waves 0..3 issue the DMA
+constexpr int CWAVES = 6;              // waves 0..5 compute
+constexpr int LOADERS = WAVES - CWAVES;  // waves 6, 7 only issue the DMA
+constexpr int MAX_BLOCKS = CWAVES;     // row blocks per workgroup
 constexpr int SLOT_U4 = 16 * 64;       // one 32-key block: 8 K + 8 V fragments of 64 x 16 bytes
 constexpr int STAGE_BLOCKS = 2;
 constexpr int STAGE_U4 = STAGE_BLOCKS * SLOT_U4;  // 32 KB
@@ -156,16 +158,18 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 
   const int32_t R = nb * G;
   const int32_t nblk = (R + 31) >> 5;
-  const int32_t per_group = (nblk + a.RG - 1) / a.RG;  // <= 8 by the host's choice of RG
+  const int32_t per_group = (nblk + a.RG - 1) / a.RG;  // <= MAX_BLOCKS by the host's choice of RG
   const int32_t first_blk = rg * per_group;
   const int32_t nblk_here = min(per_group, nblk - first_blk);
   if (nblk_here <= 0) return;  // uniform over the workgroup
-  const int32_t KG = nblk_here <= 2 ? 4 : (nblk_here <= 4 ? 2 : 1);
-  // waves of one key group sit on different SIMDs (wave w runs on SIMD w % 4)
-  const int32_t rb_shift = KG == 4 ? 1 : (KG == 2 ? 2 : 3);
-  const int32_t rb = wave & ((1 << rb_shift) - 1);
-  const int32_t kg = wave >> rb_shift;
-  const bool active = rb < nblk_here;
+  // 6 compute waves = (row block) x (key group): 1 row block x 4 key groups, 2 x 3, 3 x 2,
+  // or up to 6 x 1
+  const int32_t KG = nblk_here == 1 ? 4 : (nblk_here == 2 ? 3 : (nblk_here == 3 ? 2 : 1));
+  const int32_t NRB = nblk_here <= 3 ? nblk_here : CWAVES;  // row-block slots
+  const bool loader = wave >= CWAVES;
+  const int32_t kg = NRB == 1 ? wave : (NRB == 2 ? wave >> 1 : (NRB == 3 ? (wave >= 3 ? 1 : 0) : 0));
+  const int32_t rb = wave - kg * NRB;
+  const bool active = !loader && kg < KG && rb < nblk_here;
 
   // ---- branches of this row group
   const int32_t br0 = first_blk * BPB;
@@ -190,16 +194,15 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const bool row_valid = active && lr < rows_here;
   const int32_t r4 = lane >> 4, c16 = lane & 15;
 
-  // ---- loader role (waves 0..3): wave w fills quarter w of both block slots of a stage (the K
-  //      half for quarters 0 and 1, the V half for 2 and 3): LOADS_PER_ROUND instructions per
-  //      round, always the same number, so that vmcnt(N) means the same thing in every round.
-  //      Every instruction reads whole 256-byte rows or 512-byte runs: a load whose lanes touch
-  //      64 different cache lines costs the memory pipeline 8 times as much as one whose lanes
-  //      touch 8.
-  const bool loader = wave < LOADERS;
-  const int32_t ld_part = wave & 3;
-  const bool ld_is_k = ld_part < 2;
-  const int32_t ld_half = ld_part & 1;
+  // ---- loader role (waves 6, 7): wave 6 + j fills block slot j of a stage, quarter by quarter
+  //      (the K half in quarters 0 and 1, the V half in 2 and 3): LOADS_PER_ROUND instructions
+  //      per round, always the same number, so that vmcnt(N) means the same thing in every
+  //      round.  A loader does nothing else: under load a DMA instruction blocks the issuing
+  //      wave until the memory pipeline takes it, and whatever that wave would compute
+  //      afterwards is time in which nothing is requested (measured: bandwidth dropped by the
+  //      full compute time when the loading waves also computed).  Every instruction reads
+  //      whole 256-byte rows or 512-byte runs: a load whose lanes touch 64 different cache
+  //      lines costs the memory pipeline 8 times as much as one whose lanes touch 8.
   // MFMA row m of a score tile carries this key of the block (see the file header)
   const int32_t krow = ((n >> 4) << 4) | (((n >> 2) & 1) << 3) | (((n >> 3) & 1) << 2) | (n & 3);
   const uint16_t* kbase = k_prefix + (int64_t)hk * a.NP * D;
@@ -211,81 +214,91 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // V half of a prefix block: fragment order, straight out of the 8-key interleaved pool:
   // key halves 0 / 1 (2*D*8 elements apart) of d-blocks 2*h, 2*h+1 (32 channels * 8 apart).
   // V half of a tail tile: 32 rows of 256 bytes like K, chunk position c ^ 4*(bit 3 of k).
-  const int32_t ld_e0 = ld_is_k ? ((c16 ^ r4) << 3) : (c16 << 3);  // element offset of load 0 within a row
-  const int32_t ld_vfrag = (g2 * D + ld_half * 64 + n) * 8;      // V prefix: element offset of load 0
-  auto row_elem = [&](int f) -> int32_t {  // row-major loads: element offset within the row of load f
-    return ld_is_k ? (ld_e0 ^ (f << 5)) : (ld_e0 ^ ((f >> 1) << 5));
-  };
   auto issue_block = [&](int32_t gb_raw, uint4* dst_slot) {
     // a slot past the last block re-loads the last block (never read): the count stays fixed
     const int32_t gb = min(gb_raw, NBT - 1);
-    uint4* dst = dst_slot + ld_part * 4 * 64;
-    const uint16_t *p0, *p1, *p2, *p3;
-    if (gb < NB) {
-      const int32_t slot0 = gb < NBh ? hoff + gb * 32 : doff + (gb - NBh) * 32;
-      if (ld_is_k) {
-        const uint16_t* rowp = kbase + (int64_t)(slot0 + ld_half * 16 + r4) * D;
-        p0 = rowp + row_elem(0);
-        p1 = rowp + 4 * D + row_elem(1);
-        p2 = rowp + 8 * D + row_elem(2);
-        p3 = rowp + 12 * D + row_elem(3);
-      } else {
-        p0 = vbase + (int64_t)(slot0 / 8) * D * 8 + ld_vfrag;
-        p1 = p0 + 2 * D * 8;
-        p2 = p0 + 32 * 8;
-        p3 = p1 + 32 * 8;
-      }
+    int32_t slot0 = 0, tc = 0, tq = 0;
+    const bool prefix = gb < NB;
+    if (prefix) {
+      slot0 = gb < NBh ? hoff + gb * 32 : doff + (gb - NBh) * 32;
     } else {
       // tail tile: key k = position c*8 + k%8 of branch qd*4 + k/8; row k = h*16 + f*4 + lane/16
       // is position (f&1)*4 + lane/16 of branch 2*h + f/2.  Branches and positions past the
       // end repeat the last valid one (masked by the consumer).
       const int32_t tt = gb - NB;
-      const int32_t c = tt / NQ, qd = tt - c * NQ;
-      const int32_t bA = branch_id(min(qd * 4 + ld_half * 2, nbr_here - 1));
-      const int32_t bB = branch_id(min(qd * 4 + ld_half * 2 + 1, nbr_here - 1));
-      const int32_t posA = min(c * 8 + r4, a.step), posB = min(c * 8 + 4 + r4, a.step);
-      const uint16_t* pool = ld_is_k ? k_tail : v_tail;
-      const uint16_t* rowA = pool + ((int64_t)bA * a.Hkv + hk) * a.Tcap * D;
-      const uint16_t* rowB = pool + ((int64_t)bB * a.Hkv + hk) * a.Tcap * D;
-      p0 = rowA + (int64_t)posA * D + row_elem(0);
-      p1 = rowA + (int64_t)posB * D + row_elem(1);
-      p2 = rowB + (int64_t)posA * D + row_elem(2);
-      p3 = rowB + (int64_t)posB * D + row_elem(3);
+      tc = tt / NQ;
+      tq = tt - tc * NQ;
     }
-    HPD_GLL(p0, dst);
-    HPD_GLL(p1, dst + 64);
-    HPD_GLL(p2, dst + 128);
-    HPD_GLL(p3, dst + 192);
+#pragma nounroll
+    for (int32_t part = 0; part < 4; ++part) {
+      const bool is_k = part < 2;
+      const int32_t half = part & 1;
+      const int32_t e0 = is_k ? ((c16 ^ r4) << 3) : (c16 << 3);  // row-major loads: element in the row, load 0
+      const int32_t x1 = is_k ? 32 : 0, x2 = is_k ? 64 : 32;     // ... XORed with this for loads 1, 2 (3: both)
+      uint4* dst = dst_slot + part * 4 * 64;
+      const uint16_t *p0, *p1, *p2, *p3;
+      if (prefix) {
+        if (is_k) {
+          const uint16_t* rowp = kbase + (int64_t)(slot0 + half * 16 + r4) * D;
+          p0 = rowp + e0;
+          p1 = rowp + 4 * D + (e0 ^ x1);
+          p2 = rowp + 8 * D + (e0 ^ x2);
+          p3 = rowp + 12 * D + (e0 ^ x1 ^ x2);
+        } else {
+          p0 = vbase + (int64_t)(slot0 / 8) * D * 8 + (g2 * D + half * 64 + n) * 8;
+          p1 = p0 + 2 * D * 8;
+          p2 = p0 + 32 * 8;
+          p3 = p1 + 32 * 8;
+        }
+      } else {
+        const int32_t bA = branch_id(min(tq * 4 + half * 2, nbr_here - 1));
+        const int32_t bB = branch_id(min(tq * 4 + half * 2 + 1, nbr_here - 1));
+        const int32_t posA = min(tc * 8 + r4, a.step), posB = min(tc * 8 + 4 + r4, a.step);
+        const uint16_t* pool = is_k ? k_tail : v_tail;
+        const uint16_t* rowA = pool + ((int64_t)bA * a.Hkv + hk) * a.Tcap * D;
+        const uint16_t* rowB = pool + ((int64_t)bB * a.Hkv + hk) * a.Tcap * D;
+        p0 = rowA + (int64_t)posA * D + e0;
+        p1 = rowA + (int64_t)posB * D + (e0 ^ x1);
+        p2 = rowB + (int64_t)posA * D + (e0 ^ x2);
+        p3 = rowB + (int64_t)posB * D + (e0 ^ x1 ^ x2);
+      }
+      HPD_GLL(p0, dst);
+      HPD_GLL(p1, dst + 64);
+      HPD_GLL(p2, dst + 128);
+      HPD_GLL(p3, dst + 192);
+    }
   };
   auto issue_round = [&](int32_t r, uint4* stage) {
-    if (loader) {
-#pragma nounroll
-      for (int32_t j = 0; j < STAGE_BLOCKS; ++j) issue_block(r * STAGE_BLOCKS + j, stage + j * SLOT_U4);
-    }
+    if (loader) issue_block(r * STAGE_BLOCKS + (wave - CWAVES), stage + (wave - CWAVES) * SLOT_U4);
   };
 
-  // ---- fused mode: waves 4..7 append the newest token of the unit's branches (the
-  //      arithmetic of hpd_kv_append), 8 lanes per branch
-  auto append_newest = [&]() {
-    const int32_t t = tid - LOADERS * 64;
-    const int32_t c = (t & 7) * 8;  // channels c .. c+7 and 64+c .. 64+c+7
-    for (int32_t lb = t >> 3; lb < nbr_here; lb += (WAVES - LOADERS) * 8) {
-      const int32_t b = branch_id(lb);
-      const int32_t pos = upos >= 0 ? upos : a.tb.branch_base_pos[b] + 1 + a.step;
-      const int64_t noff = ((int64_t)(row0_live + br0 + lb) * a.Hkv + hk) * D;
-      const uint4 klo = *reinterpret_cast<const uint4*>(k_new + noff + c);
-      const uint4 khi = *reinterpret_cast<const uint4*>(k_new + noff + 64 + c);
-      const uint4 vlo = *reinterpret_cast<const uint4*>(v_new + noff + c);
-      const uint4 vhi = *reinterpret_cast<const uint4*>(v_new + noff + 64 + c);
-      float rl[8], rh[8];
-      rotate16(klo, khi, a.tb.rope + (int64_t)pos * (D / 2), c, rl, rh);
-      uint16_t* kd = k_tail + (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
-      *reinterpret_cast<uint4*>(kd + c) = __builtin_bit_cast(uint4, pack8(rl));
-      *reinterpret_cast<uint4*>(kd + 64 + c) = __builtin_bit_cast(uint4, pack8(rh));
-      uint16_t* vd = v_tail + (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
-      *reinterpret_cast<uint4*>(vd + c) = vlo;
-      *reinterpret_cast<uint4*>(vd + 64 + c) = vhi;
-    }
+  // ---- fused mode: the compute waves append the newest token of the unit's branches (the
+  //      arithmetic of hpd_kv_append), 8 lanes per branch: channels c .. c+7 and 64+c .. 64+c+7
+  const int32_t ap_c = (tid & 7) * 8;
+  struct NewRows { uint4 klo, khi, vlo, vhi; };
+  auto append_load = [&](int32_t lb) -> NewRows {
+    const int64_t noff = ((int64_t)(row0_live + br0 + lb) * a.Hkv + hk) * D;
+    NewRows r;
+    r.klo = *reinterpret_cast<const uint4*>(k_new + noff + ap_c);
+    r.khi = *reinterpret_cast<const uint4*>(k_new + noff + 64 + ap_c);
+    r.vlo = *reinterpret_cast<const uint4*>(v_new + noff + ap_c);
+    r.vhi = *reinterpret_cast<const uint4*>(v_new + noff + 64 + ap_c);
+    return r;
+  };
+  auto append_store = [&](int32_t lb, const NewRows& r) {
+    const int32_t b = branch_id(lb);
+    const int32_t pos = upos >= 0 ? upos : a.tb.branch_base_pos[b] + 1 + a.step;
+    float rl[8], rh[8];
+    rotate16(r.klo, r.khi, a.tb.rope + (int64_t)pos * (D / 2), ap_c, rl, rh);
+    uint16_t* kd = k_tail + (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
+    *reinterpret_cast<uint4*>(kd + ap_c) = __builtin_bit_cast(uint4, pack8(rl));
+    *reinterpret_cast<uint4*>(kd + 64 + ap_c) = __builtin_bit_cast(uint4, pack8(rh));
+    uint16_t* vd = v_tail + (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
+    *reinterpret_cast<uint4*>(vd + ap_c) = r.vlo;
+    *reinterpret_cast<uint4*>(vd + 64 + ap_c) = r.vhi;
+  };
+  auto append_from = [&](int32_t lb0) {
+    for (int32_t lb = lb0; lb < nbr_here; lb += CWAVES * 8) append_store(lb, append_load(lb));
   };
   // Round x >= 2 is requested right after the barrier of round max(x - 3, 0), and the first
   // tail tile sits in round NB / 2: the appending waves make sure their stores are complete
@@ -295,41 +308,44 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const bool append_first = a.fused && NB < 2 * STAGE_BLOCKS;
   const int32_t r_pub = (a.fused && !append_first && !loader) ? max(NB / STAGE_BLOCKS - 3, 0) : -1;
   if (append_first) {
-    if (!loader) append_newest();
+    if (!loader) append_from(tid >> 3);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
 
-  // ---- waves 0..3 start the DMA ring at once.  Waves 4..7 - whose memory queues stay short,
-  //      so that their loads come back with one latency - fetch the raw query rows of the row
-  //      group for everybody, 4 whole rows per instruction, and park them in stage 3 (rows
-  //      0..127) and stage 2 (rows 128..255), chunk c of row r at position c ^ (r & 15); one of
-  //      them fetches the (cos, sin) row of the shared position; then they append.
+  // ---- the loaders start the DMA ring at once.  The compute waves - whose memory queues stay
+  //      short, so that their loads come back with one latency - fetch the raw query rows of
+  //      the row group, 4 whole rows per instruction, and park them in stage 3 (rows 0..127)
+  //      and stage 2 (rows 128..191), chunk c of row r at position c ^ (r & 15); one of them
+  //      fetches the (cos, sin) row of the shared position.  The new rows of the append are
+  //      requested in the same breath and stored after the query is rotated.
+  const bool append_late = a.fused && !append_first && !loader;
+  const bool append_mine = append_late && (tid >> 3) < nbr_here;
+  NewRows new_rows = {};
   if (loader) {
     issue_round(0, ring0);
     if (NR > 1) issue_round(1, ring1);
   } else {
-    const int32_t w4 = wave - LOADERS;
-    for (int32_t i0 = w4; i0 * 4 < rows_here; i0 += 4 * (WAVES - LOADERS)) {
+    for (int32_t i0 = wave; i0 * 4 < rows_here; i0 += 4 * CWAVES) {
       uint4 v[4];
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
         v[b] = make_uint4(0, 0, 0, 0);
-        const int32_t i = i0 + b * (WAVES - LOADERS);
+        const int32_t i = i0 + b * CWAVES;
         const int32_t urow = first_blk * 32 + min(i * 4 + r4, rows_here - 1);  // row within the unit
         const int64_t off = ((int64_t)(row0_live + urow / G) * a.Hq + hk * G + urow % G) * D;
         if (i * 4 < rows_here) v[b] = *reinterpret_cast<const uint4*>(q + off + (c16 << 3));
       }
+      if (i0 == wave && append_mine) new_rows = append_load(tid >> 3);
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
-        const int32_t i = i0 + b * (WAVES - LOADERS);
+        const int32_t i = i0 + b * CWAVES;
         const int32_t row = i * 4 + r4;
         if (i * 4 < rows_here) (row < 128 ? ring3 : ring2)[(row & 127) * 16 + (c16 ^ (row & 15))] = v[b];
       }
     }
-    if (upos >= 0 && w4 == 0 && lane < 32)
+    if (upos >= 0 && wave == 0 && lane < 32)
       rope_q[lane] = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)upos * (D / 2))[lane];
-    if (a.fused && !append_first) append_newest();
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
   __builtin_amdgcn_s_barrier();        // a bare barrier: __syncthreads() would drain the DMA queue
@@ -370,7 +386,9 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   };
   // (the stage is chosen by a wave-uniform branch, not by a pointer select: the compiler must
   // see which array is read, or it drains the DMA queue first)
-  if (upos >= 0) {
+  if (loader) {
+    // nothing to rotate
+  } else if (upos >= 0) {
     if (rb < 4) rotate_query(ring3, [&](int i4) -> float4 { return rope_q[i4]; });
     else rotate_query(ring2, [&](int i4) -> float4 { return rope_q[i4]; });
   } else {
@@ -381,6 +399,10 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const float4* cs_row = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)q_pos * (D / 2));
     if (rb < 4) rotate_query(ring3, [&](int i4) -> float4 { return cs_row[i4]; });
     else rotate_query(ring2, [&](int i4) -> float4 { return cs_row[i4]; });
+  }
+  if (append_late) {
+    if (append_mine) append_store(tid >> 3, new_rows);
+    append_from((tid >> 3) + CWAVES * 8);
   }
 
   // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
@@ -472,10 +494,14 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // instructions of a wave complete in order and every loader issues LOADS_PER_ROUND per
   // round), meet, refill the stage that was consumed last round, compute.
   auto round_body = [&](int32_t r, const uint4* cur, uint4* refill, uint4* refill0) {
-    const int32_t newer = r == 0 ? min(1, NR - 1) : min(2, NR - 1 - r);  // rounds requested after r
-    if (newer >= 2 && r != r_pub) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
-    else if (newer == 1 && r != r_pub) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_ROUND) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // also: the stores of the append at r_pub
+    if (loader) {
+      const int32_t newer = r == 0 ? min(1, NR - 1) : min(2, NR - 1 - r);  // rounds requested after r
+      if (newer >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
+      else if (newer == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_ROUND) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    } else if (r == r_pub) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores of the append are complete
+    }
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS reads of the previous round are done
     __builtin_amdgcn_s_barrier();
     if (r == 0) {
@@ -522,7 +548,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 
   // ---- merge the key groups: every wave of a row block reduces its own d-blocks.
   //      Wave w parks what the others need in region w: stage (w & 3), half (w >> 2).
-  const int32_t DB = 4 / KG;  // d-blocks reduced by one wave: blocks kg*DB .. kg*DB + DB - 1
+  // d-block blk is reduced by key group blk % KG (KG = 3: group 0 takes blocks 0 and 3)
+  auto owner = [&](int blk) -> int32_t { return blk >= KG ? blk - KG : blk; };
   if (KG > 1) {
     float* const park0 = reinterpret_cast<float*>(ring0);
     float* const park1 = reinterpret_cast<float*>(ring1);
@@ -537,7 +564,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       int32_t sidx = 0;
 #pragma unroll
       for (int blk = 0; blk < 4; ++blk) {
-        if (blk / DB != kg) {  // not mine: somebody else reduces it
+        if (owner(blk) != kg) {  // not mine: somebody else reduces it
 #pragma unroll
           for (int i = 0; i < 16; ++i) buf[(sidx * 16 + i) * 64] = acc[blk][i];
           ++sidx;
@@ -552,7 +579,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       float m_new = m_used;
       for (int32_t o = 0; o < KG - 1; ++o) {
         const int32_t okg = o < kg ? o : o + 1;  // the other key groups of this row block
-        const float* buf = region((okg << rb_shift) + rb);
+        const float* buf = region(okg * NRB + rb);
         m_o[o] = buf[48 * 64];
         l_o[o] = buf[49 * 64];
         m_new = fmaxf(m_new, m_o[o]);
@@ -565,17 +592,19 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         for (int i = 0; i < 16; ++i) acc[blk][i] *= a_own;
       for (int32_t o = 0; o < KG - 1; ++o) {
         const int32_t okg = o < kg ? o : o + 1;
-        const float* buf = region((okg << rb_shift) + rb);
+        const float* buf = region(okg * NRB + rb);
         const float a_o = fast_exp2(m_o[o] - m_new);
         l_lane += l_o[o] * a_o;
         // my blocks sit in the other wave's region at the index that skips ITS own blocks
+        int32_t skipped = 0;  // blocks below blk that the other wave owns
 #pragma unroll
         for (int blk = 0; blk < 4; ++blk) {
-          if (blk / DB == kg) {
-            const int32_t sidx = blk - (blk / DB > okg ? DB : 0);
+          if (owner(blk) == kg) {
+            const int32_t sidx = blk - skipped;
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[blk][i] += buf[(sidx * 16 + i) * 64] * a_o;
           }
+          if (owner(blk) == okg) ++skipped;
         }
       }
     }
@@ -589,7 +618,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const int64_t o_off = ((int64_t)live_row * a.Hq + hk * G + lr % G) * D + g2 * 4;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
-      if (blk / DB == kg) {
+      if (KG == 1 || owner(blk) == kg) {
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) {
           const float o0 = acc[blk][cc * 4 + 0] * inv, o1 = acc[blk][cc * 4 + 1] * inv;
@@ -634,7 +663,7 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   const int G = a.Hq / a.Hkv;
   a.Tcap = L->T; a.P = L->P; a.n_docs = L->n_docs; a.NP = L->NP;
   const int32_t max_nblk = (L->max_rows[step] * G + 31) / 32;
-  a.RG = (max_nblk + 7) / 8;
+  a.RG = (max_nblk + MAX_BLOCKS - 1) / MAX_BLOCKS;
   if (a.RG < 1) a.RG = 1;
   a.out_f32 = L->cfg.out_dtype == HPD_OUT_F32 ? 1 : 0;
   a.fused = (k_new != nullptr) ? 1 : 0;
