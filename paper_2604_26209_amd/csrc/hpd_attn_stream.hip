@@ -169,7 +169,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const bool loader = wave >= CWAVES;
   const int32_t kg = NRB == 1 ? wave : (NRB == 2 ? wave >> 1 : (NRB == 3 ? (wave >= 3 ? 1 : 0) : 0));
   const int32_t rb = wave - kg * NRB;
-  const bool active = !loader && kg < KG && rb < nblk_here;
+  const bool active = kg < KG && rb < nblk_here;
 
   // ---- branches of this row group
   const int32_t br0 = first_blk * BPB;
@@ -185,9 +185,9 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t NB = NBh + NBd;
   const int32_t NQ = (nbr_here + 3) >> 2;  // quads of 4 branches
   const int32_t NC = (a.step >> 3) + 1;    // chunks of 8 positions that hold positions 0 .. step
-  const int32_t NBT = NB + NQ * NC;
+  const int32_t NTT = NQ * NC;
+  const int32_t NBT = NB + NTT;
   const int32_t NR = (NBT + STAGE_BLOCKS - 1) / STAGE_BLOCKS;
-
   // ---- rows
   const int32_t lr = rb * 32 + n;  // row within the row group
   const int32_t r_row = first_blk * 32 + lr;
@@ -268,10 +268,6 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       HPD_GLL(p3, dst + 192);
     }
   };
-  auto issue_round = [&](int32_t r, uint4* stage) {
-    if (loader) issue_block(r * STAGE_BLOCKS + (wave - CWAVES), stage + (wave - CWAVES) * SLOT_U4);
-  };
-
   // ---- fused mode: the compute waves append the newest token of the unit's branches (the
   //      arithmetic of hpd_kv_append), 8 lanes per branch: channels c .. c+7 and 64+c .. 64+c+7
   const int32_t ap_c = (tid & 7) * 8;
@@ -285,11 +281,12 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     r.vhi = *reinterpret_cast<const uint4*>(v_new + noff + 64 + ap_c);
     return r;
   };
-  auto append_store = [&](int32_t lb, const NewRows& r) {
+  auto append_store = [&](int32_t lb, const NewRows& r, bool use_rope_q) {
     const int32_t b = branch_id(lb);
     const int32_t pos = upos >= 0 ? upos : a.tb.branch_base_pos[b] + 1 + a.step;
     float rl[8], rh[8];
-    rotate16(r.klo, r.khi, a.tb.rope + (int64_t)pos * (D / 2), ap_c, rl, rh);
+    if (use_rope_q) rotate16(r.klo, r.khi, reinterpret_cast<const float2*>(rope_q), ap_c, rl, rh);
+    else rotate16(r.klo, r.khi, a.tb.rope + (int64_t)pos * (D / 2), ap_c, rl, rh);
     uint16_t* kd = k_tail + (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
     *reinterpret_cast<uint4*>(kd + ap_c) = __builtin_bit_cast(uint4, pack8(rl));
     *reinterpret_cast<uint4*>(kd + 64 + ap_c) = __builtin_bit_cast(uint4, pack8(rh));
@@ -298,20 +295,56 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     *reinterpret_cast<uint4*>(vd + 64 + ap_c) = r.vhi;
   };
   auto append_from = [&](int32_t lb0) {
-    for (int32_t lb = lb0; lb < nbr_here; lb += CWAVES * 8) append_store(lb, append_load(lb));
+    for (int32_t lb = lb0; lb < nbr_here; lb += CWAVES * 8) append_store(lb, append_load(lb), false);
   };
-  // Round x >= 2 is requested right after the barrier of round max(x - 3, 0), and the first
-  // tail tile sits in round NB / 2: the appending waves make sure their stores are complete
-  // before they enter that barrier (r_pub); until then the append runs beside the stream.
-  // Rounds 0 and 1 are requested before any barrier: if they would already hold tail tiles
-  // (a prefix of fewer than 4 blocks), the append is completed before anything is loaded.
+  // Tail tiles are requested after the barrier of round 0 at the earliest, unless the prefix
+  // has fewer than 4 blocks (rounds 0 and 1 are requested before any barrier).  The appending
+  // waves make sure their stores are complete before they enter that barrier; in the short
+  // case the append is completed before anything is loaded.
   const bool append_first = a.fused && NB < 2 * STAGE_BLOCKS;
-  const int32_t r_pub = (a.fused && !append_first && !loader) ? max(NB / STAGE_BLOCKS - 3, 0) : -1;
+  const int32_t r_pub = (a.fused && !append_first) ? 0 : -1;
   if (append_first) {
     if (!loader) append_from(tid >> 3);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
+
+  // =====================================================================================
+  // Loader waves: request round after round; meet the compute waves at every barrier
+  // =====================================================================================
+  if (loader) {
+    const int32_t lslot = wave - CWAVES;
+    auto issue_round = [&](int32_t r) {
+      const int32_t x = r & 3;  // stage of round r
+      uint4* stage = x == 0 ? ring0 : (x == 1 ? ring1 : (x == 2 ? ring2 : ring3));
+      issue_block(r * STAGE_BLOCKS + lslot, stage + lslot * SLOT_U4);
+    };
+    issue_round(0);
+    if (NR > 1) issue_round(1);
+    __builtin_amdgcn_s_barrier();  // the query rows are staged (stages 2 and 3 are taken until round 0)
+    for (int32_t r = 0; r < NR; ++r) {
+      // wait until round r has landed: the DMA instructions of a wave complete in order, every
+      // round is LOADS_PER_ROUND of them, and up to two newer rounds may stay in flight
+      const int32_t newer = r == 0 ? min(1, NR - 1) : min(2, NR - 1 - r);
+      if (newer >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
+      else if (newer == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_ROUND) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_s_barrier();  // round r is published; the stage of round r - 1 is free
+      if (r == 0) {
+        if (NR > 2) issue_round(2);
+        if (NR > 3) issue_round(3);
+      } else if (r + 3 < NR) {
+        issue_round(r + 3);
+      }
+    }
+    __syncthreads();              // end of the stream
+    if (KG > 1) __syncthreads();  // the exchange of the key groups
+    return;
+  }
+
+  // =====================================================================================
+  // Compute waves
+  // =====================================================================================
 
   // ---- the loaders start the DMA ring at once.  The compute waves - whose memory queues stay
   //      short, so that their loads come back with one latency - fetch the raw query rows of
@@ -319,13 +352,10 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   //      and stage 2 (rows 128..191), chunk c of row r at position c ^ (r & 15); one of them
   //      fetches the (cos, sin) row of the shared position.  The new rows of the append are
   //      requested in the same breath and stored after the query is rotated.
-  const bool append_late = a.fused && !append_first && !loader;
+  const bool append_late = a.fused && !append_first;
   const bool append_mine = append_late && (tid >> 3) < nbr_here;
   NewRows new_rows = {};
-  if (loader) {
-    issue_round(0, ring0);
-    if (NR > 1) issue_round(1, ring1);
-  } else {
+  {
     for (int32_t i0 = wave; i0 * 4 < rows_here; i0 += 4 * CWAVES) {
       uint4 v[4];
 #pragma unroll
@@ -349,6 +379,12 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
   __builtin_amdgcn_s_barrier();        // a bare barrier: __syncthreads() would drain the DMA queue
+
+  // ---- the append, before the rotation: the stores complete while the query is rotated
+  if (append_late) {
+    if (append_mine) append_store(tid >> 3, new_rows, upos >= 0);
+    append_from((tid >> 3) + CWAVES * 8);
+  }
 
   // ---- rotate the query: bf16 hi + lo MFMA B operands.  The softmax scale and the change to
   //      base 2 ride on the query: scores come out of the MFMA ready for exp2.
@@ -386,9 +422,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   };
   // (the stage is chosen by a wave-uniform branch, not by a pointer select: the compiler must
   // see which array is read, or it drains the DMA queue first)
-  if (loader) {
-    // nothing to rotate
-  } else if (upos >= 0) {
+  if (upos >= 0) {
     if (rb < 4) rotate_query(ring3, [&](int i4) -> float4 { return rope_q[i4]; });
     else rotate_query(ring2, [&](int i4) -> float4 { return rope_q[i4]; });
   } else {
@@ -399,10 +433,6 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const float4* cs_row = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)q_pos * (D / 2));
     if (rb < 4) rotate_query(ring3, [&](int i4) -> float4 { return cs_row[i4]; });
     else rotate_query(ring2, [&](int i4) -> float4 { return cs_row[i4]; });
-  }
-  if (append_late) {
-    if (append_mine) append_store(tid >> 3, new_rows);
-    append_from((tid >> 3) + CWAVES * 8);
   }
 
   // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
@@ -490,27 +520,11 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   auto first_bits = [](int32_t cnt) -> uint32_t { return (1u << min(max(cnt, 0), 8)) - 1u; };
   const int32_t lb_row = rb * BPB + n / G;  // this row's branch within the row group
 
-  // Round r: wait until its stage has landed (newer rounds may stay in flight: the DMA
-  // instructions of a wave complete in order and every loader issues LOADS_PER_ROUND per
-  // round), meet, refill the stage that was consumed last round, compute.
-  auto round_body = [&](int32_t r, const uint4* cur, uint4* refill, uint4* refill0) {
-    if (loader) {
-      const int32_t newer = r == 0 ? min(1, NR - 1) : min(2, NR - 1 - r);  // rounds requested after r
-      if (newer >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
-      else if (newer == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_ROUND) : "memory");
-      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    } else if (r == r_pub) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores of the append are complete
-    }
+  // Round r: meet the loaders (the stage has landed), compute.
+  auto round_body = [&](int32_t r, const uint4* cur) {
+    if (r == r_pub) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores of the append are complete
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS reads of the previous round are done
     __builtin_amdgcn_s_barrier();
-    if (r == 0) {
-      // the query staging in stages 2 and 3 has been consumed by every wave
-      if (NR > 2) issue_round(2, refill0);
-      if (NR > 3) issue_round(3, refill);
-    } else if (r + 3 < NR) {
-      issue_round(r + 3, refill);
-    }
     if (active) {
 #pragma nounroll
       for (int32_t j = 0; j < STAGE_BLOCKS; ++j) {
@@ -538,10 +552,10 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 
   // stage of round r is ring[r % 4]; round r refills ring[(r + 3) % 4] (consumed in round r-1)
   for (int32_t r = 0; r < NR; r += 4) {
-    round_body(r, ring0, ring3, ring2);
-    if (r + 1 < NR) round_body(r + 1, ring1, ring0, nullptr);
-    if (r + 2 < NR) round_body(r + 2, ring2, ring1, nullptr);
-    if (r + 3 < NR) round_body(r + 3, ring3, ring2, nullptr);
+    round_body(r, ring0);
+    if (r + 1 < NR) round_body(r + 1, ring1);
+    if (r + 2 < NR) round_body(r + 2, ring2);
+    if (r + 3 < NR) round_body(r + 3, ring3);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();  // all stages are dead from here on and get reused
