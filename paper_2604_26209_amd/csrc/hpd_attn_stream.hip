@@ -140,7 +140,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   __shared__ uint4 ring1[STAGE_U4];
   __shared__ uint4 ring2[STAGE_U4];
   __shared__ uint4 ring3[STAGE_U4];
-  __shared__ float4 rope_q[32];  // (cos, sin) row of the unit's shared position
+  __shared__ uint4 qstage[96 * 16];  // raw query rows, 96 (three row blocks) at a time: a pass
+  __shared__ float4 rope_q[32];      // (cos, sin) row of the unit's shared position
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
@@ -175,6 +176,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t br0 = first_blk * BPB;
   const int32_t nbr_here = min(nb - br0, nblk_here * BPB);
   const int32_t rows_here = nbr_here * G;
+  const int32_t q_passes = (rows_here + 95) / 96;  // the query rows are staged 96 at a time
   auto branch_id = [&](int32_t lb) -> int32_t {
     return ub0 >= 0 ? ub0 + br0 + lb : a.tb.live_branch[a.live_base + row0_live + br0 + lb];
   };
@@ -297,12 +299,12 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   auto append_from = [&](int32_t lb0) {
     for (int32_t lb = lb0; lb < nbr_here; lb += CWAVES * 8) append_store(lb, append_load(lb), false);
   };
-  // Tail tiles are requested after the barrier of round 0 at the earliest, unless the prefix
-  // has fewer than 4 blocks (rounds 0 and 1 are requested before any barrier).  The appending
-  // waves make sure their stores are complete before they enter that barrier; in the short
-  // case the append is completed before anything is loaded.
-  const bool append_first = a.fused && NB < 2 * STAGE_BLOCKS;
-  const int32_t r_pub = (a.fused && !append_first) ? 0 : -1;
+  // Rounds 0..3 are requested before any barrier; round x >= 4 after the barrier of round
+  // x - 3.  The appending waves make sure their stores are complete before they enter the
+  // barrier of round 1, so a prefix of at least 8 blocks keeps every tail tile behind it;
+  // with a shorter prefix the append is completed before anything is loaded.
+  const bool append_first = a.fused && NB < 4 * STAGE_BLOCKS;
+  const int32_t r_pub = (a.fused && !append_first) ? 1 : -1;
   if (append_first) {
     if (!loader) append_from(tid >> 3);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -319,23 +321,21 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       uint4* stage = x == 0 ? ring0 : (x == 1 ? ring1 : (x == 2 ? ring2 : ring3));
       issue_block(r * STAGE_BLOCKS + lslot, stage + lslot * SLOT_U4);
     };
-    issue_round(0);
-    if (NR > 1) issue_round(1);
-    __builtin_amdgcn_s_barrier();  // the query rows are staged (stages 2 and 3 are taken until round 0)
+    // half the ring, the barriers of the query staging (the compute waves must not wait for a
+    // loader that is stuck in the queue), the other half
+    for (int32_t r = 0; r < min(NR, 2); ++r) issue_round(r);
+    for (int32_t b = 0; b < 2 * q_passes - 1; ++b) __builtin_amdgcn_s_barrier();
+    for (int32_t r = 2; r < min(NR, 4); ++r) issue_round(r);
     for (int32_t r = 0; r < NR; ++r) {
       // wait until round r has landed: the DMA instructions of a wave complete in order, every
-      // round is LOADS_PER_ROUND of them, and up to two newer rounds may stay in flight
-      const int32_t newer = r == 0 ? min(1, NR - 1) : min(2, NR - 1 - r);
-      if (newer >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
+      // round is LOADS_PER_ROUND of them, and the newer rounds may stay in flight
+      const int32_t newer = r == 0 ? min(3, NR - 1) : min(2, NR - 1 - r);
+      if (newer >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LOADS_PER_ROUND) : "memory");
+      else if (newer == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
       else if (newer == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_ROUND) : "memory");
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();  // round r is published; the stage of round r - 1 is free
-      if (r == 0) {
-        if (NR > 2) issue_round(2);
-        if (NR > 3) issue_round(3);
-      } else if (r + 3 < NR) {
-        issue_round(r + 3);
-      }
+      if (r > 0 && r + 3 < NR) issue_round(r + 3);
     }
     __syncthreads();              // end of the stream
     if (KG > 1) __syncthreads();  // the exchange of the key groups
@@ -346,51 +346,34 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // Compute waves
   // =====================================================================================
 
-  // ---- the loaders start the DMA ring at once.  The compute waves - whose memory queues stay
-  //      short, so that their loads come back with one latency - fetch the raw query rows of
-  //      the row group, 4 whole rows per instruction, and park them in stage 3 (rows 0..127)
-  //      and stage 2 (rows 128..191), chunk c of row r at position c ^ (r & 15); one of them
-  //      fetches the (cos, sin) row of the shared position.  The new rows of the append are
-  //      requested in the same breath and stored after the query is rotated.
+  // ---- the loaders fill the ring.  The compute waves - whose memory queues stay short,
+  //      so that their loads come back with one latency - fetch the raw query rows of the row
+  //      group, 4 whole rows per instruction, and pass them through `qstage` 96 rows at a time,
+  //      chunk c of row r at position c ^ (r & 15): a pass is written by everybody and read by
+  //      the waves of its three row blocks.  One wave fetches the (cos, sin) row of the shared
+  //      position.  The new rows of the append are requested in the same breath.
   const bool append_late = a.fused && !append_first;
   const bool append_mine = append_late && (tid >> 3) < nbr_here;
   NewRows new_rows = {};
-  {
-    for (int32_t i0 = wave; i0 * 4 < rows_here; i0 += 4 * CWAVES) {
-      uint4 v[4];
+  uint4 qv[8];  // instruction i = wave + 6 b covers rows 4 i .. 4 i + 3 (MAX_BLOCKS * 32 = 192 rows = 48 instructions)
 #pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        v[b] = make_uint4(0, 0, 0, 0);
-        const int32_t i = i0 + b * CWAVES;
-        const int32_t urow = first_blk * 32 + min(i * 4 + r4, rows_here - 1);  // row within the unit
-        const int64_t off = ((int64_t)(row0_live + urow / G) * a.Hq + hk * G + urow % G) * D;
-        if (i * 4 < rows_here) v[b] = *reinterpret_cast<const uint4*>(q + off + (c16 << 3));
-      }
-      if (i0 == wave && append_mine) new_rows = append_load(tid >> 3);
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const int32_t i = i0 + b * CWAVES;
-        const int32_t row = i * 4 + r4;
-        if (i * 4 < rows_here) (row < 128 ? ring3 : ring2)[(row & 127) * 16 + (c16 ^ (row & 15))] = v[b];
-      }
-    }
-    if (upos >= 0 && wave == 0 && lane < 32)
-      rope_q[lane] = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)upos * (D / 2))[lane];
+  for (int b = 0; b < 8; ++b) {
+    qv[b] = make_uint4(0, 0, 0, 0);
+    const int32_t i = wave + b * CWAVES;
+    const int32_t urow = first_blk * 32 + min(i * 4 + r4, rows_here - 1);  // row within the unit
+    const int64_t off = ((int64_t)(row0_live + urow / G) * a.Hq + hk * G + urow % G) * D;
+    if (i * 4 < rows_here) qv[b] = *reinterpret_cast<const uint4*>(q + off + (c16 << 3));
   }
-  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
-  __builtin_amdgcn_s_barrier();        // a bare barrier: __syncthreads() would drain the DMA queue
-
-  // ---- the append, before the rotation: the stores complete while the query is rotated
-  if (append_late) {
-    if (append_mine) append_store(tid >> 3, new_rows, upos >= 0);
-    append_from((tid >> 3) + CWAVES * 8);
-  }
+  if (append_mine) new_rows = append_load(tid >> 3);
+  float4 rope_v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (upos >= 0 && wave == 0 && lane < 32)
+    rope_v = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)upos * (D / 2))[lane];
 
   // ---- rotate the query: bf16 hi + lo MFMA B operands.  The softmax scale and the change to
   //      base 2 ride on the query: scores come out of the MFMA ready for exp2.
   bf16x8 Qh[8], Ql[8];
-  auto rotate_query = [&](const uint4* stage, auto cos_sin) {
-    const uint4* qrow = stage + (lr & 127) * 16;
+  auto rotate_query = [&](auto cos_sin) {
+    const uint4* qrow = qstage + (lr % 96) * 16;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       uint4 rlo = make_uint4(0, 0, 0, 0), rhi = make_uint4(0, 0, 0, 0);
@@ -420,19 +403,41 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       Ql[kk + 4] = pack8(rh);
     }
   };
-  // (the stage is chosen by a wave-uniform branch, not by a pointer select: the compiler must
-  // see which array is read, or it drains the DMA queue first)
-  if (upos >= 0) {
-    if (rb < 4) rotate_query(ring3, [&](int i4) -> float4 { return rope_q[i4]; });
-    else rotate_query(ring2, [&](int i4) -> float4 { return rope_q[i4]; });
-  } else {
-    // per-branch positions: straight from the table (in a loader wave this load queues behind
-    // the DMA: the slow path)
-    const int32_t q_bi = min(r_row / G, nb - 1);
-    const int32_t q_pos = a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
-    const float4* cs_row = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)q_pos * (D / 2));
-    if (rb < 4) rotate_query(ring3, [&](int i4) -> float4 { return cs_row[i4]; });
-    else rotate_query(ring2, [&](int i4) -> float4 { return cs_row[i4]; });
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    Qh[kk] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+    Ql[kk] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+  }
+  for (int32_t pass = 0; pass < q_passes; ++pass) {
+    if (pass > 0) {
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave has read what it needed of the last pass
+      __builtin_amdgcn_s_barrier();
+    }
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const int32_t i = wave + b * CWAVES;
+      const int32_t row = i * 4 + r4;
+      if (i * 4 < rows_here && i / 24 == pass) qstage[(row % 96) * 16 + (c16 ^ (row & 15))] = qv[b];
+    }
+    if (pass == 0 && upos >= 0 && wave == 0 && lane < 32) rope_q[lane] = rope_v;
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
+    __builtin_amdgcn_s_barrier();        // bare barriers: __syncthreads() would wait for every store
+    if (pass == 0 && append_late) {
+      // the append, before the rotation: the stores complete while the query is rotated
+      if (append_mine) append_store(tid >> 3, new_rows, upos >= 0);
+      append_from((tid >> 3) + CWAVES * 8);
+    }
+    if (rb / 3 == pass) {
+      if (upos >= 0) {
+        rotate_query([&](int i4) -> float4 { return rope_q[i4]; });
+      } else {
+        // per-branch positions: straight from the table
+        const int32_t q_bi = min(r_row / G, nb - 1);
+        const int32_t q_pos = a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
+        const float4* cs_row = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)q_pos * (D / 2));
+        rotate_query([&](int i4) -> float4 { return cs_row[i4]; });
+      }
+    }
   }
 
   // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
