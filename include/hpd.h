@@ -212,8 +212,10 @@ int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, u
                     int32_t* s_out, void* stream);
 
 /* Selects the attention kernel: 0 = automatic, 1 = generic wave-reduction kernel for
- * everything, 2 = LDS-streaming MFMA kernel (HPD_E_UNSUPPORTED if the shape does not
- * allow it: it needs bf16, head_dim 128 and a group size of 1, 2, 4 or 8). */
+ * everything, 2 = LDS-streaming MFMA kernel, workgroup shape chosen per launch, 3 / 4 = the
+ * same with the wide / the narrow workgroup shape forced (2..4 return HPD_E_UNSUPPORTED if
+ * the shape does not allow the kernel: it needs bf16, head_dim 128 and a group size of 1,
+ * 2, 4 or 8). */
 int hpd_set_kernel_mode(hpd_layout* layout, int32_t mode);
 
 const char* hpd_status_string(int status);

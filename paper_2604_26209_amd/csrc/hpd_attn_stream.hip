@@ -60,6 +60,7 @@
 //    stream; the first barrier of the ring publishes them, and the tail tiles - which are
 //    last in the stream - read them back like any other token.  Both modes therefore add up
 //    in the same order and give identical bits.
+#include <algorithm>
 #include <cmath>
 
 #include "hpd_internal.h"
@@ -73,15 +74,29 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int D = 128;
-constexpr int WAVES = 8;
-constexpr int CWAVES = 6;              // waves 0..5 compute
-constexpr int LOADERS = WAVES - CWAVES;  // waves 6, 7 only issue the DMA
-constexpr int MAX_BLOCKS = CWAVES;     // row blocks per workgroup
-constexpr int SLOT_U4 = 16 * 64;       // one 32-key block: 8 K + 8 V fragments of 64 x 16 bytes
-constexpr int STAGE_BLOCKS = 2;
-constexpr int STAGE_U4 = STAGE_BLOCKS * SLOT_U4;  // 32 KB
-constexpr int LOADS_PER_ROUND = STAGE_BLOCKS * 16 / LOADERS;  // DMA instructions per loader wave per round
+constexpr int SLOT_U4 = 16 * 64;  // one 32-key block: 8 K + 8 V fragments of 64 x 16 bytes
 constexpr float NEG_BIG = -1.0e30f;
+
+// Two shapes of workgroup:
+//   wide    6 compute waves + 2 loaders, stages of two blocks: 128.5 KB of LDS, one workgroup
+//           per CU.  For launches with about one unit per CU: all of the CU's resources go
+//           into streaming that one unit.
+//   narrow  3 compute waves + 1 loader, stages of one block: 64.5 KB of LDS, two workgroups
+//           per CU.  For launches with many units per CU: the start (query staging, rotation)
+//           and the end (merge, stores) of one unit overlap with the stream of another.
+template <int CW_, int LW_, int SB_>
+struct Shape {
+  static constexpr int CW = CW_;                 // compute waves (waves 0 .. CW-1)
+  static constexpr int LW = LW_;                 // loader waves (waves CW ..)
+  static constexpr int SB = SB_;                 // blocks per stage
+  static constexpr int WAVES = CW + LW;
+  static constexpr int STAGE_U4 = SB * SLOT_U4;
+  static constexpr int STAGE_ROWS = STAGE_U4 / 16;        // 256-byte rows a stage can hold
+  static constexpr int LOADS_PER_ROUND = SB * 16 / LW;    // DMA instructions per loader wave per round
+  static constexpr int MAX_BLOCKS = CW;                   // row blocks per workgroup
+};
+using WideShape = Shape<6, 2, 2>;
+using NarrowShape = Shape<3, 1, 1>;
 
 struct StreamArgs {
   hpd_dev_tables tb;
@@ -127,21 +142,24 @@ __device__ __forceinline__ void rotate16(uint4 raw_lo, uint4 raw_hi, const float
   }
 }
 
-template <int G>
-__global__ void __launch_bounds__(WAVES * 64)
+template <int G, typename SH>
+__global__ void __launch_bounds__(SH::WAVES * 64, 2)
 attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_prefix,
                    const uint16_t* __restrict__ v_prefix, uint16_t* __restrict__ k_tail,
                    uint16_t* __restrict__ v_tail, const uint16_t* __restrict__ k_new,
                    const uint16_t* __restrict__ v_new, void* __restrict__ out) {
   constexpr int BPB = 32 / G;              // branches per row block
   constexpr int QPR = G >= 8 ? 1 : 8 / G;  // branch quads (tail tiles per 8 positions) per row block
+  constexpr int CWAVES = SH::CW, LOADERS = SH::LW, STAGE_BLOCKS = SH::SB, STAGE_U4 = SH::STAGE_U4;
+  constexpr int LOADS_PER_ROUND = SH::LOADS_PER_ROUND, STAGE_ROWS = SH::STAGE_ROWS;
+  static_assert(2 * STAGE_ROWS >= CWAVES * 32, "stages 2 and 3 must hold the query rows of a row group");
+  static_assert(3 * LOADS_PER_ROUND <= 63, "three rounds in flight must fit the vmcnt counter");
 
   __shared__ uint4 ring0[STAGE_U4];
   __shared__ uint4 ring1[STAGE_U4];
   __shared__ uint4 ring2[STAGE_U4];
   __shared__ uint4 ring3[STAGE_U4];
-  __shared__ uint4 qstage[96 * 16];  // raw query rows, 96 (three row blocks) at a time: a pass
-  __shared__ float4 rope_q[32];      // (cos, sin) row of the unit's shared position
+  __shared__ float4 rope_q[32];  // (cos, sin) row of the unit's shared position
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
@@ -163,12 +181,15 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t first_blk = rg * per_group;
   const int32_t nblk_here = min(per_group, nblk - first_blk);
   if (nblk_here <= 0) return;  // uniform over the workgroup
-  // 6 compute waves = (row block) x (key group): 1 row block x 4 key groups, 2 x 3, 3 x 2,
-  // or up to 6 x 1
-  const int32_t KG = nblk_here == 1 ? 4 : (nblk_here == 2 ? 3 : (nblk_here == 3 ? 2 : 1));
-  const int32_t NRB = nblk_here <= 3 ? nblk_here : CWAVES;  // row-block slots
+  // compute waves = (row block) x (key group), with as many key groups (at most 4) as fit:
+  // 6 waves: 1 row block x 4, 2 x 3, 3 x 2, 4..6 x 1; 3 waves: 1 x 3, 2..3 x 1
+  int32_t KG = 1;
+  for (int32_t k = 2; k <= 4; ++k)
+    if (k * nblk_here <= CWAVES) KG = k;
+  const int32_t NRB = KG == 1 ? CWAVES : nblk_here;  // row-block slots
   const bool loader = wave >= CWAVES;
-  const int32_t kg = NRB == 1 ? wave : (NRB == 2 ? wave >> 1 : (NRB == 3 ? (wave >= 3 ? 1 : 0) : 0));
+  int32_t kg = 0;
+  while ((kg + 1) * NRB <= wave) ++kg;
   const int32_t rb = wave - kg * NRB;
   const bool active = kg < KG && rb < nblk_here;
 
@@ -176,7 +197,6 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t br0 = first_blk * BPB;
   const int32_t nbr_here = min(nb - br0, nblk_here * BPB);
   const int32_t rows_here = nbr_here * G;
-  const int32_t q_passes = (rows_here + 95) / 96;  // the query rows are staged 96 at a time
   auto branch_id = [&](int32_t lb) -> int32_t {
     return ub0 >= 0 ? ub0 + br0 + lb : a.tb.live_branch[a.live_base + row0_live + br0 + lb];
   };
@@ -315,16 +335,18 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // Loader waves: request round after round; meet the compute waves at every barrier
   // =====================================================================================
   if (loader) {
-    const int32_t lslot = wave - CWAVES;
     auto issue_round = [&](int32_t r) {
       const int32_t x = r & 3;  // stage of round r
       uint4* stage = x == 0 ? ring0 : (x == 1 ? ring1 : (x == 2 ? ring2 : ring3));
-      issue_block(r * STAGE_BLOCKS + lslot, stage + lslot * SLOT_U4);
+      for (int32_t j = wave - CWAVES; j < STAGE_BLOCKS; j += LOADERS)
+        issue_block(r * STAGE_BLOCKS + j, stage + j * SLOT_U4);
     };
-    // half the ring, the barriers of the query staging (the compute waves must not wait for a
-    // loader that is stuck in the queue), the other half
+    // half the ring; the two barriers of the query staging, which borrows stages 2 and 3 (and
+    // the compute waves must not wait there for a loader that is stuck in the queue); the
+    // other half
     for (int32_t r = 0; r < min(NR, 2); ++r) issue_round(r);
-    for (int32_t b = 0; b < 2 * q_passes - 1; ++b) __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_s_barrier();
     for (int32_t r = 2; r < min(NR, 4); ++r) issue_round(r);
     for (int32_t r = 0; r < NR; ++r) {
       // wait until round r has landed: the DMA instructions of a wave complete in order, every
@@ -346,16 +368,16 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // Compute waves
   // =====================================================================================
 
-  // ---- the loaders fill the ring.  The compute waves - whose memory queues stay short,
-  //      so that their loads come back with one latency - fetch the raw query rows of the row
-  //      group, 4 whole rows per instruction, and pass them through `qstage` 96 rows at a time,
-  //      chunk c of row r at position c ^ (r & 15): a pass is written by everybody and read by
-  //      the waves of its three row blocks.  One wave fetches the (cos, sin) row of the shared
-  //      position.  The new rows of the append are requested in the same breath.
+  // ---- the loaders fill the ring.  The compute waves - whose memory queues stay short, so that
+  //      their loads come back with one latency - fetch the raw query rows of the row group, 4
+  //      whole rows per instruction, and exchange them through stages 2 and 3 (which the
+  //      loaders leave alone until the second barrier): chunk c of row r at position
+  //      c ^ (r & 15).  One wave fetches the (cos, sin) row of the shared position.  The new
+  //      rows of the append are requested in the same breath.
   const bool append_late = a.fused && !append_first;
   const bool append_mine = append_late && (tid >> 3) < nbr_here;
   NewRows new_rows = {};
-  uint4 qv[8];  // instruction i = wave + 6 b covers rows 4 i .. 4 i + 3 (MAX_BLOCKS * 32 = 192 rows = 48 instructions)
+  uint4 qv[8];  // instruction i = wave + CWAVES * b covers rows 4 i .. 4 i + 3 (32 * CWAVES rows at most)
 #pragma unroll
   for (int b = 0; b < 8; ++b) {
     qv[b] = make_uint4(0, 0, 0, 0);
@@ -368,22 +390,43 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   float4 rope_v = make_float4(0.f, 0.f, 0.f, 0.f);
   if (upos >= 0 && wave == 0 && lane < 32)
     rope_v = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)upos * (D / 2))[lane];
+#pragma unroll
+  for (int b = 0; b < 8; ++b) {
+    const int32_t i = wave + b * CWAVES;
+    const int32_t row = i * 4 + r4;
+    if (i * 4 < rows_here)
+      (row < STAGE_ROWS ? ring2 : ring3)[(row % STAGE_ROWS) * 16 + (c16 ^ (row & 15))] = qv[b];
+  }
+  if (upos >= 0 && wave == 0 && lane < 32) rope_q[lane] = rope_v;
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
+  __builtin_amdgcn_s_barrier();        // bare barriers: __syncthreads() would wait for every store
+  uint4 qraw[8];
+  {
+    const uint4* qrow = (lr < STAGE_ROWS ? ring2 : ring3) + (lr % STAGE_ROWS) * 16;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      qraw[kk] = make_uint4(0, 0, 0, 0);
+      if (row_valid) qraw[kk] = qrow[(kk * 2 + g2) ^ (lr & 15)];
+    }
+  }
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave has its rows
+  __builtin_amdgcn_s_barrier();        // stages 2 and 3 go back to the loaders
+
+  // ---- the append, before the rotation: the stores complete while the query is rotated
+  if (append_late) {
+    if (append_mine) append_store(tid >> 3, new_rows, upos >= 0);
+    append_from((tid >> 3) + CWAVES * 8);
+  }
 
   // ---- rotate the query: bf16 hi + lo MFMA B operands.  The softmax scale and the change to
   //      base 2 ride on the query: scores come out of the MFMA ready for exp2.
   bf16x8 Qh[8], Ql[8];
   auto rotate_query = [&](auto cos_sin) {
-    const uint4* qrow = qstage + (lr % 96) * 16;
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      uint4 rlo = make_uint4(0, 0, 0, 0), rhi = make_uint4(0, 0, 0, 0);
-      if (row_valid) {
-        rlo = qrow[(kk * 2 + g2) ^ (lr & 15)];
-        rhi = qrow[((kk + 4) * 2 + g2) ^ (lr & 15)];
-      }
       float lo[8], hi[8], rl[8], rh[8];
-      unpack8(rlo, lo);
-      unpack8(rhi, hi);
+      unpack8(qraw[kk], lo);
+      unpack8(qraw[kk + 4], hi);
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {
         const float4 cs = cos_sin(kk * 8 + g2 * 4 + e2);  // pairs kk*16 + g2*8 + 2*e2, +1
@@ -403,41 +446,14 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       Ql[kk + 4] = pack8(rh);
     }
   };
-#pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    Qh[kk] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
-    Ql[kk] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
-  }
-  for (int32_t pass = 0; pass < q_passes; ++pass) {
-    if (pass > 0) {
-      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave has read what it needed of the last pass
-      __builtin_amdgcn_s_barrier();
-    }
-#pragma unroll
-    for (int b = 0; b < 8; ++b) {
-      const int32_t i = wave + b * CWAVES;
-      const int32_t row = i * 4 + r4;
-      if (i * 4 < rows_here && i / 24 == pass) qstage[(row % 96) * 16 + (c16 ^ (row & 15))] = qv[b];
-    }
-    if (pass == 0 && upos >= 0 && wave == 0 && lane < 32) rope_q[lane] = rope_v;
-    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
-    __builtin_amdgcn_s_barrier();        // bare barriers: __syncthreads() would wait for every store
-    if (pass == 0 && append_late) {
-      // the append, before the rotation: the stores complete while the query is rotated
-      if (append_mine) append_store(tid >> 3, new_rows, upos >= 0);
-      append_from((tid >> 3) + CWAVES * 8);
-    }
-    if (rb / 3 == pass) {
-      if (upos >= 0) {
-        rotate_query([&](int i4) -> float4 { return rope_q[i4]; });
-      } else {
-        // per-branch positions: straight from the table
-        const int32_t q_bi = min(r_row / G, nb - 1);
-        const int32_t q_pos = a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
-        const float4* cs_row = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)q_pos * (D / 2));
-        rotate_query([&](int i4) -> float4 { return cs_row[i4]; });
-      }
-    }
+  if (upos >= 0) {
+    rotate_query([&](int i4) -> float4 { return rope_q[i4]; });
+  } else {
+    // per-branch positions: straight from the table
+    const int32_t q_bi = min(r_row / G, nb - 1);
+    const int32_t q_pos = a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
+    const float4* cs_row = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)q_pos * (D / 2));
+    rotate_query([&](int i4) -> float4 { return cs_row[i4]; });
   }
 
   // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
@@ -574,6 +590,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     float* const park1 = reinterpret_cast<float*>(ring1);
     float* const park2 = reinterpret_cast<float*>(ring2);
     float* const park3 = reinterpret_cast<float*>(ring3);
+    static_assert(STAGE_U4 * 16 >= (CWAVES > 4 ? 2 : 1) * 50 * 64 * 4, "a stage holds the regions of its waves");
     auto region = [&](int32_t w) -> float* {
       float* base = (w & 2) ? ((w & 1) ? park3 : park2) : ((w & 1) ? park1 : park0);
       return base + (w >> 2) * (50 * 64) + lane;
@@ -655,11 +672,11 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   }
 }
 
-template <int G>
-hipError_t launch_g(const StreamArgs& a, dim3 grid, const void* q, const void* k_prefix,
+template <int G, typename SH>
+hipError_t launch_g(const StreamArgs& a, int64_t items, const void* q, const void* k_prefix,
                     const void* v_prefix, void* k_tail, void* v_tail, const void* k_new,
                     const void* v_new, void* out, hipStream_t s) {
-  attn_stream_kernel<G><<<grid, WAVES * 64, 0, s>>>(
+  attn_stream_kernel<G, SH><<<dim3((unsigned)items), SH::WAVES * 64, 0, s>>>(
       a, (const uint16_t*)q, (const uint16_t*)k_prefix, (const uint16_t*)v_prefix, (uint16_t*)k_tail,
       (uint16_t*)v_tail, (const uint16_t*)k_new, (const uint16_t*)v_new, out);
   return hipGetLastError();
@@ -681,21 +698,37 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   a.step = step; a.Hq = L->cfg.n_q_heads; a.Hkv = L->cfg.n_kv_heads;
   const int G = a.Hq / a.Hkv;
   a.Tcap = L->T; a.P = L->P; a.n_docs = L->n_docs; a.NP = L->NP;
-  const int32_t max_nblk = (L->max_rows[step] * G + 31) / 32;
-  a.RG = (max_nblk + MAX_BLOCKS - 1) / MAX_BLOCKS;
-  if (a.RG < 1) a.RG = 1;
   a.out_f32 = L->cfg.out_dtype == HPD_OUT_F32 ? 1 : 0;
   a.fused = (k_new != nullptr) ? 1 : 0;
   a.live_base = L->live_ptr[step];
   a.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)D));
   a.tb.unit_desc = L->dev.unit_desc + (int64_t)L->unit_ptr[step] * 8;
-  const int32_t n_units = L->unit_ptr[step + 1] - L->unit_ptr[step];
-  const dim3 grid((unsigned)((int64_t)n_units * a.Hkv * a.RG));
+  const int64_t n_units = L->unit_ptr[step + 1] - L->unit_ptr[step];
+  const int32_t max_nblk = std::max(1, (L->max_rows[step] * G + 31) / 32);
+  // row groups per unit, and with them the number of workgroups, for the two shapes
+  const int32_t rg_wide = (max_nblk + WideShape::MAX_BLOCKS - 1) / WideShape::MAX_BLOCKS;
+  const int32_t rg_narrow = (max_nblk + NarrowShape::MAX_BLOCKS - 1) / NarrowShape::MAX_BLOCKS;
+  const int64_t items_wide = n_units * a.Hkv * rg_wide;
+  // kernel_mode 3 / 4 force a shape; otherwise the narrow shape from two workgroups per CU on,
+  // unless the units have so many rows (more than two narrow row groups) that the launch is
+  // bound by the matrix pipes and splitting the rows further only re-streams the prefix
+  int dev = 0, cus = 256;
+  (void)hipGetDevice(&dev);
+  (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  bool narrow = items_wide >= 2 * (int64_t)cus && max_nblk <= 2 * NarrowShape::MAX_BLOCKS;
+  if (L->kernel_mode == 3) narrow = false;
+  if (L->kernel_mode == 4) narrow = true;
+  a.RG = narrow ? rg_narrow : rg_wide;
+  const int64_t items = n_units * a.Hkv * a.RG;
+#define HPD_LAUNCH(GG)                                                                              \
+  (narrow ? launch_g<GG, NarrowShape>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s) \
+          : launch_g<GG, WideShape>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s))
   switch (G) {
-    case 1: return launch_g<1>(a, grid, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s);
-    case 2: return launch_g<2>(a, grid, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s);
-    case 4: return launch_g<4>(a, grid, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s);
-    case 8: return launch_g<8>(a, grid, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s);
+    case 1: return HPD_LAUNCH(1);
+    case 2: return HPD_LAUNCH(2);
+    case 4: return HPD_LAUNCH(4);
+    case 8: return HPD_LAUNCH(8);
     default: return hipErrorInvalidValue;
   }
+#undef HPD_LAUNCH
 }

@@ -348,8 +348,8 @@ int hpd_layout_query(const hpd_layout* L, int32_t what, void* host_out, size_t b
 }
 
 int hpd_set_kernel_mode(hpd_layout* L, int32_t mode) {
-  if (!L || mode < 0 || mode > 2) return HPD_E_INVALID;
-  if (mode == 2 && !hpd_stream_supported(L)) return HPD_E_UNSUPPORTED;
+  if (!L || mode < 0 || mode > 4) return HPD_E_INVALID;
+  if (mode >= 2 && !hpd_stream_supported(L)) return HPD_E_UNSUPPORTED;
   L->kernel_mode = mode;
   return HPD_OK;
 }
@@ -400,7 +400,7 @@ int hpd_decode_attention(const hpd_layout* L, int32_t step, const void* q, const
   const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
   if (n_live == 0) return HPD_OK;
   if (!q || !k_prefix || !v_prefix || !k_tail || !v_tail || !out) return HPD_E_INVALID;
-  const bool use_stream = L->kernel_mode == 2 || (L->kernel_mode == 0 && hpd_stream_supported(L));
+  const bool use_stream = L->kernel_mode >= 2 || (L->kernel_mode == 0 && hpd_stream_supported(L));
   if (use_stream) {
     HPD_HIP(hpd_launch_attention_stream(L, step, q, k_prefix, v_prefix, const_cast<void*>(k_tail),
                                         const_cast<void*>(v_tail), nullptr, nullptr, out,
@@ -429,7 +429,7 @@ int hpd_decode_step(const hpd_layout* L, int32_t step, const void* q, const void
   if (n_live == 0) return HPD_OK;
   if (!q || !k_new || !v_new || !k_prefix || !v_prefix || !k_tail || !v_tail || !out)
     return HPD_E_INVALID;
-  if (L->kernel_mode == 2 || (L->kernel_mode == 0 && hpd_stream_supported(L))) {
+  if (L->kernel_mode >= 2 || (L->kernel_mode == 0 && hpd_stream_supported(L))) {
     // one launch: the attention kernel rotates, stores and uses the new keys itself
     HPD_HIP(hpd_launch_attention_stream(L, step, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new,
                                         out, (hipStream_t)stream));

@@ -44,11 +44,11 @@ def test_fp32_other_head_dims_and_empty_header():
         H.check_all(wl, H.run_hip(wl), label=f"f32_D{d}")
 
 
-@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("mode", [1, 2, 3, 4])
 @pytest.mark.parametrize("seed", [11, 12])
 def test_random_ragged_bf16_both_kernels(seed, mode):
     """mode 1 = generic wave-reduction kernel, 2 = LDS-streaming MFMA kernel (the default for
-    this shape)."""
+    this shape), 3 / 4 = the same with the wide / narrow workgroup shape forced."""
     _say(f"random bf16 seed {seed} mode {mode}")
     wl = W.random_workload(seed, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=5, p=3,
                            h_range=(0, 70), l_range=(1, 150), n_range=(1, 12))
@@ -57,15 +57,16 @@ def test_random_ragged_bf16_both_kernels(seed, mode):
     _say(f"  worst err/rms {rel:.2e}")
 
 
+@pytest.mark.parametrize("mode", [3, 4])
 @pytest.mark.parametrize("g", [1, 2, 4, 8])
-def test_stream_kernel_fused_step_equals_two_calls(g):
+def test_stream_kernel_fused_step_equals_two_calls(g, mode):
     """hpd_decode_step (one launch, append inside the attention kernel) against
     hpd_kv_append + hpd_decode_attention: same tail pools, same outputs, bit for bit."""
-    _say(f"stream fused vs two-call G={g}")
+    _say(f"stream fused vs two-call G={g} mode {mode}")
     wl = W.random_workload(60 + g, dtype="bf16", hq=8, hkv=8 // g, d=128, base=500000.0, t=6, p=3,
                            h_range=(0, 90), l_range=(1, 300), n_range=(1, 14))
-    a = H.run_hip(wl, kernel_mode=2, fused=False, poison_pools="zero")
-    b = H.run_hip(wl, inputs=a["inputs"], kernel_mode=2, fused=True, poison_pools="zero")
+    a = H.run_hip(wl, kernel_mode=mode, fused=False, poison_pools="zero")
+    b = H.run_hip(wl, inputs=a["inputs"], kernel_mode=mode, fused=True, poison_pools="zero")
     for x, y in zip(a["out"], b["out"]):
         assert torch.equal(x, y)
     for x, y in zip(a["pools"][2:], b["pools"][2:]):
@@ -78,7 +79,7 @@ def test_bf16_output_is_the_fp32_output_rounded_once():
     """out_dtype = SAME writes RNE(bf16) of exactly the values out_dtype = F32 writes."""
     _say("bf16 out == rne(fp32 out)")
     wl = W.config(2, n_prompts=3)
-    for mode in (1, 2):
+    for mode in (1, 3, 4):
         a = H.run_hip(wl, kernel_mode=mode, out_f32=True)
         b = H.run_hip(wl, inputs=a["inputs"], kernel_mode=mode, out_f32=False)
         for x, y in zip(a["out"], b["out"]):
@@ -97,10 +98,11 @@ def test_mfma_edge_shapes():
         "nine_row_blocks": W.make_workload("e7", "bf16", 8, 1, 128, 500000.0, 2, [10], [2], [50, 45], [35, 3]),
     }
     for name, wl in cases.items():
-        for fused in (False, True):
-            _say(f"mfma edge {name} fused {fused}")
-            hip = H.run_hip(wl, kernel_mode=2, fused=fused)
-            H.check_all(wl, hip, label=name)
+        for mode in (3, 4):
+            for fused in (False, True):
+                _say(f"mfma edge {name} mode {mode} fused {fused}")
+                hip = H.run_hip(wl, kernel_mode=mode, fused=fused)
+                H.check_all(wl, hip, label=name)
 
 
 def test_paper_gap_positions_mode():
