@@ -210,6 +210,25 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t NTT = NQ * NC;
   const int32_t NBT = NB + NTT;
   const int32_t NR = (NBT + STAGE_BLOCKS - 1) / STAGE_BLOCKS;
+  // A round is one stage while the stream is in the prefix and two stages from the first
+  // tail tile on: a tail tile keeps a single wave busy (a prefix block: a whole key group),
+  // so the more tiles meet in a round, the more waves work on them side by side.  Two stages
+  // are what the ring allows (the other two are in flight).
+  const int32_t s_tail = NB / STAGE_BLOCKS;  // first stage that holds a tail tile
+  auto round_end = [&](int32_t s0) -> int32_t { return s0 < s_tail ? s0 + 1 : min(s0 + 2, NR); };
+  // Tail tile tt is chunk tt / NQ (8 positions) of the quad of branches quad_of(tt % NQ): the
+  // quads are taken row block by row block first (the first quad of every row block, then the
+  // second, ...), so that neighbouring tiles go to different waves.
+  auto quad_of = [&](int32_t o) -> int32_t {
+    int32_t m = 0;
+    for (;;) {
+      const int32_t n_m = (NQ - m + QPR - 1) / QPR;  // quads whose index within the row block is m
+      if (o < n_m) break;
+      o -= n_m;
+      ++m;
+    }
+    return o * QPR + m;
+  };
   // ---- rows
   const int32_t lr = rb * 32 + n;  // row within the row group
   const int32_t r_row = first_blk * 32 + lr;
@@ -249,7 +268,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       // end repeat the last valid one (masked by the consumer).
       const int32_t tt = gb - NB;
       tc = tt / NQ;
-      tq = tt - tc * NQ;
+      tq = quad_of(tt - tc * NQ);
     }
 #pragma nounroll
     for (int32_t part = 0; part < 4; ++part) {
@@ -344,20 +363,23 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     // half the ring; the two barriers of the query staging, which borrows stages 2 and 3 (and
     // the compute waves must not wait there for a loader that is stuck in the queue); the
     // other half
-    for (int32_t r = 0; r < min(NR, 2); ++r) issue_round(r);
+    int32_t issued = 0;
+    for (; issued < min(NR, 2); ++issued) issue_round(issued);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_s_barrier();
-    for (int32_t r = 2; r < min(NR, 4); ++r) issue_round(r);
-    for (int32_t r = 0; r < NR; ++r) {
-      // wait until round r has landed: the DMA instructions of a wave complete in order, every
-      // round is LOADS_PER_ROUND of them, and the newer rounds may stay in flight
-      const int32_t newer = r == 0 ? min(3, NR - 1) : min(2, NR - 1 - r);
+    for (; issued < min(NR, 4); ++issued) issue_round(issued);
+    for (int32_t s0 = 0; s0 < NR;) {
+      // wait until the stages of the round have landed: the DMA instructions of a wave complete
+      // in order, every stage is LOADS_PER_ROUND of them, and the newer ones may stay in flight
+      const int32_t s1 = round_end(s0);
+      const int32_t newer = issued - s1;
       if (newer >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LOADS_PER_ROUND) : "memory");
       else if (newer == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
       else if (newer == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_ROUND) : "memory");
       else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __builtin_amdgcn_s_barrier();  // round r is published; the stage of round r - 1 is free
-      if (r > 0 && r + 3 < NR) issue_round(r + 3);
+      __builtin_amdgcn_s_barrier();  // the round is published; the stages before s0 are free
+      for (; issued < min(NR, s0 + 4); ++issued) issue_round(issued);
+      s0 = s1;
     }
     __syncthreads();              // end of the stream
     if (KG > 1) __syncthreads();  // the exchange of the key groups
@@ -542,14 +564,17 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t lb_row = rb * BPB + n / G;  // this row's branch within the row group
 
   // Round r: meet the loaders (the stage has landed), compute.
-  auto round_body = [&](int32_t r, const uint4* cur) {
-    if (r == r_pub) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores of the append are complete
+  for (int32_t s0 = 0; s0 < NR;) {
+    const int32_t s1 = round_end(s0);
+    if (s0 == r_pub) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores of the append are complete
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS reads of the previous round are done
     __builtin_amdgcn_s_barrier();
     if (active) {
 #pragma nounroll
-      for (int32_t j = 0; j < STAGE_BLOCKS; ++j) {
-        const int32_t gb = r * STAGE_BLOCKS + j;
+      for (int32_t gb = s0 * STAGE_BLOCKS; gb < min(s1 * STAGE_BLOCKS, NBT); ++gb) {
+        const int32_t st = (gb / STAGE_BLOCKS) & 3;  // no DMA on this path: any stage may be addressed
+        const uint4* cur = (st == 0 ? ring0 : (st == 1 ? ring1 : (st == 2 ? ring2 : ring3))) +
+                           (gb % STAGE_BLOCKS) * SLOT_U4;
         bool mine = false, masked = false, tail = false;
         uint32_t ok = 0xffffu;
         if (gb < NB) {
@@ -557,26 +582,19 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
           const int32_t valid = gb < NBh ? min(32, Hlen - gb * 32) : min(32, Llen - (gb - NBh) * 32);
           masked = valid < 32;
           ok = first_bits(valid - g2 * 8) | (first_bits(valid - 16 - g2 * 8) << 8);
-        } else if (gb < NBT) {
+        } else {
           const int32_t tt = gb - NB;
-          const int32_t c = tt / NQ, qd = tt - c * NQ;
+          const int32_t c = tt / NQ, qd = quad_of(tt - c * NQ);
           mine = qd / QPR == rb && (c * QPR + qd % QPR) % KG == kg;
           masked = true;
           tail = true;
           const uint32_t pm = first_bits(a.step + 1 - c * 8);
           ok = (qd * 4 + g2 == lb_row ? pm : 0u) | (qd * 4 + 2 + g2 == lb_row ? pm << 8 : 0u);
         }
-        if (mine) compute_block(cur + j * SLOT_U4, masked, ok, tail);
+        if (mine) compute_block(cur, masked, ok, tail);
       }
     }
-  };
-
-  // stage of round r is ring[r % 4]; round r refills ring[(r + 3) % 4] (consumed in round r-1)
-  for (int32_t r = 0; r < NR; r += 4) {
-    round_body(r, ring0);
-    if (r + 1 < NR) round_body(r + 1, ring1);
-    if (r + 2 < NR) round_body(r + 2, ring2);
-    if (r + 3 < NR) round_body(r + 3, ring3);
+    s0 = s1;
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();  // all stages are dead from here on and get reused
