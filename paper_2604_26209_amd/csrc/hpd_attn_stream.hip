@@ -100,7 +100,7 @@ using NarrowShape = Shape<3, 1, 1>;
 
 struct StreamArgs {
   hpd_dev_tables tb;
-  int32_t step, Hq, Hkv, Tcap, P, n_docs, RG, out_f32, fused, live_base;
+  int32_t step, Hq, Hkv, Tcap, P, n_docs, RG, n_groups, out_f32, fused, live_base;
   int64_t NP;
   float scale_log2;
 };
@@ -168,9 +168,14 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 
   // ---- unit descriptor (one dependent load):
   //      {hoff, Hlen, doff, Llen, first live row, live branches, position | -1, first branch | -1}
-  const int32_t rg = blockIdx.x % a.RG;
-  const int32_t hk = (blockIdx.x / a.RG) % a.Hkv;
-  const int32_t u = blockIdx.x / (a.RG * a.Hkv);
+  // Workgroup b runs on XCD b % 8, and every XCD has an L2 of its own: the row groups of one
+  // (unit, kv head), which stream the same prefix, get indices 8 apart - same XCD, dispatched
+  // together - so that the second one finds the blocks in that L2.
+  const int32_t rg = (blockIdx.x >> 3) % a.RG;
+  const int32_t grp = ((blockIdx.x >> 3) / a.RG) * 8 + (blockIdx.x & 7);  // (unit, kv head)
+  if (grp >= a.n_groups) return;  // the grid is padded to a multiple of 8 groups
+  const int32_t hk = grp % a.Hkv;
+  const int32_t u = grp / a.Hkv;
   const int32_t* desc = a.tb.unit_desc + (int64_t)u * 8;  // pre-offset to this step by the host
   const int32_t hoff = desc[0], Hlen = desc[1], doff = desc[2], Llen = desc[3];
   const int32_t row0_live = desc[4], nb = desc[5], upos = desc[6], ub0 = desc[7];
@@ -737,7 +742,8 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   if (L->kernel_mode == 3) narrow = false;
   if (L->kernel_mode == 4) narrow = true;
   a.RG = narrow ? rg_narrow : rg_wide;
-  const int64_t items = n_units * a.Hkv * a.RG;
+  a.n_groups = (int32_t)(n_units * a.Hkv);
+  const int64_t items = ((int64_t)(a.n_groups + 7) / 8 * 8) * a.RG;
 #define HPD_LAUNCH(GG)                                                                              \
   (narrow ? launch_g<GG, NarrowShape>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s) \
           : launch_g<GG, WideShape>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s))
