@@ -127,6 +127,15 @@ __device__ __forceinline__ void unpack8(uint4 a, float out[8]) {
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// A 32-bit word at a wave-uniform address through the scalar data cache (read only).  The
+// loaders use it for table lookups: a vector load would have to wait for every DMA instruction
+// in front of it, because vector memory operations of a wave complete in order.
+__device__ __forceinline__ int32_t scalar_load(const int32_t* p) {
+  int32_t v;
+  asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
+  return v;
+}
+
 // 8 channel pairs (c .. c+7, 64+c .. 64+c+7) of one row, rotated at the (cos, sin) row cs_row
 __device__ __forceinline__ void rotate16(uint4 raw_lo, uint4 raw_hi, const float2* cs_row, int c,
                                          float rl[8], float rh[8]) {
@@ -297,8 +306,11 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
           p3 = p1 + 32 * 8;
         }
       } else {
-        const int32_t bA = branch_id(min(tq * 4 + half * 2, nbr_here - 1));
-        const int32_t bB = branch_id(min(tq * 4 + half * 2 + 1, nbr_here - 1));
+        // the branch of a load is the same in all lanes: a scalar lookup
+        const int32_t lbA = min(tq * 4 + half * 2, nbr_here - 1), lbB = min(tq * 4 + half * 2 + 1, nbr_here - 1);
+        const int32_t* ids = a.tb.live_branch + (a.live_base + row0_live + br0);
+        const int32_t bA = ub0 >= 0 ? ub0 + br0 + lbA : scalar_load(ids + lbA);
+        const int32_t bB = ub0 >= 0 ? ub0 + br0 + lbB : scalar_load(ids + lbB);
         const int32_t posA = min(tc * 8 + r4, a.step), posB = min(tc * 8 + 4 + r4, a.step);
         const uint16_t* pool = is_k ? k_tail : v_tail;
         const uint16_t* rowA = pool + ((int64_t)bA * a.Hkv + hk) * a.Tcap * D;
