@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this same command, each scaled by what the counter reads for a 1 GiB copy
 # (profiles/attn_stream_<workload>.txt).  None where no counter run has been made.
-MEASURED_TRAFFIC_BYTES = {2: 117.4e6}
+MEASURED_TRAFFIC_BYTES = {2: 110.5e6, 3: 784.8e6, 4: 469.1e6, 5: 2762.3e6}
 
 
 def algorithmic_bytes(wl, n_live_lists, eb):

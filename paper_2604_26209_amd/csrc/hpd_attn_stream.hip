@@ -9,16 +9,15 @@
 // consumes it from there.
 //
 //  * One stream of key blocks.  Everything a unit attends to is cut into blocks of 32 keys
-//    = 8 K fragments + 8 V fragments of 64 lanes x 16 bytes (16 KB): the header blocks, the
-//    document blocks, and then "tail tiles" that hold 8 positions of each of 4 branches
-//    (Section 4.3.3: every value still grows token by token; the tails are private to a
-//    branch, so a row keeps only the keys of its own branch in a tile and the rest get
-//    probability 0).  A tail tile is gathered by the same 16-byte loads as a prefix block
-//    from the row-major tail pools.  Its K half is in fragment order like a prefix block's;
-//    its V half arrives as 32 rows of 256 bytes (the pool order: an append then is one
-//    coalesced row, where an 8-position interleave would cost a 2-byte scatter per channel)
-//    and is transposed by the consumer's LDS reads (2-byte reads, 16-byte chunks
-//    XOR-swizzled at load time so that the two half-waves hit different banks).
+//    (16 KB: a K half and a V half): the header blocks, the document blocks, and then "tail
+//    tiles" that hold 8 positions of each of 4 branches (Section 4.3.3: every value still
+//    grows token by token; the tails are private to a branch, so a row keeps only the keys of
+//    its own branch in a tile and the rest get probability 0).  A tail tile is gathered by the
+//    same 16-byte loads as a prefix block from the row-major tail pools.  Its K half looks
+//    like a prefix block's; its V half arrives as 32 rows of 256 bytes (the pool order: an
+//    append then is one coalesced row, where an 8-position interleave would cost a 2-byte
+//    scatter per channel) and is transposed by the consumer's LDS reads (2-byte reads,
+//    16-byte chunks XOR-swizzled at load time so that the two half-waves hit different banks).
 //  * Loading.  Blocks travel HBM -> LDS with direct-to-LDS 16-byte loads
 //    (global_load_lds_dwordx4): no VGPRs are held by data in flight.  The V half of a prefix
 //    block is fetched in fragment order (a lane fetches exactly the 16 bytes that the same
@@ -26,13 +25,14 @@
 //    K half is fetched as 32 whole rows, whose 16-byte chunks are XOR-permuted at fetch time so
 //    that the per-lane fragment reads are conflict-free.  Loads that gather 32 bytes per row
 //    instead were measured to stall the issuing wave: every distinct cache line of an
-//    instruction is a separate request.  Four 32 KB stages of two blocks form a ring: while one stage is consumed
-//    up to three are in flight, and a round only waits (s_waitcnt vmcnt(N)) for its own
-//    stage.  The stages are distinct __shared__ arrays on purpose: the compiler then knows
-//    that reading one does not alias the DMA into the others and does not drain the DMA
-//    queue before every LDS read.  Only waves 0-3 load (8 instructions per round each):
-//    vector memory operations of a wave complete in order, so a wave with a deep DMA queue
-//    cannot get a latency-critical load through; waves 4-7 stay free for those.
+//    instruction is a separate request.  Four stages form a ring: while one is consumed up
+//    to three are in flight, and a round only waits (s_waitcnt vmcnt(N)) for its own stage.
+//  * Roles.  The last waves of the workgroup only load; the others only compute.  Under load
+//    a DMA instruction blocks the issuing wave until the memory pipeline takes it, so
+//    whatever a loading wave computes is time in which nothing is requested; and vector
+//    memory operations of a wave complete in order, so a wave with a deep DMA queue cannot
+//    get a latency-critical load through.  The two roles run different code paths and meet
+//    at barriers only.
 //  * Contraction (transposed):
 //        S^T[key,row] = K.Q^T   (A = K fragment, B = rotated, pre-scaled Q in registers as
 //                                bf16 hi + lo parts: two MFMA passes, Q rounding drops out)
@@ -42,24 +42,24 @@
 //    exponentiation and bf16 packing, the B operand of the second without any cross-lane
 //    movement.  The key order inside a block is permuted on the K side (an address, free) so
 //    that the 8 probabilities a lane holds for one MFMA belong to 8 consecutive keys, which
-//    is what the 8-key interleaved V pools deliver in 16 bytes.
+//    is what the 8-key interleaved V pool delivers in 16 bytes.
 //  * Softmax.  Online max/sum in registers.  The running maximum is exact (the accumulators
 //    are rescaled whenever some row of the wave sees a larger score; the rescale is skipped,
 //    wave-uniformly, when no row does).  Exactness matters for accuracy: the dominant key of a
 //    row then has probability exactly 1.0, which bf16 represents without error; with a stale
 //    maximum the largest weight would carry a 2^-9 rounding error into P.V (measured: 3x
 //    larger max-abs error).
-//  * Waves.  8 waves = (row block of 32 rows) x (key group), KG = 4 / 2 / 1 for <= 2 / <= 4 /
-//    <= 8 row blocks; key group kg takes the prefix blocks gb with gb % KG == kg, and the tail
-//    tiles of a row block go round its key groups.  At the end the groups are merged through
-//    LDS in one exchange in which every wave of a row block reduces its own 32-channel slices
+//  * Compute waves = (row block of 32 rows) x (key group), with as many key groups (at most
+//    4) as fit; key group kg takes the prefix blocks gb with gb % KG == kg, and the tail tiles
+//    of a row block go round its key groups.  At the end the groups are merged through LDS in
+//    one exchange in which every wave of a row block reduces its own 32-channel slices
 //    (identical lane layout on both sides, so the exchange is lane-private), normalises them
 //    and writes them out.
-//  * Fused mode (hpd_decode_step): waves 4-7 rotate, round and store the new keys and values
-//    of the unit's branches (the arithmetic of hpd_kv_append) while waves 0-3 start the
-//    stream; the first barrier of the ring publishes them, and the tail tiles - which are
-//    last in the stream - read them back like any other token.  Both modes therefore add up
-//    in the same order and give identical bits.
+//  * Fused mode (hpd_decode_step): the compute waves rotate, round and store the new keys and
+//    values of the unit's branches (the arithmetic of hpd_kv_append) before they rotate the
+//    query; a ring barrier publishes them before the first tail tile is requested, and the
+//    tail tiles - which are last in the stream - read them back like any other token.  Both
+//    modes therefore add up in the same order and give identical bits.
 #include <algorithm>
 #include <cmath>
 
@@ -747,10 +747,7 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   // kernel_mode 3 / 4 force a shape; otherwise the narrow shape from two workgroups per CU on,
   // unless the units have so many rows (more than two narrow row groups) that the launch is
   // bound by the matrix pipes and splitting the rows further only re-streams the prefix
-  int dev = 0, cus = 256;
-  (void)hipGetDevice(&dev);
-  (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-  bool narrow = items_wide >= 2 * (int64_t)cus && max_nblk <= 2 * NarrowShape::MAX_BLOCKS;
+  bool narrow = items_wide >= 2 * (int64_t)L->n_cus && max_nblk <= 2 * NarrowShape::MAX_BLOCKS;
   if (L->kernel_mode == 3) narrow = false;
   if (L->kernel_mode == 4) narrow = true;
   a.RG = narrow ? rg_narrow : rg_wide;

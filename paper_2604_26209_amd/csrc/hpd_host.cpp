@@ -255,6 +255,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
                  o_unit_doc = A.add(L->unit_doc), o_unit_desc = A.add(L->unit_desc);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipGetDevice(&L->device);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&L->n_cus, hipDeviceAttributeMultiprocessorCount, L->device);
     if (e == hipSuccess) e = hipMalloc(&L->d_ints, A.host.size() * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc(&L->d_rope, L->rope.size() * sizeof(float));
     if (e == hipSuccess)

@@ -43,6 +43,7 @@ struct hpd_layout {
 
   bool on_device = false;
   int device = -1;
+  int n_cus = 256;  // compute units of that device
   void* d_ints = nullptr;
   void* d_rope = nullptr;
   hpd_dev_tables dev{};
