@@ -109,8 +109,9 @@ def test_paper_gap_positions_mode():
     _say("paper-gap mode")
     wl = W.random_workload(21, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=4, p=2)
     attr = np.random.default_rng(3).integers(1, 6, size=wl.n_branches).astype(np.int32)
-    hip = H.run_hip(wl, pos_mode=1, attr_len=attr)
-    H.check_all(wl, hip, pos_mode="paper_gap", attr_len=attr, label="gap")
+    for mode, fused in ((3, False), (3, True), (4, False), (4, True)):  # wide / narrow workgroup shape
+        hip = H.run_hip(wl, pos_mode=1, attr_len=attr, kernel_mode=mode, fused=fused)
+        H.check_all(wl, hip, pos_mode="paper_gap", attr_len=attr, label=f"gap_m{mode}")
     wl = W.random_workload(22, dtype="f32", t=4, p=2)
     attr = np.random.default_rng(4).integers(1, 6, size=wl.n_branches).astype(np.int32)
     hip = H.run_hip(wl, pos_mode=1, attr_len=attr)
