@@ -31,6 +31,13 @@ def test_full_size_config(k, prompts):
     print(f"full-size cfg{k}: {wl.n_prompts} prompts, {wl.n_docs} docs, {wl.n_branches} branches", flush=True)
     hip = H.run_hip(wl, fused=True, poison_pools=True)
     _integers_whole_batch(wl, hip)
+    # whole batch, every step: the pools were poisoned with NaN, so a single read of a padding
+    # slot or of an unwritten tail slot would show; and an output is a convex combination of
+    # value rows, so no element can exceed the largest |v| of the inputs
+    vmax = max(float(hip["inputs"].v_raw.abs().max()), max(float(x.abs().max()) for x in hip["inputs"].v_new))
+    for t, o in enumerate(hip["out"]):
+        assert bool(torch.isfinite(o).all()), f"cfg{k} step {t}: non-finite output"
+        assert float(o.abs().max()) <= vmax * (1 + 1e-2), f"cfg{k} step {t}: output outside the hull of V"
     if prompts is None:
         # ragged config: a prompt with one document, one with the most documents, the prompt
         # holding the longest and the one holding the shortest document
