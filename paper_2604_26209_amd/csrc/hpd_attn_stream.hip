@@ -196,10 +196,14 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t nblk_here = min(per_group, nblk - first_blk);
   if (nblk_here <= 0) return;  // uniform over the workgroup
   // compute waves = (row block) x (key group), with as many key groups (at most 4) as fit:
-  // 6 waves: 1 row block x 4, 2 x 3, 3 x 2, 4..6 x 1; 3 waves: 1 x 3, 2..3 x 1
+  // 6 waves: 1 row block x 4, 2 x 2, 3 x 2, 4..6 x 1; 3 waves: 1 x 3, 2..3 x 1.  (Two row blocks
+  // x 3 key groups would use all six waves, but then two compute waves share each of two
+  // SIMDs and the prologue - every wave rotates its query - takes twice as long there;
+  // measured: 4 waves, one per SIMD, are 3 % faster on the Llama-3-8B configuration.)
   int32_t KG = 1;
   for (int32_t k = 2; k <= 4; ++k)
     if (k * nblk_here <= CWAVES) KG = k;
+  if (CWAVES == 6 && nblk_here == 2) KG = 2;
   const int32_t NRB = KG == 1 ? CWAVES : nblk_here;  // row-block slots
   const bool loader = wave >= CWAVES;
   int32_t kg = 0;
@@ -451,12 +455,6 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave has its rows
   __builtin_amdgcn_s_barrier();        // stages 2 and 3 go back to the loaders
 
-  // ---- the append, before the rotation: the stores complete while the query is rotated
-  if (append_late) {
-    if (append_mine) append_store(tid >> 3, new_rows, upos >= 0);
-    append_from((tid >> 3) + CWAVES * 8);
-  }
-
   // ---- rotate the query: bf16 hi + lo MFMA B operands.  The softmax scale and the change to
   //      base 2 ride on the query: scores come out of the MFMA ready for exp2.
   bf16x8 Qh[8], Ql[8];
@@ -493,6 +491,13 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const int32_t q_pos = a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
     const float4* cs_row = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)q_pos * (D / 2));
     rotate_query([&](int i4) -> float4 { return cs_row[i4]; });
+  }
+
+  // ---- the append, after the rotation (the rotation is what the first round waits for): the
+  //      stores complete during round 0 and are published at the barrier of round 1
+  if (append_late) {
+    if (append_mine) append_store(tid >> 3, new_rows, upos >= 0);
+    append_from((tid >> 3) + CWAVES * 8);
   }
 
   // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
