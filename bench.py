@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this same command, each scaled by what the counter reads for a 1 GiB copy
 # (profiles/attn_stream_<workload>.txt).  None where no counter run has been made.
-MEASURED_TRAFFIC_BYTES = {2: 110.5e6, 3: 784.8e6, 4: 469.1e6, 5: 2762.3e6}
+MEASURED_TRAFFIC_BYTES = {2: 106.3e6, 3: 734.5e6, 4: 443.9e6, 5: 2687.9e6}
 
 
 def algorithmic_bytes(wl, n_live_lists, eb):
@@ -119,12 +119,16 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5")
     ap.add_argument("--replicas", type=int, default=0, help="KV replicas (0 = enough for 2 GB)")
-    ap.add_argument("--out", default="f32", choices=["f32", "same"], help="output element type")
+    ap.add_argument("--out", default="same", choices=["f32", "same"],
+                    help="output element type: the K/V element type (default) or fp32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--two-call", action="store_true", help="hpd_kv_append + hpd_decode_attention")
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="after the timed regions, run this many 1 GiB device copies (reference "
                          "dispatches for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--per-step", action="store_true",
+                    help="second run: one event pair per decode step (all replicas of that step back "
+                         "to back), adds per_step {us, gbs} to the record")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
@@ -242,7 +246,7 @@ def main():
     events = launched
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not args.two_call and out_f32 else None,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not args.two_call and not out_f32 else None,
                 "kernel": "attn_stream_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attention_generic_kernel",
                 "launches": len(events), "avg_launch_us": round(dur_s / len(events) * 1e6, 2),
                 "algorithmic_bytes_per_launch": int(alg / len(events)),
@@ -261,6 +265,23 @@ def main():
                    "call": "hpd_kv_append+hpd_decode_attention" if args.two_call else "hpd_decode_step"},
         "roofline": roofline,
     }
+    if args.per_step and not args.two_call:
+        reps = max(1, args.steps // R)
+        pairs = []
+        for t in live_steps:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                for kp, vp, kt, vt in pools:
+                    B.hpd_decode_step(layout, t, q[t], kn[t], vn[t], kp, vp, kt, vt, outs[t])
+            e1.record()
+            pairs.append((t, e0, e1))
+        torch.cuda.synchronize()
+        us = [e0.elapsed_time(e1) * 1e3 / (reps * R) for _, e0, e1 in pairs]
+        rec["per_step"] = {"steps": live_steps, "launches_per_step": reps * R,
+                           "us": [round(x, 2) for x in us],
+                           "gbs": [round((attn_b[t] + app_b[t]) / (x * 1e-6) / 1e9, 1)
+                                   for (t, _, _), x in zip(pairs, us)]}
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

@@ -55,6 +55,10 @@
 //    one exchange in which every wave of a row block reduces its own 32-channel slices
 //    (identical lane layout on both sides, so the exchange is lane-private), normalises them
 //    and writes them out.
+//  * Cache policy.  What is touched once per launch - document blocks (when a single row
+//    group streams them), tail rows, the output rows of a wave that holds whole rows - moves
+//    with the streaming (non-temporal) hint; what is re-read (header blocks, query rows, the
+//    appended rows) does not.
 //  * Fused mode (hpd_decode_step): the compute waves rotate, round and store the new keys and
 //    values of the unit's branches (the arithmetic of hpd_kv_append) before they rotate the
 //    query; a ring barrier publishes them before the first tail tile is requested, and the
@@ -108,6 +112,10 @@ struct StreamArgs {
 #define HPD_GLL(gptr, lptr)                                                                   \
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr),   \
                                    (__attribute__((address_space(3))) void*)(lptr), 16, 0, 0)
+// the same with the streaming (non-temporal) cache hint
+#define HPD_GLL_NT(gptr, lptr)                                                                \
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr),   \
+                                   (__attribute__((address_space(3))) void*)(lptr), 16, 0, 2)
 
 __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
   floatx2 v = {lo, hi};
@@ -324,10 +332,21 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         p2 = rowB + (int64_t)posA * D + (e0 ^ x2);
         p3 = rowB + (int64_t)posB * D + (e0 ^ x1 ^ x2);
       }
-      HPD_GLL(p0, dst);
-      HPD_GLL(p1, dst + 64);
-      HPD_GLL(p2, dst + 128);
-      HPD_GLL(p3, dst + 192);
+      // Tail rows and - unless several row groups stream the same prefix - document blocks are
+      // read once per launch: ask the caches not to keep them (measured: 4-5 % on the
+      // memory-bound configurations).  The header is shared by the documents of its prompt and
+      // stays cacheable.
+      if (!prefix || (a.RG == 1 && gb >= NBh)) {
+        HPD_GLL_NT(p0, dst);
+        HPD_GLL_NT(p1, dst + 64);
+        HPD_GLL_NT(p2, dst + 128);
+        HPD_GLL_NT(p3, dst + 192);
+      } else {
+        HPD_GLL(p0, dst);
+        HPD_GLL(p1, dst + 64);
+        HPD_GLL(p2, dst + 128);
+        HPD_GLL(p3, dst + 192);
+      }
     }
   };
   // ---- fused mode: the compute waves append the newest token of the unit's branches (the
@@ -686,15 +705,75 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     }
   }
 
-  // ---- normalise and write: accumulator value i of d-block blk is channel
-  //      blk*32 + (i/4)*8 + g2*4 + i%4 of row n, so a lane stores 4 consecutive channels at a time
-  if (row_valid) {
-    const float inv = 1.0f / (l_lane + __shfl_xor(l_lane, 32));
+  // ---- normalise and write.  Accumulator value i of d-block blk is channel
+  //      blk*32 + (i/4)*8 + g2*4 + i%4 of row n.
+  const float inv = 1.0f / (l_lane + __shfl_xor(l_lane, 32));
+  if (KG == 1 && active) {
+    // The wave holds whole rows.  Stored from the accumulator layout every instruction would
+    // touch 32 rows in pieces of 8 or 16 bytes; instead the wave turns its rows through a private
+    // 16 KB of the (now dead) ring - 16-byte chunk c of row r at position c ^ r resp.
+    // c ^ (r & 15) - and stores runs of whole rows, consecutive lanes = consecutive chunks, past
+    // the L2 (nobody reads them here, and write-backs of dirty lines compete with the next
+    // workgroup's stream).  Measured: 4 % on the 96-row units of the multi-document
+    // configuration; without the streaming hint there is no gain, and the hint on the
+    // piecewise stores costs 15 %.
+    constexpr int WPS = STAGE_U4 / 1024;  // waves per stage
+    static_assert(WPS >= 1 && 4 * WPS >= CWAVES, "the ring holds 16 KB per compute wave");
+    const int32_t st = wave / WPS;
+    uint4* mine = (st == 0 ? ring0 : (st == 1 ? ring1 : (st == 2 ? ring2 : ring3))) + (wave % WPS) * 1024;
+    typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+    if (a.out_f32) {
+      float4* rowp = reinterpret_cast<float4*>(mine) + n * 32;  // 32 chunks of 4 floats per row
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc)
+          rowp[(blk * 8 + cc * 2 + g2) ^ n] =
+              make_float4(acc[blk][cc * 4 + 0] * inv, acc[blk][cc * 4 + 1] * inv,
+                          acc[blk][cc * 4 + 2] * inv, acc[blk][cc * 4 + 3] * inv);
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll 4
+      for (int32_t i = 0; i < 16; ++i) {  // 2 rows per instruction
+        const int32_t row = i * 2 + (lane >> 5), chunk = lane & 31;
+        const int32_t lrr = rb * 32 + row;
+        if (lrr < rows_here) {
+          const uint4 v = mine[row * 32 + (chunk ^ row)];
+          const int64_t off = ((int64_t)(row0_live + br0 + lrr / G) * a.Hq + hk * G + lrr % G) * D + chunk * 4;
+          u4v vv = {v.x, v.y, v.z, v.w};
+          __builtin_nontemporal_store(vv, reinterpret_cast<u4v*>(reinterpret_cast<float*>(out) + off));
+        }
+      }
+    } else {
+      uint2* rowp = reinterpret_cast<uint2*>(mine) + n * 32;  // 16 chunks of 8 bf16 per row, in halves
+#pragma unroll
+      for (int blk = 0; blk < 4; ++blk)
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc)
+          rowp[(((blk * 4 + cc) ^ (n & 15)) << 1) | g2] =
+              make_uint2(cvt_pk_bf16(acc[blk][cc * 4 + 0] * inv, acc[blk][cc * 4 + 1] * inv),
+                         cvt_pk_bf16(acc[blk][cc * 4 + 2] * inv, acc[blk][cc * 4 + 3] * inv));
+      __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll 4
+      for (int32_t i = 0; i < 8; ++i) {  // 4 rows per instruction
+        const int32_t row = i * 4 + (lane >> 4), chunk = lane & 15;
+        const int32_t lrr = rb * 32 + row;
+        if (lrr < rows_here) {
+          const uint4 v = mine[row * 16 + (chunk ^ (row & 15))];
+          const int64_t off = ((int64_t)(row0_live + br0 + lrr / G) * a.Hq + hk * G + lrr % G) * D + chunk * 8;
+          u4v vv = {v.x, v.y, v.z, v.w};
+          __builtin_nontemporal_store(vv, reinterpret_cast<u4v*>(reinterpret_cast<uint16_t*>(out) + off));
+        }
+      }
+    }
+  } else if (row_valid) {
+    // key groups: a wave owns some d-blocks of its rows; a lane stores 4 consecutive channels at a time
     const int32_t live_row = row0_live + br0 + lr / G;
     const int64_t o_off = ((int64_t)live_row * a.Hq + hk * G + lr % G) * D + g2 * 4;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
-      if (KG == 1 || owner(blk) == kg) {
+      if (owner(blk) == kg) {
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) {
           const float o0 = acc[blk][cc * 4 + 0] * inv, o1 = acc[blk][cc * 4 + 1] * inv;

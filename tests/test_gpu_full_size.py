@@ -1,7 +1,8 @@
-"""Parity at the benchmark configurations' full sizes, launched exactly as bench.py launches
-them (automatic kernel choice, fp32 outputs, fused step call), on sampled prompts the oracle
-can afford: every integer output of the whole batch bit-exact, float outputs of the sampled
-prompts within 2e-2 x RMS(step) for every step."""
+"""Parity at the benchmark configurations' full sizes, launched as bench.py launches them
+(automatic kernel choice, fused step call), on sampled prompts the oracle can afford: every
+integer output of the whole batch bit-exact, fp32 outputs of the sampled prompts within
+2e-2 x RMS(step) for every step, and the bf16 outputs that bench.py times equal to the fp32
+outputs rounded once (RNE), bit for bit, for every row of the whole batch."""
 import numpy as np
 import pytest
 import torch
@@ -49,3 +50,9 @@ def test_full_size_config(k, prompts):
     print(f"  oracle on prompts {prompts}", flush=True)
     worst = H.check_all(wl, hip, prompts=prompts, label=f"cfg{k}")
     print(f"  worst max-abs / RMS(step) = {worst:.4f}", flush=True)
+    # the launch configuration bench.py times: outputs in the K/V element type
+    print("  bf16 outputs == RNE(fp32 outputs), whole batch", flush=True)
+    hip16 = H.run_hip(wl, inputs=hip["inputs"], fused=True, poison_pools=True, out_f32=False)
+    for t, (x, y) in enumerate(zip(hip["out"], hip16["out"])):
+        assert y.dtype == torch.bfloat16
+        assert torch.equal(x.to(torch.bfloat16), y), f"cfg{k} step {t}: bf16 output is not RNE(fp32 output)"
