@@ -5,7 +5,10 @@ branch it writes out, token by token, the set of keys the method lets the
 branch see (Section 4.3.2 restricted to header + own document + own branch)
 and evaluates softmax attention with scalar loops and ``math`` functions.
 Used as one of the pins of the dense oracle; far too slow for anything but a
-few dozen tokens.
+few dozen tokens.  ``decode_all_steps_paper`` does the same for the section's
+rule taken literally over the whole prompt (every stacked document, and the
+value tokens of all earlier attributes up to the current step), with the
+position IDs of Appendix A.1 written out as a closed form.
 """
 from __future__ import annotations
 
@@ -75,6 +78,58 @@ def decode_all_steps(header_len, doc_lens, branch_lens, hq, hkv, d, base, t_max,
                 scores = [sum(qr[x] * kk[x] for x in range(d)) / math.sqrt(d) for kk in keys]
                 m = max(scores)
                 w = [math.exp(s - m) for s in scores]
+                z = sum(w)
+                row_out.append([sum(w[n] * vals[n][x] for n in range(len(keys))) / z
+                                for x in range(d)])
+            step_out.append(row_out)
+        outs.append(step_out)
+    return outs
+
+
+def decode_all_steps_paper(header_len, doc_lens, branch_lens, attr_lens, hq, hkv, d, base, t_max,
+                           k_prefix, v_prefix, q_steps, k_steps, v_steps):
+    """One prompt, the paper's own positions and its literal mask.
+
+    Prefix token i (header, then the documents one after the other) sits at position i.
+    Attribute n (0-based over all branches of the prompt, in (document, attribute) order) ends at
+    |p| + A_0 + .. + A_n - 1 + n * K_max; its value token k (1-based) one gap slot further each.
+    Branch b at step t sees: the whole prefix, tokens 0..min(t, len-1) of every earlier branch,
+    and its own tokens 0..t.  Arguments and result as in ``decode_all_steps``; ``attr_lens`` is
+    the flat list A_n.
+    """
+    group = hq // hkv
+    blen = [x for bl in branch_lens for x in bl]
+    n_prefix = header_len + sum(doc_lens)
+    base_pos, run = [], n_prefix
+    for n, a in enumerate(attr_lens):
+        run += a
+        base_pos.append(run - 1 + n * t_max)
+    tails = [[] for _ in blen]
+    outs = []
+    for t in range(t_max):
+        live = [b for b in range(len(blen)) if blen[b] > t]
+        for r, b in enumerate(live):
+            pos = base_pos[b] + 1 + t
+            kr = [_rope_scalar(k_steps[t][r][hk], pos, base) for hk in range(hkv)]
+            tails[b].append((kr, v_steps[t][r]))
+        step_out = []
+        for r, b in enumerate(live):
+            qpos = base_pos[b] + 1 + t
+            row_out = []
+            for h in range(hq):
+                hk = h // group
+                qr = _rope_scalar(q_steps[t][r][h], qpos, base)
+                keys, vals = [], []
+                for i in range(n_prefix):
+                    keys.append(_rope_scalar(k_prefix[i][hk], i, base))
+                    vals.append(v_prefix[i][hk])
+                for bb in range(b + 1):  # earlier attributes and itself, whatever is in memory
+                    for (kr, vv) in tails[bb][:t + 1]:
+                        keys.append(kr[hk])
+                        vals.append(vv[hk])
+                scores = [sum(qr[x] * kk[x] for x in range(d)) / math.sqrt(d) for kk in keys]
+                m = max(scores)
+                w = [math.exp(s_ - m) for s_ in scores]
                 z = sum(w)
                 row_out.append([sum(w[n] * vals[n][x] for n in range(len(keys))) / z
                                 for x in range(d)])

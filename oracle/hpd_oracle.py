@@ -25,8 +25,18 @@ What each piece follows
 * memory order          - Section 4.3.2 / Figure 2 caption: new tokens are
   always appended at the end of the cache, step after step.
 * mask                  - Section 4.3.2: causal in *position-ID order*, not in
-  memory order; restricted to the blocks a token may see (shared header, own
-  document, own branch), which makes Eq. 3's independence exact.
+  memory order.  ``mask_mode="block"`` restricts it to the blocks a token may
+  see (shared header, own document, own branch), which makes Eq. 3's
+  independence exact.  ``mask_mode="paper"`` is the section's rule taken
+  literally over the whole stacked prompt: a token sees every token of its
+  prompt that is already in memory and has a position ID not larger than its
+  own - all stacked documents and the value tokens of the earlier attributes
+  up to its own step (Section 5 states the same for fine-tuning: v_{n,k} may not
+  see v_{n',k'} with n' < n and k' > k, so k' <= k it does see).  It needs the
+  paper's own position IDs (``pos_mode="paper_gap"``): with positions that
+  restart per document "position order" would mix the documents.  The skeleton
+  (attribute-name) tokens shape the position IDs but are not cache entries in
+  this model, in either mode.
 * decode step           - Section 4.3.3: only the new tokens are fed, positions
   are the previous ones plus one.
 * pruning               - Section 4.3.4: a finished value is fed no more.
@@ -40,7 +50,11 @@ equality with ordinary causal attention over the contiguous sequence
 [header, own document, own branch] computed by a library routine with an
 independently written complex-number RoPE, single-branch reduction to standard
 causal decoding, RoPE identities, memory-order permutation invariance, branch
-independence, and an fp64 triple-loop brute force on tiny inputs.
+independence, and an fp64 triple-loop brute force on tiny inputs.  The
+paper-literal mask is pinned by: equality with ordinary causal attention (library
+routine) over all tokens in memory *sorted by position ID*, the closed-form row
+sums, an explicit set construction, reduction to the block mask for one document
+with one attribute, and its own scalar brute force.
 The paper-gap position mode with several stacked documents is a reading of
 this build (the paper writes Algorithm 2 for one document only); it is pinned
 by closed form only.
@@ -147,9 +161,12 @@ class PromptOracle:
 
     def __init__(self, header_len, doc_lens, branch_lens, n_q_heads, n_kv_heads, head_dim,
                  rope_base, max_new, pos_mode="contig", attr_lens=None, dtype=np.float32,
-                 cache_dtype=None):
+                 cache_dtype=None, mask_mode="block"):
         self.cache_dtype = cache_dtype
         assert cache_dtype in (None, "bf16")
+        assert mask_mode in ("block", "paper")
+        assert mask_mode == "block" or pos_mode == "paper_gap", "the literal mask needs the paper's positions"
+        self.mask_mode = mask_mode
         self.h = int(header_len)
         self.doc_lens = [int(x) for x in doc_lens]
         self.branch_lens = [[int(x) for x in bl] for bl in branch_lens]  # per doc
@@ -234,6 +251,8 @@ class PromptOracle:
     # -- mask -------------------------------------------------------------------
     def _visible_block(self, qi, ki):
         """May token qi ever look into the block token ki belongs to?"""
+        if self.mask_mode == "paper":
+            return True  # one causal order over the whole prompt: position IDs decide alone
         kk = self.kind[ki]
         if kk == KIND_HEADER:
             return True  # the header is shared by everything in the prompt
@@ -305,6 +324,8 @@ class PromptOracle:
         vis = (kind[None, :] == KIND_HEADER)
         vis = vis | ((kind[None, :] == KIND_DOC) & (qk != KIND_HEADER) & (qd == doc[None, :]))
         vis = vis | ((kind[None, :] == KIND_BRANCH) & (qk == KIND_BRANCH) & (qb == branch[None, :]))
+        if self.mask_mode == "paper":
+            vis = np.ones_like(vis)
         m = vis & (idx[None, :] <= rows[:, None]) & (pos[None, :] <= qp)
         return m.astype(np.uint8)
 
@@ -318,7 +339,7 @@ class HPDOracle:
 
     def __init__(self, header_len, doc_ptr, doc_len, branch_ptr, branch_len, n_q_heads,
                  n_kv_heads, head_dim, rope_base, max_new, pos_mode="contig", attr_len=None,
-                 dtype=np.float32, prompts=None, cache_dtype=None):
+                 dtype=np.float32, prompts=None, cache_dtype=None, mask_mode="block"):
         """``prompts``: optional subset of prompt ids to instantiate (others are
         skipped entirely; global ids keep their full-batch values)."""
         header_len = np.asarray(header_len)
@@ -353,7 +374,7 @@ class HPDOracle:
                 al = None if attr_len is None else [int(x) for x in np.asarray(attr_len)[b0:b1]]
                 self.prompts[p] = PromptOracle(int(header_len[p]), doc_len[d0:d1], bl, n_q_heads,
                                                n_kv_heads, head_dim, rope_base, max_new,
-                                               pos_mode, al, dtype, cache_dtype)
+                                               pos_mode, al, dtype, cache_dtype, mask_mode)
         self.n_prefix_tokens = tok
 
     def live(self, t):

@@ -33,11 +33,11 @@ def _values(wl, seed_off, shape):
     return W.normal_values(shape, wl.value_seed * 1000 + seed_off, "cpu", "f32").numpy()
 
 
-def _run_oracle(wl, dtype=np.float32, pos_mode="contig", attr_len=None):
+def _run_oracle(wl, dtype=np.float32, pos_mode="contig", attr_len=None, mask_mode="block"):
     """Run all steps; returns (oracle, inputs, per-step result dicts)."""
     orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len,
                       wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new,
-                      pos_mode=pos_mode, attr_len=attr_len, dtype=dtype)
+                      pos_mode=pos_mode, attr_len=attr_len, dtype=dtype, mask_mode=mask_mode)
     kp = _values(wl, 1, (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim))
     vp = _values(wl, 2, (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim))
     orc.prefill(kp, vp)
@@ -499,3 +499,162 @@ def test_planted_mistakes_are_caught(monkeypatch, mistake):
             return np.concatenate([y[..., h:], y[..., :h]], axis=-1) if y.shape[1] == 2 else y
         monkeypatch.setattr(O, "rope", bad)
     assert _main_pin_error(wl) > 1e-6
+
+
+# ---------------------------------------------------------------------------
+# The paper-literal mask (Section 4.3.2 over the whole stacked prompt)
+# ---------------------------------------------------------------------------
+def _paper_case(seed, **kw):
+    wl = W.random_workload(seed, **kw)
+    attr = np.random.default_rng(1000 + seed).integers(1, 5, size=wl.n_branches)
+    return wl, attr
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_paper_mask_set_construction_and_row_sums(seed):
+    wl, attr = _paper_case(seed, t=4, p=2, l_range=(1, 9), h_range=(0, 5), j_range=(1, 3), n_range=(1, 4))
+    orc, _, _ = _run_oracle(wl, pos_mode="paper_gap", attr_len=attr, mask_mode="paper")
+    for po in orc.prompts.values():
+        m = po.dense_mask()
+        assert np.array_equal(m, po.mask_rows_fast(list(range(len(po.kind)))))
+        s = len(po.kind)
+        for qi in range(s):
+            if po.kind[qi] != O.KIND_BRANCH:
+                continue
+            b, t = po.branch[qi], po.step_of[qi]
+            # written out: the whole prefix, earlier attributes' tokens up to this step, own tokens
+            want = set(range(po.n_prefix))
+            want |= {i for i in range(s) if po.kind[i] == O.KIND_BRANCH and po.branch[i] <= b
+                     and po.step_of[i] <= t}
+            assert set(np.nonzero(m[qi])[0]) == want
+            assert m[qi].sum() == po.n_prefix + sum(min(t + 1, po.branch_len[bb]) for bb in range(b)) + t + 1
+            # nothing with a larger position ID, nothing that was appended later
+            assert all(po.pos[i] <= po.pos[qi] and i <= qi for i in np.nonzero(m[qi])[0])
+        # ordered by position ID the whole memory is causal: lower triangular, except that a
+        # token cannot see what entered memory after it (value tokens of earlier attributes
+        # from later steps)
+        order = sorted(range(s), key=lambda i: po.pos[i])
+        assert len({po.pos[i] for i in order}) == s  # position IDs are distinct
+        sub = m[np.ix_(order, order)]
+        exists = np.asarray([[ki <= qi for ki in order] for qi in order])
+        assert np.array_equal(sub, np.tril(np.ones_like(sub)) * exists)
+
+
+def test_paper_mask_reduces_to_block_mask_for_one_document_one_attribute():
+    wl = W.make_workload("one", "f32", 4, 2, 16, 10000.0, 5, [4], [1], [7], [1])
+    attr = np.asarray([3])
+    a, _, sa = _run_oracle(wl, dtype=np.float64, pos_mode="paper_gap", attr_len=attr, mask_mode="paper")
+    b, _, sb = _run_oracle(wl, dtype=np.float64, pos_mode="paper_gap", attr_len=attr, mask_mode="block")
+    assert np.array_equal(a.prompts[0].dense_mask(), b.prompts[0].dense_mask())
+    for x, y in zip(sa, sb):
+        assert np.array_equal(x["out"], y["out"])
+
+
+def test_paper_mask_sees_more_than_block_mask():
+    wl, attr = _paper_case(5, t=3, p=1, j_range=(2, 2), n_range=(2, 2), ragged_len=False)
+    a, _, _ = _run_oracle(wl, pos_mode="paper_gap", attr_len=attr, mask_mode="paper")
+    b, _, _ = _run_oracle(wl, pos_mode="paper_gap", attr_len=attr, mask_mode="block")
+    ma, mb = a.prompts[0].dense_mask(), b.prompts[0].dense_mask()
+    po = a.prompts[0]
+    rows = [i for i in range(len(po.kind)) if po.kind[i] == O.KIND_BRANCH]
+    assert np.all(ma[rows] >= mb[rows])  # the block mask is a subset
+    last = rows[-1]  # last attribute of the last document, last step
+    assert ma[last].sum() == len(po.kind) and mb[last].sum() < ma[last].sum()
+
+
+@pytest.mark.parametrize("seed,dtype,tol", [(41, np.float64, 1e-12), (42, np.float32, 2e-5)])
+def test_paper_mask_equals_causal_attention_in_position_order(seed, dtype, tol):
+    """Section 4.3.2: appended out of order in memory, the tokens attend as if the sequence
+    were laid out by position ID.  Library causal attention (is_causal=True) over everything
+    in memory after step t, sorted by position ID, with the independent complex-number RoPE
+    at the true position IDs: the rows of the step's queries must equal the oracle's."""
+    wl, attr = _paper_case(seed, t=4, p=2, hq=4, hkv=2, d=16, j_range=(1, 3), n_range=(1, 3),
+                           h_range=(0, 5), l_range=(1, 8))
+    orc, inputs, steps = _run_oracle(wl, dtype=dtype, pos_mode="paper_gap", attr_len=attr, mask_mode="paper")
+    g = wl.n_q_heads // wl.n_kv_heads
+    for p, po in orc.prompts.items():
+        a0, a1 = orc.prefix_range[p]
+        b0, b1 = orc.branch_range[p]
+        k_all = [inputs["kp"][a0:a1]]
+        v_all = [inputs["vp"][a0:a1]]
+        q_all = [np.zeros((a1 - a0, wl.n_q_heads, wl.head_dim))]
+        pos_all = [np.arange(a1 - a0)]
+        for t in range(wl.max_new):
+            live = np.nonzero(wl.branch_len > t)[0]
+            sel = np.nonzero((live >= b0) & (live < b1))[0]
+            if len(sel) == 0:
+                continue
+            k_all.append(inputs["k"][t][sel]); v_all.append(inputs["v"][t][sel]); q_all.append(inputs["q"][t][sel])
+            # closed form of Appendix A.1 for the position IDs (not the oracle's own table)
+            n_loc = live[sel] - b0
+            plen = a1 - a0
+            pos_all.append(np.asarray([plen + int(attr[b0:b0 + n + 1].sum()) - 1 + n * wl.max_new + t + 1
+                                       for n in n_loc]))
+            k = np.concatenate(k_all).astype(np.float64)
+            v = np.concatenate(v_all).astype(np.float64)
+            q = np.concatenate(q_all).astype(np.float64)
+            pos = np.concatenate(pos_all)
+            order = np.argsort(pos, kind="stable")
+            kr = _rope_complex(k[order], pos[order], wl.rope_base)
+            qr = _rope_complex(q[order], pos[order], wl.rope_base)
+            tq = torch.from_numpy(qr).permute(1, 0, 2)[None]
+            tk = torch.from_numpy(kr).permute(1, 0, 2).repeat_interleave(g, 0)[None]
+            tv = torch.from_numpy(v[order]).permute(1, 0, 2).repeat_interleave(g, 0)[None]
+            ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)
+            ref = ref[0].permute(1, 0, 2).numpy()
+            rank = np.empty_like(order)
+            rank[order] = np.arange(len(order))
+            n_mem = len(pos)
+            mine = np.nonzero(np.isin(steps[t]["rows"], sel))[0]
+            assert len(mine) == len(sel)
+            for i, r in enumerate(mine):
+                mem_index = n_mem - len(sel) + i  # this step's tokens are the last ones in memory
+                err = np.abs(steps[t]["out"][r] - ref[rank[mem_index]]).max()
+                assert err < tol, (p, t, i, err)
+
+
+def test_paper_mask_against_scalar_brute_force():
+    wl = W.make_workload("bfp", "f32", 4, 2, 8, 10000.0, 3, [2], [2], [3, 2], [2, 1], branch_len=[3, 1, 2])
+    attr = np.asarray([2, 1, 3])
+    orc, inputs, steps = _run_oracle(wl, dtype=np.float64, pos_mode="paper_gap", attr_len=attr,
+                                     mask_mode="paper")
+    bl = [[int(x) for x in wl.branch_len[wl.branch_ptr[d]:wl.branch_ptr[d + 1]]] for d in range(wl.n_docs)]
+    ref = brute_force.decode_all_steps_paper(
+        int(wl.header_len[0]), [int(x) for x in wl.doc_len], bl, [int(x) for x in attr], wl.n_q_heads,
+        wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new, inputs["kp"].tolist(), inputs["vp"].tolist(),
+        [x.tolist() for x in inputs["q"]], [x.tolist() for x in inputs["k"]], [x.tolist() for x in inputs["v"]])
+    for t in range(wl.max_new):
+        assert np.abs(steps[t]["out"] - np.asarray(ref[t])).max() < 1e-12
+
+
+@pytest.mark.parametrize("mistake", ["sees_later_attribute", "misses_earlier_attribute", "misses_other_document"])
+def test_paper_mask_planted_mistakes_are_caught(monkeypatch, mistake):
+    wl = W.make_workload("pl", "f32", 4, 2, 8, 10000.0, 3, [2], [2], [3, 2], [2, 2])
+    attr = np.asarray([2, 1, 3, 2])
+
+    def worst():
+        orc, inputs, steps = _run_oracle(wl, dtype=np.float64, pos_mode="paper_gap", attr_len=attr,
+                                         mask_mode="paper")
+        bl = [[3, 3], [3, 3]]
+        ref = brute_force.decode_all_steps_paper(
+            2, [3, 2], bl, [2, 1, 3, 2], 4, 2, 8, 10000.0, 3, inputs["kp"].tolist(), inputs["vp"].tolist(),
+            [x.tolist() for x in inputs["q"]], [x.tolist() for x in inputs["k"]], [x.tolist() for x in inputs["v"]])
+        return max(float(np.abs(steps[t]["out"] - np.asarray(ref[t])).max()) for t in range(3))
+
+    assert worst() < 1e-12
+    real = O.PromptOracle.mask_rows_fast
+
+    def bad(self, rows):
+        m = real(self, rows)
+        kind, br, doc = np.asarray(self.kind), np.asarray(self.branch), np.asarray(self.doc)
+        for r, qi in enumerate(rows):
+            if mistake == "sees_later_attribute":
+                m[r, (kind == O.KIND_BRANCH) & (br > br[qi]) & (np.arange(len(kind)) <= qi)] = 1
+            elif mistake == "misses_earlier_attribute":
+                m[r, (kind == O.KIND_BRANCH) & (br < br[qi])] = 0
+            else:
+                m[r, (kind == O.KIND_DOC) & (doc != doc[qi])] = 0
+        return m
+
+    monkeypatch.setattr(O.PromptOracle, "mask_rows_fast", bad)
+    assert worst() > 1e-6
