@@ -71,7 +71,17 @@ enum hpd_pos_mode {
   HPD_POS_PAPER_GAP = 1 /* Algorithm 2: ordinary positions over header + documents,
                            then a gap of max_new after every attribute */
 };
-enum hpd_mask_mode { HPD_MASK_BLOCK = 0 /* header + own document + own branch */ };
+enum hpd_mask_mode {
+  HPD_MASK_BLOCK = 0, /* header + own document + own branch */
+  HPD_MASK_PAPER = 1  /* Section 4.3.2 taken literally: one causal order by position ID over
+                         the whole stacked prompt.  A branch sees the header, every document
+                         of its prompt, the tokens of every earlier branch of the prompt (in
+                         the (document, attribute) order) up to the current step, finished
+                         branches included, and its own tokens.  Needs HPD_POS_PAPER_GAP
+                         (positions that restart per document do not order a prompt).
+                         The skeleton (attribute-name) tokens shape the position IDs but are
+                         not cache entries, as in HPD_MASK_BLOCK. */
+};
 enum hpd_out_dtype {
   HPD_OUT_SAME = 0, /* `out` has the element type of the inputs */
   HPD_OUT_F32 = 1   /* `out` is fp32 whatever the inputs are: bf16 cannot resolve 2e-2 x RMS

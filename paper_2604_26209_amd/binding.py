@@ -40,6 +40,7 @@ HPD_OK, HPD_E_INVALID, HPD_E_OVERFLOW, HPD_E_UNSUPPORTED, HPD_E_HIP, HPD_E_NOMEM
 HPD_F32, HPD_BF16 = 0, 1
 HPD_POS_CONTIG, HPD_POS_PAPER_GAP = 0, 1
 HPD_MASK_BLOCK = 0
+HPD_MASK_PAPER = 1
 HPD_FLAG_HOST_ONLY = 1
 HPD_OUT_SAME, HPD_OUT_F32 = 0, 1
 HPD_KEY_BLOCK = 32
@@ -237,15 +238,16 @@ def hpd_set_kernel_mode(layout, mode: int):
 # ---------------------------------------------------------------------------
 # marshalling helpers (no arithmetic of the method)
 # ---------------------------------------------------------------------------
-def config_from_workload(wl, pos_mode=HPD_POS_CONTIG, flags=0, out_dtype=HPD_OUT_SAME) -> hpd_config:
+def config_from_workload(wl, pos_mode=HPD_POS_CONTIG, flags=0, out_dtype=HPD_OUT_SAME,
+                         mask_mode=HPD_MASK_BLOCK) -> hpd_config:
     return hpd_config(wl.n_q_heads, wl.n_kv_heads, wl.head_dim,
                       HPD_F32 if wl.dtype == "f32" else HPD_BF16, float(wl.rope_base),
-                      wl.max_new, pos_mode, HPD_MASK_BLOCK, flags, out_dtype)
+                      wl.max_new, pos_mode, mask_mode, flags, out_dtype)
 
 
 def layout_from_workload(wl, pos_mode=HPD_POS_CONTIG, attr_len=None, flags=0, stream=None,
-                         out_dtype=HPD_OUT_SAME):
-    cfg = config_from_workload(wl, pos_mode, flags, out_dtype)
+                         out_dtype=HPD_OUT_SAME, mask_mode=HPD_MASK_BLOCK):
+    cfg = config_from_workload(wl, pos_mode, flags, out_dtype, mask_mode)
     return hpd_build_layout(cfg, wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr,
                             wl.branch_len, attr_len, stream)
 

@@ -805,7 +805,8 @@ hipError_t launch_g(const StreamArgs& a, int64_t items, const void* q, const voi
 
 bool hpd_stream_supported(const hpd_layout* L) {
   const int G = L->cfg.n_q_heads / L->cfg.n_kv_heads;
-  return L->cfg.dtype == HPD_BF16 && L->cfg.head_dim == D && (G == 1 || G == 2 || G == 4 || G == 8);
+  return L->cfg.mask_mode == HPD_MASK_BLOCK && L->cfg.dtype == HPD_BF16 && L->cfg.head_dim == D &&
+         (G == 1 || G == 2 || G == 4 || G == 8);
 }
 
 hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const void* q,

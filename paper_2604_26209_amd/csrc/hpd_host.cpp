@@ -40,7 +40,8 @@ int validate_config(const hpd_config* c) {
   if (c->dtype != HPD_F32 && c->dtype != HPD_BF16) return HPD_E_UNSUPPORTED;
   if (c->head_dim % 8 != 0 || c->head_dim > 256) return HPD_E_UNSUPPORTED;
   if (c->pos_mode != HPD_POS_CONTIG && c->pos_mode != HPD_POS_PAPER_GAP) return HPD_E_UNSUPPORTED;
-  if (c->mask_mode != HPD_MASK_BLOCK) return HPD_E_UNSUPPORTED;
+  if (c->mask_mode != HPD_MASK_BLOCK && c->mask_mode != HPD_MASK_PAPER) return HPD_E_UNSUPPORTED;
+  if (c->mask_mode == HPD_MASK_PAPER && c->pos_mode != HPD_POS_PAPER_GAP) return HPD_E_INVALID;
   if (c->flags & ~HPD_FLAG_HOST_ONLY) return HPD_E_INVALID;
   if (c->out_dtype != HPD_OUT_SAME && c->out_dtype != HPD_OUT_F32) return HPD_E_UNSUPPORTED;
   return HPD_OK;
@@ -116,6 +117,9 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     L->doc_prompt.assign(n_docs, 0);
     L->branch_doc.assign(B, 0); L->branch_base_pos.assign(B, 0); L->branch_len.assign(B, T);
     if (branch_len) std::copy(branch_len, branch_len + B, L->branch_len.begin());
+    L->prompt_doc_ptr.assign(doc_ptr, doc_ptr + P + 1);
+    L->prompt_branch_ptr.resize(P + 1);
+    for (int32_t p = 0; p <= P; ++p) L->prompt_branch_ptr[p] = branch_ptr[doc_ptr[p]];
 
     // ---- segments: pool slots (each segment starts on a HPD_KEY_BLOCK boundary), raw
     //      token order [header | doc_0 | doc_1 ...] per prompt, position of first token
@@ -252,7 +256,9 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
                  o_branch_doc = A.add(L->branch_doc), o_base = A.add(L->branch_base_pos),
                  o_live_ptr = A.add(L->live_ptr), o_live_branch = A.add(L->live_branch),
                  o_dlp = A.add(L->doc_live_ptr), o_unit_ptr = A.add(L->unit_ptr),
-                 o_unit_doc = A.add(L->unit_doc), o_unit_desc = A.add(L->unit_desc);
+                 o_unit_doc = A.add(L->unit_doc), o_unit_desc = A.add(L->unit_desc),
+                 o_pdp = A.add(L->prompt_doc_ptr), o_pbp = A.add(L->prompt_branch_ptr),
+                 o_blen = A.add(L->branch_len);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipGetDevice(&L->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&L->n_cus, hipDeviceAttributeMultiprocessorCount, L->device);
@@ -279,6 +285,8 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     L->dev.live_ptr = base + o_live_ptr; L->dev.live_branch = base + o_live_branch;
     L->dev.doc_live_ptr = base + o_dlp; L->dev.unit_ptr = base + o_unit_ptr;
     L->dev.unit_doc = base + o_unit_doc; L->dev.unit_desc = base + o_unit_desc;
+    L->dev.prompt_doc_ptr = base + o_pdp; L->dev.prompt_branch_ptr = base + o_pbp;
+    L->dev.branch_len = base + o_blen;
     L->dev.rope = (const float2*)L->d_rope;
     L->on_device = true;
   }
@@ -408,13 +416,7 @@ int hpd_decode_attention(const hpd_layout* L, int32_t step, const void* q, const
                                         (hipStream_t)stream));
   } else {
     // the generic kernel keeps one score per key in LDS
-    int64_t max_keys = 0;
-    for (int32_t u = L->unit_ptr[step]; u < L->unit_ptr[step + 1]; ++u) {
-      const int32_t d = L->unit_doc[u];
-      max_keys = std::max<int64_t>(max_keys, (int64_t)L->seg_len[L->doc_prompt[d]] +
-                                                 L->seg_len[L->P + d] + step + 1);
-    }
-    if (max_keys > 15000) return HPD_E_UNSUPPORTED;
+    if (hpd_generic_max_keys(L, step) > 15000) return HPD_E_UNSUPPORTED;
     HPD_HIP(hpd_launch_attention_generic(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out,
                                          (hipStream_t)stream));
   }
@@ -445,21 +447,24 @@ int hpd_expand_mask(const hpd_layout* L, int32_t prompt, int32_t step_hi, uint8_
                     int32_t* s_out, void* stream) {
   if (!L || !L->on_device || !s_out) return HPD_E_INVALID;
   if (prompt < 0 || prompt >= L->P || step_hi < -1 || step_hi >= L->T) return HPD_E_INVALID;
-  // token descriptors in memory order: (kind, document, branch, step)
-  //   kind 0 header, 1 document, 2 branch token
+  // token descriptors in memory order: (kind, document, branch, step | position for the
+  // paper-literal mask);  kind 0 header, 1 document, 2 branch token
+  const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
   std::vector<int32_t> desc;
   const int32_t H = L->seg_len[prompt];
-  for (int32_t i = 0; i < H; ++i) { desc.insert(desc.end(), {0, -1, -1, -1}); }
+  for (int32_t i = 0; i < H; ++i) { desc.insert(desc.end(), {0, -1, -1, paper ? i : -1}); }
   int32_t d0 = -1, d1 = -1;
   for (int32_t d = 0; d < L->n_docs; ++d)
     if (L->doc_prompt[d] == prompt) { if (d0 < 0) d0 = d; d1 = d + 1; }
   for (int32_t d = d0; d >= 0 && d < d1; ++d)
-    for (int32_t i = 0; i < L->seg_len[L->P + d]; ++i) desc.insert(desc.end(), {1, d, -1, -1});
+    for (int32_t i = 0; i < L->seg_len[L->P + d]; ++i)
+      desc.insert(desc.end(), {1, d, -1, paper ? L->seg_pos0[L->P + d] + i : -1});
   for (int32_t t = 0; t <= step_hi; ++t)
     for (int32_t r = L->live_ptr[t]; r < L->live_ptr[t + 1]; ++r) {
       const int32_t b = L->live_branch[r];
       const int32_t d = L->branch_doc[b];
-      if (L->doc_prompt[d] == prompt) desc.insert(desc.end(), {2, d, b, t});
+      if (L->doc_prompt[d] == prompt)
+        desc.insert(desc.end(), {2, d, b, paper ? L->branch_base_pos[b] + 1 + t : t});
     }
   const int64_t S = (int64_t)desc.size() / 4;
   if (S > 46000) return HPD_E_OVERFLOW;
@@ -470,7 +475,7 @@ int hpd_expand_mask(const hpd_layout* L, int32_t prompt, int32_t step_hi, uint8_
   HPD_HIP(hipMalloc((void**)&d_desc, desc.size() * sizeof(int32_t)));
   hipError_t e = hipMemcpyAsync(d_desc, desc.data(), desc.size() * sizeof(int32_t),
                                 hipMemcpyHostToDevice, s);
-  if (e == hipSuccess) e = hpd_launch_expand_mask(d_desc, (int32_t)S, mask_out, s);
+  if (e == hipSuccess) e = hpd_launch_expand_mask(d_desc, (int32_t)S, paper ? 1 : 0, mask_out, s);
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   (void)hipFree(d_desc);
   if (e != hipSuccess) return hip_fail(e);

@@ -25,6 +25,9 @@ struct hpd_dev_tables {
   const int32_t* unit_ptr;      // [T+1]
   const int32_t* unit_doc;      // [total_units] documents with live branches, heaviest first
   const int32_t* unit_desc;     // [total_units][8] {hoff, Hlen, doff, Llen, first live row, live branches, position or -1, first branch id or -1}
+  const int32_t* prompt_doc_ptr;     // [P+1] first document of each prompt
+  const int32_t* prompt_branch_ptr;  // [P+1] first branch of each prompt
+  const int32_t* branch_len;         // [B] steps a branch is decoded for
   const float2* rope;           // [max_pos+1][D/2] (cos, sin)
 };
 
@@ -37,6 +40,7 @@ struct hpd_layout {
 
   std::vector<int32_t> seg_off, seg_len, seg_pos0, seg_raw_off, raw_seg;
   std::vector<int32_t> doc_prompt, branch_doc, branch_base_pos, branch_len;
+  std::vector<int32_t> prompt_doc_ptr, prompt_branch_ptr;
   std::vector<int32_t> live_ptr, live_branch, doc_live_ptr, unit_ptr, unit_doc, unit_desc;
   std::vector<int32_t> max_rows;  // [T] largest number of live branches of any document at step t
   std::vector<float> rope;        // host copy of the (cos, sin) table
@@ -64,7 +68,11 @@ hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const
                                         const void* k_prefix, const void* v_prefix,
                                         const void* k_tail, const void* v_tail, void* out,
                                         hipStream_t s);
-hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, uint8_t* mask_out, hipStream_t s);
+hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, int32_t paper, uint8_t* mask_out,
+                                  hipStream_t s);
+
+// most keys any row of the step has in the generic kernel (it keeps one score per key in LDS)
+int64_t hpd_generic_max_keys(const hpd_layout* L, int32_t step);
 
 bool hpd_stream_supported(const hpd_layout* L);
 // k_new / v_new may be null: then the newest token is read from the tail pool like the others

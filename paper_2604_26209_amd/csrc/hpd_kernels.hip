@@ -115,9 +115,11 @@ __global__ void append_kernel(hpd_dev_tables tb, int32_t step, int32_t n_live, i
 }
 
 // ---------------------------------------------------------------------------------------
-// Dense mask export (debugging aid).  desc[S][4] = (kind, document, branch, step).
+// Dense mask export (debugging aid).  desc[S][4] = (kind, document, branch, step); for the
+// paper-literal mask the last entry is the position ID and the rule is Section 4.3.2's:
+// already in memory and not later in position order.
 // ---------------------------------------------------------------------------------------
-__global__ void expand_mask_kernel(const int32_t* __restrict__ desc, int32_t S,
+__global__ void expand_mask_kernel(const int32_t* __restrict__ desc, int32_t S, int32_t paper,
                                    uint8_t* __restrict__ mask) {
   const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (gid >= (int64_t)S * S) return;
@@ -125,7 +127,8 @@ __global__ void expand_mask_kernel(const int32_t* __restrict__ desc, int32_t S,
   const int32_t qk = desc[qi * 4], qd = desc[qi * 4 + 1], qb = desc[qi * 4 + 2], qs = desc[qi * 4 + 3];
   const int32_t kk = desc[ki * 4], kd = desc[ki * 4 + 1], kb = desc[ki * 4 + 2], ks = desc[ki * 4 + 3];
   bool ok;
-  if (kk == 0) ok = (qk != 0) || (ki <= qi);                         // header key
+  if (paper) ok = ki <= qi && ks <= qs;
+  else if (kk == 0) ok = (qk != 0) || (ki <= qi);                    // header key
   else if (kk == 1) ok = (qk == 1 && qd == kd && ki <= qi) || (qk == 2 && qd == kd);  // doc key
   else ok = (qk == 2 && qb == kb && ks <= qs);                        // branch key
   mask[gid] = ok ? 1 : 0;
@@ -154,7 +157,10 @@ __device__ inline float block_reduce(float v, bool is_max, float* red) {
   return r;
 }
 
-template <typename T>
+// PAPER = the literal mask of Section 4.3.2: the keys of a row are the header, every document
+// of the prompt, and positions 0..step of every branch of the prompt up to the row's own (a
+// position a finished branch never reached gets probability 0).
+template <typename T, bool PAPER>
 __global__ void __launch_bounds__(GEN_THREADS)
 attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hkv, int32_t D,
                          int32_t Tcap, int32_t P, int64_t NP, const T* __restrict__ q,
@@ -174,11 +180,30 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
   const int32_t d = tb.branch_doc[b];
   const int32_t p = tb.doc_prompt[d];
   const int32_t pos = tb.branch_base_pos[b] + 1 + step;
-  const int32_t Hlen = tb.seg_len[p], Llen = tb.seg_len[P + d];
-  const int64_t hoff = tb.seg_off[p], doff = tb.seg_off[P + d];
-  const int32_t n_keys = Hlen + Llen + step + 1;
+  const int32_t Hlen = tb.seg_len[p];
+  const int64_t hoff = tb.seg_off[p];
+  // documents the row sees: its own, or all of its prompt
+  const int32_t d_lo = PAPER ? tb.prompt_doc_ptr[p] : d, d_hi = PAPER ? tb.prompt_doc_ptr[p + 1] : d + 1;
+  int32_t Llen = 0;
+  for (int32_t dd = d_lo; dd < d_hi; ++dd) Llen += tb.seg_len[P + dd];
+  // branches whose tails the row sees: its own, or the prompt's first .. its own
+  const int32_t b_lo = PAPER ? tb.prompt_branch_ptr[p] : b;
+  const int32_t n_tail = (b - b_lo + 1) * (step + 1);
+  const int32_t n_keys = Hlen + Llen + n_tail;
   const int32_t half = D / 2;
   const int tid = threadIdx.x;
+  // pool slot of prefix key kk (>= Hlen: the documents one after the other)
+  auto doc_slot = [&](int32_t kk) -> int64_t {
+    int32_t i = kk - Hlen, dd = d_lo;
+    while (i >= tb.seg_len[P + dd]) { i -= tb.seg_len[P + dd]; ++dd; }
+    return (int64_t)tb.seg_off[P + dd] + i;
+  };
+  // tail key i: position i % (step+1) of branch b_lo + i / (step+1); -1 if it does not exist
+  auto tail_row = [&](int32_t i) -> int64_t {
+    const int32_t bb = b_lo + i / (step + 1), tt = i % (step + 1);
+    if (tt >= tb.branch_len[bb]) return -1;
+    return (((int64_t)bb * Hkv + hk) * Tcap + tt) * D;
+  };
 
   if (tid < half) {
     const float2 cs = tb.rope[(int64_t)pos * half + tid];
@@ -189,13 +214,16 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
   __syncthreads();
 
   const float scale = 1.0f / sqrtf((float)D);
-  const int64_t tail_base = (((int64_t)b * Hkv + hk) * Tcap) * D;
   float lmax = -INFINITY;
   for (int32_t kk = tid; kk < n_keys; kk += GEN_THREADS) {
     const T* kp;
     if (kk < Hlen) kp = k_prefix + ((int64_t)hk * NP + hoff + kk) * D;
-    else if (kk < Hlen + Llen) kp = k_prefix + ((int64_t)hk * NP + doff + (kk - Hlen)) * D;
-    else kp = k_tail + tail_base + (int64_t)(kk - Hlen - Llen) * D;
+    else if (kk < Hlen + Llen) kp = k_prefix + ((int64_t)hk * NP + doc_slot(kk)) * D;
+    else {
+      const int64_t row = tail_row(kk - Hlen - Llen);
+      if (row < 0) { scores[kk] = -INFINITY; continue; }
+      kp = k_tail + row;
+    }
     float acc = 0.f;
     for (int32_t c = 0; c < D; c += 8) {
       float kv[8];
@@ -224,10 +252,12 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
     for (int32_t kk = g; kk < n_keys; kk += groups) {
       float vv;
       if (kk < Hlen + Llen) {
-        const int64_t slot = (kk < Hlen) ? hoff + kk : doff + (kk - Hlen);
+        const int64_t slot = (kk < Hlen) ? hoff + kk : doc_slot(kk);
         vv = hpd::to_float(v_prefix[((vhead + slot / 8) * D + c) * 8 + (slot & 7)]);
       } else {
-        vv = hpd::to_float(v_tail[tail_base + (int64_t)(kk - Hlen - Llen) * D + c]);
+        const int64_t row = tail_row(kk - Hlen - Llen);
+        if (row < 0) continue;  // probability 0
+        vv = hpd::to_float(v_tail[row + c]);
       }
       acc = fmaf(scores[kk], vv, acc);
     }
@@ -290,34 +320,53 @@ hipError_t hpd_launch_append(const hpd_layout* L, int32_t step, const void* k_ne
   return hipGetLastError();
 }
 
-hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const void* q,
-                                        const void* k_prefix, const void* v_prefix,
-                                        const void* k_tail, const void* v_tail, void* out,
-                                        hipStream_t s) {
-  const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
+int64_t hpd_generic_max_keys(const hpd_layout* L, int32_t step) {
   int64_t max_keys = 0;
+  if (L->cfg.mask_mode == HPD_MASK_PAPER) {
+    for (int32_t p = 0; p < L->P; ++p) {
+      int64_t n = L->seg_len[p];
+      for (int32_t d = L->prompt_doc_ptr[p]; d < L->prompt_doc_ptr[p + 1]; ++d) n += L->seg_len[L->P + d];
+      n += (int64_t)(L->prompt_branch_ptr[p + 1] - L->prompt_branch_ptr[p]) * (step + 1);
+      max_keys = std::max(max_keys, n);
+    }
+    return max_keys;
+  }
   for (int32_t u = L->unit_ptr[step]; u < L->unit_ptr[step + 1]; ++u) {
     const int32_t d = L->unit_doc[u];
     max_keys = std::max<int64_t>(max_keys, (int64_t)L->seg_len[L->doc_prompt[d]] +
                                                L->seg_len[L->P + d] + step + 1);
   }
-  const size_t smem = (size_t)(L->cfg.head_dim + 8 + GEN_THREADS + max_keys) * sizeof(float);
+  return max_keys;
+}
+
+template <typename T, bool PAPER>
+static hipError_t launch_generic(const hpd_layout* L, int32_t step, const void* q, const void* k_prefix,
+                                 const void* v_prefix, const void* k_tail, const void* v_tail, void* out,
+                                 hipStream_t s) {
+  const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
+  const size_t smem = (size_t)(L->cfg.head_dim + 8 + GEN_THREADS + hpd_generic_max_keys(L, step)) * sizeof(float);
   const dim3 grid((unsigned)((int64_t)n_live * L->cfg.n_q_heads));
-  if (L->cfg.dtype == HPD_F32)
-    attention_generic_kernel<float><<<grid, GEN_THREADS, smem, s>>>(
-        L->dev, step, L->cfg.n_q_heads, L->cfg.n_kv_heads, L->cfg.head_dim, L->T, L->P, L->NP,
-        (const float*)q, (const float*)k_prefix, (const float*)v_prefix, (const float*)k_tail,
-        (const float*)v_tail, out, 1);
-  else
-    attention_generic_kernel<hpd::bf16_t><<<grid, GEN_THREADS, smem, s>>>(
-        L->dev, step, L->cfg.n_q_heads, L->cfg.n_kv_heads, L->cfg.head_dim, L->T, L->P, L->NP,
-        (const hpd::bf16_t*)q, (const hpd::bf16_t*)k_prefix, (const hpd::bf16_t*)v_prefix,
-        (const hpd::bf16_t*)k_tail, (const hpd::bf16_t*)v_tail, out,
-        L->cfg.out_dtype == HPD_OUT_F32 ? 1 : 0);
+  const int32_t out_f32 = (L->cfg.dtype == HPD_F32 || L->cfg.out_dtype == HPD_OUT_F32) ? 1 : 0;
+  attention_generic_kernel<T, PAPER><<<grid, GEN_THREADS, smem, s>>>(
+      L->dev, step, L->cfg.n_q_heads, L->cfg.n_kv_heads, L->cfg.head_dim, L->T, L->P, L->NP, (const T*)q,
+      (const T*)k_prefix, (const T*)v_prefix, (const T*)k_tail, (const T*)v_tail, out, out_f32);
   return hipGetLastError();
 }
 
-hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, uint8_t* mask_out, hipStream_t s) {
-  expand_mask_kernel<<<grid1d((int64_t)S * S, 256), 256, 0, s>>>(d_desc, S, mask_out);
+hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const void* q,
+                                        const void* k_prefix, const void* v_prefix,
+                                        const void* k_tail, const void* v_tail, void* out,
+                                        hipStream_t s) {
+  const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
+  if (L->cfg.dtype == HPD_F32)
+    return paper ? launch_generic<float, true>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s)
+                 : launch_generic<float, false>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s);
+  return paper ? launch_generic<hpd::bf16_t, true>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s)
+               : launch_generic<hpd::bf16_t, false>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s);
+}
+
+hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, int32_t paper, uint8_t* mask_out,
+                                  hipStream_t s) {
+  expand_mask_kernel<<<grid1d((int64_t)S * S, 256), 256, 0, s>>>(d_desc, S, paper, mask_out);
   return hipGetLastError();
 }

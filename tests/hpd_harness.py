@@ -36,13 +36,13 @@ class Inputs:
 
 
 def run_hip(wl, inputs=None, kernel_mode=0, fused=False, pos_mode=0, attr_len=None,
-            poison_pools=True, steps=None, out_f32=None):
+            poison_pools=True, steps=None, out_f32=None, mask_mode=0):
     """Runs every step through the C ABI.  Returns dict(out, pos, slot per step, layout, inputs)."""
     from paper_2604_26209_amd import binding as B
 
     if out_f32 is None:  # bf16 inputs are checked on fp32 outputs (see compare_outputs)
         out_f32 = wl.dtype == "bf16"
-    layout = B.layout_from_workload(wl, pos_mode=pos_mode, attr_len=attr_len,
+    layout = B.layout_from_workload(wl, pos_mode=pos_mode, attr_len=attr_len, mask_mode=mask_mode,
                                     out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME)
     if kernel_mode:
         B.hpd_set_kernel_mode(layout, kernel_mode)
@@ -81,12 +81,12 @@ def run_hip(wl, inputs=None, kernel_mode=0, fused=False, pos_mode=0, attr_len=No
 
 
 def run_oracle(wl, inputs, prompts=None, pos_mode="contig", attr_len=None, steps=None,
-               cache_dtype="auto"):
+               cache_dtype="auto", mask_mode="block"):
     """Runs the CPU oracle on (a subset of prompts of) the same inputs.  Inputs may live on
     the GPU; only what the chosen prompts need is copied.  Returns per-step result dicts."""
     orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len,
                       wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new,
-                      pos_mode=pos_mode, attr_len=attr_len, prompts=prompts,
+                      pos_mode=pos_mode, attr_len=attr_len, prompts=prompts, mask_mode=mask_mode,
                       cache_dtype=("bf16" if wl.dtype == "bf16" else None) if cache_dtype == "auto"
                       else cache_dtype)
     kd, vd = {}, {}
@@ -146,9 +146,10 @@ def compare_outputs(wl, hip_out, ref, label="", group="step", t=None):
     return worst
 
 
-def check_all(wl, hip, prompts=None, pos_mode="contig", attr_len=None, label="", group="step"):
+def check_all(wl, hip, prompts=None, pos_mode="contig", attr_len=None, label="", group="step",
+              mask_mode="block"):
     """Bit-exact positions / slots and toleranced outputs for the chosen prompts, all steps."""
-    orc, res = run_oracle(wl, hip["inputs"], prompts, pos_mode, attr_len)
+    orc, res = run_oracle(wl, hip["inputs"], prompts, pos_mode, attr_len, mask_mode=mask_mode)
     worst = 0.0
     for t, ref in enumerate(res):
         rows = ref["rows"]

@@ -118,6 +118,32 @@ def test_paper_gap_positions_mode():
     H.check_all(wl, hip, pos_mode="paper_gap", attr_len=attr, label="gap_f32")
 
 
+def test_paper_literal_mask_mode():
+    """HPD_MASK_PAPER: one causal order by position ID over the whole stacked prompt (all
+    documents, the tokens of every earlier branch up to the current step, finished ones
+    included).  Outputs against the oracle's dense mask, and the exported mask bit-exact."""
+    from paper_2604_26209_amd import binding as B
+    cases = [("f32", dict(hq=4, hkv=2, d=64, t=5, p=2, j_range=(1, 3), n_range=(1, 5), l_range=(1, 40))),
+             ("bf16", dict(hq=8, hkv=2, d=128, base=500000.0, t=6, p=3, j_range=(1, 4), n_range=(1, 9),
+                           h_range=(0, 70), l_range=(1, 150)))]
+    for i, (dt, kw) in enumerate(cases):
+        wl = W.random_workload(70 + i, dtype=dt, **kw)
+        attr = np.random.default_rng(70 + i).integers(1, 6, size=wl.n_branches).astype(np.int32)
+        for fused in (False, True):
+            _say(f"paper mask {dt} fused {fused}")
+            hip = H.run_hip(wl, pos_mode=1, attr_len=attr, mask_mode=B.HPD_MASK_PAPER, fused=fused)
+            H.check_all(wl, hip, pos_mode="paper_gap", attr_len=attr, mask_mode="paper", label=f"paper_{dt}")
+        orc, _ = H.run_oracle(wl, hip["inputs"], pos_mode="paper_gap", attr_len=attr, mask_mode="paper")
+        for p, po in orc.prompts.items():
+            s = B.hpd_expand_mask(hip["layout"], p, wl.max_new - 1)
+            m = torch.full((s, s), 7, dtype=torch.uint8, device="cuda")
+            B.hpd_expand_mask(hip["layout"], p, wl.max_new - 1, m)
+            assert np.array_equal(m.cpu().numpy(), po.dense_mask())
+    # the literal mask orders a prompt by position ID: positions that restart per document do not
+    with pytest.raises(B.HpdError):
+        B.layout_from_workload(wl, pos_mode=0, mask_mode=B.HPD_MASK_PAPER)
+
+
 def test_mask_export_bit_exact():
     from paper_2604_26209_amd import binding as B
     _say("mask export")
