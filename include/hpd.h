@@ -119,7 +119,8 @@ enum hpd_query {
   HPD_Q_SEG_LEN = 7,     /* int32[P + n_docs] */
   HPD_Q_SEG_POS0 = 8,    /* int32[P + n_docs]: position ID of the segment's first token */
   HPD_Q_SEG_RAW_OFF = 9, /* int32[P + n_docs]: first token in hpd_prefix_fill's input order */
-  HPD_Q_N_UNITS = 10     /* int32[T]: documents with at least one live branch per step */
+  HPD_Q_N_UNITS = 10     /* int32[T]: documents (prompts, under HPD_MASK_PAPER) with at least one
+                            live branch per step: the work units of the attention kernel */
 };
 enum hpd_count {
   HPD_C_N_PROMPTS = 0,

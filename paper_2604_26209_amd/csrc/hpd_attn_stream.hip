@@ -159,7 +159,13 @@ __device__ __forceinline__ void rotate16(uint4 raw_lo, uint4 raw_hi, const float
   }
 }
 
-template <int G, typename SH>
+// PAPER = the literal mask of Section 4.3.2 (one causal order by position ID over the whole
+// stacked prompt).  The work unit is then (prompt, kv head, row group): the rows are the live
+// branches of the prompt, the prefix is the header and ALL documents of the prompt (block list
+// from a table), and the tail tiles run over every branch of the prompt from the first to the
+// row group's last - finished ones included, up to the length they reached -, a row keeping
+// the keys of the branches that are not later than its own.
+template <int G, typename SH, bool PAPER>
 __global__ void __launch_bounds__(SH::WAVES * 64, 2)
 attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_prefix,
                    const uint16_t* __restrict__ v_prefix, uint16_t* __restrict__ k_tail,
@@ -177,6 +183,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   __shared__ uint4 ring2[STAGE_U4];
   __shared__ uint4 ring3[STAGE_U4];
   __shared__ float4 rope_q[32];  // (cos, sin) row of the unit's shared position
+  constexpr int MAX_KEY_BRANCHES = 256;
+  __shared__ int32_t klen[PAPER ? MAX_KEY_BRANCHES : 1];  // tokens in memory of every key branch
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
@@ -193,9 +201,12 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   if (grp >= a.n_groups) return;  // the grid is padded to a multiple of 8 groups
   const int32_t hk = grp % a.Hkv;
   const int32_t u = grp / a.Hkv;
-  const int32_t* desc = a.tb.unit_desc + (int64_t)u * 8;  // pre-offset to this step by the host
+  // PAPER: {hoff, Hlen, first entry of the prompt's block list, document blocks, first live
+  //         row, live branches, first branch of the prompt, first live branch | -1, key branches}
+  const int32_t* desc = (PAPER ? a.tb.punit_desc : a.tb.unit_desc) + (int64_t)u * (PAPER ? 16 : 8);  // pre-offset to this step by the host
   const int32_t hoff = desc[0], Hlen = desc[1], doff = desc[2], Llen = desc[3];
-  const int32_t row0_live = desc[4], nb = desc[5], upos = desc[6], ub0 = desc[7];
+  const int32_t row0_live = desc[4], nb = desc[5], upos = PAPER ? -1 : desc[6], ub0 = desc[7];
+  const int32_t pb0 = PAPER ? desc[6] : 0;
 
   const int32_t R = nb * G;
   const int32_t nblk = (R + 31) >> 5;
@@ -223,15 +234,20 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t br0 = first_blk * BPB;
   const int32_t nbr_here = min(nb - br0, nblk_here * BPB);
   const int32_t rows_here = nbr_here * G;
-  auto branch_id = [&](int32_t lb) -> int32_t {
-    return ub0 >= 0 ? ub0 + br0 + lb : a.tb.live_branch[a.live_base + row0_live + br0 + lb];
+  // global id of the unit's li-th live branch / of the row group's lb-th
+  auto unit_branch = [&](int32_t li) -> int32_t {
+    return ub0 >= 0 ? ub0 + li : a.tb.live_branch[a.live_base + row0_live + li];
   };
+  auto branch_id = [&](int32_t lb) -> int32_t { return unit_branch(br0 + lb); };
+  // PAPER: the tails the row group sees are those of the prompt's branches 0 .. kb_end-1
+  // (numbered from the prompt's first), kb_end-1 being the branch of its last row
+  const int32_t kb_end = PAPER ? __builtin_amdgcn_readfirstlane(branch_id(nbr_here - 1)) - pb0 + 1 : 0;
 
   // ---- the stream: NB prefix blocks, then NQ * NC tail tiles (quad-major inside a chunk of 8
   //      positions), two blocks per round
-  const int32_t NBh = (Hlen + 31) >> 5, NBd = (Llen + 31) >> 5;
+  const int32_t NBh = (Hlen + 31) >> 5, NBd = PAPER ? Llen : (Llen + 31) >> 5;
   const int32_t NB = NBh + NBd;
-  const int32_t NQ = (nbr_here + 3) >> 2;  // quads of 4 branches
+  const int32_t NQ = ((PAPER ? kb_end : nbr_here) + 3) >> 2;  // quads of 4 (key) branches
   const int32_t NC = (a.step >> 3) + 1;    // chunks of 8 positions that hold positions 0 .. step
   const int32_t NTT = NQ * NC;
   const int32_t NBT = NB + NTT;
@@ -246,6 +262,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // quads are taken row block by row block first (the first quad of every row block, then the
   // second, ...), so that neighbouring tiles go to different waves.
   auto quad_of = [&](int32_t o) -> int32_t {
+    if (PAPER) return o;
     int32_t m = 0;
     for (;;) {
       const int32_t n_m = (NQ - m + QPR - 1) / QPR;  // quads whose index within the row block is m
@@ -287,7 +304,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     int32_t slot0 = 0, tc = 0, tq = 0;
     const bool prefix = gb < NB;
     if (prefix) {
-      slot0 = gb < NBh ? hoff + gb * 32 : doff + (gb - NBh) * 32;
+      if (PAPER) slot0 = gb < NBh ? hoff + gb * 32 : scalar_load(a.tb.pblk + 2 * (doff + gb - NBh));
+      else slot0 = gb < NBh ? hoff + gb * 32 : doff + (gb - NBh) * 32;
     } else {
       // tail tile: key k = position c*8 + k%8 of branch qd*4 + k/8; row k = h*16 + f*4 + lane/16
       // is position (f&1)*4 + lane/16 of branch 2*h + f/2.  Branches and positions past the
@@ -319,18 +337,29 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         }
       } else {
         // the branch of a load is the same in all lanes: a scalar lookup
-        const int32_t lbA = min(tq * 4 + half * 2, nbr_here - 1), lbB = min(tq * 4 + half * 2 + 1, nbr_here - 1);
-        const int32_t* ids = a.tb.live_branch + (a.live_base + row0_live + br0);
-        const int32_t bA = ub0 >= 0 ? ub0 + br0 + lbA : scalar_load(ids + lbA);
-        const int32_t bB = ub0 >= 0 ? ub0 + br0 + lbB : scalar_load(ids + lbB);
-        const int32_t posA = min(tc * 8 + r4, a.step), posB = min(tc * 8 + 4 + r4, a.step);
+        int32_t bA, bB, lastA = a.step, lastB = a.step;  // branch ids; last position in memory
+        if (PAPER) {
+          // key branches are consecutive ids from the prompt's first; a finished branch
+          // stops at its own length (the rows behind it were never written)
+          bA = pb0 + min(tq * 4 + half * 2, kb_end - 1);
+          bB = pb0 + min(tq * 4 + half * 2 + 1, kb_end - 1);
+          lastA = min(a.step, scalar_load(a.tb.branch_len + bA) - 1);
+          lastB = min(a.step, scalar_load(a.tb.branch_len + bB) - 1);
+        } else {
+          const int32_t lbA = min(tq * 4 + half * 2, nbr_here - 1), lbB = min(tq * 4 + half * 2 + 1, nbr_here - 1);
+          const int32_t* ids = a.tb.live_branch + (a.live_base + row0_live + br0);
+          bA = ub0 >= 0 ? ub0 + br0 + lbA : scalar_load(ids + lbA);
+          bB = ub0 >= 0 ? ub0 + br0 + lbB : scalar_load(ids + lbB);
+        }
+        const int32_t posA = min(tc * 8 + r4, lastA), posB = min(tc * 8 + 4 + r4, lastA);
+        const int32_t posC = min(tc * 8 + r4, lastB), posD = min(tc * 8 + 4 + r4, lastB);
         const uint16_t* pool = is_k ? k_tail : v_tail;
         const uint16_t* rowA = pool + ((int64_t)bA * a.Hkv + hk) * a.Tcap * D;
         const uint16_t* rowB = pool + ((int64_t)bB * a.Hkv + hk) * a.Tcap * D;
         p0 = rowA + (int64_t)posA * D + e0;
         p1 = rowA + (int64_t)posB * D + (e0 ^ x1);
-        p2 = rowB + (int64_t)posA * D + (e0 ^ x2);
-        p3 = rowB + (int64_t)posB * D + (e0 ^ x1 ^ x2);
+        p2 = rowB + (int64_t)posC * D + (e0 ^ x2);
+        p3 = rowB + (int64_t)posD * D + (e0 ^ x1 ^ x2);
       }
       // Tail rows and - unless several row groups stream the same prefix - document blocks are
       // read once per launch: ask the caches not to keep them (measured: 4-5 % on the
@@ -349,12 +378,18 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       }
     }
   };
-  // ---- fused mode: the compute waves append the newest token of the unit's branches (the
-  //      arithmetic of hpd_kv_append), 8 lanes per branch: channels c .. c+7 and 64+c .. 64+c+7
+  // ---- fused mode: the compute waves append the newest token of the row group's branches (the
+  //      arithmetic of hpd_kv_append), 8 lanes per branch: channels c .. c+7 and 64+c .. 64+c+7.
+  //      PAPER: the rows also see the newest token of every earlier live branch of the prompt,
+  //      which belongs to another row group's workgroup when there are several: every
+  //      workgroup appends all live branches up to its own last (the same bytes from every
+  //      writer) instead of waiting for its neighbours.
+  //      `li` counts the unit's live branches.
+  const int32_t ap_first = PAPER ? 0 : br0, ap_end = br0 + nbr_here;
   const int32_t ap_c = (tid & 7) * 8;
   struct NewRows { uint4 klo, khi, vlo, vhi; };
-  auto append_load = [&](int32_t lb) -> NewRows {
-    const int64_t noff = ((int64_t)(row0_live + br0 + lb) * a.Hkv + hk) * D;
+  auto append_load = [&](int32_t li) -> NewRows {
+    const int64_t noff = ((int64_t)(row0_live + li) * a.Hkv + hk) * D;
     NewRows r;
     r.klo = *reinterpret_cast<const uint4*>(k_new + noff + ap_c);
     r.khi = *reinterpret_cast<const uint4*>(k_new + noff + 64 + ap_c);
@@ -362,8 +397,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     r.vhi = *reinterpret_cast<const uint4*>(v_new + noff + 64 + ap_c);
     return r;
   };
-  auto append_store = [&](int32_t lb, const NewRows& r, bool use_rope_q) {
-    const int32_t b = branch_id(lb);
+  auto append_store = [&](int32_t li, const NewRows& r, bool use_rope_q) {
+    const int32_t b = unit_branch(li);
     const int32_t pos = upos >= 0 ? upos : a.tb.branch_base_pos[b] + 1 + a.step;
     float rl[8], rh[8];
     if (use_rope_q) rotate16(r.klo, r.khi, reinterpret_cast<const float2*>(rope_q), ap_c, rl, rh);
@@ -375,8 +410,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     *reinterpret_cast<uint4*>(vd + ap_c) = r.vlo;
     *reinterpret_cast<uint4*>(vd + 64 + ap_c) = r.vhi;
   };
-  auto append_from = [&](int32_t lb0) {
-    for (int32_t lb = lb0; lb < nbr_here; lb += CWAVES * 8) append_store(lb, append_load(lb), false);
+  auto append_from = [&](int32_t li0) {
+    for (int32_t li = li0; li < ap_end; li += CWAVES * 8) append_store(li, append_load(li), false);
   };
   // Rounds 0..3 are requested before any barrier; round x >= 4 after the barrier of round
   // x - 3.  The appending waves make sure their stores are complete before they enter the
@@ -385,7 +420,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const bool append_first = a.fused && NB < 4 * STAGE_BLOCKS;
   const int32_t r_pub = (a.fused && !append_first) ? 1 : -1;
   if (append_first) {
-    if (!loader) append_from(tid >> 3);
+    if (!loader) append_from(ap_first + (tid >> 3));
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
   }
@@ -437,7 +472,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   //      c ^ (r & 15).  One wave fetches the (cos, sin) row of the shared position.  The new
   //      rows of the append are requested in the same breath.
   const bool append_late = a.fused && !append_first;
-  const bool append_mine = append_late && (tid >> 3) < nbr_here;
+  const bool append_mine = append_late && ap_first + (tid >> 3) < ap_end;
   NewRows new_rows = {};
   uint4 qv[8];  // instruction i = wave + CWAVES * b covers rows 4 i .. 4 i + 3 (32 * CWAVES rows at most)
 #pragma unroll
@@ -448,7 +483,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const int64_t off = ((int64_t)(row0_live + urow / G) * a.Hq + hk * G + urow % G) * D;
     if (i * 4 < rows_here) qv[b] = *reinterpret_cast<const uint4*>(q + off + (c16 << 3));
   }
-  if (append_mine) new_rows = append_load(tid >> 3);
+  if (append_mine) new_rows = append_load(ap_first + (tid >> 3));
   float4 rope_v = make_float4(0.f, 0.f, 0.f, 0.f);
   if (upos >= 0 && wave == 0 && lane < 32)
     rope_v = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)upos * (D / 2))[lane];
@@ -460,6 +495,10 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       (row < STAGE_ROWS ? ring2 : ring3)[(row % STAGE_ROWS) * 16 + (c16 ^ (row & 15))] = qv[b];
   }
   if (upos >= 0 && wave == 0 && lane < 32) rope_q[lane] = rope_v;
+  if constexpr (PAPER) {
+    // tokens in memory of every key branch: min(step + 1, its length)
+    for (int32_t i = tid; i < kb_end; i += CWAVES * 64) klen[i] = min(a.step + 1, a.tb.branch_len[pb0 + i]);
+  }
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
   __builtin_amdgcn_s_barrier();        // bare barriers: __syncthreads() would wait for every store
   uint4 qraw[8];
@@ -515,8 +554,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // ---- the append, after the rotation (the rotation is what the first round waits for): the
   //      stores complete during round 0 and are published at the barrier of round 1
   if (append_late) {
-    if (append_mine) append_store(tid >> 3, new_rows, upos >= 0);
-    append_from((tid >> 3) + CWAVES * 8);
+    if (append_mine) append_store(ap_first + (tid >> 3), new_rows, upos >= 0);
+    append_from(ap_first + (tid >> 3) + CWAVES * 8);
   }
 
   // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
@@ -603,6 +642,15 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // bits 0..7 of a mask byte: the first `cnt` (clamped to 0..8) of 8 consecutive keys
   auto first_bits = [](int32_t cnt) -> uint32_t { return (1u << min(max(cnt, 0), 8)) - 1u; };
   const int32_t lb_row = rb * BPB + n / G;  // this row's branch within the row group
+  // PAPER: the branch of this row and of the last row of the row block, counted from the
+  // prompt's first branch like the key branches
+  int32_t kb_row = 0, kb_row_max = 0;
+  if constexpr (PAPER) {
+    if (active) {
+      kb_row = branch_id(min(lb_row, nbr_here - 1)) - pb0;
+      kb_row_max = __builtin_amdgcn_readfirstlane(branch_id(min(rb * BPB + BPB - 1, nbr_here - 1))) - pb0;
+    }
+  }
 
   // Round r: meet the loaders (the stage has landed), compute.
   for (int32_t s0 = 0; s0 < NR;) {
@@ -620,17 +668,27 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         uint32_t ok = 0xffffu;
         if (gb < NB) {
           mine = gb % KG == kg;
-          const int32_t valid = gb < NBh ? min(32, Hlen - gb * 32) : min(32, Llen - (gb - NBh) * 32);
+          const int32_t valid = gb < NBh ? min(32, Hlen - gb * 32)
+                                : PAPER ? a.tb.pblk[2 * (doff + gb - NBh) + 1] : min(32, Llen - (gb - NBh) * 32);
           masked = valid < 32;
           ok = first_bits(valid - g2 * 8) | (first_bits(valid - 16 - g2 * 8) << 8);
         } else {
           const int32_t tt = gb - NB;
           const int32_t c = tt / NQ, qd = quad_of(tt - c * NQ);
-          mine = qd / QPR == rb && (c * QPR + qd % QPR) % KG == kg;
           masked = true;
           tail = true;
-          const uint32_t pm = first_bits(a.step + 1 - c * 8);
-          ok = (qd * 4 + g2 == lb_row ? pm : 0u) | (qd * 4 + 2 + g2 == lb_row ? pm << 8 : 0u);
+          if constexpr (PAPER) {
+            // every row block that holds a branch not earlier than the quad's first works on
+            // the tile; a row keeps the tokens in memory of the branches up to its own
+            mine = qd * 4 <= kb_row_max && (c + qd) % KG == kg;
+            const int32_t kA = qd * 4 + g2, kB = kA + 2;
+            const int32_t cntA = kA < kb_end ? klen[kA] : 0, cntB = kB < kb_end ? klen[kB] : 0;
+            ok = (kA <= kb_row ? first_bits(cntA - c * 8) : 0u) | (kB <= kb_row ? first_bits(cntB - c * 8) << 8 : 0u);
+          } else {
+            mine = qd / QPR == rb && (c * QPR + qd % QPR) % KG == kg;
+            const uint32_t pm = first_bits(a.step + 1 - c * 8);
+            ok = (qd * 4 + g2 == lb_row ? pm : 0u) | (qd * 4 + 2 + g2 == lb_row ? pm << 8 : 0u);
+          }
         }
         if (mine) compute_block(cur, masked, ok, tail);
       }
@@ -791,11 +849,11 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   }
 }
 
-template <int G, typename SH>
+template <int G, typename SH, bool PAPER>
 hipError_t launch_g(const StreamArgs& a, int64_t items, const void* q, const void* k_prefix,
                     const void* v_prefix, void* k_tail, void* v_tail, const void* k_new,
                     const void* v_new, void* out, hipStream_t s) {
-  attn_stream_kernel<G, SH><<<dim3((unsigned)items), SH::WAVES * 64, 0, s>>>(
+  attn_stream_kernel<G, SH, PAPER><<<dim3((unsigned)items), SH::WAVES * 64, 0, s>>>(
       a, (const uint16_t*)q, (const uint16_t*)k_prefix, (const uint16_t*)v_prefix, (uint16_t*)k_tail,
       (uint16_t*)v_tail, (const uint16_t*)k_new, (const uint16_t*)v_new, out);
   return hipGetLastError();
@@ -805,8 +863,9 @@ hipError_t launch_g(const StreamArgs& a, int64_t items, const void* q, const voi
 
 bool hpd_stream_supported(const hpd_layout* L) {
   const int G = L->cfg.n_q_heads / L->cfg.n_kv_heads;
-  return L->cfg.mask_mode == HPD_MASK_BLOCK && L->cfg.dtype == HPD_BF16 && L->cfg.head_dim == D &&
-         (G == 1 || G == 2 || G == 4 || G == 8);
+  // the literal mask keeps one counter per branch of a prompt in LDS
+  if (L->cfg.mask_mode == HPD_MASK_PAPER && L->max_prompt_branches > 256) return false;
+  return L->cfg.dtype == HPD_BF16 && L->cfg.head_dim == D && (G == 1 || G == 2 || G == 4 || G == 8);
 }
 
 hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const void* q,
@@ -822,9 +881,11 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   a.fused = (k_new != nullptr) ? 1 : 0;
   a.live_base = L->live_ptr[step];
   a.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)D));
+  const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
   a.tb.unit_desc = L->dev.unit_desc + (int64_t)L->unit_ptr[step] * 8;
-  const int64_t n_units = L->unit_ptr[step + 1] - L->unit_ptr[step];
-  const int32_t max_nblk = std::max(1, (L->max_rows[step] * G + 31) / 32);
+  if (paper) a.tb.punit_desc = L->dev.punit_desc + (int64_t)L->punit_ptr[step] * 16;
+  const int64_t n_units = paper ? L->punit_ptr[step + 1] - L->punit_ptr[step] : L->unit_ptr[step + 1] - L->unit_ptr[step];
+  const int32_t max_nblk = std::max(1, ((paper ? L->pmax_rows[step] : L->max_rows[step]) * G + 31) / 32);
   // row groups per unit, and with them the number of workgroups, for the two shapes
   const int32_t rg_wide = (max_nblk + WideShape::MAX_BLOCKS - 1) / WideShape::MAX_BLOCKS;
   const int32_t rg_narrow = (max_nblk + NarrowShape::MAX_BLOCKS - 1) / NarrowShape::MAX_BLOCKS;
@@ -838,9 +899,10 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   a.RG = narrow ? rg_narrow : rg_wide;
   a.n_groups = (int32_t)(n_units * a.Hkv);
   const int64_t items = ((int64_t)(a.n_groups + 7) / 8 * 8) * a.RG;
-#define HPD_LAUNCH(GG)                                                                              \
-  (narrow ? launch_g<GG, NarrowShape>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s) \
-          : launch_g<GG, WideShape>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s))
+#define HPD_LAUNCH_M(GG, PP)                                                                            \
+  (narrow ? launch_g<GG, NarrowShape, PP>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s) \
+          : launch_g<GG, WideShape, PP>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s))
+#define HPD_LAUNCH(GG) (paper ? HPD_LAUNCH_M(GG, true) : HPD_LAUNCH_M(GG, false))
   switch (G) {
     case 1: return HPD_LAUNCH(1);
     case 2: return HPD_LAUNCH(2);
@@ -849,4 +911,5 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
     default: return hipErrorInvalidValue;
   }
 #undef HPD_LAUNCH
+#undef HPD_LAUNCH_M
 }

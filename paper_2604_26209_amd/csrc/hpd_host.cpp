@@ -230,6 +230,46 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     }
     L->total_units = (int64_t)L->unit_doc.size();
 
+    // ---- paper-literal mask: the work unit is the prompt (its rows see every document and the
+    //      tails of all earlier branches).  Document blocks of a prompt in stream order; per
+    //      step the prompts with live branches, heaviest first.
+    if (cfg->mask_mode == HPD_MASK_PAPER) {
+      L->pblk_ptr.assign(P + 1, 0);
+      for (int32_t p = 0; p < P; ++p) {
+        for (int32_t d = doc_ptr[p]; d < doc_ptr[p + 1]; ++d)
+          for (int32_t i = 0; i < doc_len[d]; i += HPD_KEY_BLOCK) {
+            L->pblk.push_back(L->seg_off[P + d] + i);
+            L->pblk.push_back(std::min<int32_t>(HPD_KEY_BLOCK, doc_len[d] - i));
+          }
+        L->pblk_ptr[p + 1] = (int32_t)(L->pblk.size() / 2);
+        L->max_prompt_branches = std::max(L->max_prompt_branches,
+                                          L->prompt_branch_ptr[p + 1] - L->prompt_branch_ptr[p]);
+      }
+      L->punit_ptr.assign(T + 1, 0);
+      L->pmax_rows.assign(T, 0);
+      for (int32_t t = 0; t < T; ++t) {
+        const int32_t* dlp = &L->doc_live_ptr[(size_t)t * (n_docs + 1)];
+        std::vector<int32_t> units;
+        for (int32_t p = 0; p < P; ++p)
+          if (dlp[doc_ptr[p + 1]] > dlp[doc_ptr[p]]) units.push_back(p);
+        std::stable_sort(units.begin(), units.end(), [&](int32_t x, int32_t y) {
+          return L->pblk_ptr[x + 1] - L->pblk_ptr[x] > L->pblk_ptr[y + 1] - L->pblk_ptr[y];
+        });
+        for (int32_t p : units) {
+          const int32_t r0 = dlp[doc_ptr[p]], nbl = dlp[doc_ptr[p + 1]] - r0;
+          const int32_t bf = L->live_branch[L->live_ptr[t] + r0];
+          const int32_t bl = L->live_branch[L->live_ptr[t] + r0 + nbl - 1];
+          const int32_t pb0 = L->prompt_branch_ptr[p];
+          const int32_t desc[16] = {L->seg_off[p], L->seg_len[p], L->pblk_ptr[p],
+                                    L->pblk_ptr[p + 1] - L->pblk_ptr[p], r0, nbl, pb0,
+                                    (bl - bf == nbl - 1) ? bf : -1, bl - pb0 + 1, 0, 0, 0, 0, 0, 0, 0};
+          L->punit_desc.insert(L->punit_desc.end(), desc, desc + 16);
+          L->pmax_rows[t] = std::max(L->pmax_rows[t], nbl);
+        }
+        L->punit_ptr[t + 1] = L->punit_ptr[t] + (int32_t)units.size();
+      }
+    }
+
     // ---- RoPE table: angles in double, stored as float (cos, sin)
     const int32_t half = cfg->head_dim / 2;
     L->rope.resize((size_t)(L->max_pos + 1) * half * 2);
@@ -258,7 +298,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
                  o_dlp = A.add(L->doc_live_ptr), o_unit_ptr = A.add(L->unit_ptr),
                  o_unit_doc = A.add(L->unit_doc), o_unit_desc = A.add(L->unit_desc),
                  o_pdp = A.add(L->prompt_doc_ptr), o_pbp = A.add(L->prompt_branch_ptr),
-                 o_blen = A.add(L->branch_len);
+                 o_blen = A.add(L->branch_len), o_pblk = A.add(L->pblk), o_pdesc = A.add(L->punit_desc);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipGetDevice(&L->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&L->n_cus, hipDeviceAttributeMultiprocessorCount, L->device);
@@ -286,7 +326,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     L->dev.doc_live_ptr = base + o_dlp; L->dev.unit_ptr = base + o_unit_ptr;
     L->dev.unit_doc = base + o_unit_doc; L->dev.unit_desc = base + o_unit_desc;
     L->dev.prompt_doc_ptr = base + o_pdp; L->dev.prompt_branch_ptr = base + o_pbp;
-    L->dev.branch_len = base + o_blen;
+    L->dev.branch_len = base + o_blen; L->dev.pblk = base + o_pblk; L->dev.punit_desc = base + o_pdesc;
     L->dev.rope = (const float2*)L->d_rope;
     L->on_device = true;
   }
@@ -337,7 +377,8 @@ int hpd_layout_query(const hpd_layout* L, int32_t what, void* host_out, size_t b
     case HPD_Q_N_UNITS: {
       if (bytes < (size_t)L->T * sizeof(int32_t)) return HPD_E_INVALID;
       int32_t* o = (int32_t*)host_out;
-      for (int32_t t = 0; t < L->T; ++t) o[t] = L->unit_ptr[t + 1] - L->unit_ptr[t];
+      const std::vector<int32_t>& up = L->cfg.mask_mode == HPD_MASK_PAPER ? L->punit_ptr : L->unit_ptr;
+      for (int32_t t = 0; t < L->T; ++t) o[t] = up[t + 1] - up[t];
       return HPD_OK;
     }
     case HPD_Q_LIVE_BRANCH: return copy32(L->live_branch, (size_t)L->total_live);

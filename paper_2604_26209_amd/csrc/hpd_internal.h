@@ -28,6 +28,9 @@ struct hpd_dev_tables {
   const int32_t* prompt_doc_ptr;     // [P+1] first document of each prompt
   const int32_t* prompt_branch_ptr;  // [P+1] first branch of each prompt
   const int32_t* branch_len;         // [B] steps a branch is decoded for
+  // paper-literal mask only: work units are prompts
+  const int32_t* pblk;        // [total document blocks][2] (first pool slot, keys) of every 32-key block of a prompt's documents
+  const int32_t* punit_desc;  // [total_punits][16] {hoff, Hlen, first pblk entry, document blocks, first live row, live branches, first branch of the prompt, first live branch id or -1, key branches (first .. last live), 0...}
   const float2* rope;           // [max_pos+1][D/2] (cos, sin)
 };
 
@@ -41,6 +44,9 @@ struct hpd_layout {
   std::vector<int32_t> seg_off, seg_len, seg_pos0, seg_raw_off, raw_seg;
   std::vector<int32_t> doc_prompt, branch_doc, branch_base_pos, branch_len;
   std::vector<int32_t> prompt_doc_ptr, prompt_branch_ptr;
+  // paper-literal mask: document blocks per prompt, per-step prompt units
+  std::vector<int32_t> pblk_ptr, pblk, punit_ptr, punit_desc, pmax_rows;
+  int32_t max_prompt_branches = 0;
   std::vector<int32_t> live_ptr, live_branch, doc_live_ptr, unit_ptr, unit_doc, unit_desc;
   std::vector<int32_t> max_rows;  // [T] largest number of live branches of any document at step t
   std::vector<float> rope;        // host copy of the (cos, sin) table

@@ -123,16 +123,19 @@ def test_paper_literal_mask_mode():
     documents, the tokens of every earlier branch up to the current step, finished ones
     included).  Outputs against the oracle's dense mask, and the exported mask bit-exact."""
     from paper_2604_26209_amd import binding as B
-    cases = [("f32", dict(hq=4, hkv=2, d=64, t=5, p=2, j_range=(1, 3), n_range=(1, 5), l_range=(1, 40))),
+    cases = [("f32", dict(hq=4, hkv=2, d=64, t=5, p=2, j_range=(1, 3), n_range=(1, 5), l_range=(1, 40)), (1,)),
              ("bf16", dict(hq=8, hkv=2, d=128, base=500000.0, t=6, p=3, j_range=(1, 4), n_range=(1, 9),
-                           h_range=(0, 70), l_range=(1, 150)))]
-    for i, (dt, kw) in enumerate(cases):
+                           h_range=(0, 70), l_range=(1, 150)), (1, 3, 4))]
+    for i, (dt, kw, modes) in enumerate(cases):
         wl = W.random_workload(70 + i, dtype=dt, **kw)
         attr = np.random.default_rng(70 + i).integers(1, 6, size=wl.n_branches).astype(np.int32)
-        for fused in (False, True):
-            _say(f"paper mask {dt} fused {fused}")
-            hip = H.run_hip(wl, pos_mode=1, attr_len=attr, mask_mode=B.HPD_MASK_PAPER, fused=fused)
-            H.check_all(wl, hip, pos_mode="paper_gap", attr_len=attr, mask_mode="paper", label=f"paper_{dt}")
+        for mode in modes:
+            for fused in (False, True):
+                _say(f"paper mask {dt} mode {mode} fused {fused}")
+                hip = H.run_hip(wl, pos_mode=1, attr_len=attr, mask_mode=B.HPD_MASK_PAPER, fused=fused,
+                                kernel_mode=mode)
+                H.check_all(wl, hip, pos_mode="paper_gap", attr_len=attr, mask_mode="paper",
+                            label=f"paper_{dt}_m{mode}")
         orc, _ = H.run_oracle(wl, hip["inputs"], pos_mode="paper_gap", attr_len=attr, mask_mode="paper")
         for p, po in orc.prompts.items():
             s = B.hpd_expand_mask(hip["layout"], p, wl.max_new - 1)
@@ -142,6 +145,29 @@ def test_paper_literal_mask_mode():
     # the literal mask orders a prompt by position ID: positions that restart per document do not
     with pytest.raises(B.HpdError):
         B.layout_from_workload(wl, pos_mode=0, mask_mode=B.HPD_MASK_PAPER)
+
+
+@pytest.mark.parametrize("g", [1, 2, 4, 8])
+def test_paper_literal_mask_stream_kernel_shapes(g):
+    """The streaming kernel under HPD_MASK_PAPER: every group size, both workgroup shapes,
+    prompts with more rows than one workgroup takes (several row groups, each appending the
+    earlier groups' newest tokens itself in the step call), finished branches as keys, a tail
+    of more than one chunk of 8 positions; the step call equals the two-call sequence bit for
+    bit."""
+    from paper_2604_26209_amd import binding as B
+    wl = W.random_workload(80 + g, dtype="bf16", hq=8, hkv=8 // g, d=128, base=500000.0, t=11, p=2,
+                           j_range=(2, 4), n_range=(3, 30 if g < 4 else 20), h_range=(0, 90), l_range=(1, 200))
+    attr = np.random.default_rng(80 + g).integers(1, 4, size=wl.n_branches).astype(np.int32)
+    for mode in (3, 4):
+        _say(f"paper mask stream G={g} mode {mode}: {wl.n_branches} branches")
+        a = H.run_hip(wl, pos_mode=1, attr_len=attr, mask_mode=B.HPD_MASK_PAPER, kernel_mode=mode,
+                      fused=False, poison_pools=True)
+        rel = H.check_all(wl, a, pos_mode="paper_gap", attr_len=attr, mask_mode="paper", label=f"paper_g{g}_m{mode}")
+        _say(f"  worst err/rms {rel:.2e}")
+        b = H.run_hip(wl, inputs=a["inputs"], pos_mode=1, attr_len=attr, mask_mode=B.HPD_MASK_PAPER,
+                      kernel_mode=mode, fused=True, poison_pools=True)
+        for x, y in zip(a["out"], b["out"]):
+            assert torch.equal(x, y)
 
 
 def test_mask_export_bit_exact():
