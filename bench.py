@@ -30,6 +30,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this same command, each scaled by what the counter reads for a 1 GiB copy
@@ -37,10 +38,13 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
 MEASURED_TRAFFIC_BYTES = {2: 106.3e6, 3: 734.5e6, 4: 443.9e6, 5: 2687.9e6}
 
 
-def algorithmic_bytes(wl, n_live_lists, eb):
+def algorithmic_bytes(wl, n_live_lists, eb, paper=False):
     """Bytes the method has to move per decode step: each shared prefix K/V once per
     (prompt | document, kv head), each tail once per (branch, kv head), Q in, O out, new K/V
-    in and out.  Returns (attention_bytes[t], append_bytes[t], flops[t])."""
+    in and out.  Returns (attention_bytes[t], append_bytes[t], flops[t]).
+    paper = the literal mask over the whole prompt: the same prefix bytes (every document of a
+    live prompt once), the tails of all branches of a live prompt up to its last live one
+    (finished ones as far as they got) once, and every row multiplies with all of them."""
     import numpy as np
 
     tok_b = 2 * wl.n_kv_heads * wl.head_dim * eb
@@ -57,11 +61,26 @@ def algorithmic_bytes(wl, n_live_lists, eb):
         attn.append(prefix + tail + qo)
         app.append(n * 2 * tok_b)
         keys = wl.header_len[prompt_of_doc[doc_of_branch[live]]] + wl.doc_len[doc_of_branch[live]] + t + 1
+        if paper:
+            in_mem = np.minimum(wl.branch_len, t + 1)
+            csum = np.concatenate([[0], np.cumsum(in_mem)])
+            p_of_b = prompt_of_doc[doc_of_branch]
+            first_b = wl.branch_ptr[wl.doc_ptr[:-1]]
+            prefix, tail = 0, 0
+            for pr in prompts:
+                d0, d1 = wl.doc_ptr[pr], wl.doc_ptr[pr + 1]
+                prefix += int(wl.header_len[pr] + wl.doc_len[d0:d1].sum()) * tok_b
+                last = live[p_of_b[live] == pr].max()
+                tail += int(csum[last + 1] - csum[first_b[pr]]) * tok_b
+            attn[-1] = prefix + tail + qo
+            plen = np.asarray([wl.header_len[pr] + wl.doc_len[wl.doc_ptr[pr]:wl.doc_ptr[pr + 1]].sum()
+                               for pr in range(wl.n_prompts)])
+            keys = plen[p_of_b[live]] + (csum[live + 1] - csum[first_b[p_of_b[live]]])
         flops.append(int(4 * wl.head_dim * wl.n_q_heads * keys.sum()))
     return attn, app, flops
 
 
-def cpu_baseline(wl, budget_s=15.0):
+def cpu_baseline(wl, budget_s=15.0, paper=False, attr_len=None):
     """Times the dense CPU oracle on as many prompts of the workload as fit the budget."""
     import numpy as np
     import torch
@@ -97,7 +116,9 @@ def cpu_baseline(wl, budget_s=15.0):
                             [[int(x) for x in wl.branch_len[int(wl.branch_ptr[d]):int(wl.branch_ptr[d + 1])]]
                              for d in range(d0, d1)],
                             wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new,
-                            cache_dtype="bf16" if wl.dtype == "bf16" else None)
+                            cache_dtype="bf16" if wl.dtype == "bf16" else None,
+                            **(dict(pos_mode="paper_gap", mask_mode="paper",
+                                    attr_lens=[int(x) for x in attr_len[b0:b1]]) if paper else {}))
         po.prefill(kr, vr)
         for t in range(wl.max_new):
             po.step(t, *ins[t])
@@ -126,6 +147,9 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0,
                     help="after the timed regions, run this many 1 GiB device copies (reference "
                          "dispatches for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--mask", default="block", choices=["block", "paper"],
+                    help="block: header + own document + own branch (the benchmark's metric); paper: "
+                         "the literal mask over the whole stacked prompt, with the paper's gap positions")
     ap.add_argument("--per-step", action="store_true",
                     help="second run: one event pair per decode step (all replicas of that step back "
                          "to back), adds per_step {us, gbs} to the record")
@@ -148,7 +172,12 @@ def main():
     wl = W.config(args.config)
     eb = 4 if wl.dtype == "f32" else 2
     out_f32 = args.out == "f32" or wl.dtype == "f32"
-    layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME)
+    paper = args.mask == "paper"
+    # skeleton (attribute-name) lengths for the gap positions: 1..4 tokens, seeded
+    attr_len = np.random.default_rng(26209100 + args.config).integers(1, 5, size=wl.n_branches).astype(np.int32)
+    layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME,
+                                    **(dict(pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr_len,
+                                            mask_mode=B.HPD_MASK_PAPER) if paper else {}))
     n_live = layout.n_live()
     live_flat = B.hpd_layout_query(layout, B.HPD_Q_LIVE_BRANCH)
     live_lists, off = [], 0
@@ -156,7 +185,7 @@ def main():
         live_lists.append(live_flat[off:off + n_live[t]])
         off += n_live[t]
     total_tokens = int(sum(n_live))
-    attn_b, app_b, flops = algorithmic_bytes(wl, live_lists, eb)
+    attn_b, app_b, flops = algorithmic_bytes(wl, live_lists, eb, paper)
 
     pool_bytes = B.hpd_layout_query(layout, B.HPD_Q_POOL_BYTES)
     footprint = int(pool_bytes.sum())
@@ -246,18 +275,20 @@ def main():
     events = launched
     roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not args.two_call and not out_f32 else None,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not (args.two_call or out_f32 or paper) else None,
                 "kernel": "attn_stream_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attention_generic_kernel",
                 "launches": len(events), "avg_launch_us": round(dur_s / len(events) * 1e6, 2),
                 "algorithmic_bytes_per_launch": int(alg / len(events)),
-                "useful_tflops": round(mfma_tflops, 1)}
+                "useful_tflops": round(mfma_tflops, 1),
+                "useful_tflops_frac_of_mfma_peak": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
 
     rec = {
         "metric": "branch tokens/s of HPD masked decode attention; achieved HBM GB/s vs peak",
         "value": round(value, 1), "unit": "branch-tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": f"configs[{args.config - 1}] {wl.name}: {wl.note}",
+        "config": {"workload": f"configs[{args.config - 1}] {wl.name}: {wl.note}"
+                               + ("; paper-literal mask over the whole prompt, gap positions" if paper else ""),
                    "prompts": wl.n_prompts, "documents": wl.n_docs, "branches": wl.n_branches,
                    "decode_steps_per_pass": wl.max_new, "branch_tokens_per_pass": total_tokens,
                    "heads": f"{wl.n_q_heads}/{wl.n_kv_heads}x{wl.head_dim}", "kv_replicas": R,
@@ -289,7 +320,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
     if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(wl)
+        rec["cpu_baseline"] = cpu_baseline(wl, paper=paper, attr_len=attr_len)
     print(json.dumps(rec))
 
 

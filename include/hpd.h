@@ -194,8 +194,9 @@ int hpd_kv_append(const hpd_layout* layout, int32_t step, const void* k_new, con
  * hpd_decode_attention - Sections 4.3.2-4.3.3.  For every live branch b and query head h:
  *   out = softmax( RoPE(q, pos) . K^T / sqrt(D) ) V  over the keys
  *   header(prompt of b)  ++  document(b)  ++  tail slots 0..step of b
- * (the block form of the position-ordered causal mask).  Call after hpd_kv_append of the
- * same step: a query attends to its own token.
+ * (the block form of the position-ordered causal mask; under HPD_MASK_PAPER: header ++ every
+ * document of the prompt ++ tail slots 0..min(step, len-1) of every branch of the prompt up
+ * to b).  Call after hpd_kv_append of the same step: a query attends to its own token.
  *   q   : device [n_live(step)][Hq][D], un-rotated
  *   out : device [n_live(step)][Hq][D]
  */
@@ -226,7 +227,7 @@ int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, u
  * everything, 2 = LDS-streaming MFMA kernel, workgroup shape chosen per launch, 3 / 4 = the
  * same with the wide / the narrow workgroup shape forced (2..4 return HPD_E_UNSUPPORTED if
  * the shape does not allow the kernel: it needs bf16, head_dim 128 and a group size of 1,
- * 2, 4 or 8). */
+ * 2, 4 or 8, and under HPD_MASK_PAPER at most 256 branches per prompt). */
 int hpd_set_kernel_mode(hpd_layout* layout, int32_t mode);
 
 const char* hpd_status_string(int status);

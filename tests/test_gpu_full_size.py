@@ -56,3 +56,30 @@ def test_full_size_config(k, prompts):
     for t, (x, y) in enumerate(zip(hip["out"], hip16["out"])):
         assert y.dtype == torch.bfloat16
         assert torch.equal(x.to(torch.bfloat16), y), f"cfg{k} step {t}: bf16 output is not RNE(fp32 output)"
+
+
+@pytest.mark.parametrize("k,prompts", [(3, [7]), (5, None)])
+def test_full_size_config_paper_literal_mask(k, prompts):
+    """The literal mask over the whole stacked prompt at full size, launched as
+    `bench.py --mask paper` launches it (automatic kernel choice, fused step call, the bench's
+    seeded skeleton lengths): integers of the whole batch, sampled prompts against the oracle.
+    Config 5 has finished branches whose tokens stay visible to the later branches."""
+    from paper_2604_26209_amd import binding as B
+    wl = W.config(k)
+    attr = np.random.default_rng(26209100 + k).integers(1, 5, size=wl.n_branches).astype(np.int32)
+    print(f"full-size cfg{k}, paper-literal mask", flush=True)
+    hip = H.run_hip(wl, fused=True, poison_pools=True, pos_mode=1, attr_len=attr, mask_mode=B.HPD_MASK_PAPER)
+    for t in range(wl.max_new):
+        live = np.nonzero(wl.branch_len > t)[0]
+        assert np.array_equal(hip["slot"][t].cpu().numpy(), live.astype(np.int64) * wl.max_new + t)
+    vmax = max(float(hip["inputs"].v_raw.abs().max()), max(float(x.abs().max()) for x in hip["inputs"].v_new))
+    for t, o in enumerate(hip["out"]):
+        assert bool(torch.isfinite(o).all()), f"cfg{k} step {t}: non-finite output"
+        assert float(o.abs().max()) <= vmax * (1 + 1e-2), f"cfg{k} step {t}: output outside the hull of V"
+    if prompts is None:
+        nd = np.diff(wl.doc_ptr)
+        prompts = sorted({int(np.argmin(nd)), int(np.argmax(nd))})
+    print(f"  oracle on prompts {prompts}", flush=True)
+    worst = H.check_all(wl, hip, prompts=prompts, pos_mode="paper_gap", attr_len=attr, mask_mode="paper",
+                        label=f"cfg{k}_paper")
+    print(f"  worst max-abs / RMS(step) = {worst:.4f}", flush=True)
