@@ -60,10 +60,13 @@
 //    with the streaming (non-temporal) hint; what is re-read (header blocks, query rows, the
 //    appended rows) does not.
 //  * Fused mode (hpd_decode_step): the compute waves rotate, round and store the new keys and
-//    values of the unit's branches (the arithmetic of hpd_kv_append) before they rotate the
-//    query; a ring barrier publishes them before the first tail tile is requested, and the
-//    tail tiles - which are last in the stream - read them back like any other token.  Both
-//    modes therefore add up in the same order and give identical bits.
+//    values of the unit's branches (the arithmetic of hpd_kv_append) right after they have
+//    rotated the query - the rotated query is what the first round waits for, the stores can
+//    complete behind it; a ring barrier publishes them before the first tail tile is
+//    requested, and the tail tiles - which are last in the stream - read them back like any
+//    other token.  Both modes therefore add up in the same order and give identical bits.
+//  * HPD_MASK_PAPER (the literal mask of Section 4.3.2 over the whole stacked prompt) is a
+//    second instantiation of the same kernel; see the comment at the kernel.
 #include <algorithm>
 #include <cmath>
 
@@ -104,7 +107,7 @@ using NarrowShape = Shape<3, 1, 1>;
 
 struct StreamArgs {
   hpd_dev_tables tb;
-  int32_t step, Hq, Hkv, Tcap, P, n_docs, RG, n_groups, out_f32, fused, live_base;
+  int32_t step, Hq, Hkv, Tcap, RG, n_groups, out_f32, fused, live_base;
   int64_t NP;
   float scale_log2;
 };
@@ -278,7 +281,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const bool row_valid = active && lr < rows_here;
   const int32_t r4 = lane >> 4, c16 = lane & 15;
 
-  // ---- loader role (waves 6, 7): wave 6 + j fills block slot j of a stage, quarter by quarter
+  // ---- loader role (the waves after the compute waves): loader j fills block slot j of a
+  //      stage (slots j, j + LW, ... if there are fewer loaders than slots), quarter by quarter
   //      (the K half in quarters 0 and 1, the V half in 2 and 3): LOADS_PER_ROUND instructions
   //      per round, always the same number, so that vmcnt(N) means the same thing in every
   //      round.  A loader does nothing else: under load a DMA instruction blocks the issuing
@@ -876,7 +880,7 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   a.tb = L->dev;
   a.step = step; a.Hq = L->cfg.n_q_heads; a.Hkv = L->cfg.n_kv_heads;
   const int G = a.Hq / a.Hkv;
-  a.Tcap = L->T; a.P = L->P; a.n_docs = L->n_docs; a.NP = L->NP;
+  a.Tcap = L->T; a.NP = L->NP;
   a.out_f32 = L->cfg.out_dtype == HPD_OUT_F32 ? 1 : 0;
   a.fused = (k_new != nullptr) ? 1 : 0;
   a.live_base = L->live_ptr[step];
