@@ -223,6 +223,26 @@ int hpd_decode_step(const hpd_layout* layout, int32_t step, const void* q, const
 int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, uint8_t* mask_out,
                     int32_t* s_out, void* stream);
 
+/*
+ * hpd_finetune_mask - Section 5 ("Fine-tuning and Distillation"), Appendix A.1.  Position IDs
+ * and attention mask of one training sequence in the regular token order
+ *   s_train = cat(p, a_1, v_1, ..., a_N, v_N):
+ * the attributes keep Algorithm 2's positions (a gap of k_max after every attribute), value
+ * token k (1-based) of attribute n sits at pos_id[end(a_n)] + k; the mask is the causal mask
+ * minus (i) v_{n,k} -> v_{n',k'} for n' < n, k' > k and (ii) attribute token -> any value
+ * token: what a token could see while being decoded in parallel.
+ *   prompt_len >= 0; attr_len [n_attr] >= 1, value_len [n_attr] in [0, k_max]: host arrays
+ *   pos_out  : device int32 [S] or NULL
+ *   mask_out : device uint8 [S][S] row-major (query row, key column) or NULL
+ *   s_out    : host int64*, receives S = prompt_len + sum(attr_len) + sum(value_len)
+ * Integer work only.  Allocates and frees a token table of 16 S bytes and synchronises the
+ * stream: a data-preparation call, not a per-step one.  HPD_E_INVALID for lengths out of
+ * range, HPD_E_OVERFLOW if S exceeds 46000 or a position 2^30.
+ */
+int hpd_finetune_mask(int32_t prompt_len, int32_t n_attr, const int32_t* attr_len,
+                      const int32_t* value_len, int32_t k_max, int32_t* pos_out, uint8_t* mask_out,
+                      int64_t* s_out, void* stream);
+
 /* Selects the attention kernel: 0 = automatic, 1 = generic wave-reduction kernel for
  * everything, 2 = LDS-streaming MFMA kernel, workgroup shape chosen per launch, 3 / 4 = the
  * same with the wide / the narrow workgroup shape forced (2..4 return HPD_E_UNSUPPORTED if

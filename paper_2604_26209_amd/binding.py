@@ -52,7 +52,7 @@ HPD_KEY_BLOCK = 32
 
 EXPORTS = ["hpd_build_layout", "hpd_layout_free", "hpd_layout_query", "hpd_prefix_fill",
            "hpd_rope_positions", "hpd_kv_append", "hpd_decode_attention", "hpd_decode_step",
-           "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_status_string"]
+           "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_status_string", "hpd_finetune_mask"]
 
 
 class hpd_config(ctypes.Structure):
@@ -77,6 +77,7 @@ _lib.hpd_decode_attention.argtypes = [_vp, _i32] + [_vp] * 7
 _lib.hpd_decode_step.argtypes = [_vp, _i32] + [_vp] * 9
 _lib.hpd_expand_mask.argtypes = [_vp, _i32, _i32, _vp, _i32p, _vp]
 _lib.hpd_set_kernel_mode.argtypes = [_vp, _i32]
+_lib.hpd_finetune_mask.argtypes = [_i32, _i32, _i32p, _i32p, _i32, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _vp]
 _lib.hpd_status_string.argtypes = [ctypes.c_int]
 _lib.hpd_status_string.restype = ctypes.c_char_p
 for _name in EXPORTS:
@@ -227,6 +228,17 @@ def hpd_expand_mask(layout, prompt, step_hi, mask_out=None, stream=None) -> int:
     s = ctypes.c_int32(0)
     _check(_lib.hpd_expand_mask(layout.handle, int(prompt), int(step_hi), _ptr(mask_out),
                                 ctypes.byref(s), _stream(stream)), "hpd_expand_mask")
+    return int(s.value)
+
+
+def hpd_finetune_mask(prompt_len, attr_len, value_len, k_max, pos_out=None, mask_out=None, stream=None) -> int:
+    """Returns S; fills the device tensors pos_out (int32 [S]) / mask_out (uint8 [S][S]) if given."""
+    a = np.ascontiguousarray(attr_len, dtype=np.int32)
+    v = np.ascontiguousarray(value_len, dtype=np.int32)
+    s = ctypes.c_int64(0)
+    _check(_lib.hpd_finetune_mask(int(prompt_len), int(a.shape[0]), a.ctypes.data_as(_i32p),
+                                  v.ctypes.data_as(_i32p), int(k_max), _ptr(pos_out), _ptr(mask_out),
+                                  ctypes.byref(s), _stream(stream)), "hpd_finetune_mask")
     return int(s.value)
 
 

@@ -523,4 +523,40 @@ int hpd_expand_mask(const hpd_layout* L, int32_t prompt, int32_t step_hi, uint8_
   return HPD_OK;
 }
 
+int hpd_finetune_mask(int32_t prompt_len, int32_t n_attr, const int32_t* attr_len,
+                      const int32_t* value_len, int32_t k_max, int32_t* pos_out, uint8_t* mask_out,
+                      int64_t* s_out, void* stream) {
+  if (!s_out || prompt_len < 0 || n_attr < 0 || k_max < 1) return HPD_E_INVALID;
+  if (n_attr > 0 && (!attr_len || !value_len)) return HPD_E_INVALID;
+  int64_t S = prompt_len;
+  for (int32_t n = 0; n < n_attr; ++n) {
+    if (attr_len[n] < 1 || value_len[n] < 0 || value_len[n] > k_max) return HPD_E_INVALID;
+    S += (int64_t)attr_len[n] + value_len[n];
+    if (S > 46000) return HPD_E_OVERFLOW;
+  }
+  if (S > 46000 || S + (int64_t)n_attr * k_max > ((int64_t)1 << 30)) return HPD_E_OVERFLOW;
+  *s_out = S;
+  if (S == 0 || (!pos_out && !mask_out)) return HPD_OK;
+  // token table in the regular order; Algorithm 2 for the skeleton, end(a_n) + k for values
+  std::vector<int32_t> desc;
+  desc.reserve((size_t)S * 4);
+  for (int32_t i = 0; i < prompt_len; ++i) desc.insert(desc.end(), {0, -1, 0, i});
+  int32_t next = prompt_len, offset = 0;
+  for (int32_t n = 0; n < n_attr; ++n) {
+    for (int32_t i = 0; i < attr_len[n]; ++i) desc.insert(desc.end(), {1, n, 0, next++ + offset});
+    const int32_t end_pos = desc[desc.size() - 1];
+    for (int32_t k = 1; k <= value_len[n]; ++k) desc.insert(desc.end(), {2, n, k, end_pos + k});
+    offset += k_max;
+  }
+  int32_t* d_desc = nullptr;
+  hipStream_t s = (hipStream_t)stream;
+  HPD_HIP(hipMalloc((void**)&d_desc, desc.size() * sizeof(int32_t)));
+  hipError_t e = hipMemcpyAsync(d_desc, desc.data(), desc.size() * sizeof(int32_t), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) e = hpd_launch_finetune_mask(d_desc, (int32_t)S, pos_out, mask_out, s);
+  if (e == hipSuccess) e = hipStreamSynchronize(s);
+  (void)hipFree(d_desc);
+  if (e != hipSuccess) return hip_fail(e);
+  return HPD_OK;
+}
+
 }  // extern "C"

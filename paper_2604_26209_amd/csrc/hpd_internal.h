@@ -77,6 +77,10 @@ hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const
 hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, int32_t paper, uint8_t* mask_out,
                                   hipStream_t s);
 
+// desc[S][4] = (kind 0 prompt / 1 attribute / 2 value, attribute index, k, position ID)
+hipError_t hpd_launch_finetune_mask(const int32_t* d_desc, int32_t S, int32_t* pos_out, uint8_t* mask_out,
+                                    hipStream_t s);
+
 // most keys any row of the step has in the generic kernel (it keeps one score per key in LDS)
 int64_t hpd_generic_max_keys(const hpd_layout* L, int32_t step);
 

@@ -135,6 +135,28 @@ __global__ void expand_mask_kernel(const int32_t* __restrict__ desc, int32_t S, 
 }
 
 // ---------------------------------------------------------------------------------------
+// Fine-tuning mask (Section 5).  desc[S][4] = (kind, attribute, k, position ID) in the regular
+// token order; kind 0 prompt, 1 attribute, 2 value token.
+// ---------------------------------------------------------------------------------------
+__global__ void finetune_mask_kernel(const int32_t* __restrict__ desc, int32_t S,
+                                     uint8_t* __restrict__ mask) {
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (int64_t)S * S) return;
+  const int32_t qi = (int32_t)(gid / S), ki = (int32_t)(gid % S);
+  const int32_t qk = desc[qi * 4], qn = desc[qi * 4 + 1], qs = desc[qi * 4 + 2];
+  const int32_t kk = desc[ki * 4], kn = desc[ki * 4 + 1], ks = desc[ki * 4 + 2];
+  bool ok = ki <= qi;                                       // causal
+  if (kk == 2 && qk == 1) ok = false;                       // attributes never see values
+  if (kk == 2 && qk == 2 && kn < qn && ks > qs) ok = false;  // not generated yet
+  mask[gid] = ok ? 1 : 0;
+}
+
+__global__ void finetune_pos_kernel(const int32_t* __restrict__ desc, int32_t S, int32_t* __restrict__ pos) {
+  const int32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < S) pos[i] = desc[i * 4 + 3];
+}
+
+// ---------------------------------------------------------------------------------------
 // Generic attention: one 256-thread block per (live row, query head).
 //   phase 1  one key per thread: full dot product with the rotated query (kept in LDS),
 //            scores to LDS, block max
@@ -368,5 +390,12 @@ hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const
 hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, int32_t paper, uint8_t* mask_out,
                                   hipStream_t s) {
   expand_mask_kernel<<<grid1d((int64_t)S * S, 256), 256, 0, s>>>(d_desc, S, paper, mask_out);
+  return hipGetLastError();
+}
+
+hipError_t hpd_launch_finetune_mask(const int32_t* d_desc, int32_t S, int32_t* pos_out, uint8_t* mask_out,
+                                    hipStream_t s) {
+  if (pos_out) finetune_pos_kernel<<<grid1d(S, 256), 256, 0, s>>>(d_desc, S, pos_out);
+  if (mask_out) finetune_mask_kernel<<<grid1d((int64_t)S * S, 256), 256, 0, s>>>(d_desc, S, mask_out);
   return hipGetLastError();
 }

@@ -145,3 +145,17 @@ def test_invalid_inputs_return_error_codes():
     with pytest.raises(B.HpdError):
         B.hpd_rope_positions(lay, 0, 0)
     assert B.hpd_status_string(B.HPD_E_INVALID) == "invalid argument"
+
+
+def test_finetune_mask_host_checks():
+    """No GPU call: sizes and argument checks of hpd_finetune_mask (outputs NULL)."""
+    assert B.hpd_finetune_mask(10, [3, 3, 3], [3, 3, 3], 7) == 28
+    assert B.hpd_finetune_mask(0, [], [], 4) == 0
+    for bad in [dict(prompt_len=-1, attr_len=[1], value_len=[1], k_max=2),
+                dict(prompt_len=1, attr_len=[0], value_len=[1], k_max=2),
+                dict(prompt_len=1, attr_len=[1], value_len=[3], k_max=2),
+                dict(prompt_len=1, attr_len=[1], value_len=[1], k_max=0)]:
+        with pytest.raises(B.HpdError):
+            B.hpd_finetune_mask(**bad)
+    with pytest.raises(B.HpdError):
+        B.hpd_finetune_mask(46000, [1], [1], 2)  # S beyond the limit

@@ -170,6 +170,28 @@ def test_paper_literal_mask_stream_kernel_shapes(g):
             assert torch.equal(x, y)
 
 
+def test_finetune_mask_and_positions_bit_exact():
+    """hpd_finetune_mask (Section 5) against the loop oracle: mask and position IDs."""
+    from oracle import finetune_mask as F
+    from paper_2604_26209_amd import binding as B
+    rng = np.random.default_rng(9)
+    cases = [(10, [3, 3, 3], [3, 3, 3], 7), (0, [1], [1], 1), (4, [2, 1, 3], [0, 5, 2], 5)]
+    for _ in range(4):
+        n = int(rng.integers(1, 20))
+        kmax = int(rng.integers(1, 31))
+        cases.append((int(rng.integers(0, 100)), [int(x) for x in rng.integers(1, 6, n)],
+                      [int(x) for x in rng.integers(0, kmax + 1, n)], kmax))
+    for plen, al, vl, kmax in cases:
+        _say(f"finetune mask: prompt {plen}, {len(al)} attributes, K_max {kmax}")
+        s = B.hpd_finetune_mask(plen, al, vl, kmax)
+        assert s == plen + sum(al) + sum(vl)
+        pos = torch.full((s,), -7, dtype=torch.int32, device="cuda")
+        m = torch.full((s, s), 7, dtype=torch.uint8, device="cuda")
+        B.hpd_finetune_mask(plen, al, vl, kmax, pos, m)
+        assert np.array_equal(pos.cpu().numpy(), F.finetune_position_ids(plen, al, vl, kmax))
+        assert np.array_equal(m.cpu().numpy(), F.finetune_mask(plen, al, vl))
+
+
 def test_mask_export_bit_exact():
     from paper_2604_26209_amd import binding as B
     _say("mask export")
