@@ -37,6 +37,10 @@ What each piece follows
   restart per document "position order" would mix the documents.  The skeleton
   (attribute-name) tokens shape the position IDs but are not cache entries in
   this model, in either mode.
+* first inference step  - Section 4.3.2 ("First Inference Step"): the whole input is fed
+  once; ``prefill_attention`` is the attention of that pass for the header and
+  document tokens (every token a query, causal in position order inside the blocks
+  it may see).
 * decode step           - Section 4.3.3: only the new tokens are fed, positions
   are the previous ones plus one.
 * pruning               - Section 4.3.4: a finished value is fed no more.
@@ -235,6 +239,18 @@ class PromptOracle:
         self.k = self._to_cache(rope(k_raw, pos, self.base, self.dtype))
         self.v = np.asarray(v_raw, dtype=self.dtype).copy()
 
+    def prefill_attention(self, q_raw):
+        """Attention outputs of the prefix tokens themselves (the first inference step):
+        q_raw [n_prefix, Hq, D] un-rotated, memory order as in ``prefill``.  Every prefix
+        token is a query at its own position ID over the mask rows of the prefix.  Call
+        after ``prefill`` and before the first decode step.  Returns [n_prefix, Hq, D]."""
+        assert len(self.kind) == self.n_prefix and self.steps_done == 0
+        assert q_raw.shape == (self.n_prefix, self.hq, self.d)
+        rows = list(range(self.n_prefix))
+        mask = self.mask_rows_fast(rows)
+        qr = rope(q_raw, np.asarray(self.pos, dtype=np.int64), self.base, self.dtype)
+        return masked_attention(qr, self.k, self.v, mask, self.hkv, self.dtype)
+
     def _to_cache(self, k_rot):
         if self.cache_dtype == "bf16":
             return round_to_bf16(k_rot).astype(self.dtype)
@@ -390,6 +406,19 @@ class HPDOracle:
             else:
                 a, b = self.prefix_range[p]
                 po.prefill(np.asarray(k_raw[a:b]), np.asarray(v_raw[a:b]))
+
+    def prefill_attention(self, q_raw):
+        """q_raw [n_prefix_tokens, Hq, D] for the whole batch (or a dict prompt -> array):
+        attention outputs of the prefix tokens of the instantiated prompts, as a dict
+        prompt -> [n_prefix(prompt), Hq, D]."""
+        out = {}
+        for p, po in self.prompts.items():
+            if isinstance(q_raw, dict):
+                out[p] = po.prefill_attention(np.asarray(q_raw[p]))
+            else:
+                a, b = self.prefix_range[p]
+                out[p] = po.prefill_attention(np.asarray(q_raw[a:b]))
+        return out
 
     def step(self, t, q, k_new, v_new):
         """q [n_live, Hq, D], k_new / v_new [n_live, Hkv, D] for ALL live branches

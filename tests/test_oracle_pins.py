@@ -658,3 +658,61 @@ def test_paper_mask_planted_mistakes_are_caught(monkeypatch, mistake):
 
     monkeypatch.setattr(O.PromptOracle, "mask_rows_fast", bad)
     assert worst() > 1e-6
+
+
+# ---------------------------------------------------------------------------
+# The first inference step: attention of the prefix tokens themselves
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("seed,dtype,tol", [(51, np.float64, 1e-12), (52, np.float32, 2e-5)])
+def test_prefill_attention_equals_causal_attention_per_document(seed, dtype, tol):
+    """Under the block mask a document token sees the header and its own document up to
+    itself: ordinary causal attention (library routine, independent complex-number RoPE) over
+    the contiguous sequence [header, document] with positions 0..n-1; the header rows are the
+    first H rows of any of them."""
+    wl = W.random_workload(seed, t=2, p=2, hq=4, hkv=2, d=16, j_range=(1, 3), h_range=(0, 6), l_range=(1, 9))
+    orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len,
+                      wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new, dtype=dtype)
+    kp = _values(wl, 1, (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim))
+    vp = _values(wl, 2, (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim))
+    qp = _values(wl, 3, (wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim))
+    orc.prefill(kp, vp)
+    got = orc.prefill_attention(qp)
+    g = wl.n_q_heads // wl.n_kv_heads
+    for p in range(wl.n_prompts):
+        a0, _ = orc.prefix_range[p]
+        h = int(wl.header_len[p])
+        off = a0 + h
+        for d in range(wl.doc_ptr[p], wl.doc_ptr[p + 1]):
+            l = int(wl.doc_len[d])
+            idx = np.concatenate([np.arange(a0, a0 + h), np.arange(off, off + l)])
+            n = len(idx)
+            kr = _rope_complex(kp[idx].astype(np.float64), np.arange(n), wl.rope_base)
+            qr = _rope_complex(qp[idx].astype(np.float64), np.arange(n), wl.rope_base)
+            tq = torch.from_numpy(qr).permute(1, 0, 2)[None]
+            tk = torch.from_numpy(kr).permute(1, 0, 2).repeat_interleave(g, 0)[None]
+            tv = torch.from_numpy(vp[idx].astype(np.float64)).permute(1, 0, 2).repeat_interleave(g, 0)[None]
+            ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)
+            ref = ref[0].permute(1, 0, 2).numpy()
+            assert np.abs(got[p][idx - a0] - ref).max() < tol, (p, d)
+            off += l
+
+
+def test_prefill_attention_planted_mistake_is_caught(monkeypatch):
+    wl = W.random_workload(53, t=2, p=1, hq=2, hkv=1, d=8, j_range=(2, 2), h_range=(2, 4), l_range=(3, 6))
+    kp = _values(wl, 1, (wl.n_prefix_tokens, 1, 8)); vp = _values(wl, 2, (wl.n_prefix_tokens, 1, 8))
+    qp = _values(wl, 3, (wl.n_prefix_tokens, 2, 8))
+
+    def run():
+        orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len, 2, 1, 8,
+                          wl.rope_base, wl.max_new, dtype=np.float64)
+        orc.prefill(kp, vp)
+        return orc.prefill_attention(qp)[0]
+
+    good = run()
+    real = O.PromptOracle.mask_rows_fast
+    monkeypatch.setattr(O.PromptOracle, "mask_rows_fast",
+                        lambda self, rows: np.tril(np.ones((len(rows), len(self.kind)), dtype=np.uint8)))
+    bad = run()  # plain causal over the stacked memory: the second document sees the first
+    h, l0 = int(wl.header_len[0]), int(wl.doc_len[0])
+    assert np.abs(good[:h + l0] - bad[:h + l0]).max() < 1e-12  # header and first document unchanged
+    assert np.abs(good[h + l0:] - bad[h + l0:]).max() > 1e-6
