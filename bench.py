@@ -133,6 +133,62 @@ def cpu_baseline(wl, budget_s=15.0, paper=False, attr_len=None):
                       f"{done_tokens} branch-tokens in {spent:.1f} s; host affinity {cores} cores"}
 
 
+def bench_prefill(args, wl, layout, B, W, torch, np, out_f32):
+    """hpd_prefill_attention on the workload's header and document tokens: every prefix token a
+    query over header + own document up to itself.  A step = one call over the whole batch."""
+    dev = "cuda"
+    eb = 4 if wl.dtype == "f32" else 2
+    base = wl.value_seed * 1000
+    shp = (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim)
+    k_raw = W.normal_values(shp, base + 1, dev, wl.dtype)
+    v_raw = W.normal_values(shp, base + 2, dev, wl.dtype)
+    q = W.normal_values((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), base + 3, dev, wl.dtype)
+    tdt = torch.float32 if (out_f32 or wl.dtype == "f32") else torch.bfloat16
+    out = torch.empty((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), dtype=tdt, device=dev)
+    kp, vp, kt, vt = B.alloc_pools(layout, dev)
+    B.hpd_prefix_fill(layout, k_raw, v_raw, kp, vp)
+    torch.cuda.synchronize()
+    # multiply-adds: a header token i sees i + 1 keys, token i of a document H + i + 1
+    keys = 0
+    for p in range(wl.n_prompts):
+        h = int(wl.header_len[p])
+        keys += h * (h + 1) // 2
+        for d in range(wl.doc_ptr[p], wl.doc_ptr[p + 1]):
+            l = int(wl.doc_len[d])
+            keys += l * h + l * (l + 1) // 2
+    flops = 4 * wl.head_dim * wl.n_q_heads * keys
+    tok_b = 2 * wl.n_kv_heads * wl.head_dim * eb
+    alg_bytes = wl.n_prefix_tokens * (tok_b + 2 * wl.n_q_heads * wl.head_dim * eb)  # K/V once, Q in, O out
+    steps, warmup = max(1, args.steps // 4), max(1, args.warmup // 4)
+    for _ in range(warmup):
+        B.hpd_prefill_attention(layout, q, kp, vp, out)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        B.hpd_prefill_attention(layout, q, kp, vp, out)
+    ev1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    dur_s = ev0.elapsed_time(ev1) * 1e-3
+    tf = flops * steps / dur_s / 1e12
+    rec = {"metric": "prefix tokens/s of HPD prefill attention (side measurement)",
+           "value": round(wl.n_prefix_tokens * steps / elapsed, 1), "unit": "prefix-tokens/s", "n_gpus": 1,
+           "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed * 1e3 / steps, 4),
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+           "data": "synthetic",
+           "config": {"workload": f"configs[{args.config - 1}] {wl.name}: {wl.note}; prefill attention",
+                      "prefix_tokens": int(wl.n_prefix_tokens), "heads": f"{wl.n_q_heads}/{wl.n_kv_heads}x{wl.head_dim}",
+                      "out_dtype": "f32" if tdt == torch.float32 else wl.dtype, "call": "hpd_prefill_attention"},
+           "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                        "kernel": "attn_stream_kernel (prefill instantiation)", "launches": steps,
+                        "avg_launch_us": round(dur_s / steps * 1e6, 2), "flops_per_launch": int(flops),
+                        "algorithmic_bytes_per_launch": int(alg_bytes)}}
+    print(json.dumps(rec))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -150,6 +206,9 @@ def main():
     ap.add_argument("--mask", default="block", choices=["block", "paper"],
                     help="block: header + own document + own branch (the benchmark's metric); paper: "
                          "the literal mask over the whole stacked prompt, with the paper's gap positions")
+    ap.add_argument("--phase", default="decode", choices=["decode", "prefill"],
+                    help="decode: the benchmark's metric; prefill: hpd_prefill_attention (the attention of "
+                         "the header and document tokens themselves, first inference step), a side measurement")
     ap.add_argument("--per-step", action="store_true",
                     help="second run: one event pair per decode step (all replicas of that step back "
                          "to back), adds per_step {us, gbs} to the record")
@@ -186,6 +245,10 @@ def main():
         off += n_live[t]
     total_tokens = int(sum(n_live))
     attn_b, app_b, flops = algorithmic_bytes(wl, live_lists, eb, paper)
+
+    if args.phase == "prefill":
+        bench_prefill(args, wl, layout, B, W, torch, np, out_f32)
+        return
 
     pool_bytes = B.hpd_layout_query(layout, B.HPD_Q_POOL_BYTES)
     footprint = int(pool_bytes.sum())

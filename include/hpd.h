@@ -213,6 +213,19 @@ int hpd_decode_step(const hpd_layout* layout, int32_t step, const void* q, const
                     void* v_tail, void* out, void* stream);
 
 /*
+ * hpd_prefill_attention - Section 4.3.2, "First Inference Step": the attention of the pass
+ * that feeds the whole input once, for the header and document tokens.  Every prefix token is
+ * a query at its own position ID; under HPD_MASK_BLOCK (the only mode supported here) a
+ * header token attends to the header up to itself, a document token to the whole header and
+ * to its own document up to itself.  Call after hpd_prefix_fill (the keys are read from the
+ * prefix pools).
+ *   q   : device [n_prefix_tokens][Hq][D], un-rotated, token order of hpd_prefix_fill
+ *   out : device [n_prefix_tokens][Hq][D] (element type per hpd_config.out_dtype)
+ */
+int hpd_prefill_attention(const hpd_layout* layout, const void* q, const void* k_prefix,
+                          const void* v_prefix, void* out, void* stream);
+
+/*
  * hpd_expand_mask - debugging export of the mask of Section 4.3.2 as the library
  * understands it.  Memory order of prompt `prompt` after step `step_hi`:
  *   [header | doc_0 | ... | step-0 live branches | step-1 live branches | ... ].

@@ -52,7 +52,8 @@ HPD_KEY_BLOCK = 32
 
 EXPORTS = ["hpd_build_layout", "hpd_layout_free", "hpd_layout_query", "hpd_prefix_fill",
            "hpd_rope_positions", "hpd_kv_append", "hpd_decode_attention", "hpd_decode_step",
-           "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_status_string", "hpd_finetune_mask"]
+           "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_status_string", "hpd_finetune_mask",
+           "hpd_prefill_attention"]
 
 
 class hpd_config(ctypes.Structure):
@@ -77,6 +78,7 @@ _lib.hpd_decode_attention.argtypes = [_vp, _i32] + [_vp] * 7
 _lib.hpd_decode_step.argtypes = [_vp, _i32] + [_vp] * 9
 _lib.hpd_expand_mask.argtypes = [_vp, _i32, _i32, _vp, _i32p, _vp]
 _lib.hpd_set_kernel_mode.argtypes = [_vp, _i32]
+_lib.hpd_prefill_attention.argtypes = [_vp] * 6
 _lib.hpd_finetune_mask.argtypes = [_i32, _i32, _i32p, _i32p, _i32, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _vp]
 _lib.hpd_status_string.argtypes = [ctypes.c_int]
 _lib.hpd_status_string.restype = ctypes.c_char_p
@@ -222,6 +224,11 @@ def hpd_decode_step(layout, step, q, k_new, v_new, k_prefix, v_prefix, k_tail, v
     _check(_lib.hpd_decode_step(layout.handle, int(step), _ptr(q), _ptr(k_new), _ptr(v_new),
                                 _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tail), _ptr(v_tail),
                                 _ptr(out), _stream(stream)), "hpd_decode_step")
+
+
+def hpd_prefill_attention(layout, q, k_prefix, v_prefix, out, stream=None):
+    _check(_lib.hpd_prefill_attention(layout.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(out),
+                                      _stream(stream)), "hpd_prefill_attention")
 
 
 def hpd_expand_mask(layout, prompt, step_hi, mask_out=None, stream=None) -> int:

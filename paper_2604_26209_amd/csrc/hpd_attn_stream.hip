@@ -168,13 +168,22 @@ __device__ __forceinline__ void rotate16(uint4 raw_lo, uint4 raw_hi, const float
 // from a table), and the tail tiles run over every branch of the prompt from the first to the
 // row group's last - finished ones included, up to the length they reached -, a row keeping
 // the keys of the branches that are not later than its own.
-template <int G, typename SH, bool PAPER>
+//
+// MODE_PREFILL = the attention of the prefix tokens themselves (Section 4.3.2, first inference
+// step, under the block mask): the work unit is (segment, kv head, row group), a segment being
+// a header or a document; the rows are the segment's tokens (x G heads), each rotated at its
+// own position ID; the keys are the header (documents only) and the segment itself up to the
+// row's token: the stream stops at the row group's last token, a wave skips the blocks behind
+// its last row, and the blocks on the diagonal get a per-row count.  No tails, no append.
+enum { MODE_BLOCK = 0, MODE_PAPER = 1, MODE_PREFILL = 2 };
+template <int G, typename SH, int MODE>
 __global__ void __launch_bounds__(SH::WAVES * 64, 2)
 attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_prefix,
                    const uint16_t* __restrict__ v_prefix, uint16_t* __restrict__ k_tail,
                    uint16_t* __restrict__ v_tail, const uint16_t* __restrict__ k_new,
                    const uint16_t* __restrict__ v_new, void* __restrict__ out) {
-  constexpr int BPB = 32 / G;              // branches per row block
+  constexpr bool PAPER = MODE == MODE_PAPER, PREFILL = MODE == MODE_PREFILL;
+  constexpr int BPB = 32 / G;              // branches (PREFILL: tokens) per row block
   constexpr int QPR = G >= 8 ? 1 : 8 / G;  // branch quads (tail tiles per 8 positions) per row block
   constexpr int CWAVES = SH::CW, LOADERS = SH::LW, STAGE_BLOCKS = SH::SB, STAGE_U4 = SH::STAGE_U4;
   constexpr int LOADS_PER_ROUND = SH::LOADS_PER_ROUND, STAGE_ROWS = SH::STAGE_ROWS;
@@ -206,10 +215,14 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t u = grp / a.Hkv;
   // PAPER: {hoff, Hlen, first entry of the prompt's block list, document blocks, first live
   //         row, live branches, first branch of the prompt, first live branch | -1, key branches}
-  const int32_t* desc = (PAPER ? a.tb.punit_desc : a.tb.unit_desc) + (int64_t)u * (PAPER ? 16 : 8);  // pre-offset to this step by the host
+  // PREFILL: {hoff, Hlen (0 for a header unit), first slot of the segment, its tokens, first
+  //         token in the order of q / out, tokens again, position ID of the first token, 0}
+  const int32_t* desc = (PAPER ? a.tb.punit_desc : PREFILL ? a.tb.funit_desc : a.tb.unit_desc) +
+                        (int64_t)u * (PAPER ? 16 : 8);  // pre-offset to this step by the host
   const int32_t hoff = desc[0], Hlen = desc[1], doff = desc[2], Llen = desc[3];
-  const int32_t row0_live = desc[4], nb = desc[5], upos = PAPER ? -1 : desc[6], ub0 = desc[7];
+  const int32_t row0_live = desc[4], nb = desc[5], upos = (PAPER || PREFILL) ? -1 : desc[6], ub0 = desc[7];
   const int32_t pb0 = PAPER ? desc[6] : 0;
+  const int32_t seg_pos0 = PREFILL ? desc[6] : 0;
 
   const int32_t R = nb * G;
   const int32_t nblk = (R + 31) >> 5;
@@ -248,11 +261,13 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 
   // ---- the stream: NB prefix blocks, then NQ * NC tail tiles (quad-major inside a chunk of 8
   //      positions), two blocks per round
-  const int32_t NBh = (Hlen + 31) >> 5, NBd = PAPER ? Llen : (Llen + 31) >> 5;
+  // (PREFILL: the document blocks up to the row group's last token)
+  const int32_t NBh = (Hlen + 31) >> 5;
+  const int32_t NBd = PAPER ? Llen : PREFILL ? ((br0 + nbr_here - 1) >> 5) + 1 : (Llen + 31) >> 5;
   const int32_t NB = NBh + NBd;
   const int32_t NQ = ((PAPER ? kb_end : nbr_here) + 3) >> 2;  // quads of 4 (key) branches
   const int32_t NC = (a.step >> 3) + 1;    // chunks of 8 positions that hold positions 0 .. step
-  const int32_t NTT = NQ * NC;
+  const int32_t NTT = PREFILL ? 0 : NQ * NC;
   const int32_t NBT = NB + NTT;
   const int32_t NR = (NBT + STAGE_BLOCKS - 1) / STAGE_BLOCKS;
   // A round is one stage while the stream is in the prefix and two stages from the first
@@ -550,7 +565,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   } else {
     // per-branch positions: straight from the table
     const int32_t q_bi = min(r_row / G, nb - 1);
-    const int32_t q_pos = a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
+    const int32_t q_pos = PREFILL ? seg_pos0 + q_bi : a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
     const float4* cs_row = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)q_pos * (D / 2));
     rotate_query([&](int i4) -> float4 { return cs_row[i4]; });
   }
@@ -672,9 +687,19 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         uint32_t ok = 0xffffu;
         if (gb < NB) {
           mine = gb % KG == kg;
-          const int32_t valid = gb < NBh ? min(32, Hlen - gb * 32)
-                                : PAPER ? a.tb.pblk[2 * (doff + gb - NBh) + 1] : min(32, Llen - (gb - NBh) * 32);
+          int32_t valid = gb < NBh ? min(32, Hlen - gb * 32)
+                          : PAPER ? a.tb.pblk[2 * (doff + gb - NBh) + 1] : min(32, Llen - (gb - NBh) * 32);
           masked = valid < 32;
+          if (PREFILL && gb >= NBh) {
+            // causal inside the segment: the row of token x keeps keys 0 .. x.  Blocks behind
+            // the last token of the row block are not this wave's; blocks that end before its
+            // first token need no mask.
+            const int32_t k0 = (gb - NBh) * 32;  // first key of the block
+            const int32_t tok_first = br0 + rb * BPB, tok_last = min(tok_first + BPB, br0 + nbr_here) - 1;
+            mine = mine && k0 <= tok_last;
+            masked = masked || k0 + 31 > tok_first;
+            valid = min(valid, br0 + min(lb_row, nbr_here - 1) - k0 + 1);
+          }
           ok = first_bits(valid - g2 * 8) | (first_bits(valid - 16 - g2 * 8) << 8);
         } else {
           const int32_t tt = gb - NB;
@@ -853,11 +878,11 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   }
 }
 
-template <int G, typename SH, bool PAPER>
+template <int G, typename SH, int MODE>
 hipError_t launch_g(const StreamArgs& a, int64_t items, const void* q, const void* k_prefix,
                     const void* v_prefix, void* k_tail, void* v_tail, const void* k_new,
                     const void* v_new, void* out, hipStream_t s) {
-  attn_stream_kernel<G, SH, PAPER><<<dim3((unsigned)items), SH::WAVES * 64, 0, s>>>(
+  attn_stream_kernel<G, SH, MODE><<<dim3((unsigned)items), SH::WAVES * 64, 0, s>>>(
       a, (const uint16_t*)q, (const uint16_t*)k_prefix, (const uint16_t*)v_prefix, (uint16_t*)k_tail,
       (uint16_t*)v_tail, (const uint16_t*)k_new, (const uint16_t*)v_new, out);
   return hipGetLastError();
@@ -906,7 +931,7 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
 #define HPD_LAUNCH_M(GG, PP)                                                                            \
   (narrow ? launch_g<GG, NarrowShape, PP>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s) \
           : launch_g<GG, WideShape, PP>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s))
-#define HPD_LAUNCH(GG) (paper ? HPD_LAUNCH_M(GG, true) : HPD_LAUNCH_M(GG, false))
+#define HPD_LAUNCH(GG) (paper ? HPD_LAUNCH_M(GG, MODE_PAPER) : HPD_LAUNCH_M(GG, MODE_BLOCK))
   switch (G) {
     case 1: return HPD_LAUNCH(1);
     case 2: return HPD_LAUNCH(2);
@@ -916,4 +941,42 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   }
 #undef HPD_LAUNCH
 #undef HPD_LAUNCH_M
+}
+
+// Attention of the prefix tokens (first inference step): one unit per header / document.
+hipError_t hpd_launch_prefill_stream(const hpd_layout* L, const void* q, const void* k_prefix,
+                                     const void* v_prefix, void* out, hipStream_t s) {
+  StreamArgs a;
+  a.tb = L->dev;
+  a.step = 0; a.Hq = L->cfg.n_q_heads; a.Hkv = L->cfg.n_kv_heads;
+  const int G = a.Hq / a.Hkv;
+  a.Tcap = L->T; a.NP = L->NP;
+  a.out_f32 = L->cfg.out_dtype == HPD_OUT_F32 ? 1 : 0;
+  a.fused = 0;
+  a.live_base = 0;
+  a.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)D));
+  const int64_t n_units = (int64_t)L->funit_desc.size() / 8;
+  if (n_units == 0) return hipSuccess;
+  const int32_t max_nblk = std::max(1, (L->fmax_rows * G + 31) / 32);
+  // the rows of a segment are many (every token is a query): the launch is bound by the matrix
+  // pipes, so the wide shape (fewer workgroups stream the same keys) unless forced
+  const bool narrow = L->kernel_mode == 4;
+  a.RG = (max_nblk + (narrow ? NarrowShape::MAX_BLOCKS : WideShape::MAX_BLOCKS) - 1) /
+         (narrow ? NarrowShape::MAX_BLOCKS : WideShape::MAX_BLOCKS);
+  a.n_groups = (int32_t)(n_units * a.Hkv);
+  const int64_t items = ((int64_t)(a.n_groups + 7) / 8 * 8) * a.RG;
+  if (items > 0x7fffffff) return hipErrorInvalidValue;
+#define HPD_LAUNCH(GG)                                                                                   \
+  (narrow ? launch_g<GG, NarrowShape, MODE_PREFILL>(a, items, q, k_prefix, v_prefix, nullptr, nullptr,  \
+                                                    nullptr, nullptr, out, s)                           \
+          : launch_g<GG, WideShape, MODE_PREFILL>(a, items, q, k_prefix, v_prefix, nullptr, nullptr,    \
+                                                  nullptr, nullptr, out, s))
+  switch (G) {
+    case 1: return HPD_LAUNCH(1);
+    case 2: return HPD_LAUNCH(2);
+    case 4: return HPD_LAUNCH(4);
+    case 8: return HPD_LAUNCH(8);
+    default: return hipErrorInvalidValue;
+  }
+#undef HPD_LAUNCH
 }

@@ -270,6 +270,28 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
       }
     }
 
+    // ---- attention of the prefix tokens (first inference step, block mask): a unit per
+    //      non-empty header and per document, the most expensive (tokens x keys) first
+    if (cfg->mask_mode == HPD_MASK_BLOCK) {
+      std::vector<int32_t> segs;
+      for (int32_t sid = 0; sid < n_seg; ++sid)
+        if (L->seg_len[sid] > 0) segs.push_back(sid);
+      std::vector<int32_t> raw_of(n_seg);
+      for (int32_t i = 0; i < n_seg; ++i) raw_of[L->raw_seg[i]] = L->seg_raw_off[i];
+      auto cost = [&](int32_t sid) -> int64_t {
+        const int64_t hl = sid < P ? 0 : L->seg_len[L->doc_prompt[sid - P]];
+        return (int64_t)L->seg_len[sid] * (hl + L->seg_len[sid]);
+      };
+      std::stable_sort(segs.begin(), segs.end(), [&](int32_t x, int32_t y) { return cost(x) > cost(y); });
+      for (int32_t sid : segs) {
+        const int32_t p = sid < P ? sid : L->doc_prompt[sid - P];
+        const int32_t desc[8] = {L->seg_off[p], sid < P ? 0 : L->seg_len[p], L->seg_off[sid], L->seg_len[sid],
+                                 raw_of[sid], L->seg_len[sid], L->seg_pos0[sid], 0};
+        L->funit_desc.insert(L->funit_desc.end(), desc, desc + 8);
+        L->fmax_rows = std::max(L->fmax_rows, L->seg_len[sid]);
+      }
+    }
+
     // ---- RoPE table: angles in double, stored as float (cos, sin)
     const int32_t half = cfg->head_dim / 2;
     L->rope.resize((size_t)(L->max_pos + 1) * half * 2);
@@ -298,7 +320,8 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
                  o_dlp = A.add(L->doc_live_ptr), o_unit_ptr = A.add(L->unit_ptr),
                  o_unit_doc = A.add(L->unit_doc), o_unit_desc = A.add(L->unit_desc),
                  o_pdp = A.add(L->prompt_doc_ptr), o_pbp = A.add(L->prompt_branch_ptr),
-                 o_blen = A.add(L->branch_len), o_pblk = A.add(L->pblk), o_pdesc = A.add(L->punit_desc);
+                 o_blen = A.add(L->branch_len), o_pblk = A.add(L->pblk), o_pdesc = A.add(L->punit_desc),
+                 o_fdesc = A.add(L->funit_desc);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipGetDevice(&L->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&L->n_cus, hipDeviceAttributeMultiprocessorCount, L->device);
@@ -327,6 +350,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     L->dev.unit_doc = base + o_unit_doc; L->dev.unit_desc = base + o_unit_desc;
     L->dev.prompt_doc_ptr = base + o_pdp; L->dev.prompt_branch_ptr = base + o_pbp;
     L->dev.branch_len = base + o_blen; L->dev.pblk = base + o_pblk; L->dev.punit_desc = base + o_pdesc;
+    L->dev.funit_desc = base + o_fdesc;
     L->dev.rope = (const float2*)L->d_rope;
     L->on_device = true;
   }
@@ -461,6 +485,26 @@ int hpd_decode_attention(const hpd_layout* L, int32_t step, const void* q, const
     HPD_HIP(hpd_launch_attention_generic(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out,
                                          (hipStream_t)stream));
   }
+  return HPD_OK;
+}
+
+int hpd_prefill_attention(const hpd_layout* L, const void* q, const void* k_prefix, const void* v_prefix,
+                          void* out, void* stream) {
+  if (!L || !L->on_device) return HPD_E_INVALID;
+  if (L->cfg.mask_mode != HPD_MASK_BLOCK) return HPD_E_UNSUPPORTED;
+  if (L->n_prefix_tokens == 0) return HPD_OK;
+  if (!q || !k_prefix || !v_prefix || !out) return HPD_E_INVALID;
+  if (L->kernel_mode >= 2 || (L->kernel_mode == 0 && hpd_stream_supported(L))) {
+    HPD_HIP(hpd_launch_prefill_stream(L, q, k_prefix, v_prefix, out, (hipStream_t)stream));
+    return HPD_OK;
+  }
+  // the generic kernel keeps one score per key in LDS
+  int64_t max_keys = 0;
+  for (int32_t d = 0; d < L->n_docs; ++d)
+    max_keys = std::max<int64_t>(max_keys, (int64_t)L->seg_len[L->doc_prompt[d]] + L->seg_len[L->P + d]);
+  for (int32_t p = 0; p < L->P; ++p) max_keys = std::max<int64_t>(max_keys, L->seg_len[p]);
+  if (max_keys > 15000) return HPD_E_UNSUPPORTED;
+  HPD_HIP(hpd_launch_prefill_generic(L, q, k_prefix, v_prefix, out, (hipStream_t)stream));
   return HPD_OK;
 }
 

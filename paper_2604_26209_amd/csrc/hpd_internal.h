@@ -31,6 +31,8 @@ struct hpd_dev_tables {
   // paper-literal mask only: work units are prompts
   const int32_t* pblk;        // [total document blocks][2] (first pool slot, keys) of every 32-key block of a prompt's documents
   const int32_t* punit_desc;  // [total_punits][16] {hoff, Hlen, first pblk entry, document blocks, first live row, live branches, first branch of the prompt, first live branch id or -1, key branches (first .. last live), 0...}
+  // attention of the prefix tokens (block mask): one unit per non-empty header / document
+  const int32_t* funit_desc;  // [n_funits][8] {hoff, Hlen (0 for a header), first slot, tokens, first token in q / out order, tokens, position ID of the first token, 0}
   const float2* rope;           // [max_pos+1][D/2] (cos, sin)
 };
 
@@ -47,6 +49,8 @@ struct hpd_layout {
   // paper-literal mask: document blocks per prompt, per-step prompt units
   std::vector<int32_t> pblk_ptr, pblk, punit_ptr, punit_desc, pmax_rows;
   int32_t max_prompt_branches = 0;
+  std::vector<int32_t> funit_desc;  // prefix-token attention units, heaviest first
+  int32_t fmax_rows = 0;            // most tokens of any segment
   std::vector<int32_t> live_ptr, live_branch, doc_live_ptr, unit_ptr, unit_doc, unit_desc;
   std::vector<int32_t> max_rows;  // [T] largest number of live branches of any document at step t
   std::vector<float> rope;        // host copy of the (cos, sin) table
@@ -85,6 +89,10 @@ hipError_t hpd_launch_finetune_mask(const int32_t* d_desc, int32_t S, int32_t* p
 int64_t hpd_generic_max_keys(const hpd_layout* L, int32_t step);
 
 bool hpd_stream_supported(const hpd_layout* L);
+hipError_t hpd_launch_prefill_stream(const hpd_layout* L, const void* q, const void* k_prefix,
+                                     const void* v_prefix, void* out, hipStream_t s);
+hipError_t hpd_launch_prefill_generic(const hpd_layout* L, const void* q, const void* k_prefix,
+                                      const void* v_prefix, void* out, hipStream_t s);
 // k_new / v_new may be null: then the newest token is read from the tail pool like the others
 hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const void* q,
                                        const void* k_prefix, const void* v_prefix, void* k_tail,

@@ -182,7 +182,12 @@ __device__ inline float block_reduce(float v, bool is_max, float* red) {
 // PAPER = the literal mask of Section 4.3.2: the keys of a row are the header, every document
 // of the prompt, and positions 0..step of every branch of the prompt up to the row's own (a
 // position a finished branch never reached gets probability 0).
-template <typename T, bool PAPER>
+// GM_PREFILL = the attention of the prefix tokens themselves (first inference step, block
+// mask): row r is token r of hpd_prefix_fill's order, at its own position ID; its keys are the
+// header (for a document token) and its own segment up to itself.  `step` then carries the
+// number of segments.
+enum { GM_BLOCK = 0, GM_PAPER = 1, GM_PREFILL = 2 };
+template <typename T, int GM>
 __global__ void __launch_bounds__(GEN_THREADS)
 attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hkv, int32_t D,
                          int32_t Tcap, int32_t P, int64_t NP, const T* __restrict__ q,
@@ -195,22 +200,47 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
   float* part = red + 8;           // [256] partial outputs
   float* scores = part + GEN_THREADS;  // [n_keys]
 
+  constexpr bool PAPER = GM == GM_PAPER, PREFILL = GM == GM_PREFILL;
   const int32_t r = blockIdx.x / Hq;
   const int32_t h = blockIdx.x % Hq;
   const int32_t hk = h / (Hq / Hkv);
-  const int32_t b = tb.live_branch[tb.live_ptr[step] + r];
-  const int32_t d = tb.branch_doc[b];
-  const int32_t p = tb.doc_prompt[d];
-  const int32_t pos = tb.branch_base_pos[b] + 1 + step;
-  const int32_t Hlen = tb.seg_len[p];
+  int32_t b = 0, d = 0, p = 0, pos = 0, Hlen = 0, Llen = 0, d_lo = 0, d_hi = 0, b_lo = 0, n_tail = 0;
+  if (PREFILL) {
+    // segment that holds token r: last entry of the sorted start table <= r (empty ones skipped)
+    const int32_t n_seg = step;
+    int32_t lo = 0, hi = n_seg;
+    while (hi - lo > 1) {
+      const int32_t mid = (lo + hi) >> 1;
+      if (tb.seg_raw_off[mid] <= r) lo = mid; else hi = mid;
+    }
+    while (lo + 1 < n_seg && tb.seg_raw_off[lo + 1] <= r) ++lo;
+    const int32_t sid = tb.raw_seg[lo], idx = r - tb.seg_raw_off[lo];
+    pos = tb.seg_pos0[sid] + idx;
+    if (sid < P) {  // a header token: the header up to itself
+      p = sid;
+      Hlen = idx + 1;
+    } else {        // a document token: the header, the document up to itself
+      d = sid - P;
+      p = tb.doc_prompt[d];
+      Hlen = tb.seg_len[p];
+      Llen = idx + 1;
+      d_lo = d; d_hi = d + 1;
+    }
+  } else {
+    b = tb.live_branch[tb.live_ptr[step] + r];
+    d = tb.branch_doc[b];
+    p = tb.doc_prompt[d];
+    pos = tb.branch_base_pos[b] + 1 + step;
+    Hlen = tb.seg_len[p];
+    // documents the row sees: its own, or all of its prompt
+    d_lo = PAPER ? tb.prompt_doc_ptr[p] : d;
+    d_hi = PAPER ? tb.prompt_doc_ptr[p + 1] : d + 1;
+    for (int32_t dd = d_lo; dd < d_hi; ++dd) Llen += tb.seg_len[P + dd];
+    // branches whose tails the row sees: its own, or the prompt's first .. its own
+    b_lo = PAPER ? tb.prompt_branch_ptr[p] : b;
+    n_tail = (b - b_lo + 1) * (step + 1);
+  }
   const int64_t hoff = tb.seg_off[p];
-  // documents the row sees: its own, or all of its prompt
-  const int32_t d_lo = PAPER ? tb.prompt_doc_ptr[p] : d, d_hi = PAPER ? tb.prompt_doc_ptr[p + 1] : d + 1;
-  int32_t Llen = 0;
-  for (int32_t dd = d_lo; dd < d_hi; ++dd) Llen += tb.seg_len[P + dd];
-  // branches whose tails the row sees: its own, or the prompt's first .. its own
-  const int32_t b_lo = PAPER ? tb.prompt_branch_ptr[p] : b;
-  const int32_t n_tail = (b - b_lo + 1) * (step + 1);
   const int32_t n_keys = Hlen + Llen + n_tail;
   const int32_t half = D / 2;
   const int tid = threadIdx.x;
@@ -361,15 +391,25 @@ int64_t hpd_generic_max_keys(const hpd_layout* L, int32_t step) {
   return max_keys;
 }
 
-template <typename T, bool PAPER>
+template <typename T, int GM>
 static hipError_t launch_generic(const hpd_layout* L, int32_t step, const void* q, const void* k_prefix,
                                  const void* v_prefix, const void* k_tail, const void* v_tail, void* out,
                                  hipStream_t s) {
-  const int32_t n_live = L->live_ptr[step + 1] - L->live_ptr[step];
-  const size_t smem = (size_t)(L->cfg.head_dim + 8 + GEN_THREADS + hpd_generic_max_keys(L, step)) * sizeof(float);
-  const dim3 grid((unsigned)((int64_t)n_live * L->cfg.n_q_heads));
+  int64_t n_rows = 0, max_keys = 0;
+  if (GM == GM_PREFILL) {
+    n_rows = L->n_prefix_tokens;
+    for (int32_t d = 0; d < L->n_docs; ++d)
+      max_keys = std::max<int64_t>(max_keys, (int64_t)L->seg_len[L->doc_prompt[d]] + L->seg_len[L->P + d]);
+    for (int32_t p = 0; p < L->P; ++p) max_keys = std::max<int64_t>(max_keys, L->seg_len[p]);
+    step = L->n_seg;
+  } else {
+    n_rows = L->live_ptr[step + 1] - L->live_ptr[step];
+    max_keys = hpd_generic_max_keys(L, step);
+  }
+  const size_t smem = (size_t)(L->cfg.head_dim + 8 + GEN_THREADS + max_keys) * sizeof(float);
+  const dim3 grid((unsigned)(n_rows * L->cfg.n_q_heads));
   const int32_t out_f32 = (L->cfg.dtype == HPD_F32 || L->cfg.out_dtype == HPD_OUT_F32) ? 1 : 0;
-  attention_generic_kernel<T, PAPER><<<grid, GEN_THREADS, smem, s>>>(
+  attention_generic_kernel<T, GM><<<grid, GEN_THREADS, smem, s>>>(
       L->dev, step, L->cfg.n_q_heads, L->cfg.n_kv_heads, L->cfg.head_dim, L->T, L->P, L->NP, (const T*)q,
       (const T*)k_prefix, (const T*)v_prefix, (const T*)k_tail, (const T*)v_tail, out, out_f32);
   return hipGetLastError();
@@ -381,10 +421,18 @@ hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const
                                         hipStream_t s) {
   const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
   if (L->cfg.dtype == HPD_F32)
-    return paper ? launch_generic<float, true>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s)
-                 : launch_generic<float, false>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s);
-  return paper ? launch_generic<hpd::bf16_t, true>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s)
-               : launch_generic<hpd::bf16_t, false>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s);
+    return paper ? launch_generic<float, GM_PAPER>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s)
+                 : launch_generic<float, GM_BLOCK>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s);
+  return paper ? launch_generic<hpd::bf16_t, GM_PAPER>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s)
+               : launch_generic<hpd::bf16_t, GM_BLOCK>(L, step, q, k_prefix, v_prefix, k_tail, v_tail, out, s);
+}
+
+hipError_t hpd_launch_prefill_generic(const hpd_layout* L, const void* q, const void* k_prefix,
+                                      const void* v_prefix, void* out, hipStream_t s) {
+  // no tail key exists: the tail pools are never addressed
+  if (L->cfg.dtype == HPD_F32)
+    return launch_generic<float, GM_PREFILL>(L, 0, q, k_prefix, v_prefix, k_prefix, v_prefix, out, s);
+  return launch_generic<hpd::bf16_t, GM_PREFILL>(L, 0, q, k_prefix, v_prefix, k_prefix, v_prefix, out, s);
 }
 
 hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, int32_t paper, uint8_t* mask_out,

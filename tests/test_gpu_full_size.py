@@ -83,3 +83,43 @@ def test_full_size_config_paper_literal_mask(k, prompts):
     worst = H.check_all(wl, hip, prompts=prompts, pos_mode="paper_gap", attr_len=attr, mask_mode="paper",
                         label=f"cfg{k}_paper")
     print(f"  worst max-abs / RMS(step) = {worst:.4f}", flush=True)
+
+
+@pytest.mark.parametrize("k,prompts", [(2, [0, 31]), (3, [11])])
+def test_full_size_prefill_attention(k, prompts):
+    """hpd_prefill_attention at full size, launched as `bench.py --phase prefill` launches it:
+    sampled prompts against the oracle (per-token RMS bound), every output finite and inside
+    the hull of V."""
+    from paper_2604_26209_amd import binding as B
+    wl = W.config(k)
+    print(f"full-size cfg{k}, prefill attention over {wl.n_prefix_tokens} tokens", flush=True)
+    layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32)
+    base = wl.value_seed * 1000
+    shp = (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim)
+    k_raw = W.normal_values(shp, base + 1, "cuda", wl.dtype)
+    v_raw = W.normal_values(shp, base + 2, "cuda", wl.dtype)
+    q = W.normal_values((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), base + 3, "cuda", wl.dtype)
+    kp, vp, kt, vt = B.alloc_pools(layout)
+    kp.fill_(float("nan")); vp.fill_(float("nan"))
+    B.hpd_prefix_fill(layout, k_raw, v_raw, kp, vp)
+    out = torch.full((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+    B.hpd_prefill_attention(layout, q, kp, vp, out)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    assert float(out.abs().max()) <= float(v_raw.abs().max()) * (1 + 1e-2)
+    from oracle import hpd_oracle as O
+    orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len, wl.n_q_heads,
+                      wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new, prompts=prompts, cache_dtype="bf16")
+    kd, vd, qd = {}, {}, {}
+    for p in prompts:
+        a, b = orc.prefix_range[p]
+        kd[p], vd[p], qd[p] = (x[a:b].float().cpu().numpy() for x in (k_raw, v_raw, q))
+    orc.prefill(kd, vd)
+    ref = orc.prefill_attention(qd)
+    for p in prompts:
+        a, b = orc.prefix_range[p]
+        got = out[a:b].cpu().numpy()
+        diff = np.abs(got - ref[p]).reshape(b - a, -1).max(axis=1)
+        rms = np.sqrt(np.mean(ref[p].astype(np.float64).reshape(b - a, -1) ** 2, axis=1))
+        assert np.all(diff <= H.BF16_TOL * rms), f"cfg{k} prompt {p}: worst {float((diff / rms).max()):.3e}"
+        print(f"  prompt {p}: worst max-abs / RMS(token) = {float((diff / rms).max()):.4f}", flush=True)

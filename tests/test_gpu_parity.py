@@ -170,6 +170,68 @@ def test_paper_literal_mask_stream_kernel_shapes(g):
             assert torch.equal(x, y)
 
 
+def _check_prefill(wl, mode, label, out_f32=None):
+    """hpd_prefill_attention against the oracle's prefill_attention, all prompts."""
+    from paper_2604_26209_amd import binding as B
+    if out_f32 is None:
+        out_f32 = wl.dtype == "bf16"
+    layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME)
+    if mode:
+        B.hpd_set_kernel_mode(layout, mode)
+    inputs = H.Inputs(wl, layout.n_live(), "cuda")
+    q = W.normal_values((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), wl.value_seed * 1000 + 3, "cuda", wl.dtype)
+    kp, vp, kt, vt = B.alloc_pools(layout)
+    for x in (kp, vp):
+        x.fill_(float("nan"))
+    B.hpd_prefix_fill(layout, inputs.k_raw, inputs.v_raw, kp, vp)
+    out = torch.full((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), float("nan"),
+                     dtype=torch.float32 if out_f32 else H.torch_dtype(wl), device="cuda")
+    B.hpd_prefill_attention(layout, q, kp, vp, out)
+    torch.cuda.synchronize()
+    orc, _ = H.run_oracle(wl, inputs, steps=[])
+    ref = orc.prefill_attention(q.float().cpu().numpy())
+    got = out.float().cpu().numpy()
+    assert np.isfinite(got).all(), f"{label}: non-finite output"
+    worst = 0.0
+    for p, want in ref.items():
+        a0, a1 = orc.prefix_range[p]
+        err = float(np.abs(got[a0:a1] - want).max())
+        if wl.dtype == "f32":
+            assert err <= H.F32_TOL, f"{label} prompt {p}: max-abs {err:.3e}"
+            worst = max(worst, err)
+        else:
+            # The RMS of a token's outputs falls from |v| (a token that sees one key) to
+            # |v| / sqrt(keys): the bound is taken per token, relative to that token's own
+            # RMS over its Hq x D outputs.
+            diff = np.abs(got[a0:a1] - want).reshape(a1 - a0, -1).max(axis=1)
+            rms = np.sqrt(np.mean(want.astype(np.float64).reshape(a1 - a0, -1) ** 2, axis=1))
+            bad = np.nonzero(diff > H.BF16_TOL * rms)[0]
+            assert bad.size == 0, (f"{label} prompt {p}: token {bad[0]} max-abs {diff[bad[0]]:.3e} > "
+                                   f"{H.BF16_TOL} * rms {rms[bad[0]]:.3e}")
+            worst = max(worst, float((diff / rms).max()))
+    return worst
+
+
+def test_prefill_attention_fp32_generic():
+    for seed, kw in [(90, dict(hq=4, hkv=2, d=64, t=2, p=3, j_range=(1, 3), h_range=(0, 20), l_range=(1, 70))),
+                     (91, dict(hq=2, hkv=2, d=32, t=1, p=2, h_range=(0, 0), l_range=(1, 5)))]:
+        wl = W.random_workload(seed, dtype="f32", **kw)
+        _say(f"prefill f32 seed {seed}: {wl.n_prefix_tokens} tokens")
+        _check_prefill(wl, 0, f"prefill_f32_{seed}")
+
+
+@pytest.mark.parametrize("g", [1, 2, 4, 8])
+def test_prefill_attention_bf16_all_kernels(g):
+    """Generic kernel and both shapes of the streaming kernel: segments shorter than a row
+    block, segments of many row groups, empty headers, ragged ends."""
+    wl = W.random_workload(92 + g, dtype="bf16", hq=8, hkv=8 // g, d=128, base=500000.0, t=2, p=3,
+                           j_range=(1, 3), h_range=(0, 90), l_range=(1, 260 if g > 1 else 700))
+    for mode in (1, 3, 4):
+        _say(f"prefill bf16 G={g} mode {mode}: {wl.n_prefix_tokens} tokens")
+        rel = _check_prefill(wl, mode, f"prefill_bf16_g{g}_m{mode}")
+        _say(f"  worst err/rms {rel:.2e}")
+
+
 def test_finetune_mask_and_positions_bit_exact():
     """hpd_finetune_mask (Section 5) against the loop oracle: mask and position IDs."""
     from oracle import finetune_mask as F
