@@ -35,7 +35,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # of this same command, each scaled by what the counter reads for a 1 GiB copy
 # (profiles/attn_stream_<workload>.txt).  None where no counter run has been made.
-MEASURED_TRAFFIC_BYTES = {2: 106.3e6, 3: 734.5e6, 4: 443.9e6, 5: 2687.9e6}
+MEASURED_TRAFFIC_BYTES = {2: 106.4e6, 3: 734.5e6, 4: 444.0e6, 5: 2687.9e6}
 
 
 def algorithmic_bytes(wl, n_live_lists, eb, paper=False):
