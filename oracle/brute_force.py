@@ -90,18 +90,23 @@ def decode_all_steps_paper(header_len, doc_lens, branch_lens, attr_lens, hq, hkv
                            k_prefix, v_prefix, q_steps, k_steps, v_steps):
     """One prompt, the paper's own positions and its literal mask.
 
-    Prefix token i (header, then the documents one after the other) sits at position i.
-    Attribute n (0-based over all branches of the prompt, in (document, attribute) order) ends at
-    |p| + A_0 + .. + A_n - 1 + n * K_max; its value token k (1-based) one gap slot further each.
-    Branch b at step t sees: the whole prefix, tokens 0..min(t, len-1) of every earlier branch,
-    and its own tokens 0..t.  Arguments and result as in ``decode_all_steps``; ``attr_lens`` is
+    Header and document token i sits at position i.  The name tokens of attribute n (0-based
+    over all branches of the prompt, in (document, attribute) order) follow in memory, attribute
+    by attribute, and end at position |p| + A_0 + .. + A_n - 1 + n * K_max; value token k
+    (1-based) of the attribute sits k slots after that.  Branch b at step t sees: header and
+    documents, the name tokens of attributes 0..b, tokens 0..min(t, len-1) of every earlier
+    branch, and its own tokens 0..t.  k_prefix / v_prefix hold header, documents and then the
+    name tokens; other arguments and the result as in ``decode_all_steps``; ``attr_lens`` is
     the flat list A_n.
     """
     group = hq // hkv
     blen = [x for bl in branch_lens for x in bl]
     n_prefix = header_len + sum(doc_lens)
     base_pos, run = [], n_prefix
+    name_tok = []  # (index in k_prefix, position, attribute) of every name token
     for n, a in enumerate(attr_lens):
+        for i in range(a):
+            name_tok.append((run + i, run + i + n * t_max, n))
         run += a
         base_pos.append(run - 1 + n * t_max)
     tails = [[] for _ in blen]
@@ -123,6 +128,10 @@ def decode_all_steps_paper(header_len, doc_lens, branch_lens, attr_lens, hq, hkv
                 for i in range(n_prefix):
                     keys.append(_rope_scalar(k_prefix[i][hk], i, base))
                     vals.append(v_prefix[i][hk])
+                for (idx, npos, n) in name_tok:  # attribute names up to the own one
+                    if n <= b:
+                        keys.append(_rope_scalar(k_prefix[idx][hk], npos, base))
+                        vals.append(v_prefix[idx][hk])
                 for bb in range(b + 1):  # earlier attributes and itself, whatever is in memory
                     for (kr, vv) in tails[bb][:t + 1]:
                         keys.append(kr[hk])

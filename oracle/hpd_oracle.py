@@ -34,9 +34,12 @@ What each piece follows
   up to its own step (Section 5 states the same for fine-tuning: v_{n,k} may not
   see v_{n',k'} with n' < n and k' > k, so k' <= k it does see).  It needs the
   paper's own position IDs (``pos_mode="paper_gap"``): with positions that
-  restart per document "position order" would mix the documents.  The skeleton
-  (attribute-name) tokens shape the position IDs but are not cache entries in
-  this model, in either mode.
+  restart per document "position order" would mix the documents.  Under this
+  mask the skeleton (attribute-name) tokens a_1..a_N are cache entries as in the
+  paper's input s = cat(p, a_1:N): they are fed with the prompt (memory order
+  [header | documents | a_1 .. a_N]) at Algorithm 2's positions, so a value token
+  also sees the attribute names up to its own.  Under the block mask they only
+  shape the position IDs.
 * first inference step  - Section 4.3.2 ("First Inference Step"): the whole input is fed
   once; ``prefill_attention`` is the attention of that pass for the header and
   document tokens (every token a query, causal in position order inside the blocks
@@ -67,7 +70,7 @@ from __future__ import annotations
 
 import numpy as np
 
-KIND_HEADER, KIND_DOC, KIND_BRANCH = 0, 1, 2
+KIND_HEADER, KIND_DOC, KIND_BRANCH, KIND_SKELETON = 0, 1, 2, 3
 
 
 # ----------------------------------------------------------------------------
@@ -176,6 +179,7 @@ class PromptOracle:
         self.branch_lens = [[int(x) for x in bl] for bl in branch_lens]  # per doc
         assert len(self.branch_lens) == len(self.doc_lens)
         self.hq, self.hkv, self.d = int(n_q_heads), int(n_kv_heads), int(head_dim)
+        self.attr_lens, self.skeleton_pos = [], []  # skeleton tokens in memory (literal mask only)
         self.base = float(rope_base)
         self.t_max = int(max_new)
         self.pos_mode = pos_mode
@@ -203,6 +207,9 @@ class PromptOracle:
                 acc += l
             pos_id, end_index = alg2_position_ids(acc, attr_lens, self.t_max)
             self.base_pos = [int(pos_id[e]) for e in end_index]
+            if mask_mode == "paper":  # the skeleton is part of the input: s = cat(p, a_1..a_N)
+                self.attr_lens = [int(a) for a in attr_lens]
+                self.skeleton_pos = [int(x) for x in pos_id[acc:]]
         else:
             raise ValueError(pos_mode)
         # ---- flat memory (grows): per-token bookkeeping + KV
@@ -214,17 +221,19 @@ class PromptOracle:
     # -- prefix ---------------------------------------------------------------
     @property
     def n_prefix(self):
-        return self.h + sum(self.doc_lens)
+        return self.h + sum(self.doc_lens) + len(self.skeleton_pos)
 
     def prefix_positions(self):
         pos = list(range(self.h))
         for j, l in enumerate(self.doc_lens):
             pos.extend(self.doc_pos0[j] + i for i in range(l))
+        pos.extend(self.skeleton_pos)
         return np.asarray(pos, dtype=np.int64)
 
     def prefill(self, k_raw, v_raw):
         """k_raw, v_raw [n_prefix, Hkv, D] un-rotated, memory order
-        [header | doc_0 | doc_1 | ...]."""
+        [header | doc_0 | doc_1 | ...] (literal mask: followed by the skeleton tokens
+        a_1 .. a_N of all attributes in (document, attribute) order)."""
         assert len(self.kind) == 0
         assert k_raw.shape == (self.n_prefix, self.hkv, self.d)
         self.kind = [KIND_HEADER] * self.h
@@ -232,7 +241,11 @@ class PromptOracle:
         for j, l in enumerate(self.doc_lens):
             self.kind.extend([KIND_DOC] * l)
             self.doc.extend([j] * l)
-        self.branch = [-1] * self.n_prefix
+        self.branch = [-1] * (self.h + sum(self.doc_lens))
+        for n, a in enumerate(self.attr_lens):
+            self.kind.extend([KIND_SKELETON] * a)
+            self.doc.extend([self.branch_doc[n]] * a)
+            self.branch.extend([n] * a)
         self.step_of = [-1] * self.n_prefix
         pos = self.prefix_positions()
         self.pos = [int(x) for x in pos]
@@ -273,6 +286,8 @@ class PromptOracle:
         if kk == KIND_HEADER:
             return True  # the header is shared by everything in the prompt
         qk = self.kind[qi]
+        if kk == KIND_SKELETON:
+            return False  # only the literal mask keeps skeleton tokens in memory
         if kk == KIND_DOC:
             return qk != KIND_HEADER and self.doc[qi] == self.doc[ki]
         # ki is a branch token: only its own branch sees it
@@ -381,6 +396,8 @@ class HPDOracle:
             d0, d1 = int(doc_ptr[p]), int(doc_ptr[p + 1])
             b0, b1 = int(branch_ptr[d0]), int(branch_ptr[d1])
             n_tok = int(header_len[p]) + int(doc_len[d0:d1].sum())
+            if mask_mode == "paper":
+                n_tok += int(np.asarray(attr_len)[b0:b1].sum())
             self.prefix_range[p] = (tok, tok + n_tok)
             self.branch_range[p] = (b0, b1)
             tok += n_tok

@@ -38,8 +38,9 @@ def _run_oracle(wl, dtype=np.float32, pos_mode="contig", attr_len=None, mask_mod
     orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len,
                       wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new,
                       pos_mode=pos_mode, attr_len=attr_len, dtype=dtype, mask_mode=mask_mode)
-    kp = _values(wl, 1, (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim))
-    vp = _values(wl, 2, (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim))
+    # (under the literal mask the prefix also holds the skeleton tokens)
+    kp = _values(wl, 1, (orc.n_prefix_tokens, wl.n_kv_heads, wl.head_dim))
+    vp = _values(wl, 2, (orc.n_prefix_tokens, wl.n_kv_heads, wl.head_dim))
     orc.prefill(kp, vp)
     steps, inputs = [], {"kp": kp, "vp": vp, "q": [], "k": [], "v": []}
     for t in range(wl.max_new):
@@ -522,12 +523,16 @@ def test_paper_mask_set_construction_and_row_sums(seed):
             if po.kind[qi] != O.KIND_BRANCH:
                 continue
             b, t = po.branch[qi], po.step_of[qi]
-            # written out: the whole prefix, earlier attributes' tokens up to this step, own tokens
-            want = set(range(po.n_prefix))
+            # written out: header and documents, the attribute names up to the own one, earlier
+            # attributes' value tokens up to this step, own tokens
+            n_hd = po.h + sum(po.doc_lens)
+            want = set(range(n_hd))
+            want |= {i for i in range(s) if po.kind[i] == O.KIND_SKELETON and po.branch[i] <= b}
             want |= {i for i in range(s) if po.kind[i] == O.KIND_BRANCH and po.branch[i] <= b
                      and po.step_of[i] <= t}
             assert set(np.nonzero(m[qi])[0]) == want
-            assert m[qi].sum() == po.n_prefix + sum(min(t + 1, po.branch_len[bb]) for bb in range(b)) + t + 1
+            assert m[qi].sum() == (n_hd + sum(po.attr_lens[:b + 1])
+                                   + sum(min(t + 1, po.branch_len[bb]) for bb in range(b)) + t + 1)
             # nothing with a larger position ID, nothing that was appended later
             assert all(po.pos[i] <= po.pos[qi] and i <= qi for i in np.nonzero(m[qi])[0])
         # ordered by position ID the whole memory is causal: lower triangular, except that a
@@ -545,9 +550,14 @@ def test_paper_mask_reduces_to_block_mask_for_one_document_one_attribute():
     attr = np.asarray([3])
     a, _, sa = _run_oracle(wl, dtype=np.float64, pos_mode="paper_gap", attr_len=attr, mask_mode="paper")
     b, _, sb = _run_oracle(wl, dtype=np.float64, pos_mode="paper_gap", attr_len=attr, mask_mode="block")
-    assert np.array_equal(a.prompts[0].dense_mask(), b.prompts[0].dense_mask())
-    for x, y in zip(sa, sb):
-        assert np.array_equal(x["out"], y["out"])
+    # the literal mask adds the attribute's own name tokens (3 of them, in memory after the
+    # document); everything else is the block mask
+    ma, mb = a.prompts[0].dense_mask(), b.prompts[0].dense_mask()
+    n_hd = 4 + 7
+    keep = [i for i in range(ma.shape[0]) if not (n_hd <= i < n_hd + 3)]
+    assert np.array_equal(ma[np.ix_(keep, keep)], mb)
+    rows = [i for i in range(ma.shape[0]) if a.prompts[0].kind[i] == O.KIND_BRANCH]
+    assert np.all(ma[np.ix_(rows, list(range(n_hd, n_hd + 3)))] == 1)
 
 
 def test_paper_mask_sees_more_than_block_mask():
@@ -557,9 +567,11 @@ def test_paper_mask_sees_more_than_block_mask():
     ma, mb = a.prompts[0].dense_mask(), b.prompts[0].dense_mask()
     po = a.prompts[0]
     rows = [i for i in range(len(po.kind)) if po.kind[i] == O.KIND_BRANCH]
-    assert np.all(ma[rows] >= mb[rows])  # the block mask is a subset
+    cols = [i for i in range(len(po.kind)) if po.kind[i] != O.KIND_SKELETON]
+    rows_b = [i for i in range(len(b.prompts[0].kind)) if b.prompts[0].kind[i] == O.KIND_BRANCH]
+    assert np.all(ma[np.ix_(rows, cols)] >= mb[rows_b])  # the block mask is a subset
     last = rows[-1]  # last attribute of the last document, last step
-    assert ma[last].sum() == len(po.kind) and mb[last].sum() < ma[last].sum()
+    assert ma[last].sum() == len(po.kind) and mb[rows_b[-1]].sum() < ma[last].sum()
 
 
 @pytest.mark.parametrize("seed,dtype,tol", [(41, np.float64, 1e-12), (42, np.float32, 2e-5)])
@@ -578,7 +590,12 @@ def test_paper_mask_equals_causal_attention_in_position_order(seed, dtype, tol):
         k_all = [inputs["kp"][a0:a1]]
         v_all = [inputs["vp"][a0:a1]]
         q_all = [np.zeros((a1 - a0, wl.n_q_heads, wl.head_dim))]
-        pos_all = [np.arange(a1 - a0)]
+        # header and documents at 0 .. |p|-1, then the attribute names: Algorithm 2 in closed
+        # form (attribute n, 0-based, is shifted by n * K_max)
+        plen = a1 - a0 - int(attr[b0:b1].sum())
+        skel = [plen + int(attr[b0:b0 + n].sum()) + i + n * wl.max_new
+                for n in range(b1 - b0) for i in range(int(attr[b0 + n]))]
+        pos_all = [np.concatenate([np.arange(plen), np.asarray(skel, dtype=np.int64)])]
         for t in range(wl.max_new):
             live = np.nonzero(wl.branch_len > t)[0]
             sel = np.nonzero((live >= b0) & (live < b1))[0]
@@ -587,7 +604,6 @@ def test_paper_mask_equals_causal_attention_in_position_order(seed, dtype, tol):
             k_all.append(inputs["k"][t][sel]); v_all.append(inputs["v"][t][sel]); q_all.append(inputs["q"][t][sel])
             # closed form of Appendix A.1 for the position IDs (not the oracle's own table)
             n_loc = live[sel] - b0
-            plen = a1 - a0
             pos_all.append(np.asarray([plen + int(attr[b0:b0 + n + 1].sum()) - 1 + n * wl.max_new + t + 1
                                        for n in n_loc]))
             k = np.concatenate(k_all).astype(np.float64)
