@@ -38,7 +38,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 MEASURED_TRAFFIC_BYTES = {2: 106.4e6, 3: 734.5e6, 4: 444.0e6, 5: 2687.9e6}
 
 
-def algorithmic_bytes(wl, n_live_lists, eb, paper=False):
+def algorithmic_bytes(wl, n_live_lists, eb, paper=False, attr_len=None):
     """Bytes the method has to move per decode step: each shared prefix K/V once per
     (prompt | document, kv head), each tail once per (branch, kv head), Q in, O out, new K/V
     in and out.  Returns (attention_bytes[t], append_bytes[t], flops[t]).
@@ -69,13 +69,16 @@ def algorithmic_bytes(wl, n_live_lists, eb, paper=False):
             prefix, tail = 0, 0
             for pr in prompts:
                 d0, d1 = wl.doc_ptr[pr], wl.doc_ptr[pr + 1]
-                prefix += int(wl.header_len[pr] + wl.doc_len[d0:d1].sum()) * tok_b
                 last = live[p_of_b[live] == pr].max()
+                prefix += int(wl.header_len[pr] + wl.doc_len[d0:d1].sum()) * tok_b
+                prefix += int(attr_len[first_b[pr]:last + 1].sum()) * tok_b  # attribute names up to the last live branch
                 tail += int(csum[last + 1] - csum[first_b[pr]]) * tok_b
             attn[-1] = prefix + tail + qo
             plen = np.asarray([wl.header_len[pr] + wl.doc_len[wl.doc_ptr[pr]:wl.doc_ptr[pr + 1]].sum()
                                for pr in range(wl.n_prompts)])
-            keys = plen[p_of_b[live]] + (csum[live + 1] - csum[first_b[p_of_b[live]]])
+            acum = np.concatenate([[0], np.cumsum(attr_len)])
+            keys = (plen[p_of_b[live]] + (csum[live + 1] - csum[first_b[p_of_b[live]]])
+                    + (acum[live + 1] - acum[first_b[p_of_b[live]]]))
         flops.append(int(4 * wl.head_dim * wl.n_q_heads * keys.sum()))
     return attn, app, flops
 
@@ -101,6 +104,8 @@ def cpu_baseline(wl, budget_s=15.0, paper=False, attr_len=None):
         d0, d1 = int(wl.doc_ptr[p]), int(wl.doc_ptr[p + 1])
         b0, b1 = int(wl.branch_ptr[d0]), int(wl.branch_ptr[d1])
         n_tok = int(wl.header_len[p] + wl.doc_len[d0:d1].sum())
+        if paper:  # the attribute names are fed with the prompt
+            n_tok += int(attr_len[b0:b1].sum())
         g = np.random.default_rng(1000 + p)
         kr = g.standard_normal((n_tok, wl.n_kv_heads, wl.head_dim), dtype=np.float32)
         vr = g.standard_normal((n_tok, wl.n_kv_heads, wl.head_dim), dtype=np.float32)
@@ -244,7 +249,7 @@ def main():
         live_lists.append(live_flat[off:off + n_live[t]])
         off += n_live[t]
     total_tokens = int(sum(n_live))
-    attn_b, app_b, flops = algorithmic_bytes(wl, live_lists, eb, paper)
+    attn_b, app_b, flops = algorithmic_bytes(wl, live_lists, eb, paper, attr_len)
 
     if args.phase == "prefill":
         bench_prefill(args, wl, layout, B, W, torch, np, out_f32)
@@ -257,8 +262,10 @@ def main():
 
     # ---- inputs (seeded), resident in HBM
     base = wl.value_seed * 1000
-    k_raw = W.normal_values((wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim), base + 1, dev, wl.dtype)
-    v_raw = W.normal_values((wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim), base + 2, dev, wl.dtype)
+    # (the layout's count: under the literal mask the attribute-name tokens are fed as well)
+    n_prefix = int(B.hpd_layout_query(layout, B.HPD_Q_COUNTS)[B.HPD_C_N_PREFIX_TOKENS])
+    k_raw = W.normal_values((n_prefix, wl.n_kv_heads, wl.head_dim), base + 1, dev, wl.dtype)
+    v_raw = W.normal_values((n_prefix, wl.n_kv_heads, wl.head_dim), base + 2, dev, wl.dtype)
     q, kn, vn, outs = [], [], [], []
     for t in range(wl.max_new):
         n = int(n_live[t])

@@ -79,8 +79,12 @@ enum hpd_mask_mode {
                          the (document, attribute) order) up to the current step, finished
                          branches included, and its own tokens.  Needs HPD_POS_PAPER_GAP
                          (positions that restart per document do not order a prompt).
-                         The skeleton (attribute-name) tokens shape the position IDs but are
-                         not cache entries, as in HPD_MASK_BLOCK. */
+                         The skeleton (attribute-name) tokens a_1..a_N of Section 4.3.1's input
+                         s = cat(p, a_1:N) are cache entries in this mode: per prompt a third
+                         kind of prefix segment (after the documents in hpd_prefix_fill's
+                         order, attribute by attribute, at Algorithm 2's positions), of which
+                         a branch sees the names up to its own.  Under HPD_MASK_BLOCK they only
+                         shape the position IDs. */
 };
 enum hpd_out_dtype {
   HPD_OUT_SAME = 0, /* `out` has the element type of the inputs */
@@ -115,10 +119,13 @@ enum hpd_query {
   HPD_Q_LIVE_BRANCH = 3, /* int32[total_live]: live lists of steps 0..T-1 back to back */
   HPD_Q_BRANCH_BASE_POS = 4, /* int32[B]: position of the token a branch continues from */
   HPD_Q_BRANCH_DOC = 5,  /* int32[B] */
-  HPD_Q_SEG_OFF = 6,     /* int32[P + n_docs]: first pool slot; headers first, then documents */
-  HPD_Q_SEG_LEN = 7,     /* int32[P + n_docs] */
-  HPD_Q_SEG_POS0 = 8,    /* int32[P + n_docs]: position ID of the segment's first token */
-  HPD_Q_SEG_RAW_OFF = 9, /* int32[P + n_docs]: first token in hpd_prefix_fill's input order */
+  /* segments: P headers, then n_docs documents, then - under HPD_MASK_PAPER only - P skeleton
+     segments (n_seg = P + n_docs [+ P]) */
+  HPD_Q_SEG_OFF = 6,     /* int32[n_seg]: first pool slot */
+  HPD_Q_SEG_LEN = 7,     /* int32[n_seg] */
+  HPD_Q_SEG_POS0 = 8,    /* int32[n_seg]: position ID of the segment's first token (-1 for a
+                            skeleton segment: its positions have gaps) */
+  HPD_Q_SEG_RAW_OFF = 9, /* int32[n_seg]: first token in hpd_prefix_fill's input order */
   HPD_Q_N_UNITS = 10     /* int32[T]: documents (prompts, under HPD_MASK_PAPER) with at least one
                             live branch per step: the work units of the attention kernel */
 };
@@ -126,7 +133,7 @@ enum hpd_count {
   HPD_C_N_PROMPTS = 0,
   HPD_C_N_DOCS = 1,
   HPD_C_N_BRANCHES = 2,
-  HPD_C_N_PREFIX_TOKENS = 3, /* header + document tokens, unpadded */
+  HPD_C_N_PREFIX_TOKENS = 3, /* header + document (+ skeleton) tokens, unpadded */
   HPD_C_N_PREFIX_SLOTS = 4,  /* NP */
   HPD_C_N_TAIL_SLOTS = 5,    /* B * T */
   HPD_C_MAX_POS = 6,         /* largest position ID any token can take */

@@ -184,6 +184,8 @@ def hpd_layout_query(layout: hpd_layout, what: int):
         c = np.zeros(HPD_N_COUNTS, dtype=np.int64)
         _check(_lib.hpd_layout_query(h, HPD_Q_COUNTS, c.ctypes.data, c.nbytes), "hpd_layout_query")
         n_seg = int(c[HPD_C_N_PROMPTS] + c[HPD_C_N_DOCS])
+        if layout.cfg.mask_mode == HPD_MASK_PAPER:  # plus one skeleton segment per prompt
+            n_seg += int(c[HPD_C_N_PROMPTS])
         size = {HPD_Q_N_LIVE: layout.cfg.max_new, HPD_Q_N_UNITS: layout.cfg.max_new,
                 HPD_Q_LIVE_BRANCH: int(c[HPD_C_TOTAL_LIVE]),
                 HPD_Q_BRANCH_BASE_POS: int(c[HPD_C_N_BRANCHES]),

@@ -663,11 +663,14 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t lb_row = rb * BPB + n / G;  // this row's branch within the row group
   // PAPER: the branch of this row and of the last row of the row block, counted from the
   // prompt's first branch like the key branches
-  int32_t kb_row = 0, kb_row_max = 0;
+  // ... and the attribute-name tokens they see (names up to the own branch's)
+  int32_t kb_row = 0, kb_row_max = 0, names_row = 0, names_max = 0;
   if constexpr (PAPER) {
     if (active) {
       kb_row = branch_id(min(lb_row, nbr_here - 1)) - pb0;
       kb_row_max = __builtin_amdgcn_readfirstlane(branch_id(min(rb * BPB + BPB - 1, nbr_here - 1))) - pb0;
+      names_row = a.tb.skel_cum[pb0 + kb_row];
+      names_max = __builtin_amdgcn_readfirstlane(a.tb.skel_cum[pb0 + kb_row_max]);
     }
   }
 
@@ -722,6 +725,13 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
           int32_t valid = gb < NBh ? min(32, Hlen - gb * 32)
                           : PAPER ? a.tb.pblk[2 * (doff + gb - NBh) + 1] : min(32, Llen - (gb - NBh) * 32);
           masked = valid < 32;
+          if (PAPER && valid >= 1000) {
+            // a block of attribute names: the row keeps the names up to its own branch's
+            const int32_t k0 = valid - 1000;  // first name token of the block
+            mine = mine && k0 < names_max;
+            masked = true;
+            valid = names_row - k0;
+          }
           if (PREFILL && gb >= NBh) {
             // causal inside the segment: the row of token x keeps keys 0 .. x.  Blocks behind
             // the last token of the row block are not this wave's; blocks that end before its

@@ -30,6 +30,7 @@ int hip_fail(hipError_t e) {
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 size_t elem_bytes(const hpd_config& c) { return c.dtype == HPD_F32 ? 4 : 2; }
+bool paper_mode(const hpd_layout* L) { return L->cfg.mask_mode == HPD_MASK_PAPER; }
 
 int validate_config(const hpd_config* c) {
   if (!c) return HPD_E_INVALID;
@@ -110,13 +111,16 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
   if (!L) return HPD_E_NOMEM;
   try {
     L->cfg = *cfg;
-    L->P = P; L->n_docs = n_docs; L->B = B; L->T = T; L->n_seg = P + n_docs;
+    const bool paper = cfg->mask_mode == HPD_MASK_PAPER;
+    // (under the literal mask every prompt has a third kind of segment: its attribute names)
+    L->P = P; L->n_docs = n_docs; L->B = B; L->T = T; L->n_seg = P + n_docs + (paper ? P : 0);
     const int32_t n_seg = L->n_seg;
     L->seg_off.assign(n_seg, 0); L->seg_len.assign(n_seg, 0); L->seg_pos0.assign(n_seg, 0);
     L->seg_raw_off.assign(n_seg + 1, 0); L->raw_seg.assign(n_seg, 0);
     L->doc_prompt.assign(n_docs, 0);
     L->branch_doc.assign(B, 0); L->branch_base_pos.assign(B, 0); L->branch_len.assign(B, T);
     if (branch_len) std::copy(branch_len, branch_len + B, L->branch_len.begin());
+    if (paper) { L->skel_cum.assign(B, 0); L->skel_seg_off.assign(P, 0); }
     L->prompt_doc_ptr.assign(doc_ptr, doc_ptr + P + 1);
     L->prompt_branch_ptr.resize(P + 1);
     for (int32_t p = 0; p <= P; ++p) L->prompt_branch_ptr[p] = branch_ptr[doc_ptr[p]];
@@ -157,6 +161,8 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
         // position plus n*K_max; a branch continues from its attribute's last token.
         int64_t idx = run_pos;  // index in s of the next skeleton token
         int64_t offset = 0;
+        int32_t cum = 0;
+        if (paper) L->skel_off.push_back((int32_t)L->skel_pos.size());
         for (int32_t d = doc_ptr[p]; d < doc_ptr[p + 1]; ++d)
           for (int32_t b = branch_ptr[d]; b < branch_ptr[d + 1]; ++b) {
             L->branch_doc[b] = d;
@@ -164,11 +170,26 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
             const int64_t bp = end + offset;
             if (bp + T > (1 << 30)) { delete L; return HPD_E_OVERFLOW; }
             L->branch_base_pos[b] = (int32_t)bp;
+            if (paper) {
+              for (int64_t i = idx; i <= end; ++i) L->skel_pos.push_back((int32_t)(i + offset));
+              cum += attr_len[b];
+              L->skel_cum[b] = cum;
+            }
             idx = end + 1;
             offset += T;
           }
+        if (paper) {
+          // the skeleton segment of the prompt: after its documents in the input order
+          const int32_t sid = P + n_docs + p;
+          L->seg_off[sid] = (int32_t)slot; L->seg_len[sid] = cum; L->seg_pos0[sid] = -1;
+          L->skel_seg_off[p] = (int32_t)slot;
+          L->seg_raw_off[ri] = (int32_t)raw; L->raw_seg[ri] = sid; ++ri;
+          slot += round_up(cum, HPD_KEY_BLOCK); raw += cum;
+          if (slot > std::numeric_limits<int32_t>::max() - 4096) { delete L; return HPD_E_OVERFLOW; }
+        }
       }
     }
+    if (paper) L->skel_off.push_back((int32_t)L->skel_pos.size());
     L->seg_raw_off[n_seg] = (int32_t)raw;
     L->n_prefix_tokens = raw;
     // slack of 128 slots so that a kernel tile that starts inside the last segment never
@@ -241,6 +262,12 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
             L->pblk.push_back(L->seg_off[P + d] + i);
             L->pblk.push_back(std::min<int32_t>(HPD_KEY_BLOCK, doc_len[d] - i));
           }
+        // then the blocks of the attribute names: a row keeps the names up to its own branch's,
+        // so the second entry is 1000 + the index of the block's first name token
+        for (int32_t i = 0; i < L->seg_len[P + n_docs + p]; i += HPD_KEY_BLOCK) {
+          L->pblk.push_back(L->skel_seg_off[p] + i);
+          L->pblk.push_back(1000 + i);
+        }
         L->pblk_ptr[p + 1] = (int32_t)(L->pblk.size() / 2);
         L->max_prompt_branches = std::max(L->max_prompt_branches,
                                           L->prompt_branch_ptr[p + 1] - L->prompt_branch_ptr[p]);
@@ -321,7 +348,8 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
                  o_unit_doc = A.add(L->unit_doc), o_unit_desc = A.add(L->unit_desc),
                  o_pdp = A.add(L->prompt_doc_ptr), o_pbp = A.add(L->prompt_branch_ptr),
                  o_blen = A.add(L->branch_len), o_pblk = A.add(L->pblk), o_pdesc = A.add(L->punit_desc),
-                 o_fdesc = A.add(L->funit_desc);
+                 o_fdesc = A.add(L->funit_desc), o_spos = A.add(L->skel_pos), o_soff = A.add(L->skel_off),
+                 o_sseg = A.add(L->skel_seg_off), o_scum = A.add(L->skel_cum);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipGetDevice(&L->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&L->n_cus, hipDeviceAttributeMultiprocessorCount, L->device);
@@ -351,6 +379,8 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     L->dev.prompt_doc_ptr = base + o_pdp; L->dev.prompt_branch_ptr = base + o_pbp;
     L->dev.branch_len = base + o_blen; L->dev.pblk = base + o_pblk; L->dev.punit_desc = base + o_pdesc;
     L->dev.funit_desc = base + o_fdesc;
+    L->dev.skel_pos = paper_mode(L) ? base + o_spos : nullptr; L->dev.skel_off = base + o_soff;
+    L->dev.skel_seg_off = base + o_sseg; L->dev.skel_cum = base + o_scum;
     L->dev.rope = (const float2*)L->d_rope;
     L->on_device = true;
   }
@@ -544,6 +574,9 @@ int hpd_expand_mask(const hpd_layout* L, int32_t prompt, int32_t step_hi, uint8_
   for (int32_t d = d0; d >= 0 && d < d1; ++d)
     for (int32_t i = 0; i < L->seg_len[L->P + d]; ++i)
       desc.insert(desc.end(), {1, d, -1, paper ? L->seg_pos0[L->P + d] + i : -1});
+  if (paper)  // the attribute names, fed with the prompt (kind 3)
+    for (int32_t i = L->skel_off[prompt]; i < L->skel_off[prompt + 1]; ++i)
+      desc.insert(desc.end(), {3, -1, -1, L->skel_pos[i]});
   for (int32_t t = 0; t <= step_hi; ++t)
     for (int32_t r = L->live_ptr[t]; r < L->live_ptr[t + 1]; ++r) {
       const int32_t b = L->live_branch[r];

@@ -31,6 +31,12 @@ struct hpd_dev_tables {
   // paper-literal mask only: work units are prompts
   const int32_t* pblk;        // [total document blocks][2] (first pool slot, keys) of every 32-key block of a prompt's documents
   const int32_t* punit_desc;  // [total_punits][16] {hoff, Hlen, first pblk entry, document blocks, first live row, live branches, first branch of the prompt, first live branch id or -1, key branches (first .. last live), 0...}
+  // paper-literal mask only: the attribute-name (skeleton) tokens of a prompt are a segment of
+  // their own (id P + n_docs + p), fed after the prompt's documents
+  const int32_t* skel_pos;      // [total name tokens] position IDs (Algorithm 2), prompt by prompt; null without skeleton segments
+  const int32_t* skel_off;      // [P+1] first entry of each prompt in skel_pos
+  const int32_t* skel_seg_off;  // [P] first pool slot of each prompt's skeleton segment
+  const int32_t* skel_cum;      // [B] name tokens of the prompt's branches up to and including b
   // attention of the prefix tokens (block mask): one unit per non-empty header / document
   const int32_t* funit_desc;  // [n_funits][8] {hoff, Hlen (0 for a header), first slot, tokens, first token in q / out order, tokens, position ID of the first token, 0}
   const float2* rope;           // [max_pos+1][D/2] (cos, sin)
@@ -49,6 +55,7 @@ struct hpd_layout {
   // paper-literal mask: document blocks per prompt, per-step prompt units
   std::vector<int32_t> pblk_ptr, pblk, punit_ptr, punit_desc, pmax_rows;
   int32_t max_prompt_branches = 0;
+  std::vector<int32_t> skel_pos, skel_off, skel_seg_off, skel_cum;
   std::vector<int32_t> funit_desc;  // prefix-token attention units, heaviest first
   int32_t fmax_rows = 0;            // most tokens of any segment
   std::vector<int32_t> live_ptr, live_branch, doc_live_ptr, unit_ptr, unit_doc, unit_desc;

@@ -14,7 +14,7 @@ namespace {
 // interleaved.  One thread per (raw token, kv head, rotation pair).
 // ---------------------------------------------------------------------------------------
 template <typename T>
-__global__ void prefix_fill_kernel(hpd_dev_tables tb, int32_t n_seg, int64_t n_tok, int32_t Hkv,
+__global__ void prefix_fill_kernel(hpd_dev_tables tb, int32_t n_seg, int32_t P, int64_t n_tok, int32_t Hkv,
                                    int32_t D, int64_t NP, const T* __restrict__ k_raw,
                                    const T* __restrict__ v_raw, T* __restrict__ k_prefix,
                                    T* __restrict__ v_prefix) {
@@ -35,7 +35,10 @@ __global__ void prefix_fill_kernel(hpd_dev_tables tb, int32_t n_seg, int64_t n_t
   while (lo + 1 < n_seg && tb.seg_raw_off[lo + 1] <= tok) ++lo;
   const int32_t sid = tb.raw_seg[lo];
   const int32_t idx = (int32_t)(tok - tb.seg_raw_off[lo]);
-  const int32_t pos = tb.seg_pos0[sid] + idx;
+  // (a skeleton segment - the last P of the segments, where there are any - has gaps between
+  // its attributes: positions from a table)
+  const bool skeleton = tb.skel_pos != nullptr && sid >= n_seg - P;
+  const int32_t pos = skeleton ? tb.skel_pos[tb.skel_off[sid - (n_seg - P)] + idx] : tb.seg_pos0[sid] + idx;
   const int64_t slot = (int64_t)tb.seg_off[sid] + idx;
   const float2 cs = tb.rope[(int64_t)pos * half + i];
   const int64_t src = (tok * Hkv + h) * D;
@@ -241,11 +244,15 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
     n_tail = (b - b_lo + 1) * (step + 1);
   }
   const int64_t hoff = tb.seg_off[p];
+  // PAPER: the attribute names up to the row's own branch, counted with the documents
+  const int32_t Dlen = Llen;
+  if (PAPER) Llen += tb.skel_cum[b];
   const int32_t n_keys = Hlen + Llen + n_tail;
   const int32_t half = D / 2;
   const int tid = threadIdx.x;
   // pool slot of prefix key kk (>= Hlen: the documents one after the other)
   auto doc_slot = [&](int32_t kk) -> int64_t {
+    if (PAPER && kk >= Hlen + Dlen) return (int64_t)tb.skel_seg_off[p] + (kk - Hlen - Dlen);
     int32_t i = kk - Hlen, dd = d_lo;
     while (i >= tb.seg_len[P + dd]) { i -= tb.seg_len[P + dd]; ++dd; }
     return (int64_t)tb.seg_off[P + dd] + i;
@@ -336,13 +343,13 @@ hipError_t hpd_launch_prefix_fill(const hpd_layout* L, const void* k_raw, const 
   const int64_t pad_total = (int64_t)L->n_seg * L->cfg.n_kv_heads * (HPD_KEY_BLOCK - 1) * L->cfg.head_dim;
   if (L->cfg.dtype == HPD_F32) {
     prefix_fill_kernel<float><<<grid1d(total, 256), 256, 0, s>>>(
-        L->dev, L->n_seg, L->n_prefix_tokens, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP,
+        L->dev, L->n_seg, L->P, L->n_prefix_tokens, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP,
         (const float*)k_raw, (const float*)v_raw, (float*)k_prefix, (float*)v_prefix);
     prefix_pad_kernel<float><<<grid1d(pad_total, 256), 256, 0, s>>>(
         L->dev, L->n_seg, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP, (float*)v_prefix);
   } else {
     prefix_fill_kernel<hpd::bf16_t><<<grid1d(total, 256), 256, 0, s>>>(
-        L->dev, L->n_seg, L->n_prefix_tokens, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP,
+        L->dev, L->n_seg, L->P, L->n_prefix_tokens, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP,
         (const hpd::bf16_t*)k_raw, (const hpd::bf16_t*)v_raw, (hpd::bf16_t*)k_prefix,
         (hpd::bf16_t*)v_prefix);
     prefix_pad_kernel<hpd::bf16_t><<<grid1d(pad_total, 256), 256, 0, s>>>(
@@ -379,6 +386,7 @@ int64_t hpd_generic_max_keys(const hpd_layout* L, int32_t step) {
       int64_t n = L->seg_len[p];
       for (int32_t d = L->prompt_doc_ptr[p]; d < L->prompt_doc_ptr[p + 1]; ++d) n += L->seg_len[L->P + d];
       n += (int64_t)(L->prompt_branch_ptr[p + 1] - L->prompt_branch_ptr[p]) * (step + 1);
+      n += L->seg_len[L->P + L->n_docs + p];  // attribute names
       max_keys = std::max(max_keys, n);
     }
     return max_keys;

@@ -20,10 +20,12 @@ class Inputs:
     """All inputs of a workload, generated once on ``device`` from the workload's seed:
     raw prefix K/V and, per step, q / k_new / v_new for that step's live branches."""
 
-    def __init__(self, wl, n_live, device):
+    def __init__(self, wl, n_live, device, n_prefix_tokens=None):
+        """``n_prefix_tokens``: the layout's count when it differs from the workload's (under the
+        literal mask the attribute-name tokens of every prompt follow its documents)."""
         self.wl = wl
         dt = wl.dtype
-        shp = (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim)
+        shp = (wl.n_prefix_tokens if n_prefix_tokens is None else int(n_prefix_tokens), wl.n_kv_heads, wl.head_dim)
         base = wl.value_seed * 1000
         self.k_raw = W.normal_values(shp, base + 1, device, dt)
         self.v_raw = W.normal_values(shp, base + 2, device, dt)
@@ -48,7 +50,7 @@ def run_hip(wl, inputs=None, kernel_mode=0, fused=False, pos_mode=0, attr_len=No
         B.hpd_set_kernel_mode(layout, kernel_mode)
     n_live = layout.n_live()
     if inputs is None:
-        inputs = Inputs(wl, n_live, "cuda")
+        inputs = Inputs(wl, n_live, "cuda", layout.counts()[B.HPD_C_N_PREFIX_TOKENS])
     kp, vp, kt, vt = B.alloc_pools(layout)
     if poison_pools == "zero":
         for x in (kp, vp, kt, vt):
