@@ -159,3 +159,35 @@ def test_finetune_mask_host_checks():
             B.hpd_finetune_mask(**bad)
     with pytest.raises(B.HpdError):
         B.hpd_finetune_mask(46000, [1], [1], 2)  # S beyond the limit
+
+
+def test_host_tables_under_the_literal_mask():
+    """HPD_MASK_PAPER, host only: one skeleton segment per prompt after its documents, sized
+    by the attribute lengths; token counts and input order agree with the oracle's."""
+    wl = W.random_workload(17, t=4, p=3, j_range=(1, 3), n_range=(1, 4))
+    attr = np.random.default_rng(17).integers(1, 5, size=wl.n_branches).astype(np.int32)
+    lay = B.layout_from_workload(wl, pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr, mask_mode=B.HPD_MASK_PAPER,
+                                 flags=B.HPD_FLAG_HOST_ONLY)
+    orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len, wl.n_q_heads,
+                      wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new, pos_mode="paper_gap",
+                      attr_len=attr, mask_mode="paper")
+    c = lay.counts()
+    assert int(c[B.HPD_C_N_PREFIX_TOKENS]) == orc.n_prefix_tokens == wl.n_prefix_tokens + int(attr.sum())
+    seg_len = B.hpd_layout_query(lay, B.HPD_Q_SEG_LEN)
+    seg_off = B.hpd_layout_query(lay, B.HPD_Q_SEG_OFF)
+    raw_off = B.hpd_layout_query(lay, B.HPD_Q_SEG_RAW_OFF)
+    P, nd = wl.n_prompts, wl.n_docs
+    assert len(seg_len) == 2 * P + nd
+    for p in range(P):
+        b0, b1 = wl.branch_ptr[wl.doc_ptr[p]], wl.branch_ptr[wl.doc_ptr[p + 1]]
+        assert seg_len[P + nd + p] == attr[b0:b1].sum()
+        assert seg_off[P + nd + p] % B.HPD_KEY_BLOCK == 0
+        a0, a1 = orc.prefix_range[p]
+        assert raw_off[p] == a0  # header first
+        assert raw_off[P + nd + p] + seg_len[P + nd + p] == a1  # the names last
+    # decode positions still follow Algorithm 2
+    base = B.hpd_layout_query(lay, B.HPD_Q_BRANCH_BASE_POS)
+    for p, po in orc.prompts.items():
+        b0, b1 = orc.branch_range[p]
+        assert list(base[b0:b1]) == po.base_pos
+        assert po.skeleton_pos[-1] == po.base_pos[-1]

@@ -315,3 +315,11 @@ def test_error_paths_on_device_layout():
         B.hpd_kv_append(lay, 0, None, None, None, None)
     with pytest.raises(B.HpdError):
         B.hpd_set_kernel_mode(lay, 2)  # fp32 / D=64 has no MFMA path
+    # the prefill attention is built for the block mask only
+    attr = np.ones(wl.n_branches, dtype=np.int32)
+    lay_p = B.layout_from_workload(wl, pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr, mask_mode=B.HPD_MASK_PAPER)
+    x = torch.zeros(8, device="cuda")
+    with pytest.raises(B.HpdError):
+        B.hpd_prefill_attention(lay_p, x, x, x, x)
+    with pytest.raises(B.HpdError):
+        B.hpd_prefill_attention(lay, None, x, x, x)
