@@ -214,6 +214,9 @@ def main():
     ap.add_argument("--phase", default="decode", choices=["decode", "prefill"],
                     help="decode: the benchmark's metric; prefill: hpd_prefill_attention (the attention of "
                          "the header and document tokens themselves, first inference step), a side measurement")
+    ap.add_argument("--kernel-mode", type=int, default=0,
+                    help="hpd_set_kernel_mode: 0 automatic (default), 1 generic kernel, 3 / 4 streaming "
+                         "kernel with the wide / narrow workgroup shape")
     ap.add_argument("--per-step", action="store_true",
                     help="second run: one event pair per decode step (all replicas of that step back "
                          "to back), adds per_step {us, gbs} to the record")
@@ -242,6 +245,8 @@ def main():
     layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME,
                                     **(dict(pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr_len,
                                             mask_mode=B.HPD_MASK_PAPER) if paper else {}))
+    if args.kernel_mode:
+        B.hpd_set_kernel_mode(layout, args.kernel_mode)
     n_live = layout.n_live()
     live_flat = B.hpd_layout_query(layout, B.HPD_Q_LIVE_BRANCH)
     live_lists, off = [], 0
