@@ -309,12 +309,18 @@ def main():
                     e1.record()
                     events.append((t, e0, e1))
 
-    def run(n_passes, events=None):
+    def run(n_passes, events=None, marks=None):
+        """`marks`: a list that receives one event per group of up to R passes (recorded after
+        the group, on the same stream), for the spread of the GPU time over the run."""
         done = 0
         while done < n_passes:
             n = min(R, n_passes - done)
             sweep(done, n, events)
             done += n
+            if marks is not None:
+                ev = torch.cuda.Event(enable_timing=True)
+                ev.record()
+                marks.append((n, ev))
 
     live_steps = [t for t in range(wl.max_new) if int(n_live[t]) > 0]
     run(args.warmup)
@@ -325,10 +331,16 @@ def main():
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
-    run(args.steps)
+    marks = []
+    run(args.steps, marks=marks)
     ev1.record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # GPU milliseconds per pass of every group of passes (R replicas, interleaved step by step)
+    group_ms, prev = [], ev0
+    for n, ev in marks:
+        group_ms.append(prev.elapsed_time(ev) / n)
+        prev = ev
     ms_per_step = elapsed * 1e3 / args.steps
     value = total_tokens * args.steps / elapsed
 
@@ -370,6 +382,8 @@ def main():
                    "kv_footprint_mb": round(footprint / 1e6, 1), "out_dtype": "f32" if out_f32 else wl.dtype,
                    "call": "hpd_kv_append+hpd_decode_attention" if args.two_call else "hpd_decode_step"},
         "roofline": roofline,
+        "gpu_ms_per_step": {"median": round(float(np.median(group_ms)), 4), "min": round(float(min(group_ms)), 4),
+                            "max": round(float(max(group_ms)), 4), "groups": len(group_ms)},
     }
     if args.per_step and not args.two_call:
         reps = max(1, args.steps // R)
