@@ -22,8 +22,9 @@
  *     is written.  No exception or abort crosses this boundary.
  *   - Global ids: prompts p in [0,P); documents d in CSR order (p, j); branches b in
  *     CSR order (p, j, n), which is Algorithm 1's d[jN+i] order.
- *   - Steps are 0-based decode steps t in [0, max_new); the paper's step t = 1 (the
- *     prefill) is outside this library.
+ *   - Steps are 0-based decode steps t in [0, max_new); of the paper's step t = 1 (the
+ *     prefill) the library has the attention over header and documents
+ *     (hpd_prefill_attention) and the filling of the prefix pools (hpd_prefix_fill).
  *   - Live rows: at step t the rows of q / k_new / v_new / out / pos_out / slot_out
  *     are the branches {b : branch_len[b] > t} in ascending b (the pruned input of
  *     Section 4.3.4).
@@ -31,7 +32,8 @@
  * KV pool layouts (element type = cfg.dtype; Hkv = n_kv_heads, D = head_dim,
  * T = max_new, B = number of branches):
  *   k_prefix : [Hkv][NP][D]          NP = HPD_Q_COUNTS.n_prefix_slots.  A segment
- *                                    (header of a prompt, or a document) occupies slots
+ *                                    (header of a prompt, a document, or - under
+ *                                    HPD_MASK_PAPER - the attribute names of a prompt) occupies slots
  *                                    [seg_off, seg_off + seg_len); seg_off is a multiple
  *                                    of HPD_KEY_BLOCK.  K is stored already rotated.
  *   v_prefix : [Hkv][NP/8][D][8]     same slots; 8 consecutive keys are interleaved so
@@ -151,8 +153,9 @@ enum hpd_count {
  *   doc_len    [n_docs]   L_d >= 1
  *   branch_ptr [n_docs+1] CSR documents -> branches, non-decreasing
  *   branch_len [B] or NULL  number of steps branch b is decoded, in [1, T]; NULL = all T
- *   attr_len   [B] or NULL  A_b >= 1, skeleton attribute lengths; required for
- *                           HPD_POS_PAPER_GAP, ignored otherwise
+ *   attr_len   [B] or NULL  A_b >= 1, skeleton attribute lengths (tokens of the attribute's
+ *                           name in the output template); required for HPD_POS_PAPER_GAP,
+ *                           ignored otherwise
  * On success *out owns the layout (release with hpd_layout_free).
  */
 int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* header_len,
@@ -169,9 +172,12 @@ int hpd_layout_query(const hpd_layout* layout, int32_t what, void* host_out, siz
  * hpd_prefix_fill - batched form of the append for the tokens that exist before
  * decoding starts (header and documents; the paper's prefill writes them).
  *   k_raw, v_raw : device [n_prefix_tokens][Hkv][D], un-rotated, token order = prompts in
- *                  order, each as [header | doc_0 | doc_1 | ...]
+ *                  order, each as [header | doc_0 | doc_1 | ...]; under HPD_MASK_PAPER
+ *                  followed by the prompt's attribute names a_1 .. a_N (A_b tokens each, in
+ *                  branch order).  n_prefix_tokens = HPD_Q_COUNTS[HPD_C_N_PREFIX_TOKENS].
  *   k_prefix, v_prefix : device pools (layouts above).  K is rotated at the token's
- *                  position ID (HPD_Q_SEG_POS0 + index in segment) and stored.
+ *                  position ID (HPD_Q_SEG_POS0 + index in segment; attribute names at
+ *                  Algorithm 2's positions) and stored.
  */
 int hpd_prefix_fill(const hpd_layout* layout, const void* k_raw, const void* v_raw,
                     void* k_prefix, void* v_prefix, void* stream);
@@ -202,8 +208,8 @@ int hpd_kv_append(const hpd_layout* layout, int32_t step, const void* k_new, con
  *   out = softmax( RoPE(q, pos) . K^T / sqrt(D) ) V  over the keys
  *   header(prompt of b)  ++  document(b)  ++  tail slots 0..step of b
  * (the block form of the position-ordered causal mask; under HPD_MASK_PAPER: header ++ every
- * document of the prompt ++ tail slots 0..min(step, len-1) of every branch of the prompt up
- * to b).  Call after hpd_kv_append of the same step: a query attends to its own token.
+ * document of the prompt ++ the attribute names up to b's ++ tail slots 0..min(step, len-1)
+ * of every branch of the prompt up to b).  Call after hpd_kv_append of the same step: a query attends to its own token.
  *   q   : device [n_live(step)][Hq][D], un-rotated
  *   out : device [n_live(step)][Hq][D]
  */
