@@ -75,6 +75,24 @@ def test_stream_kernel_fused_step_equals_two_calls(g, mode):
     _say(f"  worst err/rms {rel:.2e}")
 
 
+@pytest.mark.parametrize("seed", range(100, 108))
+def test_random_layout_sweep_stream_kernel(seed):
+    """Random small batches through the step call: group size, head count, number of steps
+    (up to four chunks of tail positions), ragged lengths, document and branch counts all
+    drawn from the seed; both workgroup shapes."""
+    rng = np.random.default_rng(seed)
+    g = int(rng.choice([1, 2, 4, 8]))
+    hkv = int(rng.choice([1, 2, 4]))
+    t = int(rng.integers(1, 27))
+    wl = W.random_workload(seed, dtype="bf16", hq=hkv * g, hkv=hkv, d=128, base=500000.0, t=t,
+                           p=int(rng.integers(1, 4)), j_range=(1, 3), n_range=(1, int(rng.integers(2, 40))),
+                           h_range=(0, int(rng.integers(1, 100))), l_range=(1, int(rng.integers(2, 400))))
+    for mode in (3, 4):
+        _say(f"sweep seed {seed}: G={g} Hkv={hkv} T={t} branches={wl.n_branches} mode {mode}")
+        hip = H.run_hip(wl, kernel_mode=mode, fused=True)
+        H.check_all(wl, hip, label=f"sweep_{seed}_m{mode}")
+
+
 def test_bf16_output_is_the_fp32_output_rounded_once():
     """out_dtype = SAME writes RNE(bf16) of exactly the values out_dtype = F32 writes."""
     _say("bf16 out == rne(fp32 out)")
