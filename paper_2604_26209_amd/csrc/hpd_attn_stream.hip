@@ -197,6 +197,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   __shared__ float4 rope_q[32];  // (cos, sin) row of the unit's shared position
   constexpr int MAX_KEY_BRANCHES = 256;
   __shared__ int32_t klen[PAPER ? MAX_KEY_BRANCHES : 1];  // tokens in memory of every key branch
+  constexpr int MAX_LIST_BLOCKS = 512;
+  __shared__ int32_t bvalid[PAPER ? MAX_LIST_BLOCKS : 1];  // second entry of the prompt's block list
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
@@ -517,6 +519,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   if constexpr (PAPER) {
     // tokens in memory of every key branch: min(step + 1, its length)
     for (int32_t i = tid; i < kb_end; i += CWAVES * 64) klen[i] = min(a.step + 1, a.tb.branch_len[pb0 + i]);
+    // the block list's key counts: a lookup in global memory per block would stall every wave
+    for (int32_t i = tid; i < NBd; i += CWAVES * 64) bvalid[i] = a.tb.pblk[2 * (doff + i) + 1];
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
   __builtin_amdgcn_s_barrier();        // bare barriers: __syncthreads() would wait for every store
@@ -723,7 +727,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         if (gb < NB) {
           mine = gb % KG == kg;
           int32_t valid = gb < NBh ? min(32, Hlen - gb * 32)
-                          : PAPER ? a.tb.pblk[2 * (doff + gb - NBh) + 1] : min(32, Llen - (gb - NBh) * 32);
+                          : PAPER ? bvalid[gb - NBh] : min(32, Llen - (gb - NBh) * 32);
           masked = valid < 32;
           if (PAPER && valid >= 1000) {
             // a block of attribute names: the row keeps the names up to its own branch's
@@ -934,8 +938,12 @@ hipError_t launch_g(const StreamArgs& a, int64_t items, const void* q, const voi
 
 bool hpd_stream_supported(const hpd_layout* L) {
   const int G = L->cfg.n_q_heads / L->cfg.n_kv_heads;
-  // the literal mask keeps one counter per branch of a prompt in LDS
-  if (L->cfg.mask_mode == HPD_MASK_PAPER && L->max_prompt_branches > 256) return false;
+  // the literal mask keeps one counter per branch and per 32-key block of a prompt in LDS
+  if (L->cfg.mask_mode == HPD_MASK_PAPER) {
+    if (L->max_prompt_branches > 256) return false;
+    for (int32_t p = 0; p < L->P; ++p)
+      if (L->pblk_ptr[p + 1] - L->pblk_ptr[p] > 512) return false;
+  }
   return L->cfg.dtype == HPD_BF16 && L->cfg.head_dim == D && (G == 1 || G == 2 || G == 4 || G == 8);
 }
 
