@@ -323,6 +323,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     // a slot past the last block re-loads the last block (never read): the count stays fixed
     const int32_t gb = min(gb_raw, NBT - 1);
     int32_t slot0 = 0, tc = 0, tq = 0;
+    int32_t last4[4] = {0, 0, 0, 0};
     const bool prefix = gb < NB;
     if (prefix) {
       if (PAPER) slot0 = gb < NBh ? hoff + gb * 32 : scalar_load(a.tb.pblk + 2 * (doff + gb - NBh));
@@ -334,6 +335,13 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       const int32_t tt = gb - NB;
       tc = tt / NQ;
       tq = quad_of(tt - tc * NQ);
+      if (PAPER) {
+        // last position in memory of the quad's four key branches (one lookup per tile): a
+        // finished branch stops at its own length, the rows behind it were never written
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          last4[i] = min(a.step, scalar_load(a.tb.branch_len + pb0 + min(tq * 4 + i, kb_end - 1)) - 1);
+      }
     }
 #pragma nounroll
     for (int32_t part = 0; part < 4; ++part) {
@@ -360,12 +368,11 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         // the branch of a load is the same in all lanes: a scalar lookup
         int32_t bA, bB, lastA = a.step, lastB = a.step;  // branch ids; last position in memory
         if (PAPER) {
-          // key branches are consecutive ids from the prompt's first; a finished branch
-          // stops at its own length (the rows behind it were never written)
+          // key branches are consecutive ids from the prompt's first
           bA = pb0 + min(tq * 4 + half * 2, kb_end - 1);
           bB = pb0 + min(tq * 4 + half * 2 + 1, kb_end - 1);
-          lastA = min(a.step, scalar_load(a.tb.branch_len + bA) - 1);
-          lastB = min(a.step, scalar_load(a.tb.branch_len + bB) - 1);
+          lastA = half ? last4[2] : last4[0];
+          lastB = half ? last4[3] : last4[1];
         } else {
           const int32_t lbA = min(tq * 4 + half * 2, nbr_here - 1), lbB = min(tq * 4 + half * 2 + 1, nbr_here - 1);
           const int32_t* ids = a.tb.live_branch + (a.live_base + row0_live + br0);
