@@ -217,6 +217,8 @@ def main():
     ap.add_argument("--kernel-mode", type=int, default=0,
                     help="hpd_set_kernel_mode: 0 automatic (default), 1 generic kernel, 3 / 4 streaming "
                          "kernel with the wide / narrow workgroup shape")
+    ap.add_argument("--dynamic", action="store_true",
+                    help="also time the passes with the live list kept on the GPU (hpd_dynamic_*)")
     ap.add_argument("--per-step", action="store_true",
                     help="second run: one event pair per decode step (all replicas of that step back "
                          "to back), adds per_step {us, gbs} to the record")
@@ -402,6 +404,38 @@ def main():
                            "us": [round(x, 2) for x in us],
                            "gbs": [round((attn_b[t] + app_b[t]) / (x * 1e-6) / 1e9, 1)
                                    for (t, _, _), x in zip(pairs, us)]}
+    if args.dynamic and not (args.two_call or paper):
+        # side measurement: the same passes with the live list kept on the GPU (flags in, no
+        # host-built lists), one pass after the other, against hpd_decode_step in that order
+        fins = [torch.from_numpy((wl.branch_len[live_lists[t]] == t + 1).astype(np.uint8)).to(dev)
+                if len(live_lists[t]) else torch.zeros(1, dtype=torch.uint8, device=dev) for t in range(wl.max_new)]
+
+        def one_pass(p, dyn):
+            kp, vp, kt, vt = pools[p % R]
+            if dyn:
+                B.hpd_dynamic_begin(layout)
+            for t in live_steps:
+                if dyn:
+                    B.hpd_dynamic_step(layout, t, q[t], kn[t], vn[t], kp, vp, kt, vt, outs[t])
+                    if t + 1 < wl.max_new:
+                        B.hpd_dynamic_prune(layout, fins[t])
+                else:
+                    B.hpd_decode_step(layout, t, q[t], kn[t], vn[t], kp, vp, kt, vt, outs[t])
+
+        res = {}
+        for dyn in (True, False, True, False):
+            for p in range(min(args.warmup, R)):
+                one_pass(p, dyn)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for p in range(args.steps):
+                one_pass(p, dyn)
+            e1.record()
+            torch.cuda.synchronize()
+            res.setdefault(dyn, []).append(e0.elapsed_time(e1) / args.steps)
+        rec["dynamic"] = {"gpu_ms_per_pass_device_lists": round(min(res[True]), 4),
+                          "gpu_ms_per_pass_host_lists": round(min(res[False]), 4),
+                          "call": "hpd_dynamic_begin + (hpd_dynamic_step, hpd_dynamic_prune) per step"}
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         dst = torch.empty_like(src)

@@ -250,6 +250,38 @@ int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, u
                     int32_t* s_out, void* stream);
 
 /*
+ * Device-side pruning - Section 4.3.4 ("Early Stopping") without a host round trip.  The
+ * calls above take the liveness of every step from branch_len, which a serving loop does not
+ * know in advance: it learns that a value has ended from the token it has just sampled.  With
+ * the calls below the live list of the next step and the work lists of the attention kernel
+ * are built on the GPU from a per-row "finished" flag; the host never reads them back (its
+ * launches cover every document; a document without live branches costs a workgroup that
+ * exits at its descriptor).  Block mask and the streaming kernel's shapes only (bf16,
+ * head_dim 128, group size 1, 2, 4 or 8), at most 65536 branches; else HPD_E_UNSUPPORTED.
+ *
+ * hpd_dynamic_begin - allocates the device-side state on first use (it lives as long as the
+ *   layout) and resets it: every branch live.  branch_len is ignored by the dynamic calls.
+ * hpd_dynamic_prune - `finished`: device uint8 [n_live] in the row order of the step just
+ *   taken; non-zero = that branch is not decoded any further.  Builds the next step's state.
+ * hpd_dynamic_step  - hpd_decode_step of step `step` for the rows of the current live list:
+ *   rows r of q / k_new / v_new / out are the live branches in ascending b, r < n_live (the
+ *   kernels touch no row beyond; buffers need n_live rows, B rows always suffice).
+ * hpd_dynamic_state - device addresses of the live list (int32 [B], first n_live valid) and of
+ *   n_live (int32 [1]) so that the caller's own kernels can gather and scatter by them.
+ * hpd_dynamic_read  - copies n_live and the first min(n_live, capacity) entries of the live
+ *   list to host memory; synchronises the stream: for tests and debugging.
+ * The first four only enqueue on `stream` (hpd_dynamic_begin allocates on its first call).
+ */
+int hpd_dynamic_begin(hpd_layout* layout, void* stream);
+int hpd_dynamic_prune(hpd_layout* layout, const uint8_t* finished, void* stream);
+int hpd_dynamic_step(const hpd_layout* layout, int32_t step, const void* q, const void* k_new,
+                     const void* v_new, const void* k_prefix, const void* v_prefix, void* k_tail,
+                     void* v_tail, void* out, void* stream);
+int hpd_dynamic_state(const hpd_layout* layout, const int32_t** live_branch, const int32_t** n_live);
+int hpd_dynamic_read(const hpd_layout* layout, int32_t* live_host, int32_t capacity, int32_t* n_live_host,
+                     void* stream);
+
+/*
  * hpd_finetune_mask - Section 5 ("Fine-tuning and Distillation"), Appendix A.1.  Position IDs
  * and attention mask of one training sequence in the regular token order
  *   s_train = cat(p, a_1, v_1, ..., a_N, v_N):

@@ -53,7 +53,8 @@ HPD_KEY_BLOCK = 32
 EXPORTS = ["hpd_build_layout", "hpd_layout_free", "hpd_layout_query", "hpd_prefix_fill",
            "hpd_rope_positions", "hpd_kv_append", "hpd_decode_attention", "hpd_decode_step",
            "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_status_string", "hpd_finetune_mask",
-           "hpd_prefill_attention"]
+           "hpd_prefill_attention", "hpd_dynamic_begin", "hpd_dynamic_prune", "hpd_dynamic_step",
+           "hpd_dynamic_state", "hpd_dynamic_read"]
 
 
 class hpd_config(ctypes.Structure):
@@ -79,6 +80,11 @@ _lib.hpd_decode_step.argtypes = [_vp, _i32] + [_vp] * 9
 _lib.hpd_expand_mask.argtypes = [_vp, _i32, _i32, _vp, _i32p, _vp]
 _lib.hpd_set_kernel_mode.argtypes = [_vp, _i32]
 _lib.hpd_prefill_attention.argtypes = [_vp] * 6
+_lib.hpd_dynamic_begin.argtypes = [_vp, _vp]
+_lib.hpd_dynamic_prune.argtypes = [_vp, _vp, _vp]
+_lib.hpd_dynamic_step.argtypes = [_vp, _i32] + [_vp] * 9
+_lib.hpd_dynamic_state.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
+_lib.hpd_dynamic_read.argtypes = [_vp, _i32p, _i32, _i32p, _vp]
 _lib.hpd_finetune_mask.argtypes = [_i32, _i32, _i32p, _i32p, _i32, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _vp]
 _lib.hpd_status_string.argtypes = [ctypes.c_int]
 _lib.hpd_status_string.restype = ctypes.c_char_p
@@ -231,6 +237,36 @@ def hpd_decode_step(layout, step, q, k_new, v_new, k_prefix, v_prefix, k_tail, v
 def hpd_prefill_attention(layout, q, k_prefix, v_prefix, out, stream=None):
     _check(_lib.hpd_prefill_attention(layout.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(out),
                                       _stream(stream)), "hpd_prefill_attention")
+
+
+def hpd_dynamic_begin(layout, stream=None):
+    _check(_lib.hpd_dynamic_begin(layout.handle, _stream(stream)), "hpd_dynamic_begin")
+
+
+def hpd_dynamic_prune(layout, finished, stream=None):
+    _check(_lib.hpd_dynamic_prune(layout.handle, _ptr(finished), _stream(stream)), "hpd_dynamic_prune")
+
+
+def hpd_dynamic_step(layout, step, q, k_new, v_new, k_prefix, v_prefix, k_tail, v_tail, out, stream=None):
+    _check(_lib.hpd_dynamic_step(layout.handle, int(step), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                 _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tail), _ptr(v_tail),
+                                 _ptr(out), _stream(stream)), "hpd_dynamic_step")
+
+
+def hpd_dynamic_state(layout):
+    """Device addresses (ints) of the live list (int32 [B]) and of n_live (int32 [1])."""
+    live, n = _vp(), _vp()
+    _check(_lib.hpd_dynamic_state(layout.handle, ctypes.byref(live), ctypes.byref(n)), "hpd_dynamic_state")
+    return int(live.value), int(n.value)
+
+
+def hpd_dynamic_read(layout, capacity, stream=None):
+    """(n_live, live list as a NumPy array) of the device-side state; synchronises."""
+    live = np.zeros(max(int(capacity), 1), dtype=np.int32)
+    n = ctypes.c_int32(0)
+    _check(_lib.hpd_dynamic_read(layout.handle, live.ctypes.data_as(_i32p), int(capacity), ctypes.byref(n),
+                                 _stream(stream)), "hpd_dynamic_read")
+    return int(n.value), live[:min(int(n.value), int(capacity))]
 
 
 def hpd_expand_mask(layout, prompt, step_hi, mask_out=None, stream=None) -> int:

@@ -957,7 +957,7 @@ bool hpd_stream_supported(const hpd_layout* L) {
 hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const void* q,
                                        const void* k_prefix, const void* v_prefix, void* k_tail,
                                        void* v_tail, const void* k_new, const void* v_new, void* out,
-                                       hipStream_t s) {
+                                       hipStream_t s, bool dynamic) {
   StreamArgs a;
   a.tb = L->dev;
   a.step = step; a.Hq = L->cfg.n_q_heads; a.Hkv = L->cfg.n_kv_heads;
@@ -970,8 +970,17 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
   a.tb.unit_desc = L->dev.unit_desc + (int64_t)L->unit_ptr[step] * 8;
   if (paper) a.tb.punit_desc = L->dev.punit_desc + (int64_t)L->punit_ptr[step] * 16;
-  const int64_t n_units = paper ? L->punit_ptr[step + 1] - L->punit_ptr[step] : L->unit_ptr[step + 1] - L->unit_ptr[step];
-  const int32_t max_nblk = std::max(1, ((paper ? L->pmax_rows[step] : L->max_rows[step]) * G + 31) / 32);
+  int64_t n_units = paper ? L->punit_ptr[step + 1] - L->punit_ptr[step] : L->unit_ptr[step + 1] - L->unit_ptr[step];
+  int32_t max_nblk = std::max(1, ((paper ? L->pmax_rows[step] : L->max_rows[step]) * G + 31) / 32);
+  if (dynamic) {
+    // liveness lives on the device: a unit per document (one without live branches exits at
+    // its descriptor), row groups for the most branches any document can have
+    a.tb.unit_desc = L->dyn_desc;
+    a.tb.live_branch = L->dyn_live;
+    a.live_base = 0;
+    n_units = L->n_docs;
+    max_nblk = std::max(1, (L->max_doc_branches * G + 31) / 32);
+  }
   // row groups per unit, and with them the number of workgroups, for the two shapes
   const int32_t rg_wide = (max_nblk + WideShape::MAX_BLOCKS - 1) / WideShape::MAX_BLOCKS;
   const int32_t rg_narrow = (max_nblk + NarrowShape::MAX_BLOCKS - 1) / NarrowShape::MAX_BLOCKS;

@@ -122,6 +122,9 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     if (branch_len) std::copy(branch_len, branch_len + B, L->branch_len.begin());
     if (paper) { L->skel_cum.assign(B, 0); L->skel_seg_off.assign(P, 0); }
     L->prompt_doc_ptr.assign(doc_ptr, doc_ptr + P + 1);
+    L->doc_branch_ptr.assign(branch_ptr, branch_ptr + n_docs + 1);
+    for (int32_t d = 0; d < n_docs; ++d)
+      L->max_doc_branches = std::max(L->max_doc_branches, branch_ptr[d + 1] - branch_ptr[d]);
     L->prompt_branch_ptr.resize(P + 1);
     for (int32_t p = 0; p <= P; ++p) L->prompt_branch_ptr[p] = branch_ptr[doc_ptr[p]];
 
@@ -390,6 +393,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
 
 void hpd_layout_free(hpd_layout* L) {
   if (!L) return;
+  if (L->d_dyn) (void)hipFree(L->d_dyn);
   if (L->d_ints) (void)hipFree(L->d_ints);
   if (L->d_rope) (void)hipFree(L->d_rope);
   delete L;
@@ -597,6 +601,98 @@ int hpd_expand_mask(const hpd_layout* L, int32_t prompt, int32_t step_hi, uint8_
   if (e == hipSuccess) e = hipStreamSynchronize(s);
   (void)hipFree(d_desc);
   if (e != hipSuccess) return hip_fail(e);
+  return HPD_OK;
+}
+
+static int dynamic_supported(const hpd_layout* L) {
+  if (!L || !L->on_device) return HPD_E_INVALID;
+  if (L->cfg.mask_mode != HPD_MASK_BLOCK || !hpd_stream_supported(L) || L->kernel_mode == 1 || L->B > 65536)
+    return HPD_E_UNSUPPORTED;
+  return HPD_OK;
+}
+
+int hpd_dynamic_begin(hpd_layout* L, void* stream) {
+  int rc = dynamic_supported(L);
+  if (rc != HPD_OK) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  if (!L->d_dyn) {
+    // alive [B], live [B], rank [B+1], n_live [4], desc [n_docs*8], order [n_docs], doc_branch_ptr [n_docs+1]
+    const size_t nB = (size_t)L->B, nD = (size_t)L->n_docs;
+    const size_t words = nB + nB + (nB + 1) + 4 + nD * 8 + nD + (nD + 1) + 16;
+    HPD_HIP(hipMalloc(&L->d_dyn, words * sizeof(int32_t)));
+    int32_t* w = (int32_t*)L->d_dyn;
+    L->dyn_alive = w; w += nB;
+    L->dyn_live = w; w += nB;
+    L->dyn_rank = w; w += nB + 1;
+    L->dyn_n_live = w; w += 4;
+    L->dyn_desc = w; w += nD * 8;
+    L->dyn_order_dev = w; w += nD;
+    L->dyn_bptr_dev = w;
+    // documents in a fixed order, the most keys first
+    L->dyn_order.resize(nD);
+    std::iota(L->dyn_order.begin(), L->dyn_order.end(), 0);
+    std::stable_sort(L->dyn_order.begin(), L->dyn_order.end(), [&](int32_t x, int32_t y) {
+      return (int64_t)L->seg_len[L->doc_prompt[x]] + L->seg_len[L->P + x] >
+             (int64_t)L->seg_len[L->doc_prompt[y]] + L->seg_len[L->P + y];
+    });
+    hipError_t e = hipMemcpyAsync(L->dyn_order_dev, L->dyn_order.data(), nD * sizeof(int32_t),
+                                  hipMemcpyHostToDevice, s);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(L->dyn_bptr_dev, L->doc_branch_ptr.data(), (nD + 1) * sizeof(int32_t),
+                         hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);  // the host vectors may change later
+    if (e != hipSuccess) {
+      (void)hipFree(L->d_dyn);
+      L->d_dyn = nullptr;
+      return hip_fail(e);
+    }
+  }
+  L->dyn_next_step = 0;
+  HPD_HIP(hpd_launch_dynamic_prune(L, 0, nullptr, s));
+  return HPD_OK;
+}
+
+int hpd_dynamic_prune(hpd_layout* L, const uint8_t* finished, void* stream) {
+  int rc = dynamic_supported(L);
+  if (rc != HPD_OK) return rc;
+  if (!L->d_dyn || !finished) return HPD_E_INVALID;
+  if (L->dyn_next_step + 1 >= L->T) return HPD_E_INVALID;  // no step left to prune for
+  L->dyn_next_step += 1;
+  HPD_HIP(hpd_launch_dynamic_prune(L, L->dyn_next_step, finished, (hipStream_t)stream));
+  return HPD_OK;
+}
+
+int hpd_dynamic_step(const hpd_layout* L, int32_t step, const void* q, const void* k_new,
+                     const void* v_new, const void* k_prefix, const void* v_prefix, void* k_tail,
+                     void* v_tail, void* out, void* stream) {
+  int rc = dynamic_supported(L);
+  if (rc != HPD_OK) return rc;
+  if (!L->d_dyn || step != L->dyn_next_step) return HPD_E_INVALID;  // the state describes another step
+  if (!q || !k_new || !v_new || !k_prefix || !v_prefix || !k_tail || !v_tail || !out) return HPD_E_INVALID;
+  if (L->n_docs == 0) return HPD_OK;
+  HPD_HIP(hpd_launch_attention_stream(L, step, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out,
+                                      (hipStream_t)stream, true));
+  return HPD_OK;
+}
+
+int hpd_dynamic_state(const hpd_layout* L, const int32_t** live_branch, const int32_t** n_live) {
+  if (!L || !L->d_dyn) return HPD_E_INVALID;
+  if (live_branch) *live_branch = L->dyn_live;
+  if (n_live) *n_live = L->dyn_n_live;
+  return HPD_OK;
+}
+
+int hpd_dynamic_read(const hpd_layout* L, int32_t* live_host, int32_t capacity, int32_t* n_live_host,
+                     void* stream) {
+  if (!L || !L->d_dyn || !n_live_host || capacity < 0 || (capacity > 0 && !live_host)) return HPD_E_INVALID;
+  hipStream_t s = (hipStream_t)stream;
+  HPD_HIP(hipMemcpyAsync(n_live_host, L->dyn_n_live, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  HPD_HIP(hipStreamSynchronize(s));
+  const int32_t n = std::min(*n_live_host, capacity);
+  if (n > 0) {
+    HPD_HIP(hipMemcpyAsync(live_host, L->dyn_live, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    HPD_HIP(hipStreamSynchronize(s));
+  }
   return HPD_OK;
 }
 

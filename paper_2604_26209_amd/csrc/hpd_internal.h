@@ -62,6 +62,14 @@ struct hpd_layout {
   std::vector<int32_t> max_rows;  // [T] largest number of live branches of any document at step t
   std::vector<float> rope;        // host copy of the (cos, sin) table
 
+  // device-side pruning: state built by dynamic_prune_kernel (one allocation, d_dyn)
+  std::vector<int32_t> doc_branch_ptr, dyn_order;  // [n_docs+1]; documents heaviest first
+  int32_t max_doc_branches = 0;
+  void* d_dyn = nullptr;
+  int32_t *dyn_alive = nullptr, *dyn_live = nullptr, *dyn_rank = nullptr, *dyn_n_live = nullptr,
+          *dyn_desc = nullptr, *dyn_order_dev = nullptr, *dyn_bptr_dev = nullptr;
+  int32_t dyn_next_step = 0;  // the step the device state describes (host-side counter)
+
   bool on_device = false;
   int device = -1;
   int n_cus = 256;  // compute units of that device
@@ -101,7 +109,11 @@ hipError_t hpd_launch_prefill_stream(const hpd_layout* L, const void* q, const v
 hipError_t hpd_launch_prefill_generic(const hpd_layout* L, const void* q, const void* k_prefix,
                                       const void* v_prefix, void* out, hipStream_t s);
 // k_new / v_new may be null: then the newest token is read from the tail pool like the others
+// dynamic: work lists and live list from the device-side pruning state instead of the tables
+// built from branch_len
 hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const void* q,
                                        const void* k_prefix, const void* v_prefix, void* k_tail,
                                        void* v_tail, const void* k_new, const void* v_new, void* out,
-                                       hipStream_t s);
+                                       hipStream_t s, bool dynamic = false);
+hipError_t hpd_launch_dynamic_prune(const hpd_layout* L, int32_t next_step, const uint8_t* finished,
+                                    hipStream_t s);

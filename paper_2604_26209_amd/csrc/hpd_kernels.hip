@@ -138,6 +138,68 @@ __global__ void expand_mask_kernel(const int32_t* __restrict__ desc, int32_t S, 
 }
 
 // ---------------------------------------------------------------------------------------
+// Device-side pruning (Section 4.3.4): one workgroup turns the "finished" flags of the step
+// just taken into the next step's live list (ascending branch id) and one work-unit
+// descriptor per document, in the fixed order `order` (documents without live branches get
+// a descriptor with 0 branches).  alive / live / rank / n_live / desc are the layout's state.
+// ---------------------------------------------------------------------------------------
+constexpr int PRUNE_THREADS = 1024;
+__global__ void __launch_bounds__(PRUNE_THREADS)
+dynamic_prune_kernel(hpd_dev_tables tb, int32_t P, int32_t n_docs, int32_t B, int32_t next_step,
+                     int32_t contig, const uint8_t* __restrict__ finished, const int32_t* __restrict__ order,
+                     const int32_t* __restrict__ doc_branch_ptr, int32_t* __restrict__ alive,
+                     int32_t* __restrict__ live, int32_t* __restrict__ rank, int32_t* __restrict__ n_live,
+                     int32_t* __restrict__ desc) {
+  __shared__ int32_t part[PRUNE_THREADS];
+  const int32_t tid = threadIdx.x;
+  // 1. the branches that ended with the step just taken (no flags: a fresh start, all live)
+  if (finished) {
+    const int32_t n_prev = n_live[0];
+    for (int32_t r = tid; r < n_prev; r += PRUNE_THREADS)
+      if (finished[r]) alive[live[r]] = 0;
+  } else {
+    for (int32_t b = tid; b < B; b += PRUNE_THREADS) alive[b] = 1;
+  }
+  __syncthreads();
+  // 2. exclusive prefix sums of `alive` over the branches: thread t owns a run of branches
+  const int32_t chunk = (B + PRUNE_THREADS - 1) / PRUNE_THREADS;
+  const int32_t b0 = min(tid * chunk, B), b1 = min(b0 + chunk, B);
+  int32_t cnt = 0;
+  for (int32_t b = b0; b < b1; ++b) cnt += alive[b];
+  part[tid] = cnt;
+  __syncthreads();
+  for (int32_t off = 1; off < PRUNE_THREADS; off <<= 1) {  // inclusive scan of the run sums
+    const int32_t v = tid >= off ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += v;
+    __syncthreads();
+  }
+  int32_t run = part[tid] - cnt;  // branches alive before this thread's run
+  for (int32_t b = b0; b < b1; ++b) {
+    rank[b] = run;
+    if (alive[b]) live[run++] = b;
+  }
+  if (tid == PRUNE_THREADS - 1) {
+    rank[B] = part[tid];
+    n_live[0] = part[tid];
+  }
+  __syncthreads();  // rank and live are read below by other threads of this workgroup
+  // 3. one descriptor per document: {hoff, Hlen, doff, Llen, first live row, live branches,
+  //    shared position | -1, first branch id if the live ones are consecutive | -1}
+  for (int32_t u = tid; u < n_docs; u += PRUNE_THREADS) {
+    const int32_t d = order[u], p = tb.doc_prompt[d];
+    const int32_t first = rank[doc_branch_ptr[d]], nb = rank[doc_branch_ptr[d + 1]] - first;
+    int32_t b_first = -1;
+    if (nb > 0 && live[first + nb - 1] - live[first] == nb - 1) b_first = live[first];
+    int32_t* o = desc + (int64_t)u * 8;
+    o[0] = tb.seg_off[p]; o[1] = tb.seg_len[p]; o[2] = tb.seg_off[P + d]; o[3] = tb.seg_len[P + d];
+    o[4] = first; o[5] = nb;
+    o[6] = contig ? tb.seg_len[p] + tb.seg_len[P + d] + next_step : -1;
+    o[7] = b_first;
+  }
+}
+
+// ---------------------------------------------------------------------------------------
 // Fine-tuning mask (Section 5).  desc[S][4] = (kind, attribute, k, position ID) in the regular
 // token order; kind 0 prompt, 1 attribute, 2 value token.
 // ---------------------------------------------------------------------------------------
@@ -453,5 +515,13 @@ hipError_t hpd_launch_finetune_mask(const int32_t* d_desc, int32_t S, int32_t* p
                                     hipStream_t s) {
   if (pos_out) finetune_pos_kernel<<<grid1d(S, 256), 256, 0, s>>>(d_desc, S, pos_out);
   if (mask_out) finetune_mask_kernel<<<grid1d((int64_t)S * S, 256), 256, 0, s>>>(d_desc, S, mask_out);
+  return hipGetLastError();
+}
+
+hipError_t hpd_launch_dynamic_prune(const hpd_layout* L, int32_t next_step, const uint8_t* finished,
+                                    hipStream_t s) {
+  dynamic_prune_kernel<<<1, PRUNE_THREADS, 0, s>>>(
+      L->dev, L->P, L->n_docs, L->B, next_step, L->cfg.pos_mode == HPD_POS_CONTIG ? 1 : 0, finished,
+      L->dyn_order_dev, L->dyn_bptr_dev, L->dyn_alive, L->dyn_live, L->dyn_rank, L->dyn_n_live, L->dyn_desc);
   return hipGetLastError();
 }

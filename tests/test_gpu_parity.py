@@ -93,6 +93,84 @@ def test_random_layout_sweep_stream_kernel(seed):
         H.check_all(wl, hip, label=f"sweep_{seed}_m{mode}")
 
 
+@pytest.mark.parametrize("seed,kw", [(120, dict(hq=8, hkv=2, p=3, j_range=(1, 4), n_range=(1, 14), l_range=(1, 200))),
+                                     (121, dict(hq=8, hkv=8, p=2, j_range=(2, 3), n_range=(3, 40), l_range=(1, 90))),
+                                     (122, dict(hq=16, hkv=2, p=2, j_range=(1, 2), n_range=(1, 30), l_range=(30, 300)))])
+def test_device_side_pruning_equals_host_lists(seed, kw):
+    """hpd_dynamic_*: the live list is built on the GPU from per-row "finished" flags (here: a
+    branch is flagged in the step that exhausts its length).  The device-side live list and
+    count must equal the layout's host-built lists of every step, and hpd_dynamic_step must
+    write the very bits hpd_decode_step writes."""
+    from paper_2604_26209_amd import binding as B
+    wl = W.random_workload(seed, dtype="bf16", d=128, base=500000.0, t=10, h_range=(0, 70), **kw)
+    ref = H.run_hip(wl, fused=True)
+    lay = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32)
+    inputs = ref["inputs"]
+    kp, vp, kt, vt = B.alloc_pools(lay)
+    for x in (kp, vp, kt, vt):
+        x.fill_(float("nan"))
+    B.hpd_prefix_fill(lay, inputs.k_raw, inputs.v_raw, kp, vp)
+    B.hpd_dynamic_begin(lay)
+    live_ptr, n_ptr = B.hpd_dynamic_state(lay)
+    assert live_ptr != 0 and n_ptr != 0
+    n_live = lay.n_live()
+    live_flat = B.hpd_layout_query(lay, B.HPD_Q_LIVE_BRANCH)
+    off = 0
+    for t in range(wl.max_new):
+        n = int(n_live[t])
+        want_live = live_flat[off:off + n]
+        off += n
+        got_n, got_live = B.hpd_dynamic_read(lay, wl.n_branches)
+        assert got_n == n, f"step {t}: n_live {got_n} != {n}"
+        assert np.array_equal(got_live, want_live), f"step {t}: live list differs"
+        out = torch.full((max(n, 1), wl.n_q_heads, wl.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+        if n:
+            B.hpd_dynamic_step(lay, t, inputs.q[t], inputs.k_new[t], inputs.v_new[t], kp, vp, kt, vt, out)
+            assert torch.equal(out[:n], ref["out"][t]), f"step {t}: outputs differ from hpd_decode_step"
+        if t + 1 < wl.max_new:
+            fin = torch.from_numpy((wl.branch_len[want_live] == t + 1).astype(np.uint8)).cuda() if n else \
+                torch.zeros(1, dtype=torch.uint8, device="cuda")
+            B.hpd_dynamic_prune(lay, fin)
+    with pytest.raises(B.HpdError):
+        B.hpd_dynamic_step(lay, 0, inputs.q[0], inputs.k_new[0], inputs.v_new[0], kp, vp, kt, vt, out)  # wrong step
+
+
+@pytest.mark.parametrize("seed", [130, 131])
+def test_device_side_pruning_with_lengths_unknown_to_the_layout(seed):
+    """The use the entry points exist for: the layout is built with every branch at the full
+    step budget (nobody knows yet where a branch ends), and branches leave when the caller
+    flags them (the stop condition of Section 4.3.4).  With flags taken from a hidden
+    length per branch, every step must match the oracle run on the workload that has those
+    lengths."""
+    import dataclasses
+    from paper_2604_26209_amd import binding as B
+    wl = W.random_workload(seed, dtype="bf16", d=128, base=500000.0, t=9, hq=8, hkv=2, p=3,
+                           j_range=(1, 3), n_range=(1, 20), l_range=(1, 260), h_range=(0, 50))
+    cap = dataclasses.replace(wl, branch_len=np.full(wl.n_branches, wl.max_new, dtype=np.int32))
+    ref = H.run_hip(wl, fused=True)  # for the inputs, positions and slots of the hidden lengths
+    inputs = ref["inputs"]
+    lay = B.layout_from_workload(cap, out_dtype=B.HPD_OUT_F32)
+    kp, vp, kt, vt = B.alloc_pools(lay)
+    B.hpd_prefix_fill(lay, inputs.k_raw, inputs.v_raw, kp, vp)
+    B.hpd_dynamic_begin(lay)
+    outs = []
+    for t in range(wl.max_new):
+        live = np.nonzero(wl.branch_len > t)[0]
+        got_n, got_live = B.hpd_dynamic_read(lay, wl.n_branches)
+        assert got_n == len(live) and np.array_equal(got_live, live), f"step {t}: live list differs"
+        out = torch.full((max(len(live), 1), wl.n_q_heads, wl.head_dim), float("nan"), dtype=torch.float32,
+                         device="cuda")
+        if len(live):
+            B.hpd_dynamic_step(lay, t, inputs.q[t], inputs.k_new[t], inputs.v_new[t], kp, vp, kt, vt, out)
+        outs.append(out[:len(live)])
+        if t + 1 < wl.max_new:
+            fin = (wl.branch_len[live] == t + 1).astype(np.uint8) if len(live) else np.zeros(1, np.uint8)
+            B.hpd_dynamic_prune(lay, torch.from_numpy(fin).cuda())
+    hip = dict(ref)
+    hip["out"] = outs
+    H.check_all(wl, hip, label=f"dynamic_{seed}")
+
+
 def test_bf16_output_is_the_fp32_output_rounded_once():
     """out_dtype = SAME writes RNE(bf16) of exactly the values out_dtype = F32 writes."""
     _say("bf16 out == rne(fp32 out)")
