@@ -144,6 +144,14 @@ def test_invalid_inputs_return_error_codes():
     lay = build()
     with pytest.raises(B.HpdError):
         B.hpd_rope_positions(lay, 0, 0)
+    # so do the device-side pruning calls; the state does not exist before hpd_dynamic_begin
+    with pytest.raises(B.HpdError) as e:
+        B.hpd_dynamic_begin(lay)
+    assert e.value.status == B.HPD_E_INVALID
+    with pytest.raises(B.HpdError):
+        B.hpd_dynamic_state(lay)
+    with pytest.raises(B.HpdError):
+        B.hpd_dynamic_read(lay, 4)
     assert B.hpd_status_string(B.HPD_E_INVALID) == "invalid argument"
 
 
