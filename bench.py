@@ -217,6 +217,9 @@ def main():
     ap.add_argument("--kernel-mode", type=int, default=0,
                     help="hpd_set_kernel_mode: 0 automatic (default), 1 generic kernel, 3 / 4 streaming "
                          "kernel with the wide / narrow workgroup shape")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="side measurement: tail pools paged (hpd_set_tail_pages) with this page size, "
+                         "pages in a seeded random order")
     ap.add_argument("--dynamic", action="store_true",
                     help="also time the passes with the live list kept on the GPU (hpd_dynamic_*)")
     ap.add_argument("--per-step", action="store_true",
@@ -249,6 +252,11 @@ def main():
                                             mask_mode=B.HPD_MASK_PAPER) if paper else {}))
     if args.kernel_mode:
         B.hpd_set_kernel_mode(layout, args.kernel_mode)
+    if args.page_size and not paper:
+        ppb = -(-wl.max_new // args.page_size)
+        page_table = torch.from_numpy(np.random.default_rng(26209200).permutation(wl.n_branches * ppb)
+                                      .astype(np.int32).reshape(wl.n_branches, ppb)).cuda()
+        B.hpd_set_tail_pages(layout, args.page_size, wl.n_branches * ppb, page_table)
     n_live = layout.n_live()
     live_flat = B.hpd_layout_query(layout, B.HPD_Q_LIVE_BRANCH)
     live_lists, off = [], 0
@@ -382,6 +390,7 @@ def main():
                    "decode_steps_per_pass": wl.max_new, "branch_tokens_per_pass": total_tokens,
                    "heads": f"{wl.n_q_heads}/{wl.n_kv_heads}x{wl.head_dim}", "kv_replicas": R,
                    "kv_footprint_mb": round(footprint / 1e6, 1), "out_dtype": "f32" if out_f32 else wl.dtype,
+                   **({"tail_page_size": args.page_size} if args.page_size and not paper else {}),
                    "call": "hpd_kv_append+hpd_decode_attention" if args.two_call else "hpd_decode_step"},
         "roofline": roofline,
         "gpu_ms_per_step": {"median": round(float(np.median(group_ms)), 4), "min": round(float(min(group_ms)), 4),

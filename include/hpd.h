@@ -44,6 +44,8 @@
  *   hpd_prefix_fill zeroes the V padding slots between a segment's end and the next
  *   multiple of HPD_KEY_BLOCK; K padding and unwritten tail slots may hold anything
  *   (including NaN patterns).  HPD_Q_POOL_BYTES reports the four sizes.
+ *   With a page table (hpd_set_tail_pages) the tail pools are [n_pages][Hkv][page_size][D]
+ *   instead and slot page(b, t / page_size) * page_size + t % page_size holds that token.
  */
 #ifndef HPD_H
 #define HPD_H
@@ -280,6 +282,27 @@ int hpd_dynamic_step(const hpd_layout* layout, int32_t step, const void* q, cons
 int hpd_dynamic_state(const hpd_layout* layout, const int32_t** live_branch, const int32_t** n_live);
 int hpd_dynamic_read(const hpd_layout* layout, int32_t* live_host, int32_t capacity, int32_t* n_live_host,
                      void* stream);
+
+/*
+ * hpd_set_tail_pages - paged tail pools (the paper's Limitations paragraph names paged
+ * attention as an untried combination).  B*T tail slots are reserved for values that mostly
+ * end early (Section 4.3.4); with a page table the pools hold n_pages pages of page_size
+ * consecutive steps of one branch, [n_pages][Hkv][page_size][D], and the pages of a pruned
+ * branch can be handed to another one.
+ *   page_size  : 8, 16, 32, ... (a power of two, at least 8); 0 switches paging off again
+ *   n_pages    : pages the caller's tail pools hold (at least 1)
+ *   page_table : device int32 [B][ceil(T / page_size)], owned and updated by the caller (on the
+ *                stream of the calls that read it).  Entry (b, i) must name b's page for steps
+ *                i*page_size .. (i+1)*page_size - 1 before the first call for such a step in
+ *                which b is live, and must not change while b is live; entries of pages a branch
+ *                has not reached, and those of branches that are no longer live, are not read.
+ *                The kernels clamp an entry to [0, n_pages) instead of trusting it.
+ * Affects hpd_kv_append (slot_out reports page * page_size + t % page_size), hpd_decode_attention,
+ * hpd_decode_step and hpd_dynamic_step of this layout from the next call on, and the tail
+ * sizes HPD_Q_POOL_BYTES reports.  Host-side only: nothing is enqueued.  HPD_MASK_PAPER
+ * layouts read the tails of finished branches as well and are refused (HPD_E_UNSUPPORTED).
+ */
+int hpd_set_tail_pages(hpd_layout* layout, int32_t page_size, int32_t n_pages, const int32_t* page_table);
 
 /*
  * hpd_finetune_mask - Section 5 ("Fine-tuning and Distillation"), Appendix A.1.  Position IDs

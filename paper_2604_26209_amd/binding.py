@@ -54,7 +54,7 @@ EXPORTS = ["hpd_build_layout", "hpd_layout_free", "hpd_layout_query", "hpd_prefi
            "hpd_rope_positions", "hpd_kv_append", "hpd_decode_attention", "hpd_decode_step",
            "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_status_string", "hpd_finetune_mask",
            "hpd_prefill_attention", "hpd_dynamic_begin", "hpd_dynamic_prune", "hpd_dynamic_step",
-           "hpd_dynamic_state", "hpd_dynamic_read"]
+           "hpd_dynamic_state", "hpd_dynamic_read", "hpd_set_tail_pages"]
 
 
 class hpd_config(ctypes.Structure):
@@ -85,6 +85,7 @@ _lib.hpd_dynamic_prune.argtypes = [_vp, _vp, _vp]
 _lib.hpd_dynamic_step.argtypes = [_vp, _i32] + [_vp] * 9
 _lib.hpd_dynamic_state.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
 _lib.hpd_dynamic_read.argtypes = [_vp, _i32p, _i32, _i32p, _vp]
+_lib.hpd_set_tail_pages.argtypes = [_vp, _i32, _i32, _vp]
 _lib.hpd_finetune_mask.argtypes = [_i32, _i32, _i32p, _i32p, _i32, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _vp]
 _lib.hpd_status_string.argtypes = [ctypes.c_int]
 _lib.hpd_status_string.restype = ctypes.c_char_p
@@ -258,6 +259,17 @@ def hpd_dynamic_state(layout):
     live, n = _vp(), _vp()
     _check(_lib.hpd_dynamic_state(layout.handle, ctypes.byref(live), ctypes.byref(n)), "hpd_dynamic_state")
     return int(live.value), int(n.value)
+
+
+def hpd_set_tail_pages(layout, page_size, n_pages=0, page_table=None) -> None:
+    """page_table: int32 device tensor [B][ceil(T / page_size)] that the caller keeps alive and
+    updates; page_size = 0 switches paging off."""
+    if page_table is not None and not isinstance(page_table, int):
+        import torch
+        if page_table.dtype != torch.int32 or not page_table.is_cuda or not page_table.is_contiguous():
+            raise TypeError("page_table: a contiguous int32 device tensor")
+    _check(_lib.hpd_set_tail_pages(layout.handle, int(page_size), int(n_pages), _ptr(page_table)),
+           "hpd_set_tail_pages")
 
 
 def hpd_dynamic_read(layout, capacity, stream=None):

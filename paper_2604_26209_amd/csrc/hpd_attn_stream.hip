@@ -175,14 +175,15 @@ __device__ __forceinline__ void rotate16(uint4 raw_lo, uint4 raw_hi, const float
 // own position ID; the keys are the header (documents only) and the segment itself up to the
 // row's token: the stream stops at the row group's last token, a wave skips the blocks behind
 // its last row, and the blocks on the diagonal get a per-row count.  No tails, no append.
-enum { MODE_BLOCK = 0, MODE_PAPER = 1, MODE_PREFILL = 2 };
+// MODE_PAGED = MODE_BLOCK with the tail rows found through the caller's page table.
+enum { MODE_BLOCK = 0, MODE_PAPER = 1, MODE_PREFILL = 2, MODE_PAGED = 3 };
 template <int G, typename SH, int MODE>
 __global__ void __launch_bounds__(SH::WAVES * 64, 2)
 attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_prefix,
                    const uint16_t* __restrict__ v_prefix, uint16_t* __restrict__ k_tail,
                    uint16_t* __restrict__ v_tail, const uint16_t* __restrict__ k_new,
                    const uint16_t* __restrict__ v_new, void* __restrict__ out) {
-  constexpr bool PAPER = MODE == MODE_PAPER, PREFILL = MODE == MODE_PREFILL;
+  constexpr bool PAPER = MODE == MODE_PAPER, PREFILL = MODE == MODE_PREFILL, PAGED = MODE == MODE_PAGED;
   constexpr int BPB = 32 / G;              // branches (PREFILL: tokens) per row block
   constexpr int QPR = G >= 8 ? 1 : 8 / G;  // branch quads (tail tiles per 8 positions) per row block
   constexpr int CWAVES = SH::CW, LOADERS = SH::LW, STAGE_BLOCKS = SH::SB, STAGE_U4 = SH::STAGE_U4;
@@ -379,11 +380,25 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
           bA = ub0 >= 0 ? ub0 + br0 + lbA : scalar_load(ids + lbA);
           bB = ub0 >= 0 ? ub0 + br0 + lbB : scalar_load(ids + lbB);
         }
-        const int32_t posA = min(tc * 8 + r4, lastA), posB = min(tc * 8 + 4 + r4, lastA);
-        const int32_t posC = min(tc * 8 + r4, lastB), posD = min(tc * 8 + 4 + r4, lastB);
+        int32_t posA = min(tc * 8 + r4, lastA), posB = min(tc * 8 + 4 + r4, lastA);
+        int32_t posC = min(tc * 8 + r4, lastB), posD = min(tc * 8 + 4 + r4, lastB);
         const uint16_t* pool = is_k ? k_tail : v_tail;
-        const uint16_t* rowA = pool + ((int64_t)bA * a.Hkv + hk) * a.Tcap * D;
-        const uint16_t* rowB = pool + ((int64_t)bB * a.Hkv + hk) * a.Tcap * D;
+        const uint16_t *rowA, *rowB;
+        if constexpr (PAGED) {
+          // a page holds a multiple of 8 steps, so the 8 positions of the tile (clamped to the
+          // current step, which lies in or behind them) share one page per branch
+          const int32_t pi = (tc * 8) >> a.tb.page_shift, pmask = (1 << a.tb.page_shift) - 1;
+          int32_t pgA = scalar_load(a.tb.tail_pages + (int64_t)bA * a.tb.pages_per_branch + pi);
+          int32_t pgB = scalar_load(a.tb.tail_pages + (int64_t)bB * a.tb.pages_per_branch + pi);
+          pgA = min(max(pgA, 0), a.tb.n_pages - 1);
+          pgB = min(max(pgB, 0), a.tb.n_pages - 1);
+          rowA = pool + ((((int64_t)pgA * a.Hkv + hk)) << a.tb.page_shift) * D;
+          rowB = pool + ((((int64_t)pgB * a.Hkv + hk)) << a.tb.page_shift) * D;
+          posA &= pmask, posB &= pmask, posC &= pmask, posD &= pmask;
+        } else {
+          rowA = pool + ((int64_t)bA * a.Hkv + hk) * a.Tcap * D;
+          rowB = pool + ((int64_t)bB * a.Hkv + hk) * a.Tcap * D;
+        }
         p0 = rowA + (int64_t)posA * D + e0;
         p1 = rowA + (int64_t)posB * D + (e0 ^ x1);
         p2 = rowB + (int64_t)posC * D + (e0 ^ x2);
@@ -431,10 +446,12 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     float rl[8], rh[8];
     if (use_rope_q) rotate16(r.klo, r.khi, reinterpret_cast<const float2*>(rope_q), ap_c, rl, rh);
     else rotate16(r.klo, r.khi, a.tb.rope + (int64_t)pos * (D / 2), ap_c, rl, rh);
-    uint16_t* kd = k_tail + (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
+    const int64_t trow = (PAGED ? hpd_tail_row(a.tb, b, hk, a.Hkv, a.Tcap, a.step)
+                                : ((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
+    uint16_t* kd = k_tail + trow;
     *reinterpret_cast<uint4*>(kd + ap_c) = __builtin_bit_cast(uint4, pack8(rl));
     *reinterpret_cast<uint4*>(kd + 64 + ap_c) = __builtin_bit_cast(uint4, pack8(rh));
-    uint16_t* vd = v_tail + (((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
+    uint16_t* vd = v_tail + trow;
     *reinterpret_cast<uint4*>(vd + ap_c) = r.vlo;
     *reinterpret_cast<uint4*>(vd + 64 + ap_c) = r.vhi;
   };
@@ -692,7 +709,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // full except the last of the header and the last of the document; the key group of a
   // block is counted along instead of divided out.
   int32_t s_first = 0;
-  if constexpr (MODE == MODE_BLOCK) {
+  if constexpr (MODE == MODE_BLOCK || MODE == MODE_PAGED) {
     int32_t ph = 0;  // (block index) % KG
     const int32_t gb_h_part = (Hlen & 31) ? NBh - 1 : -1, gb_d_part = (Llen & 31) ? NB - 1 : -1;
     for (int32_t s0 = 0; s0 < s_tail; ++s0) {
@@ -997,7 +1014,9 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
 #define HPD_LAUNCH_M(GG, PP)                                                                            \
   (narrow ? launch_g<GG, NarrowShape, PP>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s) \
           : launch_g<GG, WideShape, PP>(a, items, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out, s))
-#define HPD_LAUNCH(GG) (paper ? HPD_LAUNCH_M(GG, MODE_PAPER) : HPD_LAUNCH_M(GG, MODE_BLOCK))
+#define HPD_LAUNCH(GG)                                                   \
+  (paper ? HPD_LAUNCH_M(GG, MODE_PAPER)                                  \
+         : a.tb.tail_pages ? HPD_LAUNCH_M(GG, MODE_PAGED) : HPD_LAUNCH_M(GG, MODE_BLOCK))
   switch (G) {
     case 1: return HPD_LAUNCH(1);
     case 2: return HPD_LAUNCH(2);

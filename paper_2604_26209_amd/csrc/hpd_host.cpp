@@ -421,8 +421,9 @@ int hpd_layout_query(const hpd_layout* L, int32_t what, void* host_out, size_t b
     case HPD_Q_POOL_BYTES: {
       if (bytes < 4 * sizeof(int64_t)) return HPD_E_INVALID;
       const int64_t per_slot = (int64_t)L->cfg.n_kv_heads * L->cfg.head_dim * (int64_t)eb;
-      int64_t c[4] = {L->NP * per_slot, L->NP * per_slot, (int64_t)L->B * L->T * per_slot,
-                      (int64_t)L->B * L->T * per_slot};
+      const int64_t tail_slots = L->dev.tail_pages ? ((int64_t)L->dev.n_pages << L->dev.page_shift)
+                                                   : (int64_t)L->B * L->T;
+      int64_t c[4] = {L->NP * per_slot, L->NP * per_slot, tail_slots * per_slot, tail_slots * per_slot};
       std::memcpy(host_out, c, sizeof(c));
       return HPD_OK;
     }
@@ -693,6 +694,25 @@ int hpd_dynamic_read(const hpd_layout* L, int32_t* live_host, int32_t capacity, 
     HPD_HIP(hipMemcpyAsync(live_host, L->dyn_live, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, s));
     HPD_HIP(hipStreamSynchronize(s));
   }
+  return HPD_OK;
+}
+
+int hpd_set_tail_pages(hpd_layout* L, int32_t page_size, int32_t n_pages, const int32_t* page_table) {
+  if (!L || !L->on_device) return HPD_E_INVALID;
+  if (page_size == 0) {
+    L->dev.tail_pages = nullptr;
+    L->dev.page_shift = L->dev.pages_per_branch = L->dev.n_pages = 0;
+    return HPD_OK;
+  }
+  if (page_size < 8 || (page_size & (page_size - 1)) != 0 || n_pages < 1 || !page_table) return HPD_E_INVALID;
+  if (L->cfg.mask_mode != HPD_MASK_BLOCK) return HPD_E_UNSUPPORTED;
+  if ((int64_t)n_pages * page_size > ((int64_t)1 << 40)) return HPD_E_OVERFLOW;
+  int32_t shift = 0;
+  while ((1 << shift) < page_size) ++shift;
+  L->dev.tail_pages = page_table;
+  L->dev.page_shift = shift;
+  L->dev.pages_per_branch = (L->T + page_size - 1) / page_size;
+  L->dev.n_pages = n_pages;
   return HPD_OK;
 }
 

@@ -40,7 +40,21 @@ struct hpd_dev_tables {
   // attention of the prefix tokens (block mask): one unit per non-empty header / document
   const int32_t* funit_desc;  // [n_funits][8] {hoff, Hlen (0 for a header), first slot, tokens, first token in q / out order, tokens, position ID of the first token, 0}
   const float2* rope;           // [max_pos+1][D/2] (cos, sin)
+  // paged tails (null: token t of branch b is row b*T + t of every kv head's tail rows)
+  const int32_t* tail_pages;    // [B][pages_per_branch], the caller's device memory
+  int32_t page_shift, pages_per_branch, n_pages;
 };
+
+// Row (of D elements) of the tail pools that holds token t of branch b for kv head hk:
+// [B][Hkv][T] rows, or [n_pages][Hkv][page] rows under a page table.  A page id is clamped
+// to the pool instead of trusted.
+__device__ __forceinline__ int64_t hpd_tail_row(const hpd_dev_tables& tb, int32_t b, int32_t hk,
+                                                int32_t Hkv, int32_t Tcap, int32_t t) {
+  if (!tb.tail_pages) return ((int64_t)b * Hkv + hk) * Tcap + t;
+  int32_t pg = tb.tail_pages[(int64_t)b * tb.pages_per_branch + (t >> tb.page_shift)];
+  pg = min(max(pg, 0), tb.n_pages - 1);
+  return ((((int64_t)pg * Hkv + hk)) << tb.page_shift) + (t & ((1 << tb.page_shift) - 1));
+}
 
 struct hpd_layout {
   hpd_config cfg;

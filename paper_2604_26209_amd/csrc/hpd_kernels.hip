@@ -86,7 +86,8 @@ __global__ void positions_kernel(hpd_dev_tables tb, int32_t step, int32_t n_live
 }
 
 // ---------------------------------------------------------------------------------------
-// Append: RoPE(K) + store K, V of every live branch at tail slot b*T + step.
+// Append: RoPE(K) + store K, V of every live branch at tail slot b*T + step (or the slot its
+// page table names).
 // ---------------------------------------------------------------------------------------
 template <typename T>
 __global__ void append_kernel(hpd_dev_tables tb, int32_t step, int32_t n_live, int32_t Hkv,
@@ -102,12 +103,14 @@ __global__ void append_kernel(hpd_dev_tables tb, int32_t step, int32_t n_live, i
   const int32_t r = (int32_t)(gid / ((int64_t)half * Hkv));
   const int32_t b = tb.live_branch[tb.live_ptr[step] + r];
   const int32_t pos = tb.branch_base_pos[b] + 1 + step;
-  const int64_t slot = (int64_t)b * Tcap + step;
   const float2 cs = tb.rope[(int64_t)pos * half + i];
   const int64_t src = ((int64_t)r * Hkv + h) * D;
   const float a = hpd::to_float(k_new[src + i]);
   const float bb = hpd::to_float(k_new[src + i + half]);
-  const int64_t dst = (((int64_t)b * Hkv + h) * Tcap + step) * D;
+  const int64_t row = hpd_tail_row(tb, b, h, Hkv, Tcap, step);
+  const int64_t dst = row * D;
+  // the slot number leaves the kv heads out: the row of a pool with one kv head
+  const int64_t slot = hpd_tail_row(tb, b, 0, 1, Tcap, step);
   float r1, r2;
   hpd::rope_pair(a, bb, cs.x, cs.y, r1, r2);
   k_tail[dst + i] = hpd::from_float<T>(r1);
@@ -323,7 +326,7 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
   auto tail_row = [&](int32_t i) -> int64_t {
     const int32_t bb = b_lo + i / (step + 1), tt = i % (step + 1);
     if (tt >= tb.branch_len[bb]) return -1;
-    return (((int64_t)bb * Hkv + hk) * Tcap + tt) * D;
+    return hpd_tail_row(tb, bb, hk, Hkv, Tcap, tt) * D;
   };
 
   if (tid < half) {

@@ -171,6 +171,121 @@ def test_device_side_pruning_with_lengths_unknown_to_the_layout(seed):
     H.check_all(wl, hip, label=f"dynamic_{seed}")
 
 
+class _PageAllocator:
+    """Host-side page allocator of the paged-tail tests: pages come from a shuffled free list,
+    a branch takes one when it reaches a page boundary and gives all of them back when it
+    ends, so pages are reused and hold stale rows of other branches."""
+
+    def __init__(self, wl, page_size, seed):
+        self.wl, self.ps = wl, page_size
+        self.ppb = -(-wl.max_new // page_size)
+        need, held = 0, 0
+        for t in range(wl.max_new):  # pages in use at the same time
+            if t % page_size == 0:
+                held += int((wl.branch_len > t).sum())
+            need = max(need, held)
+            held -= int(((wl.branch_len == t + 1) * (-(-(t + 1) // page_size))).sum())
+        self.n_pages = max(need, 1)
+        self.free = list(np.random.default_rng(seed).permutation(self.n_pages))
+        self.table = np.full((wl.n_branches, self.ppb), -7, dtype=np.int32)  # -7: never assigned
+
+    def before_step(self, t):
+        if t % self.ps == 0:
+            for b in np.nonzero(self.wl.branch_len > t)[0]:
+                self.table[b, t // self.ps] = self.free.pop()
+
+    def after_step(self, t):
+        for b in np.nonzero(self.wl.branch_len == t + 1)[0]:
+            for i in range(self.ppb):
+                if self.table[b, i] >= 0:
+                    self.free.append(int(self.table[b, i]))
+                    self.table[b, i] = -7
+
+    def slots(self, live, t):
+        return self.table[live, t // self.ps].astype(np.int64) * self.ps + t % self.ps
+
+
+@pytest.mark.parametrize("case", ["stream_fused", "stream_two_call", "generic_f32", "dynamic"])
+def test_paged_tails(case):
+    """hpd_set_tail_pages: tail pools of n_pages pages (fewer than B * T slots; pages of ended
+    branches are reused) against the contiguous pools: same outputs bit for bit, slots as the
+    page table says, and within tolerance of the oracle."""
+    from paper_2604_26209_amd import binding as B
+    _say(f"paged tails: {case}")
+    f32 = case == "generic_f32"
+    if f32:
+        wl = W.random_workload(140, dtype="f32", hq=4, hkv=2, d=64, t=19, p=2, n_range=(1, 9))
+    else:
+        wl = W.random_workload(141, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=21, p=3,
+                               j_range=(1, 3), n_range=(1, 14), h_range=(0, 80), l_range=(1, 200))
+    ps = 8
+    ref = H.run_hip(wl, fused=(case != "stream_two_call"))
+    inputs = ref["inputs"]
+    lay = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_SAME if f32 else B.HPD_OUT_F32)
+    alloc = _PageAllocator(wl, ps, seed=7)
+    assert alloc.n_pages * ps < wl.n_branches * wl.max_new, "the case must save memory"
+    table = torch.from_numpy(alloc.table).cuda()
+    full = B.hpd_layout_query(lay, B.HPD_Q_POOL_BYTES)
+    B.hpd_set_tail_pages(lay, ps, alloc.n_pages, table)
+    paged = B.hpd_layout_query(lay, B.HPD_Q_POOL_BYTES)
+    assert paged[2] * wl.n_branches * wl.max_new == full[2] * alloc.n_pages * ps and paged[0] == full[0]
+    kp, vp, kt, vt = B.alloc_pools(lay)
+    for x in (kp, vp, kt, vt):
+        x.fill_(float("nan"))
+    B.hpd_prefix_fill(lay, inputs.k_raw, inputs.v_raw, kp, vp)
+    if case == "dynamic":
+        B.hpd_dynamic_begin(lay)
+    outs = []
+    for t in range(wl.max_new):
+        live = np.nonzero(wl.branch_len > t)[0]
+        n = len(live)
+        alloc.before_step(t)
+        table.copy_(torch.from_numpy(alloc.table))
+        out = torch.full((n, wl.n_q_heads, wl.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+        slot = torch.full((max(n, 1),), -1, dtype=torch.int64, device="cuda")
+        if n:
+            a = (lay, t, inputs.q[t], inputs.k_new[t], inputs.v_new[t], kp, vp, kt, vt, out)
+            if case == "dynamic":
+                B.hpd_dynamic_step(*a)
+            elif case == "stream_two_call":
+                B.hpd_kv_append(lay, t, inputs.k_new[t], inputs.v_new[t], kt, vt, slot)
+                B.hpd_decode_attention(lay, t, inputs.q[t], kp, vp, kt, vt, out)
+                assert np.array_equal(slot[:n].cpu().numpy(), alloc.slots(live, t)), f"step {t}: slots"
+            else:
+                B.hpd_decode_step(*a)
+            assert torch.equal(out, ref["out"][t]), f"step {t}: paged and contiguous outputs differ"
+        outs.append(out)
+        if case == "dynamic" and t + 1 < wl.max_new:
+            fin = (wl.branch_len[live] == t + 1).astype(np.uint8) if n else np.zeros(1, np.uint8)
+            B.hpd_dynamic_prune(lay, torch.from_numpy(fin).cuda())
+        torch.cuda.synchronize()  # the table is rewritten on the host for the next step
+        alloc.after_step(t)
+    hip = dict(ref)
+    hip["out"] = outs
+    H.check_all(wl, hip, label=f"paged_{case}")
+    # switching paging off restores the contiguous sizes; bad arguments are refused
+    B.hpd_set_tail_pages(lay, 0)
+    assert np.array_equal(B.hpd_layout_query(lay, B.HPD_Q_POOL_BYTES), full)
+    for bad in (4, 12, -8):
+        with pytest.raises(B.HpdError):
+            B.hpd_set_tail_pages(lay, bad, 4, table)
+    with pytest.raises(B.HpdError):
+        B.hpd_set_tail_pages(lay, 8, 0, table)
+    with pytest.raises(B.HpdError):
+        B.hpd_set_tail_pages(lay, 8, 4, None)
+
+
+def test_paged_tails_refused_under_the_literal_mask():
+    from paper_2604_26209_amd import binding as B
+    wl = W.random_workload(142, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=4, p=1)
+    attr_len = np.ones(wl.n_branches, dtype=np.int32)
+    lay = B.layout_from_workload(wl, pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr_len, mask_mode=B.HPD_MASK_PAPER)
+    table = torch.zeros((wl.n_branches, 1), dtype=torch.int32, device="cuda")
+    with pytest.raises(B.HpdError) as e:
+        B.hpd_set_tail_pages(lay, 8, 4, table)
+    assert e.value.status == B.HPD_E_UNSUPPORTED
+
+
 def test_bf16_output_is_the_fp32_output_rounded_once():
     """out_dtype = SAME writes RNE(bf16) of exactly the values out_dtype = F32 writes."""
     _say("bf16 out == rne(fp32 out)")
