@@ -123,3 +123,38 @@ def test_full_size_prefill_attention(k, prompts):
         rms = np.sqrt(np.mean(ref[p].astype(np.float64).reshape(b - a, -1) ** 2, axis=1))
         assert np.all(diff <= H.BF16_TOL * rms), f"cfg{k} prompt {p}: worst {float((diff / rms).max()):.3e}"
         print(f"  prompt {p}: worst max-abs / RMS(token) = {float((diff / rms).max()):.4f}", flush=True)
+
+
+@pytest.mark.parametrize("k", [2, 5])
+def test_full_size_device_lists_and_paged_tails_equal_decode_step(k):
+    """The two variants of the step call at a benchmark configuration's full size: live lists
+    kept on the GPU (flags in) and tail pools behind a page table (pages in a seeded random
+    order, as bench.py --page-size sets them up), both at once, must write the very bits
+    hpd_decode_step writes with host-built lists and contiguous tails - whole batch, every step."""
+    from paper_2604_26209_amd import binding as B
+    wl = W.config(k)
+    print(f"full-size cfg{k}: device-side lists + paged tails", flush=True)
+    ref = H.run_hip(wl, fused=True, poison_pools=True, out_f32=False)
+    inputs = ref["inputs"]
+    lay = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_SAME)
+    ps = 8
+    ppb = -(-wl.max_new // ps)
+    table = torch.from_numpy(np.random.default_rng(k).permutation(wl.n_branches * ppb).astype(np.int32)
+                             .reshape(wl.n_branches, ppb)).cuda()
+    B.hpd_set_tail_pages(lay, ps, wl.n_branches * ppb, table)
+    kp, vp, kt, vt = B.alloc_pools(lay)
+    for x in (kp, vp, kt, vt):
+        x.fill_(float("nan"))
+    B.hpd_prefix_fill(lay, inputs.k_raw, inputs.v_raw, kp, vp)
+    B.hpd_dynamic_begin(lay)
+    for t in range(wl.max_new):
+        live = np.nonzero(wl.branch_len > t)[0]
+        if len(live) == 0:
+            break
+        got_n, got_live = B.hpd_dynamic_read(lay, wl.n_branches)
+        assert got_n == len(live) and np.array_equal(got_live, live), f"cfg{k} step {t}: live list"
+        out = torch.full_like(ref["out"][t], float("nan"))
+        B.hpd_dynamic_step(lay, t, inputs.q[t], inputs.k_new[t], inputs.v_new[t], kp, vp, kt, vt, out)
+        assert torch.equal(out, ref["out"][t]), f"cfg{k} step {t}: outputs differ"
+        if t + 1 < wl.max_new:
+            B.hpd_dynamic_prune(lay, torch.from_numpy((wl.branch_len[live] == t + 1).astype(np.uint8)).cuda())
