@@ -17,7 +17,8 @@
  *     is caller-owned (e.g. a torch tensor's data_ptr); the library allocates only the
  *     small tables inside hpd_layout.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Per-step
- *     calls only enqueue work; they never synchronise or allocate.
+ *     calls only enqueue work; they never synchronise or allocate (the two exceptions say
+ *     so where they are declared: the first hpd_dynamic_begin of a layout, hpd_dynamic_read).
  *   - Every function returns HPD_OK (0) or a negative HPD_E_* code; on error no output
  *     is written.  No exception or abort crosses this boundary.
  *   - Global ids: prompts p in [0,P); documents d in CSR order (p, j); branches b in
