@@ -617,31 +617,34 @@ int hpd_dynamic_begin(hpd_layout* L, void* stream) {
   if (rc != HPD_OK) return rc;
   hipStream_t s = (hipStream_t)stream;
   if (!L->d_dyn) {
-    // alive [B], live [B], rank [B+1], n_live [4], desc [n_docs*8], order [n_docs], doc_branch_ptr [n_docs+1]
+    // desc [n_docs*8], fixed [n_docs*8] (both read and written 16 bytes at a time), n_live [4], live [B]
     const size_t nB = (size_t)L->B, nD = (size_t)L->n_docs;
-    const size_t words = nB + nB + (nB + 1) + 4 + nD * 8 + nD + (nD + 1) + 16;
+    const size_t words = nD * 8 + nD * 8 + 4 + nB + 16;
     HPD_HIP(hipMalloc(&L->d_dyn, words * sizeof(int32_t)));
     int32_t* w = (int32_t*)L->d_dyn;
-    L->dyn_alive = w; w += nB;
-    L->dyn_live = w; w += nB;
-    L->dyn_rank = w; w += nB + 1;
-    L->dyn_n_live = w; w += 4;
     L->dyn_desc = w; w += nD * 8;
-    L->dyn_order_dev = w; w += nD;
-    L->dyn_bptr_dev = w;
-    // documents in a fixed order, the most keys first
-    L->dyn_order.resize(nD);
-    std::iota(L->dyn_order.begin(), L->dyn_order.end(), 0);
-    std::stable_sort(L->dyn_order.begin(), L->dyn_order.end(), [&](int32_t x, int32_t y) {
+    L->dyn_fixed_dev = w; w += nD * 8;
+    L->dyn_n_live = w; w += 4;
+    L->dyn_live = w;
+    // what never changes, one record per document, the documents with the most keys first:
+    // {hoff, Hlen, doff, Llen, first branch, end of branches, position of step 0 | -1, 0}
+    std::vector<int32_t> order(nD);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
       return (int64_t)L->seg_len[L->doc_prompt[x]] + L->seg_len[L->P + x] >
              (int64_t)L->seg_len[L->doc_prompt[y]] + L->seg_len[L->P + y];
     });
-    hipError_t e = hipMemcpyAsync(L->dyn_order_dev, L->dyn_order.data(), nD * sizeof(int32_t),
+    L->dyn_fixed.assign(nD * 8, 0);
+    for (size_t u = 0; u < nD; ++u) {
+      const int32_t d = order[u], p = L->doc_prompt[d];
+      int32_t* o = L->dyn_fixed.data() + u * 8;
+      o[0] = L->seg_off[p]; o[1] = L->seg_len[p]; o[2] = L->seg_off[L->P + d]; o[3] = L->seg_len[L->P + d];
+      o[4] = L->doc_branch_ptr[d]; o[5] = L->doc_branch_ptr[d + 1];
+      o[6] = L->cfg.pos_mode == HPD_POS_CONTIG ? L->seg_len[p] + L->seg_len[L->P + d] : -1;
+    }
+    hipError_t e = hipMemcpyAsync(L->dyn_fixed_dev, L->dyn_fixed.data(), nD * 8 * sizeof(int32_t),
                                   hipMemcpyHostToDevice, s);
-    if (e == hipSuccess)
-      e = hipMemcpyAsync(L->dyn_bptr_dev, L->doc_branch_ptr.data(), (nD + 1) * sizeof(int32_t),
-                         hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipStreamSynchronize(s);  // the host vectors may change later
+    if (e == hipSuccess) e = hipStreamSynchronize(s);  // the copy has left the host vector
     if (e != hipSuccess) {
       (void)hipFree(L->d_dyn);
       L->d_dyn = nullptr;

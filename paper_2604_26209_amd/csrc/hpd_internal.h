@@ -77,11 +77,11 @@ struct hpd_layout {
   std::vector<float> rope;        // host copy of the (cos, sin) table
 
   // device-side pruning: state built by dynamic_prune_kernel (one allocation, d_dyn)
-  std::vector<int32_t> doc_branch_ptr, dyn_order;  // [n_docs+1]; documents heaviest first
+  std::vector<int32_t> doc_branch_ptr;  // [n_docs+1]
+  std::vector<int32_t> dyn_fixed;       // [n_docs][8] per-document constants of the descriptors, heaviest first
   int32_t max_doc_branches = 0;
   void* d_dyn = nullptr;
-  int32_t *dyn_alive = nullptr, *dyn_live = nullptr, *dyn_rank = nullptr, *dyn_n_live = nullptr,
-          *dyn_desc = nullptr, *dyn_order_dev = nullptr, *dyn_bptr_dev = nullptr;
+  int32_t *dyn_live = nullptr, *dyn_n_live = nullptr, *dyn_desc = nullptr, *dyn_fixed_dev = nullptr;
   int32_t dyn_next_step = 0;  // the step the device state describes (host-side counter)
 
   bool on_device = false;

@@ -141,64 +141,99 @@ __global__ void expand_mask_kernel(const int32_t* __restrict__ desc, int32_t S, 
 }
 
 // ---------------------------------------------------------------------------------------
-// Device-side pruning (Section 4.3.4): one workgroup turns the "finished" flags of the step
-// just taken into the next step's live list (ascending branch id) and one work-unit
-// descriptor per document, in the fixed order `order` (documents without live branches get
-// a descriptor with 0 branches).  alive / live / rank / n_live / desc are the layout's state.
+// Device-side pruning (Section 4.3.4): one workgroup turns the live list of the step just
+// taken and its "finished" flags into the next step's live list (ascending branch id) and one
+// work-unit descriptor per document, in the order of `fixed` (documents without live branches
+// get a descriptor with 0 branches).  live / n_live / desc are the layout's state; `fixed` holds
+// {hoff, Hlen, doff, Llen, first branch, end of branches, position of step 0 | -1, 0} per
+// document.  The liveness of every branch is kept in LDS, one byte each, for the length of
+// the kernel; nothing the kernel writes to global memory is read back.
 // ---------------------------------------------------------------------------------------
 constexpr int PRUNE_THREADS = 1024;
+constexpr int PRUNE_MAX_BRANCHES = 65536;
 __global__ void __launch_bounds__(PRUNE_THREADS)
-dynamic_prune_kernel(hpd_dev_tables tb, int32_t P, int32_t n_docs, int32_t B, int32_t next_step,
-                     int32_t contig, const uint8_t* __restrict__ finished, const int32_t* __restrict__ order,
-                     const int32_t* __restrict__ doc_branch_ptr, int32_t* __restrict__ alive,
-                     int32_t* __restrict__ live, int32_t* __restrict__ rank, int32_t* __restrict__ n_live,
-                     int32_t* __restrict__ desc) {
-  __shared__ int32_t part[PRUNE_THREADS];
-  const int32_t tid = threadIdx.x;
-  // 1. the branches that ended with the step just taken (no flags: a fresh start, all live)
+dynamic_prune_kernel(int32_t n_docs, int32_t B, int32_t next_step, const uint8_t* __restrict__ finished,
+                     const int4* __restrict__ fixed, int32_t* __restrict__ live,
+                     int32_t* __restrict__ n_live, int4* __restrict__ desc) {
+  __shared__ uint32_t al_words[PRUNE_MAX_BRANCHES / 4];
+  __shared__ int32_t pex[PRUNE_THREADS];   // branches alive before each thread's run
+  __shared__ int32_t wsum[PRUNE_THREADS / 64];
+  uint8_t* al = reinterpret_cast<uint8_t*>(al_words);
+  const int32_t tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the first document of this thread: requested now, needed at the end
+  int4 fx0 = make_int4(0, 0, 0, 0), fx1 = fx0;
+  if (tid < n_docs) { fx0 = fixed[2 * tid]; fx1 = fixed[2 * tid + 1]; }
+  // 1. liveness after the step just taken (no flags: a fresh start, all live)
+  const uint32_t fill = finished ? 0u : 0x01010101u;
+  for (int32_t w = tid; w < (B + 3) / 4; w += PRUNE_THREADS) al_words[w] = fill;
+  __syncthreads();
   if (finished) {
     const int32_t n_prev = n_live[0];
-    for (int32_t r = tid; r < n_prev; r += PRUNE_THREADS)
-      if (finished[r]) alive[live[r]] = 0;
-  } else {
-    for (int32_t b = tid; b < B; b += PRUNE_THREADS) alive[b] = 1;
+    // eight rows per thread and pass, all sixteen loads requested before the first is used
+    for (int32_t r0 = tid; r0 < n_prev; r0 += 8 * PRUNE_THREADS) {
+      uint8_t f[8];
+      int32_t lb[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int32_t r = r0 + k * PRUNE_THREADS;
+        f[k] = r < n_prev ? finished[r] : (uint8_t)1;
+        lb[k] = r < n_prev ? live[r] : 0;
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (!f[k]) al[lb[k]] = 1;
+    }
+    __syncthreads();  // the old list has been read; it is overwritten below
   }
-  __syncthreads();
-  // 2. exclusive prefix sums of `alive` over the branches: thread t owns a run of branches
+  // 2. exclusive prefix sums over the branches: thread t owns a run of `chunk` branches; the
+  //    run sums are scanned inside each wave, the 16 wave sums by every thread for itself
   const int32_t chunk = (B + PRUNE_THREADS - 1) / PRUNE_THREADS;
   const int32_t b0 = min(tid * chunk, B), b1 = min(b0 + chunk, B);
   int32_t cnt = 0;
-  for (int32_t b = b0; b < b1; ++b) cnt += alive[b];
-  part[tid] = cnt;
+  for (int32_t b = b0; b < b1; ++b) cnt += al[b];
+  int32_t incl = cnt;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int32_t v = __shfl_up(incl, o);
+    if (lane >= o) incl += v;
+  }
+  if (lane == 63) wsum[wave] = incl;
   __syncthreads();
-  for (int32_t off = 1; off < PRUNE_THREADS; off <<= 1) {  // inclusive scan of the run sums
-    const int32_t v = tid >= off ? part[tid - off] : 0;
-    __syncthreads();
-    part[tid] += v;
-    __syncthreads();
+  int32_t run = incl - cnt, total = 0;
+#pragma unroll
+  for (int w = 0; w < PRUNE_THREADS / 64; ++w) {
+    const int32_t x = wsum[w];
+    if (w < wave) run += x;
+    total += x;
   }
-  int32_t run = part[tid] - cnt;  // branches alive before this thread's run
-  for (int32_t b = b0; b < b1; ++b) {
-    rank[b] = run;
-    if (alive[b]) live[run++] = b;
-  }
-  if (tid == PRUNE_THREADS - 1) {
-    rank[B] = part[tid];
-    n_live[0] = part[tid];
-  }
-  __syncthreads();  // rank and live are read below by other threads of this workgroup
+  pex[tid] = run;
+  for (int32_t b = b0; b < b1; ++b)
+    if (al[b]) live[run++] = b;
+  if (tid == 0) n_live[0] = total;
+  __syncthreads();  // pex is read below by other threads
+  // live branches with an id below x
+  auto rank = [&](int32_t x) -> int32_t {
+    if (x >= B) return total;
+    const int32_t t = x / chunk;
+    int32_t r = pex[t];
+    for (int32_t b = t * chunk; b < x; ++b) r += al[b];
+    return r;
+  };
   // 3. one descriptor per document: {hoff, Hlen, doff, Llen, first live row, live branches,
   //    shared position | -1, first branch id if the live ones are consecutive | -1}
   for (int32_t u = tid; u < n_docs; u += PRUNE_THREADS) {
-    const int32_t d = order[u], p = tb.doc_prompt[d];
-    const int32_t first = rank[doc_branch_ptr[d]], nb = rank[doc_branch_ptr[d + 1]] - first;
+    if (u != tid) { fx0 = fixed[2 * u]; fx1 = fixed[2 * u + 1]; }
+    const int32_t lo = fx1.x, hi = fx1.y;
+    const int32_t first = rank(lo), nb = rank(hi) - first;
     int32_t b_first = -1;
-    if (nb > 0 && live[first + nb - 1] - live[first] == nb - 1) b_first = live[first];
-    int32_t* o = desc + (int64_t)u * 8;
-    o[0] = tb.seg_off[p]; o[1] = tb.seg_len[p]; o[2] = tb.seg_off[P + d]; o[3] = tb.seg_len[P + d];
-    o[4] = first; o[5] = nb;
-    o[6] = contig ? tb.seg_len[p] + tb.seg_len[P + d] + next_step : -1;
-    o[7] = b_first;
+    if (nb > 0) {
+      int32_t x = lo, y = hi - 1;  // the document's first and last live branch
+      while (!al[x]) ++x;
+      while (!al[y]) --y;
+      if (y - x == nb - 1) b_first = x;
+    }
+    desc[2 * u] = fx0;
+    desc[2 * u + 1] = make_int4(first, nb, fx1.z >= 0 ? fx1.z + next_step : -1, b_first);
   }
 }
 
@@ -523,8 +558,8 @@ hipError_t hpd_launch_finetune_mask(const int32_t* d_desc, int32_t S, int32_t* p
 
 hipError_t hpd_launch_dynamic_prune(const hpd_layout* L, int32_t next_step, const uint8_t* finished,
                                     hipStream_t s) {
-  dynamic_prune_kernel<<<1, PRUNE_THREADS, 0, s>>>(
-      L->dev, L->P, L->n_docs, L->B, next_step, L->cfg.pos_mode == HPD_POS_CONTIG ? 1 : 0, finished,
-      L->dyn_order_dev, L->dyn_bptr_dev, L->dyn_alive, L->dyn_live, L->dyn_rank, L->dyn_n_live, L->dyn_desc);
+  dynamic_prune_kernel<<<1, PRUNE_THREADS, 0, s>>>(L->n_docs, L->B, next_step, finished,
+                                                   (const int4*)L->dyn_fixed_dev, L->dyn_live, L->dyn_n_live,
+                                                   (int4*)L->dyn_desc);
   return hipGetLastError();
 }
