@@ -732,3 +732,61 @@ def test_prefill_attention_planted_mistake_is_caught(monkeypatch):
     h, l0 = int(wl.header_len[0]), int(wl.doc_len[0])
     assert np.abs(good[:h + l0] - bad[:h + l0]).max() < 1e-12  # header and first document unchanged
     assert np.abs(good[h + l0:] - bad[h + l0:]).max() > 1e-6
+
+
+@pytest.mark.parametrize("seed,dtype,tol", [(61, np.float64, 1e-12), (62, np.float32, 2e-5)])
+def test_prefill_attention_under_the_literal_mask_is_plain_causal_attention(seed, dtype, tol):
+    """First inference step, Section 4.3.2 taken literally: header, stacked documents and the
+    attribute names are one sequence and the mask is the standard causal one.  Library causal
+    attention over each prompt's prefix in memory order, with the independent complex-number
+    RoPE at positions 0 .. |p|-1 for header and documents and Algorithm 2's closed form for the
+    names (attribute n shifted by n * K_max): every row must equal the oracle's, the names'
+    rows - the ones whose outputs start the branches - included."""
+    wl, attr = _paper_case(seed, t=3, p=2, hq=4, hkv=2, d=16, j_range=(1, 3), n_range=(1, 3),
+                           h_range=(0, 5), l_range=(1, 8))
+    orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len,
+                      wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new,
+                      pos_mode="paper_gap", attr_len=attr, dtype=dtype, mask_mode="paper")
+    n_tok = orc.n_prefix_tokens
+    assert n_tok == wl.n_prefix_tokens + int(attr.sum())
+    kp = _values(wl, 1, (n_tok, wl.n_kv_heads, wl.head_dim))
+    vp = _values(wl, 2, (n_tok, wl.n_kv_heads, wl.head_dim))
+    qp = _values(wl, 3, (n_tok, wl.n_q_heads, wl.head_dim))
+    orc.prefill(kp, vp)
+    got = orc.prefill_attention(qp)
+    g = wl.n_q_heads // wl.n_kv_heads
+    for p in range(wl.n_prompts):
+        a0, a1 = orc.prefix_range[p]
+        b0, b1 = orc.branch_range[p]
+        plen = a1 - a0 - int(attr[b0:b1].sum())
+        skel = [plen + int(attr[b0:b0 + n].sum()) + i + n * wl.max_new
+                for n in range(b1 - b0) for i in range(int(attr[b0 + n]))]
+        pos = np.concatenate([np.arange(plen), np.asarray(skel, dtype=np.int64)])
+        assert len(pos) == a1 - a0 and np.all(np.diff(pos) > 0)  # memory order is position order
+        kr = _rope_complex(kp[a0:a1].astype(np.float64), pos, wl.rope_base)
+        qr = _rope_complex(qp[a0:a1].astype(np.float64), pos, wl.rope_base)
+        tq = torch.from_numpy(qr).permute(1, 0, 2)[None]
+        tk = torch.from_numpy(kr).permute(1, 0, 2).repeat_interleave(g, 0)[None]
+        tv = torch.from_numpy(vp[a0:a1].astype(np.float64)).permute(1, 0, 2).repeat_interleave(g, 0)[None]
+        ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)[0].permute(1, 0, 2).numpy()
+        assert np.abs(got[p] - ref).max() < tol, p
+
+
+def test_prefill_attention_literal_and_block_masks_differ_only_behind_the_first_document():
+    """Same prompt under both masks: header and first-document rows are identical (they see the
+    same keys at the same positions); a later document's rows are not."""
+    wl = W.random_workload(63, t=2, p=1, hq=2, hkv=1, d=8, j_range=(2, 2), n_range=(1, 2), h_range=(2, 4), l_range=(3, 6))
+    attr = np.ones(wl.n_branches, dtype=np.int64)
+    outs = {}
+    for mode, pos_mode in (("block", "paper_gap"), ("paper", "paper_gap")):
+        orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len, 2, 1, 8,
+                          wl.rope_base, wl.max_new, pos_mode=pos_mode, attr_len=attr, dtype=np.float64,
+                          mask_mode=mode)
+        n_tok = orc.n_prefix_tokens
+        kp = _values(wl, 1, (n_tok, 1, 8)); vp = _values(wl, 2, (n_tok, 1, 8)); qp = _values(wl, 3, (n_tok, 2, 8))
+        orc.prefill(kp, vp)
+        outs[mode] = orc.prefill_attention(qp)[0]
+    h, l0 = int(wl.header_len[0]), int(wl.doc_len[0])
+    n = wl.n_prefix_tokens
+    assert np.abs(outs["block"][:h + l0] - outs["paper"][:h + l0]).max() < 1e-12
+    assert np.abs(outs["block"][h + l0:n] - outs["paper"][h + l0:n]).max() > 1e-6
