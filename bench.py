@@ -138,18 +138,21 @@ def cpu_baseline(wl, budget_s=15.0, paper=False, attr_len=None):
                       f"{done_tokens} branch-tokens in {spent:.1f} s; host affinity {cores} cores"}
 
 
-def bench_prefill(args, wl, layout, B, W, torch, np, out_f32):
+def bench_prefill(args, wl, layout, B, W, torch, np, out_f32, attr_len=None):
     """hpd_prefill_attention on the workload's header and document tokens: every prefix token a
-    query over header + own document up to itself.  A step = one call over the whole batch."""
+    query over header + own document up to itself.  With `attr_len` (the literal mask): header,
+    documents and attribute names of a prompt as one causal sequence.  A step = one call over
+    the whole batch."""
     dev = "cuda"
     eb = 4 if wl.dtype == "f32" else 2
     base = wl.value_seed * 1000
-    shp = (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim)
+    n_tok = int(B.hpd_layout_query(layout, B.HPD_Q_COUNTS)[B.HPD_C_N_PREFIX_TOKENS])
+    shp = (n_tok, wl.n_kv_heads, wl.head_dim)
     k_raw = W.normal_values(shp, base + 1, dev, wl.dtype)
     v_raw = W.normal_values(shp, base + 2, dev, wl.dtype)
-    q = W.normal_values((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), base + 3, dev, wl.dtype)
+    q = W.normal_values((n_tok, wl.n_q_heads, wl.head_dim), base + 3, dev, wl.dtype)
     tdt = torch.float32 if (out_f32 or wl.dtype == "f32") else torch.bfloat16
-    out = torch.empty((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), dtype=tdt, device=dev)
+    out = torch.empty((n_tok, wl.n_q_heads, wl.head_dim), dtype=tdt, device=dev)
     kp, vp, kt, vt = B.alloc_pools(layout, dev)
     B.hpd_prefix_fill(layout, k_raw, v_raw, kp, vp)
     torch.cuda.synchronize()
@@ -161,9 +164,14 @@ def bench_prefill(args, wl, layout, B, W, torch, np, out_f32):
         for d in range(wl.doc_ptr[p], wl.doc_ptr[p + 1]):
             l = int(wl.doc_len[d])
             keys += l * h + l * (l + 1) // 2
+        if attr_len is not None:  # one causal sequence: header, documents, names
+            n = h + int(wl.doc_len[wl.doc_ptr[p]:wl.doc_ptr[p + 1]].sum()) + \
+                int(attr_len[wl.branch_ptr[wl.doc_ptr[p]]:wl.branch_ptr[wl.doc_ptr[p + 1]]].sum())
+            keys += n * (n + 1) // 2 - (h * (h + 1) // 2 + sum(
+                int(l) * h + int(l) * (int(l) + 1) // 2 for l in wl.doc_len[wl.doc_ptr[p]:wl.doc_ptr[p + 1]]))
     flops = 4 * wl.head_dim * wl.n_q_heads * keys
     tok_b = 2 * wl.n_kv_heads * wl.head_dim * eb
-    alg_bytes = wl.n_prefix_tokens * (tok_b + 2 * wl.n_q_heads * wl.head_dim * eb)  # K/V once, Q in, O out
+    alg_bytes = n_tok * (tok_b + 2 * wl.n_q_heads * wl.head_dim * eb)  # K/V once, Q in, O out
     steps, warmup = max(1, args.steps // 4), max(1, args.warmup // 4)
     for _ in range(warmup):
         B.hpd_prefill_attention(layout, q, kp, vp, out)
@@ -179,12 +187,13 @@ def bench_prefill(args, wl, layout, B, W, torch, np, out_f32):
     dur_s = ev0.elapsed_time(ev1) * 1e-3
     tf = flops * steps / dur_s / 1e12
     rec = {"metric": "prefix tokens/s of HPD prefill attention (side measurement)",
-           "value": round(wl.n_prefix_tokens * steps / elapsed, 1), "unit": "prefix-tokens/s", "n_gpus": 1,
+           "value": round(n_tok * steps / elapsed, 1), "unit": "prefix-tokens/s", "n_gpus": 1,
            "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed * 1e3 / steps, 4),
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
            "data": "synthetic",
-           "config": {"workload": f"configs[{args.config - 1}] {wl.name}: {wl.note}; prefill attention",
-                      "prefix_tokens": int(wl.n_prefix_tokens), "heads": f"{wl.n_q_heads}/{wl.n_kv_heads}x{wl.head_dim}",
+           "config": {"workload": f"configs[{args.config - 1}] {wl.name}: {wl.note}; prefill attention"
+                                  + ("; paper-literal mask, attribute names included" if attr_len is not None else ""),
+                      "prefix_tokens": n_tok, "heads": f"{wl.n_q_heads}/{wl.n_kv_heads}x{wl.head_dim}",
                       "out_dtype": "f32" if tdt == torch.float32 else wl.dtype, "call": "hpd_prefill_attention"},
            "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                         "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
@@ -267,7 +276,7 @@ def main():
     attn_b, app_b, flops = algorithmic_bytes(wl, live_lists, eb, paper, attr_len)
 
     if args.phase == "prefill":
-        bench_prefill(args, wl, layout, B, W, torch, np, out_f32)
+        bench_prefill(args, wl, layout, B, W, torch, np, out_f32, attr_len if paper else None)
         return
 
     pool_bytes = B.hpd_layout_query(layout, B.HPD_Q_POOL_BYTES)

@@ -230,11 +230,13 @@ int hpd_decode_step(const hpd_layout* layout, int32_t step, const void* q, const
 
 /*
  * hpd_prefill_attention - Section 4.3.2, "First Inference Step": the attention of the pass
- * that feeds the whole input once, for the header and document tokens.  Every prefix token is
- * a query at its own position ID; under HPD_MASK_BLOCK (the only mode supported here) a
- * header token attends to the header up to itself, a document token to the whole header and
- * to its own document up to itself.  Call after hpd_prefix_fill (the keys are read from the
- * prefix pools).
+ * that feeds the whole input once.  Every prefix token is a query at its own position ID.
+ * Under HPD_MASK_BLOCK a header token attends to the header up to itself, a document token to
+ * the whole header and to its own document up to itself.  Under HPD_MASK_PAPER header,
+ * documents and attribute names of a prompt are one causal sequence, as the section has it: a
+ * document token also sees the earlier documents, a name token everything before it; the rows
+ * of the names' last tokens are the ones whose outputs start the branches.  Call after
+ * hpd_prefix_fill (the keys are read from the prefix pools).
  *   q   : device [n_prefix_tokens][Hq][D], un-rotated, token order of hpd_prefix_fill
  *   out : device [n_prefix_tokens][Hq][D] (element type per hpd_config.out_dtype)
  */

@@ -176,14 +176,18 @@ __device__ __forceinline__ void rotate16(uint4 raw_lo, uint4 raw_hi, const float
 // row's token: the stream stops at the row group's last token, a wave skips the blocks behind
 // its last row, and the blocks on the diagonal get a per-row count.  No tails, no append.
 // MODE_PAGED = MODE_BLOCK with the tail rows found through the caller's page table.
-enum { MODE_BLOCK = 0, MODE_PAPER = 1, MODE_PREFILL = 2, MODE_PAGED = 3 };
+// MODE_PREFILL_LIST = MODE_PREFILL under the literal mask: what a segment sees in full (the
+// header and the earlier documents of its prompt) is a list of blocks with a key count each
+// instead of the header's run of slots, and the names' positions come from a table.
+enum { MODE_BLOCK = 0, MODE_PAPER = 1, MODE_PREFILL = 2, MODE_PAGED = 3, MODE_PREFILL_LIST = 4 };
 template <int G, typename SH, int MODE>
 __global__ void __launch_bounds__(SH::WAVES * 64, 2)
 attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_prefix,
                    const uint16_t* __restrict__ v_prefix, uint16_t* __restrict__ k_tail,
                    uint16_t* __restrict__ v_tail, const uint16_t* __restrict__ k_new,
                    const uint16_t* __restrict__ v_new, void* __restrict__ out) {
-  constexpr bool PAPER = MODE == MODE_PAPER, PREFILL = MODE == MODE_PREFILL, PAGED = MODE == MODE_PAGED;
+  constexpr bool PAPER = MODE == MODE_PAPER, PAGED = MODE == MODE_PAGED, PLIST = MODE == MODE_PREFILL_LIST;
+  constexpr bool PREFILL = MODE == MODE_PREFILL || PLIST;
   constexpr int BPB = 32 / G;              // branches (PREFILL: tokens) per row block
   constexpr int QPR = G >= 8 ? 1 : 8 / G;  // branch quads (tail tiles per 8 positions) per row block
   constexpr int CWAVES = SH::CW, LOADERS = SH::LW, STAGE_BLOCKS = SH::SB, STAGE_U4 = SH::STAGE_U4;
@@ -199,7 +203,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   constexpr int MAX_KEY_BRANCHES = 256;
   __shared__ int32_t klen[PAPER ? MAX_KEY_BRANCHES : 1];  // tokens in memory of every key branch
   constexpr int MAX_LIST_BLOCKS = 512;
-  __shared__ int32_t bvalid[PAPER ? MAX_LIST_BLOCKS : 1];  // second entry of the prompt's block list
+  __shared__ int32_t bvalid[(PAPER || PLIST) ? MAX_LIST_BLOCKS : 1];  // second entry of the prompt's block list
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
@@ -220,6 +224,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   //         row, live branches, first branch of the prompt, first live branch | -1, key branches}
   // PREFILL: {hoff, Hlen (0 for a header unit), first slot of the segment, its tokens, first
   //         token in the order of q / out, tokens again, position ID of the first token, 0}
+  // PLIST:  {first entry of the prompt's block list, list blocks the segment sees in full, then
+  //         as PREFILL; for the names the position entry is -(1 + first entry in skel_pos)}
   const int32_t* desc = (PAPER ? a.tb.punit_desc : PREFILL ? a.tb.funit_desc : a.tb.unit_desc) +
                         (int64_t)u * (PAPER ? 16 : 8);  // pre-offset to this step by the host
   const int32_t hoff = desc[0], Hlen = desc[1], doff = desc[2], Llen = desc[3];
@@ -265,7 +271,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // ---- the stream: NB prefix blocks, then NQ * NC tail tiles (quad-major inside a chunk of 8
   //      positions), two blocks per round
   // (PREFILL: the document blocks up to the row group's last token)
-  const int32_t NBh = (Hlen + 31) >> 5;
+  const int32_t NBh = PLIST ? Hlen : (Hlen + 31) >> 5;
   const int32_t NBd = PAPER ? Llen : PREFILL ? ((br0 + nbr_here - 1) >> 5) + 1 : (Llen + 31) >> 5;
   const int32_t NB = NBh + NBd;
   const int32_t NQ = ((PAPER ? kb_end : nbr_here) + 3) >> 2;  // quads of 4 (key) branches
@@ -328,6 +334,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const bool prefix = gb < NB;
     if (prefix) {
       if (PAPER) slot0 = gb < NBh ? hoff + gb * 32 : scalar_load(a.tb.pblk + 2 * (doff + gb - NBh));
+      else if (PLIST) slot0 = gb < NBh ? scalar_load(a.tb.fblk + 2 * (hoff + gb)) : doff + (gb - NBh) * 32;
       else slot0 = gb < NBh ? hoff + gb * 32 : doff + (gb - NBh) * 32;
     } else {
       // tail tile: key k = position c*8 + k%8 of branch qd*4 + k/8; row k = h*16 + f*4 + lane/16
@@ -546,6 +553,9 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     // the block list's key counts: a lookup in global memory per block would stall every wave
     for (int32_t i = tid; i < NBd; i += CWAVES * 64) bvalid[i] = a.tb.pblk[2 * (doff + i) + 1];
   }
+  if constexpr (PLIST) {
+    for (int32_t i = tid; i < NBh; i += CWAVES * 64) bvalid[i] = a.tb.fblk[2 * (hoff + i) + 1];
+  }
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
   __builtin_amdgcn_s_barrier();        // bare barriers: __syncthreads() would wait for every store
   uint4 qraw[8];
@@ -593,7 +603,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   } else {
     // per-branch positions: straight from the table
     const int32_t q_bi = min(r_row / G, nb - 1);
-    const int32_t q_pos = PREFILL ? seg_pos0 + q_bi : a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
+    const int32_t q_pos = PREFILL ? ((!PLIST || seg_pos0 >= 0) ? seg_pos0 + q_bi : a.tb.skel_pos[q_bi - seg_pos0 - 1])
+                                  : a.tb.branch_base_pos[branch_id(q_bi - br0)] + 1 + a.step;
     const float4* cs_row = reinterpret_cast<const float4*>(a.tb.rope + (int64_t)q_pos * (D / 2));
     rotate_query([&](int i4) -> float4 { return cs_row[i4]; });
   }
@@ -750,7 +761,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         uint32_t ok = 0xffffu;
         if (gb < NB) {
           mine = gb % KG == kg;
-          int32_t valid = gb < NBh ? min(32, Hlen - gb * 32)
+          int32_t valid = gb < NBh ? (PLIST ? bvalid[gb] : min(32, Hlen - gb * 32))
                           : PAPER ? bvalid[gb - NBh] : min(32, Llen - (gb - NBh) * 32);
           masked = valid < 32;
           if (PAPER && valid >= 1000) {
@@ -1053,11 +1064,13 @@ hipError_t hpd_launch_prefill_stream(const hpd_layout* L, const void* q, const v
   a.n_groups = (int32_t)(n_units * a.Hkv);
   const int64_t items = ((int64_t)(a.n_groups + 7) / 8 * 8) * a.RG;
   if (items > 0x7fffffff) return hipErrorInvalidValue;
-#define HPD_LAUNCH(GG)                                                                                   \
-  (narrow ? launch_g<GG, NarrowShape, MODE_PREFILL>(a, items, q, k_prefix, v_prefix, nullptr, nullptr,  \
-                                                    nullptr, nullptr, out, s)                           \
-          : launch_g<GG, WideShape, MODE_PREFILL>(a, items, q, k_prefix, v_prefix, nullptr, nullptr,    \
-                                                  nullptr, nullptr, out, s))
+  const bool list = L->cfg.mask_mode == HPD_MASK_PAPER;
+#define HPD_LAUNCH_M(GG, PP)                                                                   \
+  (narrow ? launch_g<GG, NarrowShape, PP>(a, items, q, k_prefix, v_prefix, nullptr, nullptr,  \
+                                          nullptr, nullptr, out, s)                           \
+          : launch_g<GG, WideShape, PP>(a, items, q, k_prefix, v_prefix, nullptr, nullptr,    \
+                                        nullptr, nullptr, out, s))
+#define HPD_LAUNCH(GG) (list ? HPD_LAUNCH_M(GG, MODE_PREFILL_LIST) : HPD_LAUNCH_M(GG, MODE_PREFILL))
   switch (G) {
     case 1: return HPD_LAUNCH(1);
     case 2: return HPD_LAUNCH(2);
@@ -1066,4 +1079,5 @@ hipError_t hpd_launch_prefill_stream(const hpd_layout* L, const void* q, const v
     default: return hipErrorInvalidValue;
   }
 #undef HPD_LAUNCH
+#undef HPD_LAUNCH_M
 }

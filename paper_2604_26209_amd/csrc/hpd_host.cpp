@@ -322,6 +322,47 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
       }
     }
 
+    // ---- the same under the literal mask: header, documents and attribute names of a prompt
+    //      are one causal sequence.  A segment sees the earlier segments of its prompt in full -
+    //      a list of their 32-key blocks (first pool slot, keys), of which every segment takes
+    //      a prefix - and itself up to the query.  A unit per non-empty segment:
+    //      {first list entry of the prompt, list blocks the segment sees, first slot, tokens,
+    //       first token in q / out order, tokens, position ID of the first token or
+    //       -(1 + first entry in skel_pos) for the names, 0}
+    if (cfg->mask_mode == HPD_MASK_PAPER) {
+      std::vector<int32_t> raw_of(n_seg), before(n_seg, 0), list0(n_seg, 0);
+      for (int32_t i = 0; i < n_seg; ++i) raw_of[L->raw_seg[i]] = L->seg_raw_off[i];
+      for (int32_t p = 0; p < P; ++p) {
+        const int32_t base = (int32_t)(L->fblk.size() / 2);
+        auto add = [&](int32_t sid, bool keys) {
+          list0[sid] = base;
+          before[sid] = (int32_t)(L->fblk.size() / 2) - base;
+          for (int32_t i = 0; keys && i < L->seg_len[sid]; i += HPD_KEY_BLOCK) {
+            L->fblk.push_back(L->seg_off[sid] + i);
+            L->fblk.push_back(std::min<int32_t>(HPD_KEY_BLOCK, L->seg_len[sid] - i));
+          }
+        };
+        add(p, true);
+        for (int32_t d = doc_ptr[p]; d < doc_ptr[p + 1]; ++d) add(P + d, true);
+        add(P + n_docs + p, false);  // nothing comes after the names
+      }
+      std::vector<int32_t> segs;
+      for (int32_t sid = 0; sid < n_seg; ++sid)
+        if (L->seg_len[sid] > 0) segs.push_back(sid);
+      auto cost = [&](int32_t sid) -> int64_t {
+        return (int64_t)L->seg_len[sid] * ((int64_t)before[sid] * HPD_KEY_BLOCK + L->seg_len[sid]);
+      };
+      std::stable_sort(segs.begin(), segs.end(), [&](int32_t x, int32_t y) { return cost(x) > cost(y); });
+      for (int32_t sid : segs) {
+        const bool names = sid >= P + n_docs;
+        const int32_t desc[8] = {list0[sid], before[sid], L->seg_off[sid], L->seg_len[sid], raw_of[sid],
+                                 L->seg_len[sid], names ? -(1 + L->skel_off[sid - P - n_docs]) : L->seg_pos0[sid], 0};
+        L->funit_desc.insert(L->funit_desc.end(), desc, desc + 8);
+        L->fmax_rows = std::max(L->fmax_rows, L->seg_len[sid]);
+        L->fmax_list_blocks = std::max(L->fmax_list_blocks, before[sid]);
+      }
+    }
+
     // ---- RoPE table: angles in double, stored as float (cos, sin)
     const int32_t half = cfg->head_dim / 2;
     L->rope.resize((size_t)(L->max_pos + 1) * half * 2);
@@ -352,7 +393,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
                  o_pdp = A.add(L->prompt_doc_ptr), o_pbp = A.add(L->prompt_branch_ptr),
                  o_blen = A.add(L->branch_len), o_pblk = A.add(L->pblk), o_pdesc = A.add(L->punit_desc),
                  o_fdesc = A.add(L->funit_desc), o_spos = A.add(L->skel_pos), o_soff = A.add(L->skel_off),
-                 o_sseg = A.add(L->skel_seg_off), o_scum = A.add(L->skel_cum);
+                 o_sseg = A.add(L->skel_seg_off), o_scum = A.add(L->skel_cum), o_fblk = A.add(L->fblk);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipGetDevice(&L->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&L->n_cus, hipDeviceAttributeMultiprocessorCount, L->device);
@@ -381,7 +422,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     L->dev.unit_doc = base + o_unit_doc; L->dev.unit_desc = base + o_unit_desc;
     L->dev.prompt_doc_ptr = base + o_pdp; L->dev.prompt_branch_ptr = base + o_pbp;
     L->dev.branch_len = base + o_blen; L->dev.pblk = base + o_pblk; L->dev.punit_desc = base + o_pdesc;
-    L->dev.funit_desc = base + o_fdesc;
+    L->dev.funit_desc = base + o_fdesc; L->dev.fblk = base + o_fblk;
     L->dev.skel_pos = paper_mode(L) ? base + o_spos : nullptr; L->dev.skel_off = base + o_soff;
     L->dev.skel_seg_off = base + o_sseg; L->dev.skel_cum = base + o_scum;
     L->dev.rope = (const float2*)L->d_rope;
@@ -526,10 +567,12 @@ int hpd_decode_attention(const hpd_layout* L, int32_t step, const void* q, const
 int hpd_prefill_attention(const hpd_layout* L, const void* q, const void* k_prefix, const void* v_prefix,
                           void* out, void* stream) {
   if (!L || !L->on_device) return HPD_E_INVALID;
-  if (L->cfg.mask_mode != HPD_MASK_BLOCK) return HPD_E_UNSUPPORTED;
   if (L->n_prefix_tokens == 0) return HPD_OK;
   if (!q || !k_prefix || !v_prefix || !out) return HPD_E_INVALID;
-  if (L->kernel_mode >= 2 || (L->kernel_mode == 0 && hpd_stream_supported(L))) {
+  const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
+  // (the streaming kernel keeps the key counts of a unit's block list in LDS: 512 entries)
+  if ((L->kernel_mode >= 2 || (L->kernel_mode == 0 && hpd_stream_supported(L))) &&
+      (!paper || L->fmax_list_blocks <= 512)) {
     HPD_HIP(hpd_launch_prefill_stream(L, q, k_prefix, v_prefix, out, (hipStream_t)stream));
     return HPD_OK;
   }
@@ -538,6 +581,12 @@ int hpd_prefill_attention(const hpd_layout* L, const void* q, const void* k_pref
   for (int32_t d = 0; d < L->n_docs; ++d)
     max_keys = std::max<int64_t>(max_keys, (int64_t)L->seg_len[L->doc_prompt[d]] + L->seg_len[L->P + d]);
   for (int32_t p = 0; p < L->P; ++p) max_keys = std::max<int64_t>(max_keys, L->seg_len[p]);
+  if (paper)  // a prompt's last name token sees the whole prefix of the prompt
+    for (int32_t p = 0; p < L->P; ++p) {
+      int64_t keys = (int64_t)L->seg_len[p] + L->seg_len[L->P + L->n_docs + p];
+      for (int32_t d = L->prompt_doc_ptr[p]; d < L->prompt_doc_ptr[p + 1]; ++d) keys += L->seg_len[L->P + d];
+      max_keys = std::max(max_keys, keys);
+    }
   if (max_keys > 15000) return HPD_E_UNSUPPORTED;
   HPD_HIP(hpd_launch_prefill_generic(L, q, k_prefix, v_prefix, out, (hipStream_t)stream));
   return HPD_OK;

@@ -39,6 +39,10 @@ struct hpd_dev_tables {
   const int32_t* skel_cum;      // [B] name tokens of the prompt's branches up to and including b
   // attention of the prefix tokens (block mask): one unit per non-empty header / document
   const int32_t* funit_desc;  // [n_funits][8] {hoff, Hlen (0 for a header), first slot, tokens, first token in q / out order, tokens, position ID of the first token, 0}
+  // the same under the literal mask: one unit per non-empty header / document / names segment,
+  // {first entry of the prompt in fblk, list blocks seen in full, first slot, tokens, first token in
+  //  q / out order, tokens, position ID of the first token | -(1 + first entry in skel_pos), 0}
+  const int32_t* fblk;        // [total header and document blocks][2] (first pool slot, keys), prompt by prompt
   const float2* rope;           // [max_pos+1][D/2] (cos, sin)
   // paged tails (null: token t of branch b is row b*T + t of every kv head's tail rows)
   const int32_t* tail_pages;    // [B][pages_per_branch], the caller's device memory
@@ -71,7 +75,9 @@ struct hpd_layout {
   int32_t max_prompt_branches = 0;
   std::vector<int32_t> skel_pos, skel_off, skel_seg_off, skel_cum;
   std::vector<int32_t> funit_desc;  // prefix-token attention units, heaviest first
+  std::vector<int32_t> fblk;        // literal mask: header and document blocks of every prompt
   int32_t fmax_rows = 0;            // most tokens of any segment
+  int32_t fmax_list_blocks = 0;     // literal mask: most list blocks any segment sees in full
   std::vector<int32_t> live_ptr, live_branch, doc_live_ptr, unit_ptr, unit_doc, unit_desc;
   std::vector<int32_t> max_rows;  // [T] largest number of live branches of any document at step t
   std::vector<float> rope;        // host copy of the (cos, sin) table

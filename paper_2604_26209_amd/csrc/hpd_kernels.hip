@@ -289,7 +289,10 @@ __device__ inline float block_reduce(float v, bool is_max, float* red) {
 // mask): row r is token r of hpd_prefix_fill's order, at its own position ID; its keys are the
 // header (for a document token) and its own segment up to itself.  `step` then carries the
 // number of segments.
-enum { GM_BLOCK = 0, GM_PAPER = 1, GM_PREFILL = 2 };
+// GM_PREFILL_PAPER = the same under the literal mask: header, documents and attribute names of
+// a prompt are one causal sequence (a document token also sees the earlier documents, a name
+// token everything before it).
+enum { GM_BLOCK = 0, GM_PAPER = 1, GM_PREFILL = 2, GM_PREFILL_PAPER = 3 };
 template <typename T, int GM>
 __global__ void __launch_bounds__(GEN_THREADS)
 attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hkv, int32_t D,
@@ -303,11 +306,12 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
   float* part = red + 8;           // [256] partial outputs
   float* scores = part + GEN_THREADS;  // [n_keys]
 
-  constexpr bool PAPER = GM == GM_PAPER, PREFILL = GM == GM_PREFILL;
+  constexpr bool PAPER = GM == GM_PAPER, PPL = GM == GM_PREFILL_PAPER, PREFILL = GM == GM_PREFILL || PPL;
   const int32_t r = blockIdx.x / Hq;
   const int32_t h = blockIdx.x % Hq;
   const int32_t hk = h / (Hq / Hkv);
   int32_t b = 0, d = 0, p = 0, pos = 0, Hlen = 0, Llen = 0, d_lo = 0, d_hi = 0, b_lo = 0, n_tail = 0;
+  int32_t n_names = 0;  // PPL: name tokens the row sees (itself included)
   if (PREFILL) {
     // segment that holds token r: last entry of the sorted start table <= r (empty ones skipped)
     const int32_t n_seg = step;
@@ -319,15 +323,27 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
     while (lo + 1 < n_seg && tb.seg_raw_off[lo + 1] <= r) ++lo;
     const int32_t sid = tb.raw_seg[lo], idx = r - tb.seg_raw_off[lo];
     pos = tb.seg_pos0[sid] + idx;
+    const int32_t n_docs = PPL ? n_seg - 2 * P : n_seg - P;
     if (sid < P) {  // a header token: the header up to itself
       p = sid;
       Hlen = idx + 1;
-    } else {        // a document token: the header, the document up to itself
+    } else if (sid < P + n_docs) {  // a document token: the header, the document up to itself
       d = sid - P;
       p = tb.doc_prompt[d];
       Hlen = tb.seg_len[p];
       Llen = idx + 1;
       d_lo = d; d_hi = d + 1;
+      if (PPL) {    // ... and the earlier documents of the prompt
+        d_lo = tb.prompt_doc_ptr[p];
+        for (int32_t dd = d_lo; dd < d; ++dd) Llen += tb.seg_len[P + dd];
+      }
+    } else {        // a name token: header, every document, the names up to itself
+      p = sid - P - n_docs;
+      Hlen = tb.seg_len[p];
+      d_lo = tb.prompt_doc_ptr[p]; d_hi = tb.prompt_doc_ptr[p + 1];
+      for (int32_t dd = d_lo; dd < d_hi; ++dd) Llen += tb.seg_len[P + dd];
+      n_names = idx + 1;
+      pos = tb.skel_pos[tb.skel_off[p] + idx];
     }
   } else {
     b = tb.live_branch[tb.live_ptr[step] + r];
@@ -347,12 +363,13 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
   // PAPER: the attribute names up to the row's own branch, counted with the documents
   const int32_t Dlen = Llen;
   if (PAPER) Llen += tb.skel_cum[b];
+  if (PPL) Llen += n_names;
   const int32_t n_keys = Hlen + Llen + n_tail;
   const int32_t half = D / 2;
   const int tid = threadIdx.x;
   // pool slot of prefix key kk (>= Hlen: the documents one after the other)
   auto doc_slot = [&](int32_t kk) -> int64_t {
-    if (PAPER && kk >= Hlen + Dlen) return (int64_t)tb.skel_seg_off[p] + (kk - Hlen - Dlen);
+    if ((PAPER || PPL) && kk >= Hlen + Dlen) return (int64_t)tb.skel_seg_off[p] + (kk - Hlen - Dlen);
     int32_t i = kk - Hlen, dd = d_lo;
     while (i >= tb.seg_len[P + dd]) { i -= tb.seg_len[P + dd]; ++dd; }
     return (int64_t)tb.seg_off[P + dd] + i;
@@ -504,8 +521,14 @@ static hipError_t launch_generic(const hpd_layout* L, int32_t step, const void* 
                                  const void* v_prefix, const void* k_tail, const void* v_tail, void* out,
                                  hipStream_t s) {
   int64_t n_rows = 0, max_keys = 0;
-  if (GM == GM_PREFILL) {
+  if (GM == GM_PREFILL || GM == GM_PREFILL_PAPER) {
     n_rows = L->n_prefix_tokens;
+    if (GM == GM_PREFILL_PAPER)  // a prompt's last name token sees the whole prefix of the prompt
+      for (int32_t p = 0; p < L->P; ++p) {
+        int64_t keys = (int64_t)L->seg_len[p] + L->seg_len[L->P + L->n_docs + p];
+        for (int32_t d = L->prompt_doc_ptr[p]; d < L->prompt_doc_ptr[p + 1]; ++d) keys += L->seg_len[L->P + d];
+        max_keys = std::max(max_keys, keys);
+      }
     for (int32_t d = 0; d < L->n_docs; ++d)
       max_keys = std::max<int64_t>(max_keys, (int64_t)L->seg_len[L->doc_prompt[d]] + L->seg_len[L->P + d]);
     for (int32_t p = 0; p < L->P; ++p) max_keys = std::max<int64_t>(max_keys, L->seg_len[p]);
@@ -538,9 +561,12 @@ hipError_t hpd_launch_attention_generic(const hpd_layout* L, int32_t step, const
 hipError_t hpd_launch_prefill_generic(const hpd_layout* L, const void* q, const void* k_prefix,
                                       const void* v_prefix, void* out, hipStream_t s) {
   // no tail key exists: the tail pools are never addressed
+  const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
   if (L->cfg.dtype == HPD_F32)
-    return launch_generic<float, GM_PREFILL>(L, 0, q, k_prefix, v_prefix, k_prefix, v_prefix, out, s);
-  return launch_generic<hpd::bf16_t, GM_PREFILL>(L, 0, q, k_prefix, v_prefix, k_prefix, v_prefix, out, s);
+    return paper ? launch_generic<float, GM_PREFILL_PAPER>(L, 0, q, k_prefix, v_prefix, k_prefix, v_prefix, out, s)
+                 : launch_generic<float, GM_PREFILL>(L, 0, q, k_prefix, v_prefix, k_prefix, v_prefix, out, s);
+  return paper ? launch_generic<hpd::bf16_t, GM_PREFILL_PAPER>(L, 0, q, k_prefix, v_prefix, k_prefix, v_prefix, out, s)
+               : launch_generic<hpd::bf16_t, GM_PREFILL>(L, 0, q, k_prefix, v_prefix, k_prefix, v_prefix, out, s);
 }
 
 hipError_t hpd_launch_expand_mask(const int32_t* d_desc, int32_t S, int32_t paper, uint8_t* mask_out,

@@ -85,31 +85,39 @@ def test_full_size_config_paper_literal_mask(k, prompts):
     print(f"  worst max-abs / RMS(step) = {worst:.4f}", flush=True)
 
 
-@pytest.mark.parametrize("k,prompts", [(2, [0, 31]), (3, [11])])
-def test_full_size_prefill_attention(k, prompts):
-    """hpd_prefill_attention at full size, launched as `bench.py --phase prefill` launches it:
-    sampled prompts against the oracle (per-token RMS bound), every output finite and inside
-    the hull of V."""
+@pytest.mark.parametrize("k,prompts,literal", [(2, [0, 31], False), (3, [11], False), (3, [20], True), (5, None, True)])
+def test_full_size_prefill_attention(k, prompts, literal):
+    """hpd_prefill_attention at full size, launched as `bench.py --phase prefill` (and
+    `--mask paper`) launches it: sampled prompts against the oracle (per-token RMS bound),
+    every output finite and inside the hull of V."""
     from paper_2604_26209_amd import binding as B
     wl = W.config(k)
-    print(f"full-size cfg{k}, prefill attention over {wl.n_prefix_tokens} tokens", flush=True)
-    layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32)
+    attr = np.random.default_rng(26209100 + k).integers(1, 5, size=wl.n_branches).astype(np.int32) if literal else None
+    layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32,
+                                    **(dict(pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr,
+                                            mask_mode=B.HPD_MASK_PAPER) if literal else {}))
+    n_tok = int(layout.counts()[B.HPD_C_N_PREFIX_TOKENS])
+    print(f"full-size cfg{k}, prefill attention over {n_tok} tokens, literal mask: {literal}", flush=True)
+    if prompts is None:  # ragged config: the prompts with the fewest and the most documents
+        nd = np.diff(wl.doc_ptr)
+        prompts = sorted({int(np.argmin(nd)), int(np.argmax(nd))})
     base = wl.value_seed * 1000
-    shp = (wl.n_prefix_tokens, wl.n_kv_heads, wl.head_dim)
+    shp = (n_tok, wl.n_kv_heads, wl.head_dim)
     k_raw = W.normal_values(shp, base + 1, "cuda", wl.dtype)
     v_raw = W.normal_values(shp, base + 2, "cuda", wl.dtype)
-    q = W.normal_values((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), base + 3, "cuda", wl.dtype)
+    q = W.normal_values((n_tok, wl.n_q_heads, wl.head_dim), base + 3, "cuda", wl.dtype)
     kp, vp, kt, vt = B.alloc_pools(layout)
     kp.fill_(float("nan")); vp.fill_(float("nan"))
     B.hpd_prefix_fill(layout, k_raw, v_raw, kp, vp)
-    out = torch.full((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+    out = torch.full((n_tok, wl.n_q_heads, wl.head_dim), float("nan"), dtype=torch.float32, device="cuda")
     B.hpd_prefill_attention(layout, q, kp, vp, out)
     torch.cuda.synchronize()
     assert bool(torch.isfinite(out).all())
     assert float(out.abs().max()) <= float(v_raw.abs().max()) * (1 + 1e-2)
     from oracle import hpd_oracle as O
     orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len, wl.n_q_heads,
-                      wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new, prompts=prompts, cache_dtype="bf16")
+                      wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new, prompts=prompts, cache_dtype="bf16",
+                      **(dict(pos_mode="paper_gap", attr_len=attr, mask_mode="paper") if literal else {}))
     kd, vd, qd = {}, {}, {}
     for p in prompts:
         a, b = orc.prefix_range[p]

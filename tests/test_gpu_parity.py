@@ -381,25 +381,32 @@ def test_paper_literal_mask_stream_kernel_shapes(g):
             assert torch.equal(x, y)
 
 
-def _check_prefill(wl, mode, label, out_f32=None):
-    """hpd_prefill_attention against the oracle's prefill_attention, all prompts."""
+def _check_prefill(wl, mode, label, out_f32=None, attr_len=None):
+    """hpd_prefill_attention against the oracle's prefill_attention, all prompts.  With
+    `attr_len`: the literal mask (gap positions), whose prefix also holds the attribute names."""
     from paper_2604_26209_amd import binding as B
     if out_f32 is None:
         out_f32 = wl.dtype == "bf16"
-    layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME)
+    paper = attr_len is not None
+    layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME,
+                                    **(dict(pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr_len,
+                                            mask_mode=B.HPD_MASK_PAPER) if paper else {}))
     if mode:
         B.hpd_set_kernel_mode(layout, mode)
-    inputs = H.Inputs(wl, layout.n_live(), "cuda")
-    q = W.normal_values((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), wl.value_seed * 1000 + 3, "cuda", wl.dtype)
+    n_tok = int(layout.counts()[B.HPD_C_N_PREFIX_TOKENS])
+    assert n_tok == wl.n_prefix_tokens + (int(np.sum(attr_len)) if paper else 0)
+    inputs = H.Inputs(wl, layout.n_live(), "cuda", n_tok)
+    q = W.normal_values((n_tok, wl.n_q_heads, wl.head_dim), wl.value_seed * 1000 + 3, "cuda", wl.dtype)
     kp, vp, kt, vt = B.alloc_pools(layout)
     for x in (kp, vp):
         x.fill_(float("nan"))
     B.hpd_prefix_fill(layout, inputs.k_raw, inputs.v_raw, kp, vp)
-    out = torch.full((wl.n_prefix_tokens, wl.n_q_heads, wl.head_dim), float("nan"),
+    out = torch.full((n_tok, wl.n_q_heads, wl.head_dim), float("nan"),
                      dtype=torch.float32 if out_f32 else H.torch_dtype(wl), device="cuda")
     B.hpd_prefill_attention(layout, q, kp, vp, out)
     torch.cuda.synchronize()
-    orc, _ = H.run_oracle(wl, inputs, steps=[])
+    orc, _ = H.run_oracle(wl, inputs, steps=[], **(dict(pos_mode="paper_gap", attr_len=attr_len,
+                                                        mask_mode="paper") if paper else {}))
     ref = orc.prefill_attention(q.float().cpu().numpy())
     got = out.float().cpu().numpy()
     assert np.isfinite(got).all(), f"{label}: non-finite output"
@@ -440,6 +447,28 @@ def test_prefill_attention_bf16_all_kernels(g):
     for mode in (1, 3, 4):
         _say(f"prefill bf16 G={g} mode {mode}: {wl.n_prefix_tokens} tokens")
         rel = _check_prefill(wl, mode, f"prefill_bf16_g{g}_m{mode}")
+        _say(f"  worst err/rms {rel:.2e}")
+
+
+def test_prefill_attention_literal_mask_fp32_generic():
+    """First inference step under HPD_MASK_PAPER: header, stacked documents and attribute names
+    as one causal sequence; the names' rows are the ones whose outputs start the branches."""
+    for seed, kw in [(95, dict(hq=4, hkv=2, d=64, t=3, p=3, j_range=(1, 3), h_range=(0, 20), l_range=(1, 70))),
+                     (96, dict(hq=2, hkv=2, d=32, t=2, p=2, h_range=(0, 0), l_range=(1, 5)))]:
+        wl = W.random_workload(seed, dtype="f32", **kw)
+        attr = np.random.default_rng(seed).integers(1, 5, size=wl.n_branches).astype(np.int32)
+        _say(f"prefill literal f32 seed {seed}: {wl.n_prefix_tokens} + {int(attr.sum())} tokens")
+        _check_prefill(wl, 0, f"prefill_literal_f32_{seed}", attr_len=attr)
+
+
+@pytest.mark.parametrize("g", [1, 2, 4, 8])
+def test_prefill_attention_literal_mask_bf16_all_kernels(g):
+    wl = W.random_workload(97 + g, dtype="bf16", hq=8, hkv=8 // g, d=128, base=500000.0, t=2, p=3,
+                           j_range=(1, 4), n_range=(1, 30), h_range=(0, 90), l_range=(1, 200 if g > 1 else 500))
+    attr = np.random.default_rng(97 + g).integers(1, 5, size=wl.n_branches).astype(np.int32)
+    for mode in (1, 3, 4):
+        _say(f"prefill literal bf16 G={g} mode {mode}: {wl.n_prefix_tokens} + {int(attr.sum())} tokens")
+        rel = _check_prefill(wl, mode, f"prefill_literal_bf16_g{g}_m{mode}", attr_len=attr)
         _say(f"  worst err/rms {rel:.2e}")
 
 
@@ -526,11 +555,6 @@ def test_error_paths_on_device_layout():
         B.hpd_kv_append(lay, 0, None, None, None, None)
     with pytest.raises(B.HpdError):
         B.hpd_set_kernel_mode(lay, 2)  # fp32 / D=64 has no MFMA path
-    # the prefill attention is built for the block mask only
-    attr = np.ones(wl.n_branches, dtype=np.int32)
-    lay_p = B.layout_from_workload(wl, pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr, mask_mode=B.HPD_MASK_PAPER)
     x = torch.zeros(8, device="cuda")
-    with pytest.raises(B.HpdError):
-        B.hpd_prefill_attention(lay_p, x, x, x, x)
     with pytest.raises(B.HpdError):
         B.hpd_prefill_attention(lay, None, x, x, x)
