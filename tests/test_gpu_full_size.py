@@ -166,3 +166,36 @@ def test_full_size_device_lists_and_paged_tails_equal_decode_step(k):
         assert torch.equal(out, ref["out"][t]), f"cfg{k} step {t}: outputs differ"
         if t + 1 < wl.max_new:
             B.hpd_dynamic_prune(lay, torch.from_numpy((wl.branch_len[live] == t + 1).astype(np.uint8)).cuda())
+
+
+@pytest.mark.parametrize("k,prompt,literal", [(2, 31, False), (3, 40, False), (3, 9, True), (5, None, False)])
+def test_full_size_mask_export_bit_exact(k, prompt, literal):
+    """The exported dense mask of one prompt of a benchmark configuration after its last decode
+    step (every token the prompt ever holds) against the oracle's mask, bit for bit; for the
+    ragged configuration the prompt with the most documents."""
+    from oracle import hpd_oracle as O
+    from paper_2604_26209_amd import binding as B
+    wl = W.config(k)
+    if prompt is None:
+        prompt = int(np.argmax(np.diff(wl.doc_ptr)))
+    attr = np.random.default_rng(26209100 + k).integers(1, 5, size=wl.n_branches).astype(np.int32) if literal else None
+    kw = dict(pos_mode="paper_gap", attr_len=attr, mask_mode="paper") if literal else {}
+    orc = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len, 1, 1, 2,
+                      wl.rope_base, wl.max_new, prompts=[prompt], **kw)  # one head of two channels: only the mask matters
+    a0, a1 = orc.prefix_range[prompt]
+    z = np.zeros((a1 - a0, 1, 2), dtype=np.float32)
+    orc.prefill({prompt: z}, {prompt: z})
+    for t in range(wl.max_new):
+        n = int((wl.branch_len > t).sum())
+        x = np.zeros((n, 1, 2), dtype=np.float32)
+        orc.step(t, x, x, x)
+    po = orc.prompts[prompt]
+    want = po.mask_rows_fast(list(range(len(po.kind))))
+    layout = B.layout_from_workload(wl, **(dict(pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr,
+                                                mask_mode=B.HPD_MASK_PAPER) if literal else {}))
+    s = B.hpd_expand_mask(layout, prompt, wl.max_new - 1)
+    print(f"full-size cfg{k} prompt {prompt}: mask of {s} tokens, literal: {literal}", flush=True)
+    assert s == len(po.kind)
+    m = torch.full((s, s), 7, dtype=torch.uint8, device="cuda")
+    B.hpd_expand_mask(layout, prompt, wl.max_new - 1, m)
+    assert np.array_equal(m.cpu().numpy(), want)
