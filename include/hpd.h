@@ -268,7 +268,10 @@ int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, u
  *   layout) and resets it: every branch live.  branch_len is ignored by the dynamic calls.
  * hpd_dynamic_prune - `finished`: device uint8 [n_live] in the row order of the step just
  *   taken; non-zero = that branch is not decoded any further.  Builds the next step's state.
- * hpd_dynamic_step  - hpd_decode_step of step `step` for the rows of the current live list:
+ * hpd_dynamic_step  - hpd_decode_step of step `step` for the rows of the current live list
+ *   (the same kernel; a document's rows are split over workgroups by its full branch count,
+ *   the live count being unknown to the host, so sums may be grouped differently and results
+ *   agree with hpd_decode_step to rounding, not always bit for bit):
  *   rows r of q / k_new / v_new / out are the live branches in ascending b, r < n_live (the
  *   kernels touch no row beyond; buffers need n_live rows, B rows always suffice).
  * hpd_dynamic_state - device addresses of the live list (int32 [B], first n_live valid) and of

@@ -275,6 +275,62 @@ def test_paged_tails(case):
         B.hpd_set_tail_pages(lay, 8, 4, None)
 
 
+@pytest.mark.parametrize("seed", range(150, 158))
+def test_paged_tails_random_sweep(seed):
+    """Page size, group size, workgroup shape, step budget and batch drawn from the seed: the
+    paged step call against the contiguous one, bit for bit.  Odd seeds use the device-side
+    lists, whose launches split a document's rows by its full branch count (the host does not
+    know the live count), so sums may be grouped differently than in hpd_decode_step: those
+    are checked against the oracle."""
+    from paper_2604_26209_amd import binding as B
+    rng = np.random.default_rng(seed)
+    g = (1, 2, 4, 8)[seed % 4]
+    hkv = int(rng.choice([1, 2]))
+    ps = (8, 16, 32)[seed % 3]
+    t_max = int(rng.integers(2, 41))
+    mode = 3 + (seed // 2) % 2
+    wl = W.random_workload(seed, dtype="bf16", hq=hkv * g, hkv=hkv, d=128, base=500000.0, t=t_max,
+                           p=int(rng.integers(1, 4)), j_range=(1, 3), n_range=(1, int(rng.integers(2, 30))),
+                           h_range=(0, 60), l_range=(1, int(rng.integers(2, 300))))
+    _say(f"paged sweep seed {seed}: G={g} Hkv={hkv} T={t_max} page {ps} mode {mode} branches {wl.n_branches}")
+    ref = H.run_hip(wl, kernel_mode=mode, fused=True)
+    inputs = ref["inputs"]
+    lay = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32)
+    B.hpd_set_kernel_mode(lay, mode)
+    alloc = _PageAllocator(wl, ps, seed=seed)
+    table = torch.from_numpy(alloc.table).cuda()
+    B.hpd_set_tail_pages(lay, ps, alloc.n_pages, table)
+    kp, vp, kt, vt = B.alloc_pools(lay)
+    for x in (kp, vp, kt, vt):
+        x.fill_(float("nan"))
+    B.hpd_prefix_fill(lay, inputs.k_raw, inputs.v_raw, kp, vp)
+    dynamic = seed % 2 == 1
+    if dynamic:
+        B.hpd_dynamic_begin(lay)
+    outs = []
+    for t in range(wl.max_new):
+        live = np.nonzero(wl.branch_len > t)[0]
+        if len(live) == 0:
+            break
+        alloc.before_step(t)
+        table.copy_(torch.from_numpy(alloc.table))
+        out = torch.full((len(live), wl.n_q_heads, wl.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+        a = (lay, t, inputs.q[t], inputs.k_new[t], inputs.v_new[t], kp, vp, kt, vt, out)
+        (B.hpd_dynamic_step if dynamic else B.hpd_decode_step)(*a)
+        if not dynamic:
+            assert torch.equal(out, ref["out"][t]), f"seed {seed} step {t}: paged and contiguous outputs differ"
+        outs.append(out)
+        if dynamic and t + 1 < wl.max_new:
+            B.hpd_dynamic_prune(lay, torch.from_numpy((wl.branch_len[live] == t + 1).astype(np.uint8)).cuda())
+        torch.cuda.synchronize()
+        alloc.after_step(t)
+    while len(outs) < wl.max_new:
+        outs.append(torch.zeros((0, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device="cuda"))
+    hip = dict(ref)
+    hip["out"] = outs
+    H.check_all(wl, hip, label=f"paged_sweep_{seed}")
+
+
 def test_paged_tails_refused_under_the_literal_mask():
     from paper_2604_26209_amd import binding as B
     wl = W.random_workload(142, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=4, p=1)
