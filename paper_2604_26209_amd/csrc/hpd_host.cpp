@@ -363,6 +363,20 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
       }
     }
 
+    // ---- for hpd_prefix_fill: which segment owns a 32-slot block of the pools, and where its
+    //      first token sits in the input order
+    {
+      std::vector<int32_t> raw_of(n_seg);
+      for (int32_t i = 0; i < n_seg; ++i) raw_of[L->raw_seg[i]] = L->seg_raw_off[i];
+      L->fill_blk.assign((size_t)(L->NP / HPD_KEY_BLOCK) * 2, -1);
+      for (int32_t sid = 0; sid < n_seg; ++sid)
+        for (int32_t i = 0; i < L->seg_len[sid]; i += HPD_KEY_BLOCK) {
+          const size_t b = (size_t)(L->seg_off[sid] + i) / HPD_KEY_BLOCK;
+          L->fill_blk[2 * b] = sid;
+          L->fill_blk[2 * b + 1] = raw_of[sid] + i;
+        }
+    }
+
     // ---- RoPE table: angles in double, stored as float (cos, sin)
     const int32_t half = cfg->head_dim / 2;
     L->rope.resize((size_t)(L->max_pos + 1) * half * 2);
@@ -393,7 +407,8 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
                  o_pdp = A.add(L->prompt_doc_ptr), o_pbp = A.add(L->prompt_branch_ptr),
                  o_blen = A.add(L->branch_len), o_pblk = A.add(L->pblk), o_pdesc = A.add(L->punit_desc),
                  o_fdesc = A.add(L->funit_desc), o_spos = A.add(L->skel_pos), o_soff = A.add(L->skel_off),
-                 o_sseg = A.add(L->skel_seg_off), o_scum = A.add(L->skel_cum), o_fblk = A.add(L->fblk);
+                 o_sseg = A.add(L->skel_seg_off), o_scum = A.add(L->skel_cum), o_fblk = A.add(L->fblk),
+                 o_fill = A.add(L->fill_blk);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipGetDevice(&L->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&L->n_cus, hipDeviceAttributeMultiprocessorCount, L->device);
@@ -423,6 +438,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     L->dev.prompt_doc_ptr = base + o_pdp; L->dev.prompt_branch_ptr = base + o_pbp;
     L->dev.branch_len = base + o_blen; L->dev.pblk = base + o_pblk; L->dev.punit_desc = base + o_pdesc;
     L->dev.funit_desc = base + o_fdesc; L->dev.fblk = base + o_fblk;
+    L->dev.fill_blk = base + o_fill;
     L->dev.skel_pos = paper_mode(L) ? base + o_spos : nullptr; L->dev.skel_off = base + o_soff;
     L->dev.skel_seg_off = base + o_sseg; L->dev.skel_cum = base + o_scum;
     L->dev.rope = (const float2*)L->d_rope;

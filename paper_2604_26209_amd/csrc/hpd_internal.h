@@ -43,6 +43,7 @@ struct hpd_dev_tables {
   // {first entry of the prompt in fblk, list blocks seen in full, first slot, tokens, first token in
   //  q / out order, tokens, position ID of the first token | -(1 + first entry in skel_pos), 0}
   const int32_t* fblk;        // [total header and document blocks][2] (first pool slot, keys), prompt by prompt
+  const int32_t* fill_blk;    // [NP/32][2] (segment that owns the 32-slot block | -1, raw index of its first token)
   const float2* rope;           // [max_pos+1][D/2] (cos, sin)
   // paged tails (null: token t of branch b is row b*T + t of every kv head's tail rows)
   const int32_t* tail_pages;    // [B][pages_per_branch], the caller's device memory
@@ -76,6 +77,7 @@ struct hpd_layout {
   std::vector<int32_t> skel_pos, skel_off, skel_seg_off, skel_cum;
   std::vector<int32_t> funit_desc;  // prefix-token attention units, heaviest first
   std::vector<int32_t> fblk;        // literal mask: header and document blocks of every prompt
+  std::vector<int32_t> fill_blk;    // owner and first raw token of every 32-slot block of the prefix pools
   int32_t fmax_rows = 0;            // most tokens of any segment
   int32_t fmax_list_blocks = 0;     // literal mask: most list blocks any segment sees in full
   std::vector<int32_t> live_ptr, live_branch, doc_live_ptr, unit_ptr, unit_doc, unit_desc;

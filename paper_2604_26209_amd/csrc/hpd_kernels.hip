@@ -54,6 +54,70 @@ __global__ void prefix_fill_kernel(hpd_dev_tables tb, int32_t n_seg, int32_t P, 
   v_prefix[(vblk + i + half) * 8 + (slot & 7)] = v_raw[src + i + half];
 }
 
+// The same for bf16 with 128 channels, the shape the streaming attention kernel serves: one
+// 256-thread workgroup per (32-slot block of the pools, kv head), a wave per 8 slots.  Rows move
+// as 16-byte pieces (8 lanes per K row); the 8-key interleave of the V pool is a transpose of
+// 8 rows x 128 channels through LDS, written back as one contiguous 2 KB run per wave.  Slots
+// behind the segment's end get V = 0 (what prefix_pad_kernel does for the general kernel).
+// fill_blk[b] = (segment that owns block b | -1, raw index of the block's first token).
+__global__ void __launch_bounds__(256)
+prefix_fill_bf16_128_kernel(hpd_dev_tables tb, int32_t n_seg, int32_t P, int32_t Hkv, int64_t NP,
+                            const int32_t* __restrict__ fill_blk, const uint16_t* __restrict__ k_raw,
+                            const uint16_t* __restrict__ v_raw, uint16_t* __restrict__ k_prefix,
+                            uint16_t* __restrict__ v_prefix) {
+  constexpr int D = 128;
+  __shared__ uint16_t vt[4][8][D];
+  const int32_t blk = blockIdx.x / Hkv, h = blockIdx.x % Hkv;
+  const int32_t sid = fill_blk[2 * blk];
+  if (sid < 0) return;  // uniform over the workgroup
+  const int32_t raw0 = fill_blk[2 * blk + 1];
+  const int32_t idx0 = blk * 32 - tb.seg_off[sid], len = tb.seg_len[sid];
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane >> 3, cc = lane & 7;
+  const int32_t idx = idx0 + wave * 8 + r;
+  const bool valid = idx < len;
+  const int64_t slot = (int64_t)blk * 32 + wave * 8 + r;
+  uint4 vlo = make_uint4(0, 0, 0, 0), vhi = vlo;
+  if (valid) {
+    const int64_t src = ((int64_t)(raw0 + wave * 8 + r) * Hkv + h) * D;
+    const uint4 klo = *reinterpret_cast<const uint4*>(k_raw + src + cc * 8);
+    const uint4 khi = *reinterpret_cast<const uint4*>(k_raw + src + 64 + cc * 8);
+    vlo = *reinterpret_cast<const uint4*>(v_raw + src + cc * 8);
+    vhi = *reinterpret_cast<const uint4*>(v_raw + src + 64 + cc * 8);
+    const bool skeleton = tb.skel_pos != nullptr && sid >= n_seg - P;
+    const int32_t pos = skeleton ? tb.skel_pos[tb.skel_off[sid - (n_seg - P)] + idx] : tb.seg_pos0[sid] + idx;
+    const float4* cs = reinterpret_cast<const float4*>(tb.rope + (int64_t)pos * (D / 2) + cc * 8);
+    const uint32_t lo[4] = {klo.x, klo.y, klo.z, klo.w}, hi[4] = {khi.x, khi.y, khi.z, khi.w};
+    uint32_t olo[4], ohi[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      const float4 c4 = cs[e2];  // (cos, sin) of pairs 2*e2, 2*e2 + 1
+      float a0, b0, a1, b1;
+      hpd::rope_pair(hpd::bf16_bits_to_float(lo[e2] & 0xffffu), hpd::bf16_bits_to_float(hi[e2] & 0xffffu),
+                     c4.x, c4.y, a0, b0);
+      hpd::rope_pair(hpd::bf16_bits_to_float(lo[e2] >> 16), hpd::bf16_bits_to_float(hi[e2] >> 16),
+                     c4.z, c4.w, a1, b1);
+      olo[e2] = hpd::float_to_bf16_bits(a0) | (hpd::float_to_bf16_bits(a1) << 16);
+      ohi[e2] = hpd::float_to_bf16_bits(b0) | (hpd::float_to_bf16_bits(b1) << 16);
+    }
+    uint16_t* kd = k_prefix + ((int64_t)h * NP + slot) * D;
+    *reinterpret_cast<uint4*>(kd + cc * 8) = make_uint4(olo[0], olo[1], olo[2], olo[3]);
+    *reinterpret_cast<uint4*>(kd + 64 + cc * 8) = make_uint4(ohi[0], ohi[1], ohi[2], ohi[3]);
+  }
+  *reinterpret_cast<uint4*>(&vt[wave][r][cc * 8]) = vlo;
+  *reinterpret_cast<uint4*>(&vt[wave][r][64 + cc * 8]) = vhi;
+  __syncthreads();
+  uint16_t* vd = v_prefix + (((int64_t)h * (NP / 8) + (int64_t)blk * 4 + wave) * D) * 8;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int c = half * 64 + lane;
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2)
+      w[e2] = (uint32_t)vt[wave][2 * e2][c] | ((uint32_t)vt[wave][2 * e2 + 1][c] << 16);
+    *reinterpret_cast<uint4*>(vd + (int64_t)c * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
 // Zero values in the padding slots between a segment's end and the next multiple of the key
 // block: the attention kernels give those keys probability 0 and rely on 0 * V being 0.
 // One thread per (segment, kv head, padding slot, channel).
@@ -458,6 +522,14 @@ hipError_t hpd_launch_prefix_fill(const hpd_layout* L, const void* k_raw, const 
   const int64_t total = L->n_prefix_tokens * L->cfg.n_kv_heads * (L->cfg.head_dim / 2);
   if (total == 0) return hipSuccess;
   const int64_t pad_total = (int64_t)L->n_seg * L->cfg.n_kv_heads * (HPD_KEY_BLOCK - 1) * L->cfg.head_dim;
+  if (L->cfg.dtype == HPD_BF16 && L->cfg.head_dim == 128 && L->kernel_mode != 1 && L->dev.fill_blk) {
+    const int64_t items = (L->NP / HPD_KEY_BLOCK) * L->cfg.n_kv_heads;
+    if (items > 0x7fffffff) return hipErrorInvalidValue;
+    prefix_fill_bf16_128_kernel<<<dim3((unsigned)items), 256, 0, s>>>(
+        L->dev, L->n_seg, L->P, L->cfg.n_kv_heads, L->NP, L->dev.fill_blk, (const uint16_t*)k_raw,
+        (const uint16_t*)v_raw, (uint16_t*)k_prefix, (uint16_t*)v_prefix);
+    return hipGetLastError();
+  }
   if (L->cfg.dtype == HPD_F32) {
     prefix_fill_kernel<float><<<grid1d(total, 256), 256, 0, s>>>(
         L->dev, L->n_seg, L->P, L->n_prefix_tokens, L->cfg.n_kv_heads, L->cfg.head_dim, L->NP,

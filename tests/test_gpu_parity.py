@@ -528,6 +528,35 @@ def test_prefill_attention_literal_mask_bf16_all_kernels(g):
         _say(f"  worst err/rms {rel:.2e}")
 
 
+@pytest.mark.parametrize("literal", [False, True])
+def test_prefix_fill_fast_kernel_equals_general_kernel(literal):
+    """hpd_prefix_fill for bf16 / 128 channels (16-byte moves, V interleave through LDS, V padding
+    zeroed in the same pass) against the element-wise kernel (kernel_mode 1): the same bits in
+    every slot of both pools, ragged segments, empty headers, attribute-name segments."""
+    from paper_2604_26209_amd import binding as B
+    wl = W.random_workload(170 + int(literal), dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=3, p=4,
+                           j_range=(1, 4), n_range=(1, 12), h_range=(0, 70), l_range=(1, 150))
+    attr = np.random.default_rng(170).integers(1, 5, size=wl.n_branches).astype(np.int32)
+    kw = dict(pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr, mask_mode=B.HPD_MASK_PAPER) if literal else {}
+    pools = []
+    for mode in (0, 1):
+        lay = B.layout_from_workload(wl, **kw)
+        if mode:
+            B.hpd_set_kernel_mode(lay, mode)
+        n_tok = int(lay.counts()[B.HPD_C_N_PREFIX_TOKENS])
+        k_raw = W.normal_values((n_tok, wl.n_kv_heads, wl.head_dim), 1, "cuda", wl.dtype)
+        v_raw = W.normal_values((n_tok, wl.n_kv_heads, wl.head_dim), 2, "cuda", wl.dtype)
+        kp, vp, _, _ = B.alloc_pools(lay)
+        kp.fill_(3.0), vp.fill_(3.0)  # K padding is left alone by both kernels
+        B.hpd_prefix_fill(lay, k_raw, v_raw, kp, vp)
+        pools.append((kp, vp))
+    torch.cuda.synchronize()
+    _say(f"prefix fill, literal {literal}: {n_tok} tokens, {pools[0][0].numel()} pool elements")
+    assert torch.equal(pools[0][0].view(torch.int16), pools[1][0].view(torch.int16))
+    assert torch.equal(pools[0][1].view(torch.int16), pools[1][1].view(torch.int16))
+    assert bool((pools[0][0] != 3.0).any())
+
+
 def test_finetune_mask_and_positions_bit_exact():
     """hpd_finetune_mask (Section 5) against the loop oracle: mask and position IDs."""
     from oracle import finetune_mask as F
