@@ -18,7 +18,10 @@
  *     small tables inside hpd_layout.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Per-step
  *     calls only enqueue work; they never synchronise or allocate (the two exceptions say
- *     so where they are declared: the first hpd_dynamic_begin of a layout, hpd_dynamic_read).
+ *     so where they are declared: the first hpd_dynamic_begin of a layout, hpd_dynamic_read),
+ *     and they enqueue kernels only (no memset or copy nodes): a decode pass may be captured
+ *     in a HIP graph and replayed.  The host-side step counter of the hpd_dynamic_* calls
+ *     advances at capture time, not at replay.
  *   - Every function returns HPD_OK (0) or a negative HPD_E_* code; on error no output
  *     is written.  No exception or abort crosses this boundary.
  *   - Global ids: prompts p in [0,P); documents d in CSR order (p, j); branches b in

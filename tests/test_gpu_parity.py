@@ -331,6 +331,58 @@ def test_paged_tails_random_sweep(seed):
     H.check_all(wl, hip, label=f"paged_sweep_{seed}")
 
 
+@pytest.mark.parametrize("dynamic", [False, True])
+def test_decode_pass_replayed_from_a_hip_graph(dynamic):
+    """The step calls only enqueue kernels (no allocation, no synchronisation, no memset), so a
+    whole decode pass can be captured in a HIP graph.  The graph is replayed three times, with
+    eager work and synchronisations in between (tails cleared, outputs poisoned), and every
+    replay must reproduce the eager pass bit for bit."""
+    from paper_2604_26209_amd import binding as B
+    wl = W.random_workload(180, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=9, p=3,
+                           j_range=(1, 3), n_range=(1, 10), h_range=(0, 60), l_range=(1, 150))
+    ref = H.run_hip(wl, fused=True)
+    inputs = ref["inputs"]
+    lay = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32)
+    kp, vp, kt, vt = B.alloc_pools(lay)
+    kp.zero_(), vp.zero_()
+    B.hpd_prefix_fill(lay, inputs.k_raw, inputs.v_raw, kp, vp)
+    n_live = lay.n_live()
+    outs = [torch.zeros((int(n_live[t]), wl.n_q_heads, wl.head_dim), dtype=torch.float32, device="cuda")
+            for t in range(wl.max_new)]
+    fins = [torch.from_numpy((wl.branch_len[np.nonzero(wl.branch_len > t)[0]] == t + 1).astype(np.uint8)).cuda()
+            for t in range(wl.max_new)]
+
+    def one_pass():
+        if dynamic:
+            B.hpd_dynamic_begin(lay)
+        for t in range(wl.max_new):
+            if int(n_live[t]) == 0:
+                break
+            a = (lay, t, inputs.q[t], inputs.k_new[t], inputs.v_new[t], kp, vp, kt, vt, outs[t])
+            (B.hpd_dynamic_step if dynamic else B.hpd_decode_step)(*a)
+            if dynamic and t + 1 < wl.max_new and int(n_live[t + 1]) > 0:
+                B.hpd_dynamic_prune(lay, fins[t])
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        one_pass()  # also the first hpd_dynamic_begin, which allocates and synchronises
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        one_pass()
+    for rep in range(3):
+        kt.fill_(float("nan")), vt.fill_(float("nan"))
+        for o in outs:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for t in range(wl.max_new):
+            assert torch.equal(outs[t], ref["out"][t]), f"replay {rep} step {t}: differs from the eager pass"
+
+
 def test_paged_tails_refused_under_the_literal_mask():
     from paper_2604_26209_amd import binding as B
     wl = W.random_workload(142, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=4, p=1)
