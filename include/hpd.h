@@ -265,7 +265,8 @@ int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, u
  * are built on the GPU from a per-row "finished" flag; the host never reads them back (its
  * launches cover every document; a document without live branches costs a workgroup that
  * exits at its descriptor).  Block mask and the streaming kernel's shapes only (bf16,
- * head_dim 128, group size 1, 2, 4 or 8), at most 65536 branches; else HPD_E_UNSUPPORTED.
+ * head_dim 128, at most 8 query heads per kv head), at most 65536 branches; else
+ * HPD_E_UNSUPPORTED.
  *
  * hpd_dynamic_begin - allocates the device-side state on first use (it lives as long as the
  *   layout) and resets it: every branch live.  branch_len is ignored by the dynamic calls.

@@ -108,6 +108,7 @@ using NarrowShape = Shape<3, 1, 1>;
 struct StreamArgs {
   hpd_dev_tables tb;
   int32_t step, Hq, Hkv, Tcap, RG, n_groups, out_f32, fused, live_base;
+  int32_t Gr;  // query heads per kv head; the kernel's G is the next power of two (padding rows are neither loaded nor stored)
   int64_t NP;
   float scale_log2;
 };
@@ -532,8 +533,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     qv[b] = make_uint4(0, 0, 0, 0);
     const int32_t i = wave + b * CWAVES;
     const int32_t urow = first_blk * 32 + min(i * 4 + r4, rows_here - 1);  // row within the unit
-    const int64_t off = ((int64_t)(row0_live + urow / G) * a.Hq + hk * G + urow % G) * D;
-    if (i * 4 < rows_here) qv[b] = *reinterpret_cast<const uint4*>(q + off + (c16 << 3));
+    const int64_t off = ((int64_t)(row0_live + urow / G) * a.Hq + hk * a.Gr + urow % G) * D;
+    if (i * 4 < rows_here && urow % G < a.Gr) qv[b] = *reinterpret_cast<const uint4*>(q + off + (c16 << 3));
   }
   if (append_mine) new_rows = append_load(ap_first + (tid >> 3));
   float4 rope_v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -905,9 +906,9 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       for (int32_t i = 0; i < 16; ++i) {  // 2 rows per instruction
         const int32_t row = i * 2 + (lane >> 5), chunk = lane & 31;
         const int32_t lrr = rb * 32 + row;
-        if (lrr < rows_here) {
+        if (lrr < rows_here && lrr % G < a.Gr) {
           const uint4 v = mine[row * 32 + (chunk ^ row)];
-          const int64_t off = ((int64_t)(row0_live + br0 + lrr / G) * a.Hq + hk * G + lrr % G) * D + chunk * 4;
+          const int64_t off = ((int64_t)(row0_live + br0 + lrr / G) * a.Hq + hk * a.Gr + lrr % G) * D + chunk * 4;
           u4v vv = {v.x, v.y, v.z, v.w};
           __builtin_nontemporal_store(vv, reinterpret_cast<u4v*>(reinterpret_cast<float*>(out) + off));
         }
@@ -927,18 +928,18 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       for (int32_t i = 0; i < 8; ++i) {  // 4 rows per instruction
         const int32_t row = i * 4 + (lane >> 4), chunk = lane & 15;
         const int32_t lrr = rb * 32 + row;
-        if (lrr < rows_here) {
+        if (lrr < rows_here && lrr % G < a.Gr) {
           const uint4 v = mine[row * 16 + (chunk ^ (row & 15))];
-          const int64_t off = ((int64_t)(row0_live + br0 + lrr / G) * a.Hq + hk * G + lrr % G) * D + chunk * 8;
+          const int64_t off = ((int64_t)(row0_live + br0 + lrr / G) * a.Hq + hk * a.Gr + lrr % G) * D + chunk * 8;
           u4v vv = {v.x, v.y, v.z, v.w};
           __builtin_nontemporal_store(vv, reinterpret_cast<u4v*>(reinterpret_cast<uint16_t*>(out) + off));
         }
       }
     }
-  } else if (row_valid) {
+  } else if (row_valid && lr % G < a.Gr) {
     // key groups: a wave owns some d-blocks of its rows; a lane stores 4 consecutive channels at a time
     const int32_t live_row = row0_live + br0 + lr / G;
-    const int64_t o_off = ((int64_t)live_row * a.Hq + hk * G + lr % G) * D + g2 * 4;
+    const int64_t o_off = ((int64_t)live_row * a.Hq + hk * a.Gr + lr % G) * D + g2 * 4;
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
       if (owner(blk) == kg) {
@@ -979,7 +980,7 @@ bool hpd_stream_supported(const hpd_layout* L) {
     for (int32_t p = 0; p < L->P; ++p)
       if (L->pblk_ptr[p + 1] - L->pblk_ptr[p] > 512) return false;
   }
-  return L->cfg.dtype == HPD_BF16 && L->cfg.head_dim == D && (G == 1 || G == 2 || G == 4 || G == 8);
+  return L->cfg.dtype == HPD_BF16 && L->cfg.head_dim == D && G >= 1 && G <= 8;
 }
 
 hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const void* q,
@@ -989,7 +990,8 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
   StreamArgs a;
   a.tb = L->dev;
   a.step = step; a.Hq = L->cfg.n_q_heads; a.Hkv = L->cfg.n_kv_heads;
-  const int G = a.Hq / a.Hkv;
+  a.Gr = a.Hq / a.Hkv;
+  const int G = a.Gr <= 2 ? a.Gr : a.Gr <= 4 ? 4 : 8;  // the kernel's rows per branch
   a.Tcap = L->T; a.NP = L->NP;
   a.out_f32 = L->cfg.out_dtype == HPD_OUT_F32 ? 1 : 0;
   a.fused = (k_new != nullptr) ? 1 : 0;
@@ -1045,7 +1047,8 @@ hipError_t hpd_launch_prefill_stream(const hpd_layout* L, const void* q, const v
   StreamArgs a;
   a.tb = L->dev;
   a.step = 0; a.Hq = L->cfg.n_q_heads; a.Hkv = L->cfg.n_kv_heads;
-  const int G = a.Hq / a.Hkv;
+  a.Gr = a.Hq / a.Hkv;
+  const int G = a.Gr <= 2 ? a.Gr : a.Gr <= 4 ? 4 : 8;  // the kernel's rows per token
   a.Tcap = L->T; a.NP = L->NP;
   a.out_f32 = L->cfg.out_dtype == HPD_OUT_F32 ? 1 : 0;
   a.fused = 0;

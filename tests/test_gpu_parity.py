@@ -93,6 +93,31 @@ def test_random_layout_sweep_stream_kernel(seed):
         H.check_all(wl, hip, label=f"sweep_{seed}_m{mode}")
 
 
+@pytest.mark.parametrize("g", [3, 5, 6, 7])
+def test_stream_kernel_group_sizes_that_are_not_powers_of_two(g):
+    """Group sizes such as 40 query heads over 8 kv heads (5) run on the streaming kernel with
+    the rows of a branch padded to the next power of two; padding rows are neither loaded nor
+    stored.  Decode (both masks, fused = two-call) and prefill, both workgroup shapes."""
+    rng = np.random.default_rng(190 + g)
+    hkv = int(rng.choice([1, 2]))
+    wl = W.random_workload(190 + g, dtype="bf16", hq=hkv * g, hkv=hkv, d=128, base=500000.0,
+                           t=int(rng.integers(2, 20)), p=3, j_range=(1, 3), n_range=(1, 30),
+                           h_range=(0, 100), l_range=(1, 300))
+    attr = rng.integers(1, 5, size=wl.n_branches).astype(np.int32)
+    from paper_2604_26209_amd import binding as B
+    for paper in (False, True):
+        kw = dict(pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr, mask_mode=B.HPD_MASK_PAPER) if paper else {}
+        okw = dict(pos_mode="paper_gap", attr_len=attr, mask_mode="paper") if paper else {}
+        for mode in (3, 4):
+            _say(f"G={g} Hkv={hkv} T={wl.max_new} branches={wl.n_branches} literal={paper} mode {mode}")
+            a = H.run_hip(wl, kernel_mode=mode, fused=True, **kw)
+            H.check_all(wl, a, label=f"g{g}_m{mode}", **okw)
+            b = H.run_hip(wl, inputs=a["inputs"], kernel_mode=mode, fused=False, **kw)
+            for x, y in zip(a["out"], b["out"]):
+                assert torch.equal(x, y)
+            _check_prefill(wl, mode, f"g{g}_prefill_m{mode}", attr_len=attr if paper else None)
+
+
 @pytest.mark.parametrize("seed,kw", [(120, dict(hq=8, hkv=2, p=3, j_range=(1, 4), n_range=(1, 14), l_range=(1, 200))),
                                      (121, dict(hq=8, hkv=8, p=2, j_range=(2, 3), n_range=(3, 40), l_range=(1, 90))),
                                      (122, dict(hq=16, hkv=2, p=2, j_range=(1, 2), n_range=(1, 30), l_range=(30, 300)))])
