@@ -264,9 +264,11 @@ int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, u
  * the calls below the live list of the next step and the work lists of the attention kernel
  * are built on the GPU from a per-row "finished" flag; the host never reads them back (its
  * launches cover every document; a document without live branches costs a workgroup that
- * exits at its descriptor).  Block mask and the streaming kernel's shapes only (bf16,
- * head_dim 128, at most 8 query heads per kv head), at most 65536 branches; else
- * HPD_E_UNSUPPORTED.
+ * exits at its descriptor; under HPD_MASK_PAPER the units are prompts, and the device also
+ * keeps how many tokens every branch that has left had reached, since the later branches
+ * still see them).  The streaming kernel's shapes only (bf16, head_dim 128, at most 8 query
+ * heads per kv head; under HPD_MASK_PAPER at most 256 branches per prompt), at most 65536
+ * branches; else HPD_E_UNSUPPORTED.
  *
  * hpd_dynamic_begin - allocates the device-side state on first use (it lives as long as the
  *   layout) and resets it: every branch live.  branch_len is ignored by the dynamic calls.

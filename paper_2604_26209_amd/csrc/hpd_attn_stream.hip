@@ -1010,6 +1010,12 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
     a.live_base = 0;
     n_units = L->n_docs;
     max_nblk = std::max(1, (L->max_doc_branches * G + 31) / 32);
+    if (paper) {  // units are prompts; a finished branch stays visible as far as it got
+      a.tb.punit_desc = L->dyn_desc;
+      a.tb.branch_len = L->dyn_len;
+      n_units = L->P;
+      max_nblk = std::max(1, (L->max_prompt_branches * G + 31) / 32);
+    }
   }
   // row groups per unit, and with them the number of workgroups, for the two shapes
   const int32_t rg_wide = (max_nblk + WideShape::MAX_BLOCKS - 1) / WideShape::MAX_BLOCKS;

@@ -672,8 +672,7 @@ int hpd_expand_mask(const hpd_layout* L, int32_t prompt, int32_t step_hi, uint8_
 
 static int dynamic_supported(const hpd_layout* L) {
   if (!L || !L->on_device) return HPD_E_INVALID;
-  if (L->cfg.mask_mode != HPD_MASK_BLOCK || !hpd_stream_supported(L) || L->kernel_mode == 1 || L->B > 65536)
-    return HPD_E_UNSUPPORTED;
+  if (!hpd_stream_supported(L) || L->kernel_mode == 1 || L->B > 65536) return HPD_E_UNSUPPORTED;
   return HPD_OK;
 }
 
@@ -682,32 +681,43 @@ int hpd_dynamic_begin(hpd_layout* L, void* stream) {
   if (rc != HPD_OK) return rc;
   hipStream_t s = (hipStream_t)stream;
   if (!L->d_dyn) {
-    // desc [n_docs*8], fixed [n_docs*8] (both read and written 16 bytes at a time), n_live [4], live [B]
-    const size_t nB = (size_t)L->B, nD = (size_t)L->n_docs;
-    const size_t words = nD * 8 + nD * 8 + 4 + nB + 16;
+    // desc [units*8 | 16], fixed [units*8] (both read and written 16 bytes at a time), n_live [4],
+    // live [B], and for the literal mask len [B]; units = documents, or prompts under the literal mask
+    const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
+    const size_t nB = (size_t)L->B, nU = paper ? (size_t)L->P : (size_t)L->n_docs, dw = paper ? 16 : 8;
+    const size_t words = nU * dw + nU * 8 + 4 + nB + (paper ? nB : 0) + 16;
     HPD_HIP(hipMalloc(&L->d_dyn, words * sizeof(int32_t)));
     int32_t* w = (int32_t*)L->d_dyn;
-    L->dyn_desc = w; w += nD * 8;
-    L->dyn_fixed_dev = w; w += nD * 8;
+    L->dyn_desc = w; w += nU * dw;
+    L->dyn_fixed_dev = w; w += nU * 8;
     L->dyn_n_live = w; w += 4;
-    L->dyn_live = w;
-    // what never changes, one record per document, the documents with the most keys first:
-    // {hoff, Hlen, doff, Llen, first branch, end of branches, position of step 0 | -1, 0}
-    std::vector<int32_t> order(nD);
+    L->dyn_live = w; w += nB;
+    L->dyn_len = paper ? w : nullptr;
+    // what never changes, one record per unit, the units with the most keys first.  Documents:
+    // {hoff, Hlen, doff, Llen, first branch, end of branches, position of step 0 | -1, 0};
+    // prompts: {hoff, Hlen, first entry of the block list, its blocks, first branch, end of branches, 0, 0}
+    std::vector<int32_t> order(nU);
     std::iota(order.begin(), order.end(), 0);
     std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+      if (paper) return L->pblk_ptr[x + 1] - L->pblk_ptr[x] > L->pblk_ptr[y + 1] - L->pblk_ptr[y];
       return (int64_t)L->seg_len[L->doc_prompt[x]] + L->seg_len[L->P + x] >
              (int64_t)L->seg_len[L->doc_prompt[y]] + L->seg_len[L->P + y];
     });
-    L->dyn_fixed.assign(nD * 8, 0);
-    for (size_t u = 0; u < nD; ++u) {
-      const int32_t d = order[u], p = L->doc_prompt[d];
+    L->dyn_fixed.assign(nU * 8, 0);
+    for (size_t u = 0; u < nU; ++u) {
       int32_t* o = L->dyn_fixed.data() + u * 8;
-      o[0] = L->seg_off[p]; o[1] = L->seg_len[p]; o[2] = L->seg_off[L->P + d]; o[3] = L->seg_len[L->P + d];
-      o[4] = L->doc_branch_ptr[d]; o[5] = L->doc_branch_ptr[d + 1];
-      o[6] = L->cfg.pos_mode == HPD_POS_CONTIG ? L->seg_len[p] + L->seg_len[L->P + d] : -1;
+      if (paper) {
+        const int32_t p = order[u];
+        o[0] = L->seg_off[p]; o[1] = L->seg_len[p]; o[2] = L->pblk_ptr[p]; o[3] = L->pblk_ptr[p + 1] - L->pblk_ptr[p];
+        o[4] = L->prompt_branch_ptr[p]; o[5] = L->prompt_branch_ptr[p + 1];
+      } else {
+        const int32_t d = order[u], p = L->doc_prompt[d];
+        o[0] = L->seg_off[p]; o[1] = L->seg_len[p]; o[2] = L->seg_off[L->P + d]; o[3] = L->seg_len[L->P + d];
+        o[4] = L->doc_branch_ptr[d]; o[5] = L->doc_branch_ptr[d + 1];
+        o[6] = L->cfg.pos_mode == HPD_POS_CONTIG ? L->seg_len[p] + L->seg_len[L->P + d] : -1;
+      }
     }
-    hipError_t e = hipMemcpyAsync(L->dyn_fixed_dev, L->dyn_fixed.data(), nD * 8 * sizeof(int32_t),
+    hipError_t e = hipMemcpyAsync(L->dyn_fixed_dev, L->dyn_fixed.data(), nU * 8 * sizeof(int32_t),
                                   hipMemcpyHostToDevice, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);  // the copy has left the host vector
     if (e != hipSuccess) {

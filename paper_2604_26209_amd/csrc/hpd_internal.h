@@ -89,7 +89,8 @@ struct hpd_layout {
   std::vector<int32_t> dyn_fixed;       // [n_docs][8] per-document constants of the descriptors, heaviest first
   int32_t max_doc_branches = 0;
   void* d_dyn = nullptr;
-  int32_t *dyn_live = nullptr, *dyn_n_live = nullptr, *dyn_desc = nullptr, *dyn_fixed_dev = nullptr;
+  int32_t *dyn_live = nullptr, *dyn_n_live = nullptr, *dyn_desc = nullptr, *dyn_fixed_dev = nullptr,
+          *dyn_len = nullptr;  // literal mask: tokens every branch has reached (the step budget while it runs)
   int32_t dyn_next_step = 0;  // the step the device state describes (host-side counter)
 
   bool on_device = false;

@@ -212,13 +212,18 @@ __global__ void expand_mask_kernel(const int32_t* __restrict__ desc, int32_t S, 
 // {hoff, Hlen, doff, Llen, first branch, end of branches, position of step 0 | -1, 0} per
 // document.  The liveness of every branch is kept in LDS, one byte each, for the length of
 // the kernel; nothing the kernel writes to global memory is read back.
+// Literal mask (`len` given): the units are prompts - `fixed` holds {hoff, Hlen, first entry
+// of the prompt's block list, its blocks, first branch, end of branches, 0, 0} and a descriptor
+// has 16 words, as the host builds them - and since a finished branch stays visible to the
+// later ones, the number of tokens it reached is kept in `len` (the step budget while it runs).
 // ---------------------------------------------------------------------------------------
 constexpr int PRUNE_THREADS = 1024;
 constexpr int PRUNE_MAX_BRANCHES = 65536;
 __global__ void __launch_bounds__(PRUNE_THREADS)
 dynamic_prune_kernel(int32_t n_docs, int32_t B, int32_t next_step, const uint8_t* __restrict__ finished,
                      const int4* __restrict__ fixed, int32_t* __restrict__ live,
-                     int32_t* __restrict__ n_live, int4* __restrict__ desc) {
+                     int32_t* __restrict__ n_live, int4* __restrict__ desc, int32_t* __restrict__ len,
+                     int32_t Tcap) {
   __shared__ uint32_t al_words[PRUNE_MAX_BRANCHES / 4];
   __shared__ int32_t pex[PRUNE_THREADS];   // branches alive before each thread's run
   __shared__ int32_t wsum[PRUNE_THREADS / 64];
@@ -244,11 +249,15 @@ dynamic_prune_kernel(int32_t n_docs, int32_t B, int32_t next_step, const uint8_t
         lb[k] = r < n_prev ? live[r] : 0;
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k)
+      for (int k = 0; k < 8; ++k) {
         if (!f[k]) al[lb[k]] = 1;
+        else if (len && r0 + k * PRUNE_THREADS < n_prev) len[lb[k]] = next_step;  // tokens 0 .. next_step-1 exist
+      }
     }
     __syncthreads();  // the old list has been read; it is overwritten below
   }
+  if (!finished && len)
+    for (int32_t b = tid; b < B; b += PRUNE_THREADS) len[b] = Tcap;
   // 2. exclusive prefix sums over the branches: thread t owns a run of `chunk` branches; the
   //    run sums are scanned inside each wave, the 16 wave sums by every thread for itself
   const int32_t chunk = (B + PRUNE_THREADS - 1) / PRUNE_THREADS;
@@ -296,8 +305,19 @@ dynamic_prune_kernel(int32_t n_docs, int32_t B, int32_t next_step, const uint8_t
       while (!al[y]) --y;
       if (y - x == nb - 1) b_first = x;
     }
-    desc[2 * u] = fx0;
-    desc[2 * u + 1] = make_int4(first, nb, fx1.z >= 0 ? fx1.z + next_step : -1, b_first);
+    if (!len) {
+      desc[2 * u] = fx0;
+      desc[2 * u + 1] = make_int4(first, nb, fx1.z >= 0 ? fx1.z + next_step : -1, b_first);
+    } else {
+      // {hoff, Hlen, list entry, blocks | first live row, live branches, first branch of the
+      //  prompt, first live branch if consecutive | key branches: first .. last live | 0}
+      int32_t y = hi - 1;
+      while (nb > 0 && !al[y]) --y;
+      desc[4 * u] = fx0;
+      desc[4 * u + 1] = make_int4(first, nb, lo, b_first);
+      desc[4 * u + 2] = make_int4(nb > 0 ? y - lo + 1 : 0, 0, 0, 0);
+      desc[4 * u + 3] = make_int4(0, 0, 0, 0);
+    }
   }
 }
 
@@ -656,8 +676,9 @@ hipError_t hpd_launch_finetune_mask(const int32_t* d_desc, int32_t S, int32_t* p
 
 hipError_t hpd_launch_dynamic_prune(const hpd_layout* L, int32_t next_step, const uint8_t* finished,
                                     hipStream_t s) {
-  dynamic_prune_kernel<<<1, PRUNE_THREADS, 0, s>>>(L->n_docs, L->B, next_step, finished,
+  const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
+  dynamic_prune_kernel<<<1, PRUNE_THREADS, 0, s>>>(paper ? L->P : L->n_docs, L->B, next_step, finished,
                                                    (const int4*)L->dyn_fixed_dev, L->dyn_live, L->dyn_n_live,
-                                                   (int4*)L->dyn_desc);
+                                                   (int4*)L->dyn_desc, paper ? L->dyn_len : nullptr, L->T);
   return hipGetLastError();
 }

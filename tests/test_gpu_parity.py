@@ -160,21 +160,26 @@ def test_device_side_pruning_equals_host_lists(seed, kw):
         B.hpd_dynamic_step(lay, 0, inputs.q[0], inputs.k_new[0], inputs.v_new[0], kp, vp, kt, vt, out)  # wrong step
 
 
+@pytest.mark.parametrize("literal", [False, True])
 @pytest.mark.parametrize("seed", [130, 131])
-def test_device_side_pruning_with_lengths_unknown_to_the_layout(seed):
+def test_device_side_pruning_with_lengths_unknown_to_the_layout(seed, literal):
     """The use the entry points exist for: the layout is built with every branch at the full
     step budget (nobody knows yet where a branch ends), and branches leave when the caller
     flags them (the stop condition of Section 4.3.4).  With flags taken from a hidden
     length per branch, every step must match the oracle run on the workload that has those
-    lengths."""
+    lengths.  Under the literal mask a branch that has left stays visible to the later ones
+    as far as it got: the device keeps the number of tokens it reached."""
     import dataclasses
     from paper_2604_26209_amd import binding as B
     wl = W.random_workload(seed, dtype="bf16", d=128, base=500000.0, t=9, hq=8, hkv=2, p=3,
                            j_range=(1, 3), n_range=(1, 20), l_range=(1, 260), h_range=(0, 50))
     cap = dataclasses.replace(wl, branch_len=np.full(wl.n_branches, wl.max_new, dtype=np.int32))
-    ref = H.run_hip(wl, fused=True)  # for the inputs, positions and slots of the hidden lengths
+    attr = np.random.default_rng(seed).integers(1, 5, size=wl.n_branches).astype(np.int32)
+    kw = dict(pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr, mask_mode=B.HPD_MASK_PAPER) if literal else {}
+    okw = dict(pos_mode="paper_gap", attr_len=attr, mask_mode="paper") if literal else {}
+    ref = H.run_hip(wl, fused=True, **kw)  # for the inputs, positions and slots of the hidden lengths
     inputs = ref["inputs"]
-    lay = B.layout_from_workload(cap, out_dtype=B.HPD_OUT_F32)
+    lay = B.layout_from_workload(cap, out_dtype=B.HPD_OUT_F32, **kw)
     kp, vp, kt, vt = B.alloc_pools(lay)
     B.hpd_prefix_fill(lay, inputs.k_raw, inputs.v_raw, kp, vp)
     B.hpd_dynamic_begin(lay)
@@ -193,7 +198,7 @@ def test_device_side_pruning_with_lengths_unknown_to_the_layout(seed):
             B.hpd_dynamic_prune(lay, torch.from_numpy(fin).cuda())
     hip = dict(ref)
     hip["out"] = outs
-    H.check_all(wl, hip, label=f"dynamic_{seed}")
+    H.check_all(wl, hip, label=f"dynamic_{seed}", **okw)
 
 
 class _PageAllocator:
