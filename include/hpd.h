@@ -308,11 +308,12 @@ int hpd_dynamic_read(const hpd_layout* layout, int32_t* live_host, int32_t capac
  *                i*page_size .. (i+1)*page_size - 1 before the first call for such a step in
  *                which b is live, and must not change while b is live; entries of pages a branch
  *                has not reached, and those of branches that are no longer live, are not read.
+ *                (Under HPD_MASK_PAPER the later branches of a prompt keep reading the tokens of
+ *                a branch that has left: its pages stay until the prompt's last branch has left.)
  *                The kernels clamp an entry to [0, n_pages) instead of trusting it.
  * Affects hpd_kv_append (slot_out reports page * page_size + t % page_size), hpd_decode_attention,
  * hpd_decode_step and hpd_dynamic_step of this layout from the next call on, and the tail
- * sizes HPD_Q_POOL_BYTES reports.  Host-side only: nothing is enqueued.  HPD_MASK_PAPER
- * layouts read the tails of finished branches as well and are refused (HPD_E_UNSUPPORTED).
+ * sizes HPD_Q_POOL_BYTES reports.  Host-side only: nothing is enqueued.
  */
 int hpd_set_tail_pages(hpd_layout* layout, int32_t page_size, int32_t n_pages, const int32_t* page_table);
 

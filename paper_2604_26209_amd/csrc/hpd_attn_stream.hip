@@ -392,12 +392,13 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         int32_t posC = min(tc * 8 + r4, lastB), posD = min(tc * 8 + 4 + r4, lastB);
         const uint16_t* pool = is_k ? k_tail : v_tail;
         const uint16_t *rowA, *rowB;
-        if constexpr (PAGED) {
+        if (PAGED || (PAPER && a.tb.tail_pages)) {
           // a page holds a multiple of 8 steps, so the 8 positions of the tile (clamped to the
-          // current step, which lies in or behind them) share one page per branch
-          const int32_t pi = (tc * 8) >> a.tb.page_shift, pmask = (1 << a.tb.page_shift) - 1;
-          int32_t pgA = scalar_load(a.tb.tail_pages + (int64_t)bA * a.tb.pages_per_branch + pi);
-          int32_t pgB = scalar_load(a.tb.tail_pages + (int64_t)bB * a.tb.pages_per_branch + pi);
+          // newest row of the branch, which lies in or behind them) share one page per branch
+          const int32_t pmask = (1 << a.tb.page_shift) - 1;
+          const int32_t piA = min(tc * 8, lastA) >> a.tb.page_shift, piB = min(tc * 8, lastB) >> a.tb.page_shift;
+          int32_t pgA = scalar_load(a.tb.tail_pages + (int64_t)bA * a.tb.pages_per_branch + piA);
+          int32_t pgB = scalar_load(a.tb.tail_pages + (int64_t)bB * a.tb.pages_per_branch + piB);
           pgA = min(max(pgA, 0), a.tb.n_pages - 1);
           pgB = min(max(pgB, 0), a.tb.n_pages - 1);
           rowA = pool + ((((int64_t)pgA * a.Hkv + hk)) << a.tb.page_shift) * D;
@@ -454,7 +455,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     float rl[8], rh[8];
     if (use_rope_q) rotate16(r.klo, r.khi, reinterpret_cast<const float2*>(rope_q), ap_c, rl, rh);
     else rotate16(r.klo, r.khi, a.tb.rope + (int64_t)pos * (D / 2), ap_c, rl, rh);
-    const int64_t trow = (PAGED ? hpd_tail_row(a.tb, b, hk, a.Hkv, a.Tcap, a.step)
+    const int64_t trow = ((PAGED || PAPER) ? hpd_tail_row(a.tb, b, hk, a.Hkv, a.Tcap, a.step)
                                 : ((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
     uint16_t* kd = k_tail + trow;
     *reinterpret_cast<uint4*>(kd + ap_c) = __builtin_bit_cast(uint4, pack8(rl));

@@ -783,7 +783,6 @@ int hpd_set_tail_pages(hpd_layout* L, int32_t page_size, int32_t n_pages, const 
     return HPD_OK;
   }
   if (page_size < 8 || (page_size & (page_size - 1)) != 0 || n_pages < 1 || !page_table) return HPD_E_INVALID;
-  if (L->cfg.mask_mode != HPD_MASK_BLOCK) return HPD_E_UNSUPPORTED;
   if ((int64_t)n_pages * page_size > ((int64_t)1 << 40)) return HPD_E_OVERFLOW;
   int32_t shift = 0;
   while ((1 << shift) < page_size) ++shift;

@@ -413,15 +413,55 @@ def test_decode_pass_replayed_from_a_hip_graph(dynamic):
             assert torch.equal(outs[t], ref["out"][t]), f"replay {rep} step {t}: differs from the eager pass"
 
 
-def test_paged_tails_refused_under_the_literal_mask():
+@pytest.mark.parametrize("dynamic", [False, True])
+def test_paged_tails_under_the_literal_mask(dynamic):
+    """Under HPD_MASK_PAPER a branch that has left is still read by the later branches of its
+    prompt, so its pages stay; the pools still hold only the pages that were ever reached.
+    Paged step calls (host lists / device-side lists) against the contiguous ones."""
     from paper_2604_26209_amd import binding as B
-    wl = W.random_workload(142, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=4, p=1)
-    attr_len = np.ones(wl.n_branches, dtype=np.int32)
-    lay = B.layout_from_workload(wl, pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr_len, mask_mode=B.HPD_MASK_PAPER)
-    table = torch.zeros((wl.n_branches, 1), dtype=torch.int32, device="cuda")
-    with pytest.raises(B.HpdError) as e:
-        B.hpd_set_tail_pages(lay, 8, 4, table)
-    assert e.value.status == B.HPD_E_UNSUPPORTED
+    wl = W.random_workload(143 + int(dynamic), dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=20, p=3,
+                           j_range=(1, 3), n_range=(1, 12), h_range=(0, 60), l_range=(1, 150))
+    attr = np.random.default_rng(143).integers(1, 5, size=wl.n_branches).astype(np.int32)
+    kw = dict(pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr, mask_mode=B.HPD_MASK_PAPER)
+    ref = H.run_hip(wl, fused=True, **kw)
+    inputs = ref["inputs"]
+    lay = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32, **kw)
+    ps = 8
+    ppb = -(-wl.max_new // ps)
+    need = int(np.sum(-(-wl.branch_len // ps)))  # pages ever reached
+    assert need < wl.n_branches * ppb
+    order = list(np.random.default_rng(5).permutation(need))
+    table_h = np.full((wl.n_branches, ppb), -7, dtype=np.int32)
+    table = torch.from_numpy(table_h).cuda()
+    B.hpd_set_tail_pages(lay, ps, need, table)
+    kp, vp, kt, vt = B.alloc_pools(lay)
+    for x in (kp, vp, kt, vt):
+        x.fill_(float("nan"))
+    B.hpd_prefix_fill(lay, inputs.k_raw, inputs.v_raw, kp, vp)
+    if dynamic:
+        B.hpd_dynamic_begin(lay)
+    outs = []
+    for t in range(wl.max_new):
+        live = np.nonzero(wl.branch_len > t)[0]
+        if t % ps == 0:
+            for b in live:
+                table_h[b, t // ps] = order.pop()
+            table.copy_(torch.from_numpy(table_h))
+        out = torch.full((len(live), wl.n_q_heads, wl.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+        if len(live):
+            a = (lay, t, inputs.q[t], inputs.k_new[t], inputs.v_new[t], kp, vp, kt, vt, out)
+            (B.hpd_dynamic_step if dynamic else B.hpd_decode_step)(*a)
+            if not dynamic:
+                assert torch.equal(out, ref["out"][t]), f"step {t}: paged and contiguous outputs differ"
+        outs.append(out)
+        if dynamic and t + 1 < wl.max_new:
+            fin = (wl.branch_len[live] == t + 1).astype(np.uint8) if len(live) else np.zeros(1, np.uint8)
+            B.hpd_dynamic_prune(lay, torch.from_numpy(fin).cuda())
+        torch.cuda.synchronize()
+    assert not order
+    hip = dict(ref)
+    hip["out"] = outs
+    H.check_all(wl, hip, label="paged_literal", pos_mode="paper_gap", attr_len=attr, mask_mode="paper")
 
 
 def test_bf16_output_is_the_fp32_output_rounded_once():
