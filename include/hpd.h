@@ -144,7 +144,9 @@ enum hpd_count {
   HPD_C_N_PREFIX_TOKENS = 3, /* header + document (+ skeleton) tokens, unpadded */
   HPD_C_N_PREFIX_SLOTS = 4,  /* NP */
   HPD_C_N_TAIL_SLOTS = 5,    /* B * T */
-  HPD_C_MAX_POS = 6,         /* largest position ID any token can take */
+  HPD_C_MAX_POS = 6,         /* largest position ID any token can take within the step budget
+                                (base position + max_new, whatever branch_len says: the
+                                hpd_dynamic_* calls may decode a branch up to step max_new - 1) */
   HPD_C_TOTAL_LIVE = 7,      /* sum over steps of live branches = sum of branch_len */
   HPD_N_COUNTS = 8
 };
@@ -318,7 +320,7 @@ int hpd_dynamic_read(const hpd_layout* layout, int32_t* live_host, int32_t capac
 int hpd_set_tail_pages(hpd_layout* layout, int32_t page_size, int32_t n_pages, const int32_t* page_table);
 
 /*
- * hpd_finetune_mask - Section 5 ("Fine-tuning and Distillation"), Appendix A.1.  Position IDs
+ * hpd_finetune_mask - Section 4.4 ("Fine-tuning and Distillation"), Appendix A.1.  Position IDs
  * and attention mask of one training sequence in the regular token order
  *   s_train = cat(p, a_1, v_1, ..., a_N, v_N):
  * the attributes keep Algorithm 2's positions (a gap of k_max after every attribute), value

@@ -1,6 +1,6 @@
 """CPU oracle for the fine-tuning mask of Hyper-Parallel Decoding.  TEST INFRASTRUCTURE ONLY.
 
-Section 5 ("Fine-tuning and Distillation"): a training sequence holds the prompt and, in the
+Section 4.4 ("Fine-tuning and Distillation"): a training sequence holds the prompt and, in the
 regular token order, every attribute followed by its ground-truth value,
 
     s_train = cat(p, a_1, v_1, a_2, v_2, ..., a_N, v_N),

@@ -31,7 +31,7 @@ What each piece follows
   literally over the whole stacked prompt: a token sees every token of its
   prompt that is already in memory and has a position ID not larger than its
   own - all stacked documents and the value tokens of the earlier attributes
-  up to its own step (Section 5 states the same for fine-tuning: v_{n,k} may not
+  up to its own step (Section 4.4 states the same for fine-tuning: v_{n,k} may not
   see v_{n',k'} with n' < n and k' > k, so k' <= k it does see).  It needs the
   paper's own position IDs (``pos_mode="paper_gap"``): with positions that
   restart per document "position order" would mix the documents.  Under this
@@ -62,6 +62,12 @@ paper-literal mask is pinned by: equality with ordinary causal attention (librar
 routine) over all tokens in memory *sorted by position ID*, the closed-form row
 sums, an explicit set construction, reduction to the block mask for one document
 with one attribute, and its own scalar brute force.
+The bf16 key cache is pinned by: ``round_to_bf16`` against the library's float32 ->
+bfloat16 conversion bit for bit over every exponent, hand-computed ties, carries,
+subnormals and infinities; and the cached oracle against the unrounded one (only
+the stored keys differ, by exactly that conversion; outputs equal the plain
+definition over the converted keys).  Algorithm 2 is also pinned by a token-by-token
+walk along s that reserves K_max IDs behind every attribute.
 The paper-gap position mode with several stacked documents is a reading of
 this build (the paper writes Algorithm 2 for one document only); it is pinned
 by closed form only.
@@ -77,21 +83,18 @@ KIND_HEADER, KIND_DOC, KIND_BRANCH, KIND_SKELETON = 0, 1, 2, 3
 # Position IDs
 # ----------------------------------------------------------------------------
 def alg2_position_ids(prompt_len: int, attr_lens, k_max: int):
-    """Algorithm 2: position IDs of s = cat(p, a_1..a_N) with a gap of K_max
-    opened after every attribute.  Returns (pos_id[|s|], end_index[N]) where
-    end_index[n] is the index in s of the last token of attribute n."""
-    attr_lens = [int(a) for a in attr_lens]
-    s_len = int(prompt_len) + sum(attr_lens)
-    pos_id = np.arange(s_len, dtype=np.int64)
-    end_index = np.zeros(len(attr_lens), dtype=np.int64)
-    offset = 0
-    start = int(prompt_len)
-    for n, a in enumerate(attr_lens):
-        end = start + a - 1
-        pos_id[start:end + 1] += offset
-        offset += int(k_max)
-        end_index[n] = end
-        start = end + 1
+    """Position IDs of s = cat(p, a_1..a_N) with room for K_max value tokens behind
+    every attribute (Appendix A.1, Algorithm 2), in closed form: the prompt keeps
+    0 .. |p|-1, and token i (0-based) of attribute n (0-based) - whose index in s is
+    |p| + A_0 + .. + A_{n-1} + i - sits n * K_max further on, one gap for every
+    attribute in front of it.  Returns (pos_id[|s|], end_index[N]) where end_index[n]
+    is the index in s of the last token of attribute n."""
+    a = np.asarray([int(x) for x in attr_lens], dtype=np.int64)
+    first = int(prompt_len) + np.concatenate([[0], np.cumsum(a)[:-1]]).astype(np.int64)  # index in s
+    gaps_before = np.repeat(np.arange(len(a), dtype=np.int64), a)  # attribute of every skeleton token
+    pos_id = np.concatenate([np.arange(int(prompt_len), dtype=np.int64),
+                             int(prompt_len) + np.arange(int(a.sum()), dtype=np.int64) + gaps_before * int(k_max)])
+    end_index = (first + a - 1).astype(np.int64)
     return pos_id, end_index
 
 

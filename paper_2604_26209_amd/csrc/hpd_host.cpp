@@ -198,8 +198,11 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     // slack of 128 slots so that a kernel tile that starts inside the last segment never
     // leaves the pool
     L->NP = round_up(slot, HPD_KEY_BLOCK) + 128;
+    // the RoPE table covers the whole step budget of every branch, not only the steps branch_len
+    // announces: the device-side pruning calls ignore branch_len and keep a branch alive until
+    // its flag comes, at most up to step T - 1 (position base + T)
     for (int32_t b = 0; b < B; ++b)
-      max_pos = std::max<int64_t>(max_pos, (int64_t)L->branch_base_pos[b] + L->branch_len[b]);
+      max_pos = std::max<int64_t>(max_pos, (int64_t)L->branch_base_pos[b] + T);
     if (max_pos > (1 << 30)) { delete L; return HPD_E_OVERFLOW; }
     L->max_pos = (int32_t)max_pos;
 

@@ -322,7 +322,7 @@ dynamic_prune_kernel(int32_t n_docs, int32_t B, int32_t next_step, const uint8_t
 }
 
 // ---------------------------------------------------------------------------------------
-// Fine-tuning mask (Section 5).  desc[S][4] = (kind, attribute, k, position ID) in the regular
+// Fine-tuning mask (Section 4.4).  desc[S][4] = (kind, attribute, k, position ID) in the regular
 // token order; kind 0 prompt, 1 attribute, 2 value token.
 // ---------------------------------------------------------------------------------------
 __global__ void finetune_mask_kernel(const int32_t* __restrict__ desc, int32_t S,

@@ -10,6 +10,10 @@ from paper_2604_26209_amd import workloads as W
 
 F32_TOL = 1e-4  # max-abs, fp32 inputs
 BF16_TOL = 2e-2  # max-abs relative to the RMS of the reference outputs, bf16 inputs
+# bf16 inputs against the oracle WITHOUT the bf16 key cache (rotated keys kept in fp32): the
+# stored key's rounding alone moves the outputs by 2.2-3.7e-2 x RMS at the benchmark sizes,
+# whatever the kernel does; this bound keeps that distance from drifting unseen
+BF16_TOL_UNROUNDED_CACHE = 4e-2
 
 
 def torch_dtype(wl):
@@ -37,6 +41,29 @@ class Inputs:
             self.v_new.append(W.normal_values((n, wl.n_kv_heads, wl.head_dim), base + 12 + 3 * t, device, dt))
 
 
+GUARD_ELEMS = 4096   # elements in front of and behind a guarded buffer
+GUARD_BYTE = 0x5A
+
+
+def guarded(x, guards):
+    """A copy of tensor ``x`` that sits between two guard bands filled with GUARD_BYTE; the
+    bands are appended to ``guards`` for check_guards.  The view keeps x's shape and a 256-byte
+    aligned start."""
+    n = x.numel()
+    buf = torch.empty(n + 2 * GUARD_ELEMS, dtype=x.dtype, device=x.device)
+    buf.view(torch.uint8).fill_(GUARD_BYTE)
+    inner = buf[GUARD_ELEMS:GUARD_ELEMS + n].view(x.shape)
+    inner.copy_(x)
+    guards.append((buf[:GUARD_ELEMS].view(torch.uint8), buf[GUARD_ELEMS + n:].view(torch.uint8)))
+    return inner
+
+
+def check_guards(guards, label=""):
+    for i, (front, back) in enumerate(guards):
+        assert bool((front == GUARD_BYTE).all()) and bool((back == GUARD_BYTE).all()), \
+            f"{label}: a write landed next to guarded buffer {i}"
+
+
 def run_hip(wl, inputs=None, kernel_mode=0, fused=False, pos_mode=0, attr_len=None,
             poison_pools=True, steps=None, out_f32=None, mask_mode=0):
     """Runs every step through the C ABI.  Returns dict(out, pos, slot per step, layout, inputs)."""
@@ -52,6 +79,11 @@ def run_hip(wl, inputs=None, kernel_mode=0, fused=False, pos_mode=0, attr_len=No
     if inputs is None:
         inputs = Inputs(wl, n_live, "cuda", layout.counts()[B.HPD_C_N_PREFIX_TOKENS])
     kp, vp, kt, vt = B.alloc_pools(layout)
+    # guard bands in front of and behind the tail pools (and the outputs, below): a stray write of
+    # the append or of an output store next to its buffer changes them (NaN poisoning only
+    # catches stray reads)
+    guards = []
+    kt, vt = guarded(kt, guards), guarded(vt, guards)
     if poison_pools == "zero":
         for x in (kp, vp, kt, vt):
             x.zero_()
@@ -65,7 +97,7 @@ def run_hip(wl, inputs=None, kernel_mode=0, fused=False, pos_mode=0, attr_len=No
         n = int(n_live[t])
         pos = torch.full((max(n, 1),), -1, dtype=torch.int32, device="cuda")
         slot = torch.full((max(n, 1),), -1, dtype=torch.int64, device="cuda")
-        out = torch.full((n, wl.n_q_heads, wl.head_dim), float("nan"), dtype=dt, device="cuda")
+        out = guarded(torch.full((n, wl.n_q_heads, wl.head_dim), float("nan"), dtype=dt, device="cuda"), guards)
         got = B.hpd_rope_positions(layout, t, pos)
         assert got == n
         if fused:
@@ -77,6 +109,7 @@ def run_hip(wl, inputs=None, kernel_mode=0, fused=False, pos_mode=0, attr_len=No
         outs.append(out)
         poss.append(pos[:n])
         slots.append(slot[:n])
+        check_guards(guards, f"{wl.name} step {t}")
     torch.cuda.synchronize()
     return {"out": outs, "pos": poss, "slot": slots, "layout": layout, "inputs": inputs,
             "pools": (kp, vp, kt, vt), "n_live": n_live}
@@ -162,4 +195,23 @@ def check_all(wl, hip, prompts=None, pos_mode="contig", attr_len=None, label="",
             assert np.array_equal(hip["slot"][t][ridx].cpu().numpy(), ref["slot"]), \
                 f"{label} step {t}: slots differ"
         worst = max(worst, compare_outputs(wl, hip["out"][t], ref, f"{label} step {t}", group))
+    return worst
+
+
+def distance_to_unrounded_oracle(wl, hip, prompts, steps, label=""):
+    """bf16 inputs: max-abs / RMS(step) between the HIP outputs and the oracle that keeps its
+    rotated keys unrounded (fp32 cache), over the given prompts and the first ``steps`` steps.
+    Asserts BF16_TOL_UNROUNDED_CACHE and returns the worst ratio."""
+    orc, res = run_oracle(wl, hip["inputs"], prompts, steps=range(steps), cache_dtype=None)
+    worst = 0.0
+    for t, ref in enumerate(res):
+        rows = ref["rows"]
+        if len(rows) == 0:
+            continue
+        got = hip["out"][t][torch.from_numpy(rows).to(hip["out"][t].device)].float().cpu().numpy()
+        rms = float(np.sqrt(np.mean(ref["out"].astype(np.float64) ** 2)))
+        e = float(np.abs(got - ref["out"]).max()) / rms
+        assert e <= BF16_TOL_UNROUNDED_CACHE, \
+            f"{label} step {t}: {e:.3e} x RMS from the fp32-cache oracle > {BF16_TOL_UNROUNDED_CACHE}"
+        worst = max(worst, e)
     return worst

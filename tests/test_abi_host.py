@@ -199,3 +199,19 @@ def test_host_tables_under_the_literal_mask():
         b0, b1 = orc.branch_range[p]
         assert list(base[b0:b1]) == po.base_pos
         assert po.skeleton_pos[-1] == po.base_pos[-1]
+
+
+def test_rope_table_covers_the_step_budget_not_only_the_announced_lengths():
+    """The device-side pruning calls ignore branch_len and may decode any branch up to step
+    T - 1, so the (cos, sin) table must reach base_pos + T for every branch."""
+    T = 8
+    # the branch with the largest base position announces a single step
+    wl = W.make_workload("short_len", "bf16", 4, 2, 128, 500000.0, T, [5], [2], [10, 40], [2, 3],
+                         branch_len=[T, T, 1, 1, 1])
+    lay = _host_layout(wl)
+    base = B.hpd_layout_query(lay, B.HPD_Q_BRANCH_BASE_POS).astype(np.int64)
+    assert int(lay.counts()[B.HPD_C_MAX_POS]) == int(base.max()) + T == 5 + 40 - 1 + T
+    attr = np.asarray([2, 1, 3, 1, 2], dtype=np.int32)
+    lay = _host_layout(wl, B.HPD_POS_PAPER_GAP, attr_len=attr)
+    base = B.hpd_layout_query(lay, B.HPD_Q_BRANCH_BASE_POS).astype(np.int64)
+    assert int(lay.counts()[B.HPD_C_MAX_POS]) == int(base.max()) + T

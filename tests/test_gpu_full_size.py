@@ -50,6 +50,11 @@ def test_full_size_config(k, prompts):
     print(f"  oracle on prompts {prompts}", flush=True)
     worst = H.check_all(wl, hip, prompts=prompts, label=f"cfg{k}")
     print(f"  worst max-abs / RMS(step) = {worst:.4f}", flush=True)
+    # the price of the bf16 key cache, made visible: the same outputs against the oracle whose
+    # cache keeps the rotated keys in fp32 (first two steps of one sampled prompt)
+    far = H.distance_to_unrounded_oracle(wl, hip, prompts[:1], min(2, wl.max_new), label=f"cfg{k}")
+    print(f"  against the oracle with an unrounded (fp32) key cache: worst max-abs / RMS(step) = {far:.4f} "
+          f"(bound {H.BF16_TOL_UNROUNDED_CACHE})", flush=True)
     # the launch configuration bench.py times: outputs in the K/V element type
     print("  bf16 outputs == RNE(fp32 outputs), whole batch", flush=True)
     hip16 = H.run_hip(wl, inputs=hip["inputs"], fused=True, poison_pools=True, out_f32=False)

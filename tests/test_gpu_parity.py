@@ -680,7 +680,7 @@ def test_prefix_fill_fast_kernel_equals_general_kernel(literal):
 
 
 def test_finetune_mask_and_positions_bit_exact():
-    """hpd_finetune_mask (Section 5) against the loop oracle: mask and position IDs."""
+    """hpd_finetune_mask (Section 4.4) against the loop oracle: mask and position IDs."""
     from oracle import finetune_mask as F
     from paper_2604_26209_amd import binding as B
     rng = np.random.default_rng(9)
@@ -748,6 +748,67 @@ def test_kv_pools_hold_rotated_keys_at_reported_slots():
             b, t = b0 + po.branch[idx], po.step_of[idx]
             assert np.abs(kt[b, :, t, :] - po.k[idx]).max() < 1e-5
             assert np.array_equal(vt[b, :, t, :], po.v[idx])
+
+
+@pytest.mark.parametrize("kernel_mode,fused", [(0, False), (0, True), (1, False)])
+def test_bf16_kv_pools_hold_the_rounded_rotated_keys(kernel_mode, fused):
+    """The bf16 pools themselves (not only the attention outputs computed from them): prefix and
+    tail keys must be the bf16 rounding of the oracle's fp32-rotated keys - the same 16 bits,
+    except where the kernels' fused multiply-add lands on the other side of a rounding tie: such
+    elements may differ by one bf16 ulp and must be rare -, values must be the input bits,
+    through the 8-key interleave of the prefix pool.  Covers the 128-channel fill kernel and
+    the fused append of the streaming kernel (mode 0), the two-call append kernel, and the
+    element-wise fill kernel (mode 1)."""
+    from paper_2604_26209_amd import binding as B
+    _say(f"bf16 pool contents mode {kernel_mode} fused {fused}")
+    wl = W.random_workload(52, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=10, p=3,
+                           j_range=(1, 3), n_range=(1, 9), l_range=(1, 150), h_range=(0, 70))
+    hip = H.run_hip(wl, poison_pools="zero", kernel_mode=kernel_mode, fused=fused)
+    orc, res = H.run_oracle(wl, hip["inputs"])  # bf16 key cache
+    bits = lambda x: x.view(torch.int16).cpu().numpy().view(np.uint16)
+    kp, vp, kt, vt = [bits(x) for x in hip["pools"]]
+    lay = hip["layout"]
+    c = lay.counts()
+    NP, T, Hkv, D = int(c[B.HPD_C_N_PREFIX_SLOTS]), wl.max_new, wl.n_kv_heads, wl.head_dim
+    kp = kp.reshape(Hkv, NP, D)
+    vp = vp.reshape(Hkv, NP // 8, D, 8)
+    kt = kt.reshape(wl.n_branches, Hkv, T, D)
+    vt = vt.reshape(wl.n_branches, Hkv, T, D)
+    as_bits = lambda a: (np.ascontiguousarray(a, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    seg_off = B.hpd_layout_query(lay, B.HPD_Q_SEG_OFF)
+    n_keys = n_off = 0
+
+    def check_k(got, want_f32):
+        nonlocal n_keys, n_off
+        want = as_bits(want_f32)
+        assert not np.any(np.ascontiguousarray(want_f32, dtype=np.float32).view(np.uint32) & 0xFFFF)
+        diff = np.abs(got.astype(np.int32) - want.astype(np.int32))
+        assert diff.max() <= 1, "a stored key is more than one bf16 ulp from the rounded oracle key"
+        n_keys += diff.size
+        n_off += int((diff != 0).sum())
+
+    for p, po in orc.prompts.items():
+        segs = [(p, 0, po.h)]
+        run = po.h
+        for j, d in enumerate(range(wl.doc_ptr[p], wl.doc_ptr[p + 1])):
+            segs.append((wl.n_prompts + d, run, po.doc_lens[j]))
+            run += po.doc_lens[j]
+        for sid, first, n in segs:
+            for i in range(n):
+                slot = seg_off[sid] + i
+                check_k(kp[:, slot, :], po.k[first + i])
+                assert np.array_equal(vp[:, slot // 8, :, slot % 8], as_bits(po.v[first + i]))
+            # the V padding behind the segment is zero (masked keys must contribute 0 * V = 0)
+            for slot in range(seg_off[sid] + n, -(-(seg_off[sid] + n) // 32) * 32):
+                assert not vp[:, slot // 8, :, slot % 8].any()
+        b0, _ = orc.branch_range[p]
+        for idx in range(po.n_prefix, len(po.kind)):
+            b, t = b0 + po.branch[idx], po.step_of[idx]
+            check_k(kt[b, :, t, :], po.k[idx])
+            assert np.array_equal(vt[b, :, t, :], as_bits(po.v[idx]))
+    print(f"bf16 pools: {n_off} of {n_keys} stored key elements one ulp from the rounded oracle key "
+          f"({n_off / n_keys:.2e})")
+    assert n_off <= 2e-3 * n_keys
 
 
 def test_error_paths_on_device_layout():

@@ -1,4 +1,4 @@
-"""Pins of the fine-tuning-mask oracle (Section 5) against the paper and against an
+"""Pins of the fine-tuning-mask oracle (Section 4.4) against the paper and against an
 independent construction of the inference-time pattern (Section 4.3.2)."""
 import os
 
@@ -88,7 +88,7 @@ def test_mask_set_construction_and_row_sums(case):
 
 @pytest.mark.parametrize("case", _cases())
 def test_pattern_equals_the_inference_pattern(case):
-    """Section 5's claim (and the caption of its mask figure): the fine-tuning mask replicates
+    """Section 4.4's claim (and the caption of its mask figure): the fine-tuning mask replicates
     what a token can see at inference.  The inference side is built from Section 4.3.2 alone:
     memory order [p, a_1..a_N, values of step 1 (attribute order), values of step 2, ...]; a
     key is visible iff it is in memory no later than the query and its position ID is not

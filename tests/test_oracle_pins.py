@@ -790,3 +790,118 @@ def test_prefill_attention_literal_and_block_masks_differ_only_behind_the_first_
     n = wl.n_prefix_tokens
     assert np.abs(outs["block"][:h + l0] - outs["paper"][:h + l0]).max() < 1e-12
     assert np.abs(outs["block"][h + l0:n] - outs["paper"][h + l0:n]).max() > 1e-6
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 2 by a walk along s, independent of the oracle's closed form
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("seed", range(6))
+def test_alg2_equals_a_walk_that_reserves_k_max_ids_behind_every_attribute(seed):
+    """Appendix A.1 in words: positions run on along s, and behind every attribute K_max IDs
+    are left free for its value.  Walk s token by token with a counter."""
+    rng = np.random.default_rng(100 + seed)
+    plen = int(rng.integers(0, 40))
+    attr = [int(x) for x in rng.integers(1, 7, size=int(rng.integers(1, 9)))]
+    kmax = int(rng.integers(1, 33))
+    want, ends, counter = [], [], 0
+    for _ in range(plen):
+        want.append(counter)
+        counter += 1
+    for a in attr:
+        for _ in range(a):
+            want.append(counter)
+            counter += 1
+        ends.append(len(want) - 1)
+        counter += kmax  # the IDs of the value tokens to come
+    pos_id, end_index = O.alg2_position_ids(plen, attr, kmax)
+    assert [int(x) for x in pos_id] == want
+    assert [int(x) for x in end_index] == ends
+
+
+# ---------------------------------------------------------------------------
+# The bf16 key cache (Appendix B: bf16 inference): rounding and where it is applied
+# ---------------------------------------------------------------------------
+def _bf16_via_torch(x):
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16).float().numpy()
+
+
+def test_round_to_bf16_equals_the_library_conversion_over_the_whole_exponent_range():
+    rng = np.random.default_rng(5)
+    # every exponent (subnormals, normals, the largest finite ones), random mantissas and signs
+    bits = rng.integers(0, 1 << 32, size=1 << 20, dtype=np.uint64).astype(np.uint32)
+    x = bits.view(np.float32)
+    x = x[np.isfinite(x)]
+    got, want = O.round_to_bf16(x), _bf16_via_torch(x)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    # N(0,1) magnitudes, the values the parity tests feed
+    y = rng.standard_normal(1 << 18).astype(np.float32)
+    assert np.array_equal(O.round_to_bf16(y).view(np.uint32), _bf16_via_torch(y).view(np.uint32))
+    # the low 16 bits are gone and the value moved by at most half a bf16 ulp
+    assert not np.any(O.round_to_bf16(y).view(np.uint32) & 0xFFFF)
+    ulp = np.float32(2.0) ** (np.floor(np.log2(np.abs(y))) - 7)
+    assert np.all(np.abs(O.round_to_bf16(y) - y) <= ulp / 2)
+
+
+def test_round_to_bf16_hand_computed_cases():
+    f = lambda bits: np.asarray([bits], dtype=np.uint32).view(np.float32)
+    r = lambda bits: int(O.round_to_bf16(f(bits)).view(np.uint32)[0])
+    # ties go to the even neighbour, in both directions
+    assert r(0x3F808000) == 0x3F800000   # 1 + 2^-8: halfway between 1.0 (even) and 1 + 2^-7
+    assert r(0x3F818000) == 0x3F820000   # 1 + 3*2^-8: halfway, the odd one below goes up
+    assert r(0x3F808001) == 0x3F810000   # just above the tie: up
+    assert r(0x3F807FFF) == 0x3F800000   # just below: down
+    assert r(0xBF808000) == 0xBF800000 and r(0xBF818000) == 0xBF820000  # sign carried along
+    # zeros, infinities, representable values stay
+    for bits in (0x00000000, 0x80000000, 0x7F800000, 0xFF800000, 0x3F800000, 0x40490000, 0x00010000):
+        assert r(bits) == bits
+    # a carry out of the mantissa raises the exponent; the largest finite fp32 overflows to inf
+    assert r(0x3FFFFFFF) == 0x40000000
+    assert r(0x7F7FFFFF) == 0x7F800000
+    # subnormals: the smallest fp32 subnormal rounds to zero, half the smallest bf16 one ties to zero
+    assert r(0x00000001) == 0x00000000 and r(0x00008000) == 0x00000000 and r(0x00008001) == 0x00010000
+    # exact small numbers: 0.1f = 0x3DCCCCCD -> 0x3DCD0000
+    assert r(0x3DCCCCCD) == 0x3DCD0000
+
+
+def test_bf16_cache_changes_the_stored_key_and_nothing_else():
+    """cache_dtype="bf16" = the unrounded oracle whose rotated keys are rounded on entry: same
+    values, positions, masks; outputs equal the plain definition fed with pre-rounded keys."""
+    wl = W.random_workload(21, t=4, p=2)
+    kw = dict(pos_mode="contig")
+    plain = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len, wl.n_q_heads,
+                        wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new, **kw)
+    cached = O.HPDOracle(wl.header_len, wl.doc_ptr, wl.doc_len, wl.branch_ptr, wl.branch_len, wl.n_q_heads,
+                         wl.n_kv_heads, wl.head_dim, wl.rope_base, wl.max_new, cache_dtype="bf16", **kw)
+    kp = _values(wl, 1, (plain.n_prefix_tokens, wl.n_kv_heads, wl.head_dim))
+    vp = _values(wl, 2, (plain.n_prefix_tokens, wl.n_kv_heads, wl.head_dim))
+    plain.prefill(kp, vp), cached.prefill(kp, vp)
+    differs = False
+    for t in range(wl.max_new):
+        n_live = int((wl.branch_len > t).sum())
+        q = _values(wl, 10 + 3 * t, (n_live, wl.n_q_heads, wl.head_dim))
+        k = _values(wl, 11 + 3 * t, (n_live, wl.n_kv_heads, wl.head_dim))
+        v = _values(wl, 12 + 3 * t, (n_live, wl.n_kv_heads, wl.head_dim))
+        a, b = plain.step(t, q, k, v), cached.step(t, q, k, v)
+        for key in ("rows", "pos", "slot", "flat"):
+            assert np.array_equal(a[key], b[key])
+        for p in plain.prompts:
+            pa, pb = plain.prompts[p], cached.prompts[p]
+            # the cache: keys are the library's bf16 conversion of the unrounded ones, values untouched
+            assert np.array_equal(pb.k.view(np.uint32), _bf16_via_torch(pa.k).view(np.uint32))
+            assert np.array_equal(pb.v, pa.v)
+            assert pa.pos == pb.pos and pa.kind == pb.kind
+            assert np.array_equal(pa.mask_rows_fast(list(range(len(pa.kind)))),
+                                  pb.mask_rows_fast(list(range(len(pb.kind)))))
+            # outputs: the plain definition over the rounded keys, with the query rotated in fp32
+            live = [x for x in pa.live(t)]
+            b0, _ = plain.branch_range[p]
+            sel = np.nonzero(np.isin(a["rows"], np.nonzero(np.isin(plain.live(t), np.asarray(live) + b0))[0]))[0]
+            rows = list(range(len(pa.kind) - len(live), len(pa.kind)))
+            qr = O.rope(q[a["rows"][sel]], a["pos"][sel], wl.rope_base)
+            want = O.masked_attention(qr, _bf16_via_torch(pa.k), pa.v, pa.mask_rows(rows), wl.n_kv_heads)
+            assert np.array_equal(b["out"][sel], want)
+        differs |= not np.array_equal(a["out"], b["out"])
+        # ... and the rounding of the keys moves the outputs by little (2^-9 relative per key)
+        rms = float(np.sqrt(np.mean(a["out"].astype(np.float64) ** 2)))
+        assert np.abs(a["out"] - b["out"]).max() <= 5e-2 * rms
+    assert differs  # the mode is not a no-op
