@@ -380,6 +380,36 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
         }
     }
 
+    // ---- device-side pruning: what never changes, one record of 8 words per unit (document, or
+    //      prompt under the literal mask), the units with the most keys first.  Documents:
+    //      {hoff, Hlen, doff, Llen, first branch, end of branches, position of step 0 | -1, 0};
+    //      prompts: {hoff, Hlen, first entry of the block list, its blocks, first branch, end of
+    //      branches, 0, 0}
+    {
+      const size_t nU = paper ? (size_t)P : (size_t)n_docs;
+      std::vector<int32_t> order(nU);
+      std::iota(order.begin(), order.end(), 0);
+      std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+        if (paper) return L->pblk_ptr[x + 1] - L->pblk_ptr[x] > L->pblk_ptr[y + 1] - L->pblk_ptr[y];
+        return (int64_t)L->seg_len[L->doc_prompt[x]] + L->seg_len[L->P + x] >
+               (int64_t)L->seg_len[L->doc_prompt[y]] + L->seg_len[L->P + y];
+      });
+      L->dyn_fixed.assign(nU * 8, 0);
+      for (size_t u = 0; u < nU; ++u) {
+        int32_t* o = L->dyn_fixed.data() + u * 8;
+        if (paper) {
+          const int32_t p = order[u];
+          o[0] = L->seg_off[p]; o[1] = L->seg_len[p]; o[2] = L->pblk_ptr[p]; o[3] = L->pblk_ptr[p + 1] - L->pblk_ptr[p];
+          o[4] = L->prompt_branch_ptr[p]; o[5] = L->prompt_branch_ptr[p + 1];
+        } else {
+          const int32_t d = order[u], p = L->doc_prompt[d];
+          o[0] = L->seg_off[p]; o[1] = L->seg_len[p]; o[2] = L->seg_off[L->P + d]; o[3] = L->seg_len[L->P + d];
+          o[4] = L->doc_branch_ptr[d]; o[5] = L->doc_branch_ptr[d + 1];
+          o[6] = L->cfg.pos_mode == HPD_POS_CONTIG ? L->seg_len[p] + L->seg_len[L->P + d] : -1;
+        }
+      }
+    }
+
     // ---- RoPE table: angles in double, stored as float (cos, sin)
     const int32_t half = cfg->head_dim / 2;
     L->rope.resize((size_t)(L->max_pos + 1) * half * 2);
@@ -411,7 +441,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
                  o_blen = A.add(L->branch_len), o_pblk = A.add(L->pblk), o_pdesc = A.add(L->punit_desc),
                  o_fdesc = A.add(L->funit_desc), o_spos = A.add(L->skel_pos), o_soff = A.add(L->skel_off),
                  o_sseg = A.add(L->skel_seg_off), o_scum = A.add(L->skel_cum), o_fblk = A.add(L->fblk),
-                 o_fill = A.add(L->fill_blk);
+                 o_fill = A.add(L->fill_blk), o_dynfix = A.add(L->dyn_fixed);
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = hipGetDevice(&L->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&L->n_cus, hipDeviceAttributeMultiprocessorCount, L->device);
@@ -442,6 +472,7 @@ int hpd_build_layout(const hpd_config* cfg, int32_t n_prompts, const int32_t* he
     L->dev.branch_len = base + o_blen; L->dev.pblk = base + o_pblk; L->dev.punit_desc = base + o_pdesc;
     L->dev.funit_desc = base + o_fdesc; L->dev.fblk = base + o_fblk;
     L->dev.fill_blk = base + o_fill;
+    L->dyn_fixed_dev = const_cast<int32_t*>(base) + o_dynfix;
     L->dev.skel_pos = paper_mode(L) ? base + o_spos : nullptr; L->dev.skel_off = base + o_soff;
     L->dev.skel_seg_off = base + o_sseg; L->dev.skel_cum = base + o_scum;
     L->dev.rope = (const float2*)L->d_rope;
@@ -679,56 +710,32 @@ static int dynamic_supported(const hpd_layout* L) {
   return HPD_OK;
 }
 
+// words of device-side pruning state a layout needs: desc [units * 8 | 16] (read and written 16
+// bytes at a time), n_live [4], live [B], and for the literal mask len [B]; units = documents, or
+// prompts under the literal mask
+static size_t dynamic_state_words(const hpd_layout* L) {
+  const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
+  const size_t nB = (size_t)L->B, nU = paper ? (size_t)L->P : (size_t)L->n_docs, dw = paper ? 16 : 8;
+  return nU * dw + 4 + nB + (paper ? nB : 0) + 16;
+}
+
+// points the layout's state at `mem` (dynamic_state_words(L) words, 16-byte aligned)
+static void dynamic_state_bind(hpd_layout* L, void* mem) {
+  const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
+  const size_t nB = (size_t)L->B, nU = paper ? (size_t)L->P : (size_t)L->n_docs, dw = paper ? 16 : 8;
+  int32_t* w = (int32_t*)mem;
+  L->dyn_desc = w; w += nU * dw;
+  L->dyn_n_live = w; w += 4;
+  L->dyn_live = w; w += nB;
+  L->dyn_len = paper ? w : nullptr;
+}
+
 int hpd_dynamic_begin(hpd_layout* L, void* stream) {
   int rc = dynamic_supported(L);
   if (rc != HPD_OK) return rc;
   hipStream_t s = (hipStream_t)stream;
-  if (!L->d_dyn) {
-    // desc [units*8 | 16], fixed [units*8] (both read and written 16 bytes at a time), n_live [4],
-    // live [B], and for the literal mask len [B]; units = documents, or prompts under the literal mask
-    const bool paper = L->cfg.mask_mode == HPD_MASK_PAPER;
-    const size_t nB = (size_t)L->B, nU = paper ? (size_t)L->P : (size_t)L->n_docs, dw = paper ? 16 : 8;
-    const size_t words = nU * dw + nU * 8 + 4 + nB + (paper ? nB : 0) + 16;
-    HPD_HIP(hipMalloc(&L->d_dyn, words * sizeof(int32_t)));
-    int32_t* w = (int32_t*)L->d_dyn;
-    L->dyn_desc = w; w += nU * dw;
-    L->dyn_fixed_dev = w; w += nU * 8;
-    L->dyn_n_live = w; w += 4;
-    L->dyn_live = w; w += nB;
-    L->dyn_len = paper ? w : nullptr;
-    // what never changes, one record per unit, the units with the most keys first.  Documents:
-    // {hoff, Hlen, doff, Llen, first branch, end of branches, position of step 0 | -1, 0};
-    // prompts: {hoff, Hlen, first entry of the block list, its blocks, first branch, end of branches, 0, 0}
-    std::vector<int32_t> order(nU);
-    std::iota(order.begin(), order.end(), 0);
-    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
-      if (paper) return L->pblk_ptr[x + 1] - L->pblk_ptr[x] > L->pblk_ptr[y + 1] - L->pblk_ptr[y];
-      return (int64_t)L->seg_len[L->doc_prompt[x]] + L->seg_len[L->P + x] >
-             (int64_t)L->seg_len[L->doc_prompt[y]] + L->seg_len[L->P + y];
-    });
-    L->dyn_fixed.assign(nU * 8, 0);
-    for (size_t u = 0; u < nU; ++u) {
-      int32_t* o = L->dyn_fixed.data() + u * 8;
-      if (paper) {
-        const int32_t p = order[u];
-        o[0] = L->seg_off[p]; o[1] = L->seg_len[p]; o[2] = L->pblk_ptr[p]; o[3] = L->pblk_ptr[p + 1] - L->pblk_ptr[p];
-        o[4] = L->prompt_branch_ptr[p]; o[5] = L->prompt_branch_ptr[p + 1];
-      } else {
-        const int32_t d = order[u], p = L->doc_prompt[d];
-        o[0] = L->seg_off[p]; o[1] = L->seg_len[p]; o[2] = L->seg_off[L->P + d]; o[3] = L->seg_len[L->P + d];
-        o[4] = L->doc_branch_ptr[d]; o[5] = L->doc_branch_ptr[d + 1];
-        o[6] = L->cfg.pos_mode == HPD_POS_CONTIG ? L->seg_len[p] + L->seg_len[L->P + d] : -1;
-      }
-    }
-    hipError_t e = hipMemcpyAsync(L->dyn_fixed_dev, L->dyn_fixed.data(), nU * 8 * sizeof(int32_t),
-                                  hipMemcpyHostToDevice, s);
-    if (e == hipSuccess) e = hipStreamSynchronize(s);  // the copy has left the host vector
-    if (e != hipSuccess) {
-      (void)hipFree(L->d_dyn);
-      L->d_dyn = nullptr;
-      return hip_fail(e);
-    }
-  }
+  if (!L->d_dyn) HPD_HIP(hipMalloc(&L->d_dyn, dynamic_state_words(L) * sizeof(int32_t)));
+  dynamic_state_bind(L, L->d_dyn);
   L->dyn_next_step = 0;
   HPD_HIP(hpd_launch_dynamic_prune(L, 0, nullptr, s));
   return HPD_OK;
@@ -737,7 +744,7 @@ int hpd_dynamic_begin(hpd_layout* L, void* stream) {
 int hpd_dynamic_prune(hpd_layout* L, const uint8_t* finished, void* stream) {
   int rc = dynamic_supported(L);
   if (rc != HPD_OK) return rc;
-  if (!L->d_dyn || !finished) return HPD_E_INVALID;
+  if (!L->dyn_live || !finished) return HPD_E_INVALID;
   if (L->dyn_next_step + 1 >= L->T) return HPD_E_INVALID;  // no step left to prune for
   L->dyn_next_step += 1;
   HPD_HIP(hpd_launch_dynamic_prune(L, L->dyn_next_step, finished, (hipStream_t)stream));
@@ -749,7 +756,7 @@ int hpd_dynamic_step(const hpd_layout* L, int32_t step, const void* q, const voi
                      void* v_tail, void* out, void* stream) {
   int rc = dynamic_supported(L);
   if (rc != HPD_OK) return rc;
-  if (!L->d_dyn || step != L->dyn_next_step) return HPD_E_INVALID;  // the state describes another step
+  if (!L->dyn_live || step != L->dyn_next_step) return HPD_E_INVALID;  // the state describes another step
   if (!q || !k_new || !v_new || !k_prefix || !v_prefix || !k_tail || !v_tail || !out) return HPD_E_INVALID;
   if (L->n_docs == 0) return HPD_OK;
   HPD_HIP(hpd_launch_attention_stream(L, step, q, k_prefix, v_prefix, k_tail, v_tail, k_new, v_new, out,
@@ -758,7 +765,7 @@ int hpd_dynamic_step(const hpd_layout* L, int32_t step, const void* q, const voi
 }
 
 int hpd_dynamic_state(const hpd_layout* L, const int32_t** live_branch, const int32_t** n_live) {
-  if (!L || !L->d_dyn) return HPD_E_INVALID;
+  if (!L || !L->dyn_live) return HPD_E_INVALID;
   if (live_branch) *live_branch = L->dyn_live;
   if (n_live) *n_live = L->dyn_n_live;
   return HPD_OK;
@@ -766,7 +773,7 @@ int hpd_dynamic_state(const hpd_layout* L, const int32_t** live_branch, const in
 
 int hpd_dynamic_read(const hpd_layout* L, int32_t* live_host, int32_t capacity, int32_t* n_live_host,
                      void* stream) {
-  if (!L || !L->d_dyn || !n_live_host || capacity < 0 || (capacity > 0 && !live_host)) return HPD_E_INVALID;
+  if (!L || !L->dyn_live || !n_live_host || capacity < 0 || (capacity > 0 && !live_host)) return HPD_E_INVALID;
   hipStream_t s = (hipStream_t)stream;
   HPD_HIP(hipMemcpyAsync(n_live_host, L->dyn_n_live, sizeof(int32_t), hipMemcpyDeviceToHost, s));
   HPD_HIP(hipStreamSynchronize(s));

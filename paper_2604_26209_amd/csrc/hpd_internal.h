@@ -86,7 +86,7 @@ struct hpd_layout {
 
   // device-side pruning: state built by dynamic_prune_kernel (one allocation, d_dyn)
   std::vector<int32_t> doc_branch_ptr;  // [n_docs+1]
-  std::vector<int32_t> dyn_fixed;       // [n_docs][8] per-document constants of the descriptors, heaviest first
+  std::vector<int32_t> dyn_fixed;       // [units][8] per-unit constants of the descriptors, heaviest first (uploaded with the tables)
   int32_t max_doc_branches = 0;
   void* d_dyn = nullptr;
   int32_t *dyn_live = nullptr, *dyn_n_live = nullptr, *dyn_desc = nullptr, *dyn_fixed_dev = nullptr,
