@@ -13,9 +13,19 @@ layer 1, ... of layer R-1, then step t+1 of layer 0, ... - as the layers of a re
 would be, so that every launch finds its KV evicted.  (Running all T steps of one replica
 back to back would serve steps 1..T-1 out of the Infinity Cache.)
 
-Prints ONE JSON line.  `roofline` is measured live with events around every attention launch
-in a second, identical timed region; `cpu_baseline` times the CPU oracle on a bounded sample
-of the same workload on this machine's host cores.
+Prints ONE JSON line.  Without --config the headline (value, ms_per_step, roofline,
+cpu_baseline) is the largest single-GPU configuration (configs[4], the ragged mixed batch: the
+only one with every feature of the path in it - stacked documents of different lengths, ragged
+branch counts, early stopping) timed over exactly --steps passes, and `per_config` carries the
+same measurement for all five configurations (each timed for at least MIN_TIMED_S), the 70B-like
+one against both roofs.  With --config k the line is that configuration's alone (used for the
+profiler runs and for side measurements).  `roofline.achieved` = algorithmic bytes of the timed
+launches / their GPU time, taken live with one pair of HIP events around the timed region (on
+the stream the kernels are launched on); `roofline.traffic` is NOT measured by this run: it is
+read from the rocprofv3 counter summary under profiles/ that `traffic_source` names.
+`measured_peaks` are three reference kernels of the library (plain read, plain copy, independent
+MFMAs) timed in this run.  `cpu_baseline` times the CPU oracle on a bounded sample of the
+headline workload on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -32,10 +42,25 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# of this same command, each scaled by what the counter reads for a 1 GiB copy
-# (profiles/attn_stream_<workload>.txt).  None where no counter run has been made.
-MEASURED_TRAFFIC_BYTES = {2: 106.4e6, 3: 734.5e6, 4: 444.0e6, 5: 2687.9e6}
+MIN_WARMUP_S = 0.2   # warm-up lasts at least this long (clocks, caches, code objects)
+MIN_TIMED_S = 0.3    # per_config entries other than the headline are timed at least this long
+
+# rocprofv3 counter summaries (FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy) of
+# `bench.py --config k`: the line "total traffic X MB per launch" is what roofline.traffic quotes
+PROFILE_OF_CONFIG = {2: "profiles/attn_stream_cfg2_llama3_8b.txt", 3: "profiles/attn_stream_cfg3_stacked.txt",
+                     4: "profiles/attn_stream_cfg4_long_70b.txt", 5: "profiles/attn_stream_cfg5_ragged.txt"}
+
+
+def profiled_traffic(k):
+    """(HBM bytes per launch, file) from the committed profiler summary of configuration k, or
+    (None, None)."""
+    import re
+    rel = PROFILE_OF_CONFIG.get(k)
+    try:
+        m = re.search(r"total traffic ([0-9.]+) MB per launch", open(os.path.join(ROOT, rel)).read())
+        return (float(m.group(1)) * 1e6, rel) if m else (None, None)
+    except (OSError, TypeError):
+        return None, None
 
 
 def algorithmic_bytes(wl, n_live_lists, eb, paper=False, attr_len=None):
@@ -203,59 +228,52 @@ def bench_prefill(args, wl, layout, B, W, torch, np, out_f32, attr_len=None):
     print(json.dumps(rec))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5")
-    ap.add_argument("--replicas", type=int, default=0, help="KV replicas (0 = enough for 2 GB)")
-    ap.add_argument("--out", default="same", choices=["f32", "same"],
-                    help="output element type: the K/V element type (default) or fp32")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--two-call", action="store_true", help="hpd_kv_append + hpd_decode_attention")
-    ap.add_argument("--copy-calibration", type=int, default=0,
-                    help="after the timed regions, run this many 1 GiB device copies (reference "
-                         "dispatches for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--mask", default="block", choices=["block", "paper"],
-                    help="block: header + own document + own branch (the benchmark's metric); paper: "
-                         "the literal mask over the whole stacked prompt, with the paper's gap positions")
-    ap.add_argument("--phase", default="decode", choices=["decode", "prefill"],
-                    help="decode: the benchmark's metric; prefill: hpd_prefill_attention (the attention of "
-                         "the header and document tokens themselves, first inference step), a side measurement")
-    ap.add_argument("--kernel-mode", type=int, default=0,
-                    help="hpd_set_kernel_mode: 0 automatic (default), 1 generic kernel, 3 / 4 streaming "
-                         "kernel with the wide / narrow workgroup shape")
-    ap.add_argument("--page-size", type=int, default=0,
-                    help="side measurement: tail pools paged (hpd_set_tail_pages) with this page size, "
-                         "pages in a seeded random order")
-    ap.add_argument("--dynamic", action="store_true",
-                    help="also time the passes with the live list kept on the GPU (hpd_dynamic_*)")
-    ap.add_argument("--per-step", action="store_true",
-                    help="second run: one event pair per decode step (all replicas of that step back "
-                         "to back), adds per_step {us, gbs} to the record")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
-              "--gpus must be 1", file=sys.stderr)
-        sys.exit(2)
-
-    import numpy as np
-    import torch
-
-    from paper_2604_26209_amd import binding as B
-    from paper_2604_26209_amd import workloads as W
-
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
+def measured_peaks(B, torch):
+    """Three reference kernels of the library, timed with HIP events on the current stream: what a
+    plain read, a plain copy and a loop of independent bf16 MFMAs reach on this GPU."""
     dev = "cuda"
-    wl = W.config(args.config)
+    n = 1 << 30  # bytes per buffer: four times the 256 MB Infinity Cache
+    a = torch.empty(n // 4, dtype=torch.float32, device=dev).normal_()
+    b = torch.empty(n // 4, dtype=torch.float32, device=dev).normal_()
+    c = torch.empty(n // 4, dtype=torch.float32, device=dev)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+
+    def timed(fn, reps):
+        fn(), fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / reps
+
+    def read2():  # alternating buffers: every launch finds its input evicted
+        B.hpd_peak_read(a, n, sink)
+        B.hpd_peak_read(b, n, sink)
+
+    t_read = timed(read2, 10) / 2
+    t_copy = timed(lambda: (B.hpd_peak_copy(c, a, n), B.hpd_peak_copy(c, b, n)), 10) / 2
+    flops = []
+    t_mfma = timed(lambda: flops.append(B.hpd_peak_mfma(sink, 4000)), 5)
+    return {"hbm_read_gbs": round(n / t_read / 1e9, 1), "hbm_copy_gbs_read_plus_write": round(2 * n / t_copy / 1e9, 1),
+            "mfma_bf16_tflops": round(flops[-1] / t_mfma / 1e12, 1),
+            "kernels": "hpd_peak_read / hpd_peak_copy over 1 GiB buffers (alternating), hpd_peak_mfma "
+                       "(4 independent v_mfma_f32_32x32x16_bf16 chains per wave, 8 waves per CU)",
+            "published": {"hbm_gbs": HBM_PEAK_GBS, "mfma_bf16_tflops": MFMA_BF16_PEAK_TFLOPS}}
+
+
+def measure_decode(args, k, steps, warmup, B, W, torch, np, min_timed_s=0.0):
+    """Times `steps` passes (at least min_timed_s seconds' worth) of configuration k's decode and
+    returns the record of that configuration (no cpu_baseline)."""
+    dev = "cuda"
+    wl = W.config(k)
     eb = 4 if wl.dtype == "f32" else 2
     out_f32 = args.out == "f32" or wl.dtype == "f32"
     paper = args.mask == "paper"
     # skeleton (attribute-name) lengths for the gap positions: 1..4 tokens, seeded
-    attr_len = np.random.default_rng(26209100 + args.config).integers(1, 5, size=wl.n_branches).astype(np.int32)
+    attr_len = np.random.default_rng(26209100 + k).integers(1, 5, size=wl.n_branches).astype(np.int32)
     layout = B.layout_from_workload(wl, out_dtype=B.HPD_OUT_F32 if out_f32 else B.HPD_OUT_SAME,
                                     **(dict(pos_mode=B.HPD_POS_PAPER_GAP, attr_len=attr_len,
                                             mask_mode=B.HPD_MASK_PAPER) if paper else {}))
@@ -277,12 +295,13 @@ def main():
 
     if args.phase == "prefill":
         bench_prefill(args, wl, layout, B, W, torch, np, out_f32, attr_len if paper else None)
-        return
+        return None
 
     pool_bytes = B.hpd_layout_query(layout, B.HPD_Q_POOL_BYTES)
     footprint = int(pool_bytes.sum())
     R = args.replicas or max(2, -(-(2 << 30) // footprint))
     tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+    stream_kernel = wl.dtype == "bf16" and wl.head_dim == 128 and args.kernel_mode != 1
 
     # ---- inputs (seeded), resident in HBM
     base = wl.value_seed * 1000
@@ -342,8 +361,20 @@ def main():
                 marks.append((n, ev))
 
     live_steps = [t for t in range(wl.max_new) if int(n_live[t]) > 0]
-    run(args.warmup)
+    # warm-up: at least `warmup` passes and at least MIN_WARMUP_S of GPU work
+    t_w = time.perf_counter()
+    run(max(1, warmup))
     torch.cuda.synchronize()
+    warm_passes = max(1, warmup)
+    while time.perf_counter() - t_w < MIN_WARMUP_S:
+        run(R)
+        torch.cuda.synchronize()
+        warm_passes += R
+    pass_s = (time.perf_counter() - t_w) / warm_passes
+    # passes of the timed region: `steps`, more if that would be shorter than min_timed_s, and
+    # never fewer than five groups of R passes (for the spread)
+    if min_timed_s > 0:
+        steps = max(steps, 5 * R, min(int(min_timed_s / pass_s) + 1, 4000))
     # The timed region.  In the fused call it holds launches of the dominant kernel only, back
     # to back on one stream, so one pair of events around it gives that kernel's average launch
     # duration (an event pair around every launch would add about 2 us of dispatch gap to each).
@@ -351,7 +382,7 @@ def main():
     t0 = time.perf_counter()
     ev0.record()
     marks = []
-    run(args.steps, marks=marks)
+    run(steps, marks=marks)
     ev1.record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
@@ -360,53 +391,70 @@ def main():
     for n, ev in marks:
         group_ms.append(prev.elapsed_time(ev) / n)
         prev = ev
-    ms_per_step = elapsed * 1e3 / args.steps
-    value = total_tokens * args.steps / elapsed
+    ms_per_step = elapsed * 1e3 / steps
+    value = total_tokens * steps / elapsed
 
     # ---- roofline of the dominant kernel (attention), live
     if args.two_call:
         # the append kernel sits between the attention launches: bracket each attention launch
         events = []
-        run(args.steps, events)
+        run(steps, events)
         torch.cuda.synchronize()
         dur_s = sum(e0.elapsed_time(e1) for _, e0, e1 in events) * 1e-3
         launched = [t for t, _, _ in events]
     else:
         dur_s = ev0.elapsed_time(ev1) * 1e-3
-        launched = live_steps * args.steps
+        launched = live_steps * steps
     # the fused step kernel also does the append (new K/V in, rotated K/V out)
     alg = sum(attn_b[t] + (0 if args.two_call else app_b[t]) for t in launched)
     achieved = alg / dur_s / 1e9
     mfma_tflops = sum(flops[t] for t in launched) / dur_s / 1e12
-    events = launched
-    roofline = {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if not (args.two_call or out_f32 or paper) else None,
-                "kernel": "attn_stream_kernel" if wl.dtype == "bf16" and wl.head_dim == 128 else "attention_generic_kernel",
-                "launches": len(events), "avg_launch_us": round(dur_s / len(events) * 1e6, 2),
-                "algorithmic_bytes_per_launch": int(alg / len(events)),
+    traffic, traffic_src = (None, None) if (args.two_call or out_f32 or paper or args.page_size or args.kernel_mode) \
+        else profiled_traffic(k)
+    # arithmetic intensity decides the binding roof: above the ridge of the published peaks
+    # (2500 TFLOP/s / 8 TB/s = 312 flop/byte) or within reach of it the matrix pipes bind first
+    intensity = sum(flops[t] for t in launched) / alg
+    bound = "mfma" if intensity > 150 else "hbm"
+    roofline = {"bound": bound,
+                "achieved": round(mfma_tflops if bound == "mfma" else achieved, 1),
+                "peak": MFMA_BF16_PEAK_TFLOPS if bound == "mfma" else HBM_PEAK_GBS,
+                "unit": "TFLOP/s" if bound == "mfma" else "GB/s",
+                "frac": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS if bound == "mfma" else achieved / HBM_PEAK_GBS, 4),
+                "traffic": traffic,
+                "traffic_source": (f"{traffic_src}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of `bench.py --config {k}`, "
+                                   "not measured by this run") if traffic_src else None,
+                "kernel": ("attn_stream_kernel" if stream_kernel else
+                           "append_kernel + attention_generic_kernel (two launches per step)"),
+                "launches": len(launched), "avg_launch_us": round(dur_s / len(launched) * 1e6, 2),
+                "algorithmic_bytes_per_launch": int(alg / len(launched)),
+                "hbm_gbs": round(achieved, 1), "frac_of_hbm_peak": round(achieved / HBM_PEAK_GBS, 4),
                 "useful_tflops": round(mfma_tflops, 1),
-                "useful_tflops_frac_of_mfma_peak": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4)}
+                "useful_tflops_frac_of_mfma_peak": round(mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                "flop_per_byte": round(intensity, 1)}
 
     rec = {
         "metric": "branch tokens/s of HPD masked decode attention; achieved HBM GB/s vs peak",
-        "value": round(value, 1), "unit": "branch-tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "value": round(value, 1), "unit": "branch-tokens/s", "n_gpus": 1, "steps": steps,
+        "warmup": warm_passes, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype, "data": "synthetic",
-        "config": {"workload": f"configs[{args.config - 1}] {wl.name}: {wl.note}"
+        "config": {"workload": f"configs[{k - 1}] {wl.name}: {wl.note}"
                                + ("; paper-literal mask over the whole prompt, gap positions" if paper else ""),
                    "prompts": wl.n_prompts, "documents": wl.n_docs, "branches": wl.n_branches,
                    "decode_steps_per_pass": wl.max_new, "branch_tokens_per_pass": total_tokens,
                    "heads": f"{wl.n_q_heads}/{wl.n_kv_heads}x{wl.head_dim}", "kv_replicas": R,
                    "kv_footprint_mb": round(footprint / 1e6, 1), "out_dtype": "f32" if out_f32 else wl.dtype,
                    **({"tail_page_size": args.page_size} if args.page_size and not paper else {}),
-                   "call": "hpd_kv_append+hpd_decode_attention" if args.two_call else "hpd_decode_step"},
+                   "call": "hpd_kv_append+hpd_decode_attention" if args.two_call else "hpd_decode_step",
+                   "parity_checked_on": ("fp32 outputs against the CPU oracle (tests/test_gpu_full_size.py, this "
+                                         "configuration's full size and launch shape), and bf16 outputs == "
+                                         "RNE(fp32 outputs) bit for bit for every row" if wl.dtype == "bf16" else
+                                         "fp32 outputs against the CPU oracle, every row")},
         "roofline": roofline,
         "gpu_ms_per_step": {"median": round(float(np.median(group_ms)), 4), "min": round(float(min(group_ms)), 4),
                             "max": round(float(max(group_ms)), 4), "groups": len(group_ms)},
     }
     if args.per_step and not args.two_call:
-        reps = max(1, args.steps // R)
+        reps = max(1, steps // R)
         pairs = []
         for t in live_steps:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -442,15 +490,15 @@ def main():
 
         res = {}
         for dyn in (True, False, True, False):
-            for p in range(min(args.warmup, R)):
+            for p in range(min(warmup, R)):
                 one_pass(p, dyn)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            for p in range(args.steps):
+            for p in range(steps):
                 one_pass(p, dyn)
             e1.record()
             torch.cuda.synchronize()
-            res.setdefault(dyn, []).append(e0.elapsed_time(e1) / args.steps)
+            res.setdefault(dyn, []).append(e0.elapsed_time(e1) / steps)
         rec["dynamic"] = {"gpu_ms_per_pass_device_lists": round(min(res[True]), 4),
                           "gpu_ms_per_pass_host_lists": round(min(res[False]), 4),
                           "call": "hpd_dynamic_begin + (hpd_dynamic_step, hpd_dynamic_prune) per step"}
@@ -460,9 +508,112 @@ def main():
         for _ in range(args.copy_calibration):
             dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
+    rec["_workload"] = (wl, paper, attr_len)
+    del pools, q, kn, vn, outs
+    torch.cuda.empty_cache()
+    return rec
+
+
+HEADLINE_CONFIG = 5
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=0,
+                    help="0 (default): headline on configs[4] plus per_config for all five; 1..5: that "
+                         "configuration alone")
+    ap.add_argument("--replicas", type=int, default=0, help="KV replicas (0 = enough for 2 GB)")
+    ap.add_argument("--out", default="same", choices=["f32", "same"],
+                    help="output element type: the K/V element type (default) or fp32")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the measured_peaks reference kernels")
+    ap.add_argument("--two-call", action="store_true", help="hpd_kv_append + hpd_decode_attention")
+    ap.add_argument("--copy-calibration", type=int, default=0,
+                    help="after the timed regions, run this many 1 GiB device copies (reference "
+                         "dispatches for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--mask", default="block", choices=["block", "paper"],
+                    help="block: header + own document + own branch (the benchmark's metric); paper: "
+                         "the literal mask over the whole stacked prompt, with the paper's gap positions")
+    ap.add_argument("--phase", default="decode", choices=["decode", "prefill"],
+                    help="decode: the benchmark's metric; prefill: hpd_prefill_attention (the attention of "
+                         "the header and document tokens themselves, first inference step), a side measurement")
+    ap.add_argument("--kernel-mode", type=int, default=0,
+                    help="hpd_set_kernel_mode: 0 automatic (default), 1 generic kernel, 3 / 4 streaming "
+                         "kernel with the wide / narrow workgroup shape")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="side measurement: tail pools paged (hpd_set_tail_pages) with this page size, "
+                         "pages in a seeded random order")
+    ap.add_argument("--dynamic", action="store_true",
+                    help="also time the passes with the live list kept on the GPU (hpd_dynamic_*)")
+    ap.add_argument("--per-step", action="store_true",
+                    help="second run: one event pair per decode step (all replicas of that step back "
+                         "to back), adds per_step {us, gbs} to the record")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2604_26209_amd import binding as B
+    from paper_2604_26209_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+
+    if args.config:  # one configuration, exactly --steps passes
+        rec = measure_decode(args, args.config, args.steps, args.warmup, B, W, torch, np)
+        if rec is None:
+            return
+        wl, paper, attr_len = rec.pop("_workload")
+        if not args.no_cpu_baseline:
+            rec["cpu_baseline"] = cpu_baseline(wl, paper=paper, attr_len=attr_len)
+        print(json.dumps(rec))
+        return
+
+    # ---- the full record: headline on the largest configuration, every configuration in per_config
+    if args.phase != "decode":
+        print("bench.py: --phase prefill needs --config k", file=sys.stderr)
+        sys.exit(2)
+    per_config, head = {}, None
+    for k in (1, 2, 3, 4, 5):
+        print(f"bench: configuration {k}", file=sys.stderr, flush=True)
+        if k == HEADLINE_CONFIG:
+            r = measure_decode(args, k, args.steps, args.warmup, B, W, torch, np)  # exactly --steps passes
+            head = r
+        else:
+            r = measure_decode(args, k, args.steps, args.warmup, B, W, torch, np, min_timed_s=MIN_TIMED_S)
+        rf = r["roofline"]
+        per_config[str(k)] = {
+            "workload": r["config"]["workload"], "value": r["value"], "unit": r["unit"],
+            "passes_timed": r["steps"], "ms_per_pass": r["ms_per_step"],
+            "gpu_ms_per_pass": r["gpu_ms_per_step"], "kernel": rf["kernel"],
+            "avg_launch_us": rf["avg_launch_us"], "launches": rf["launches"],
+            "algorithmic_bytes_per_launch": rf["algorithmic_bytes_per_launch"],
+            "hbm_gbs": rf["hbm_gbs"], "frac": rf["frac_of_hbm_peak"],
+            "useful_tflops": rf["useful_tflops"], "frac_of_mfma_peak": rf["useful_tflops_frac_of_mfma_peak"],
+            "flop_per_byte": rf["flop_per_byte"], "bound": rf["bound"],
+            "traffic": rf["traffic"], "traffic_source": rf["traffic_source"]}
+        if k == 1:
+            per_config["1"]["note"] = ("the correctness configuration: 0.2 MB per step, bound by launch latency "
+                                       "(generic fp32 kernels, two launches per step)")
+    wl, paper, attr_len = head.pop("_workload")
+    head["config"]["headline"] = ("configs[4] is the largest single-GPU configuration (2.6 GB of algorithmic bytes "
+                                  "per launch) and the only one with every part of the path in it: stacked documents "
+                                  "of ragged lengths, ragged branch counts, early stopping")
+    head["per_config"] = per_config
+    if not args.no_peaks:
+        head["measured_peaks"] = measured_peaks(B, torch)
     if not args.no_cpu_baseline:
-        rec["cpu_baseline"] = cpu_baseline(wl, paper=paper, attr_len=attr_len)
-    print(json.dumps(rec))
+        head["cpu_baseline"] = cpu_baseline(wl, paper=paper, attr_len=attr_len)
+    print(json.dumps(head))
 
 
 if __name__ == "__main__":

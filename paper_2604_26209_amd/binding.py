@@ -55,6 +55,8 @@ EXPORTS = ["hpd_build_layout", "hpd_layout_free", "hpd_layout_query", "hpd_prefi
            "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_status_string", "hpd_finetune_mask",
            "hpd_prefill_attention", "hpd_dynamic_begin", "hpd_dynamic_prune", "hpd_dynamic_step",
            "hpd_dynamic_state", "hpd_dynamic_read", "hpd_set_tail_pages"]
+# include/hpd_peaks.h: reference kernels for the benchmark's measured peaks
+PEAK_EXPORTS = ["hpd_peak_read", "hpd_peak_copy", "hpd_peak_mfma"]
 
 
 class hpd_config(ctypes.Structure):
@@ -87,6 +89,11 @@ _lib.hpd_dynamic_state.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp)
 _lib.hpd_dynamic_read.argtypes = [_vp, _i32p, _i32, _i32p, _vp]
 _lib.hpd_set_tail_pages.argtypes = [_vp, _i32, _i32, _vp]
 _lib.hpd_finetune_mask.argtypes = [_i32, _i32, _i32p, _i32p, _i32, _vp, _vp, ctypes.POINTER(ctypes.c_int64), _vp]
+_lib.hpd_peak_read.argtypes = [_vp, ctypes.c_size_t, _vp, _vp]
+_lib.hpd_peak_copy.argtypes = [_vp, _vp, ctypes.c_size_t, _vp]
+_lib.hpd_peak_mfma.argtypes = [_vp, _i32, ctypes.POINTER(ctypes.c_double), _vp]
+for _name in PEAK_EXPORTS:
+    getattr(_lib, _name).restype = ctypes.c_int
 _lib.hpd_status_string.argtypes = [ctypes.c_int]
 _lib.hpd_status_string.restype = ctypes.c_char_p
 for _name in EXPORTS:
@@ -297,6 +304,21 @@ def hpd_finetune_mask(prompt_len, attr_len, value_len, k_max, pos_out=None, mask
                                   v.ctypes.data_as(_i32p), int(k_max), _ptr(pos_out), _ptr(mask_out),
                                   ctypes.byref(s), _stream(stream)), "hpd_finetune_mask")
     return int(s.value)
+
+
+def hpd_peak_read(src, nbytes, sink, stream=None):
+    _check(_lib.hpd_peak_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)), "hpd_peak_read")
+
+
+def hpd_peak_copy(dst, src, nbytes, stream=None):
+    _check(_lib.hpd_peak_copy(_ptr(dst), _ptr(src), int(nbytes), _stream(stream)), "hpd_peak_copy")
+
+
+def hpd_peak_mfma(sink, iters, stream=None) -> float:
+    """Enqueues the MFMA loop; returns the floating-point operations of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check(_lib.hpd_peak_mfma(_ptr(sink), int(iters), ctypes.byref(flops), _stream(stream)), "hpd_peak_mfma")
+    return float(flops.value)
 
 
 def hpd_set_kernel_mode(layout, mode: int):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhpd.so")
-SOURCES = ["hpd_host.cpp", "hpd_kernels.hip", "hpd_attn_stream.hip"]
+SOURCES = ["hpd_host.cpp", "hpd_kernels.hip", "hpd_attn_stream.hip", "hpd_peaks.hip"]
 # packed fp32 instructions are switched off for all device code
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -23,6 +23,13 @@ def test_library_exports_every_declared_symbol():
     for name in declared:
         assert hasattr(lib, name), name
     assert declared == set(B.EXPORTS)
+    # the benchmark's reference kernels have a header of their own
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "hpd_peaks.h")).read(), flags=re.S)
+    peaks = set(re.findall(r"\b(hpd_[a-z_]+)\s*\(", text))
+    assert peaks == set(B.PEAK_EXPORTS)
+    for name in peaks:
+        assert hasattr(lib, name), name
+    assert sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h")) == ["hpd.h", "hpd_peaks.h"]
 
 
 def _host_layout(wl, pos_mode=B.HPD_POS_CONTIG, attr_len=None):
