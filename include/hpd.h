@@ -69,7 +69,9 @@ enum hpd_status {
   HPD_E_OVERFLOW = -2,    /* a position or an offset does not fit its integer type */
   HPD_E_UNSUPPORTED = -3, /* dtype / head_dim / mode the kernels do not cover */
   HPD_E_HIP = -4,         /* HIP runtime error; hpd_status_string(HPD_E_HIP) gives the text */
-  HPD_E_NOMEM = -5
+  HPD_E_NOMEM = -5,
+  HPD_E_CAPACITY = -6     /* the layout needs more than the fixed scratch memory of an
+                             allocation-free call (hpd_dynamic_begin_static) */
 };
 
 enum hpd_dtype { HPD_F32 = 0, HPD_BF16 = 1 };
@@ -289,6 +291,27 @@ int hpd_expand_mask(const hpd_layout* layout, int32_t prompt, int32_t step_hi, u
  * The first four only enqueue on `stream` (hpd_dynamic_begin allocates on its first call).
  */
 int hpd_dynamic_begin(hpd_layout* layout, void* stream);
+
+/*
+ * hpd_dynamic_begin_static - hpd_dynamic_begin for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same
+ * effect - every branch live, hpd_dynamic_prune / _step / _state / _read then work on this state -
+ * but the state lives in a file-scope device array of HPD_DYNAMIC_STATIC_MAX_BYTES that every
+ * GPU the library runs on holds until the process ends, and the call allocates and frees
+ * nothing, on the device or on the host: it only enqueues the kernel that writes the state
+ * (the first call on a device also looks the array's address up).
+ *   - The state needs 4 * (8 * n_docs + B + 20) bytes (HPD_MASK_PAPER: 4 * (16 * P + 2 * B + 20));
+ *     a layout that needs more than HPD_DYNAMIC_STATIC_MAX_BYTES gets HPD_E_CAPACITY and nothing
+ *     is enqueued.
+ *   - One state per GPU: the array is shared by every layout and every call on that GPU and
+ *     keeps the last call's contents (the kernel rewrites every word it later reads; nothing
+ *     has to be cleared).  A second hpd_dynamic_begin_static on the same GPU - for this or
+ *     another layout - replaces the state of the first; calls whose work overlaps on one GPU
+ *     (different streams, different threads) race.  hpd_dynamic_begin switches a layout back to
+ *     a state of its own.
+ */
+#define HPD_DYNAMIC_STATIC_MAX_BYTES (1 << 20)
+int hpd_dynamic_begin_static(hpd_layout* layout, void* stream);
 int hpd_dynamic_prune(hpd_layout* layout, const uint8_t* finished, void* stream);
 int hpd_dynamic_step(const hpd_layout* layout, int32_t step, const void* q, const void* k_new,
                      const void* v_new, const void* k_prefix, const void* v_prefix, void* k_tail,

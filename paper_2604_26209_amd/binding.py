@@ -36,7 +36,8 @@ def _load():
 
 _lib = _load()
 
-HPD_OK, HPD_E_INVALID, HPD_E_OVERFLOW, HPD_E_UNSUPPORTED, HPD_E_HIP, HPD_E_NOMEM = 0, -1, -2, -3, -4, -5
+HPD_OK, HPD_E_INVALID, HPD_E_OVERFLOW, HPD_E_UNSUPPORTED, HPD_E_HIP, HPD_E_NOMEM, HPD_E_CAPACITY = 0, -1, -2, -3, -4, -5, -6
+HPD_DYNAMIC_STATIC_MAX_BYTES = 1 << 20
 HPD_F32, HPD_BF16 = 0, 1
 HPD_POS_CONTIG, HPD_POS_PAPER_GAP = 0, 1
 HPD_MASK_BLOCK = 0
@@ -54,7 +55,7 @@ EXPORTS = ["hpd_build_layout", "hpd_layout_free", "hpd_layout_query", "hpd_prefi
            "hpd_rope_positions", "hpd_kv_append", "hpd_decode_attention", "hpd_decode_step",
            "hpd_expand_mask", "hpd_set_kernel_mode", "hpd_status_string", "hpd_finetune_mask",
            "hpd_prefill_attention", "hpd_dynamic_begin", "hpd_dynamic_prune", "hpd_dynamic_step",
-           "hpd_dynamic_state", "hpd_dynamic_read", "hpd_set_tail_pages"]
+           "hpd_dynamic_state", "hpd_dynamic_read", "hpd_set_tail_pages", "hpd_dynamic_begin_static"]
 # include/hpd_peaks.h: reference kernels for the benchmark's measured peaks
 PEAK_EXPORTS = ["hpd_peak_read", "hpd_peak_copy", "hpd_peak_mfma"]
 
@@ -83,6 +84,7 @@ _lib.hpd_expand_mask.argtypes = [_vp, _i32, _i32, _vp, _i32p, _vp]
 _lib.hpd_set_kernel_mode.argtypes = [_vp, _i32]
 _lib.hpd_prefill_attention.argtypes = [_vp] * 6
 _lib.hpd_dynamic_begin.argtypes = [_vp, _vp]
+_lib.hpd_dynamic_begin_static.argtypes = [_vp, _vp]
 _lib.hpd_dynamic_prune.argtypes = [_vp, _vp, _vp]
 _lib.hpd_dynamic_step.argtypes = [_vp, _i32] + [_vp] * 9
 _lib.hpd_dynamic_state.argtypes = [_vp, ctypes.POINTER(_vp), ctypes.POINTER(_vp)]
@@ -249,6 +251,10 @@ def hpd_prefill_attention(layout, q, k_prefix, v_prefix, out, stream=None):
 
 def hpd_dynamic_begin(layout, stream=None):
     _check(_lib.hpd_dynamic_begin(layout.handle, _stream(stream)), "hpd_dynamic_begin")
+
+
+def hpd_dynamic_begin_static(layout, stream=None):
+    _check(_lib.hpd_dynamic_begin_static(layout.handle, _stream(stream)), "hpd_dynamic_begin_static")
 
 
 def hpd_dynamic_prune(layout, finished, stream=None):

@@ -74,6 +74,7 @@ const char* hpd_status_string(int status) {
     case HPD_E_UNSUPPORTED: return "unsupported dtype, head_dim or mode";
     case HPD_E_HIP: return g_hip_text.c_str();
     case HPD_E_NOMEM: return "out of host memory";
+    case HPD_E_CAPACITY: return "the layout exceeds the fixed scratch memory of the allocation-free call";
     default: return "unknown status";
   }
 }
@@ -738,6 +739,20 @@ int hpd_dynamic_begin(hpd_layout* L, void* stream) {
   dynamic_state_bind(L, L->d_dyn);
   L->dyn_next_step = 0;
   HPD_HIP(hpd_launch_dynamic_prune(L, 0, nullptr, s));
+  return HPD_OK;
+}
+
+int hpd_dynamic_begin_static(hpd_layout* L, void* stream) {
+  int rc = dynamic_supported(L);
+  if (rc != HPD_OK) return rc;
+  if (dynamic_state_words(L) * sizeof(int32_t) > (size_t)HPD_DYNAMIC_STATIC_MAX_BYTES) return HPD_E_CAPACITY;
+  void* mem = nullptr;
+  size_t bytes = 0;
+  HPD_HIP(hpd_dynamic_scratch(L->device, &mem, &bytes));
+  if (dynamic_state_words(L) * sizeof(int32_t) > bytes) return HPD_E_CAPACITY;
+  dynamic_state_bind(L, mem);
+  L->dyn_next_step = 0;
+  HPD_HIP(hpd_launch_dynamic_prune(L, 0, nullptr, (hipStream_t)stream));
   return HPD_OK;
 }
 

@@ -140,3 +140,6 @@ hipError_t hpd_launch_attention_stream(const hpd_layout* L, int32_t step, const 
                                        hipStream_t s, bool dynamic = false);
 hipError_t hpd_launch_dynamic_prune(const hpd_layout* L, int32_t next_step, const uint8_t* finished,
                                     hipStream_t s);
+// Address (on `device`) and size of the library's file-scope scratch array, resolved on first
+// use per device.  Allocates nothing.
+hipError_t hpd_dynamic_scratch(int device, void** ptr, size_t* bytes);

@@ -3,6 +3,7 @@
 // covers fp32, odd shapes and serves as the fallback.  The MFMA shared-prefix kernel is
 // in hpd_attn_stream.hip.
 #include <algorithm>
+#include <mutex>
 
 #include "hpd_internal.h"
 #include "hpd_device.h"
@@ -672,6 +673,40 @@ hipError_t hpd_launch_finetune_mask(const int32_t* d_desc, int32_t S, int32_t* p
   if (pos_out) finetune_pos_kernel<<<grid1d(S, 256), 256, 0, s>>>(d_desc, S, pos_out);
   if (mask_out) finetune_mask_kernel<<<grid1d((int64_t)S * S, 256), 256, 0, s>>>(d_desc, S, mask_out);
   return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// File-scope device memory for hpd_dynamic_begin_static (callers that cannot allocate): the
+// pruning state of one layout per GPU.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address kernels may use is looked up once per device, with that
+// device current, and kept.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) int32_t scratch[HPD_DYNAMIC_STATIC_MAX_BYTES / sizeof(int32_t)];
+
+hipError_t hpd_dynamic_scratch(int device, void** ptr, size_t* bytes) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex mu;
+  static void* dev_ptr[MAX_DEVICES] = {};
+  if (device < 0 || device >= MAX_DEVICES || !ptr || !bytes) return hipErrorInvalidValue;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!dev_ptr[device]) {
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return e;
+    if (cur != device && (e = hipSetDevice(device)) != hipSuccess) return e;
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (cur != device) {
+      const hipError_t e2 = hipSetDevice(cur);
+      if (e == hipSuccess) e = e2;
+    }
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    dev_ptr[device] = p;
+  }
+  *ptr = dev_ptr[device];
+  *bytes = sizeof(scratch);
+  return hipSuccess;
 }
 
 hipError_t hpd_launch_dynamic_prune(const hpd_layout* L, int32_t next_step, const uint8_t* finished,

@@ -29,6 +29,7 @@ hipError_t hpd_launch_prefill_generic(const hpd_layout*, const void*, const void
 hipError_t hpd_launch_attention_stream(const hpd_layout*, int32_t, const void*, const void*, const void*, void*,
                                        void*, const void*, const void*, void*, hipStream_t, bool) STUB()
 hipError_t hpd_launch_dynamic_prune(const hpd_layout*, int32_t, const uint8_t*, hipStream_t) STUB()
+hipError_t hpd_dynamic_scratch(int, void**, size_t*) STUB()
 
 #define CHECK(cond)                                                          \
   do {                                                                       \
@@ -125,6 +126,7 @@ int main() {
     CHECK(hpd_prefix_fill(L, &none, &none, &none, &none, nullptr) == HPD_E_INVALID);
     CHECK(hpd_prefill_attention(L, &none, &none, &none, &none, nullptr) == HPD_E_INVALID);
     CHECK(hpd_dynamic_begin(L, nullptr) == HPD_E_INVALID);
+    CHECK(hpd_dynamic_begin_static(L, nullptr) == HPD_E_INVALID);
     CHECK(hpd_set_tail_pages(L, 8, 4, &none) == HPD_E_INVALID);
     int32_t s_out = 0;
     CHECK(hpd_expand_mask(L, 0, -1, nullptr, &s_out, nullptr) == HPD_E_INVALID);
