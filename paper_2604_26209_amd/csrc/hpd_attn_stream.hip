@@ -143,6 +143,14 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // loaders use it for table lookups: a vector load would have to wait for every DMA instruction
 // in front of it, because vector memory operations of a wave complete in order.
 __device__ __forceinline__ int32_t scalar_load(const int32_t* p) {
+  // (the address is wave-uniform by the caller's construction; where the compiler keeps it in
+  // vector registers all the same, it is moved to scalar ones here)
+  const uint64_t u = reinterpret_cast<uint64_t>(p);
+  // (readfirstlane returns a signed int: without the casts a low half with its top bit set
+  // would be sign-extended over the high half)
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(u >> 32));
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int32_t)(uint32_t)u);
+  p = reinterpret_cast<const int32_t*>(((uint64_t)hi << 32) | (uint64_t)lo);
   int32_t v;
   asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(p) : "memory");
   return v;
@@ -201,6 +209,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   __shared__ uint4 ring2[STAGE_U4];
   __shared__ uint4 ring3[STAGE_U4];
   __shared__ float4 rope_q[32];  // (cos, sin) row of the unit's shared position
+  // first pool row of the newest chunk of tail positions, per branch of the row group
+  __shared__ int64_t chunk_row[(MODE == MODE_BLOCK || MODE == MODE_PAGED) ? SH::CW * 32 : 1];
   constexpr int MAX_KEY_BRANCHES = 256;
   __shared__ int32_t klen[PAPER ? MAX_KEY_BRANCHES : 1];  // tokens in memory of every key branch
   constexpr int MAX_LIST_BLOCKS = 512;
@@ -277,7 +287,19 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   const int32_t NB = NBh + NBd;
   const int32_t NQ = ((PAPER ? kb_end : nbr_here) + 3) >> 2;  // quads of 4 (key) branches
   const int32_t NC = (a.step >> 3) + 1;    // chunks of 8 positions that hold positions 0 .. step
-  const int32_t NTT = PREFILL ? 0 : NQ * NC;
+  // The newest chunk holds step % 8 + 1 positions.  A tile of 8 positions x 4 branches would
+  // be loaded and multiplied in full for them; instead the tile takes fewer positions of more
+  // branches - 4 x 8, 2 x 16 or 1 x 32, key k = position k % NPOS of branch k / NPOS - so that
+  // the number of tiles, hence of loads and of matrix blocks, follows the number of tail keys
+  // that exist (which is what the tails cost in bytes).  The rows come from everywhere in the
+  // tail pools; where each branch's rows start is kept in LDS (chunk_row).
+  constexpr bool FMT = MODE == MODE_BLOCK || MODE == MODE_PAGED;
+  const int32_t newest = (a.step & 7) + 1;  // positions in the newest chunk
+  const int32_t fmt_lg = !FMT ? 3 : newest <= 1 ? 0 : newest <= 2 ? 1 : newest <= 4 ? 2 : 3;  // log2(NPOS)
+  const bool use_fmt = FMT && fmt_lg < 3;
+  const int32_t n_full_tiles = use_fmt ? NQ * (NC - 1) : NQ * NC;  // tiles of 8 positions x 4 branches
+  const int32_t n_fmt_tiles = use_fmt ? (nbr_here + (32 >> fmt_lg) - 1) >> (5 - fmt_lg) : 0;
+  const int32_t NTT = PREFILL ? 0 : n_full_tiles + n_fmt_tiles;
   const int32_t NBT = NB + NTT;
   const int32_t NR = (NBT + STAGE_BLOCKS - 1) / STAGE_BLOCKS;
   // A round is one stage while the stream is in the prefix and two stages from the first
@@ -318,8 +340,6 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   //      lines costs the memory pipeline 8 times as much as one whose lanes touch 8.
   // MFMA row m of a score tile carries this key of the block (see the file header)
   const int32_t krow = ((n >> 4) << 4) | (((n >> 2) & 1) << 3) | (((n >> 3) & 1) << 2) | (n & 3);
-  const uint16_t* kbase = k_prefix + (int64_t)hk * a.NP * D;
-  const uint16_t* vbase = v_prefix + (int64_t)hk * (a.NP / 8) * D * 8;
   // K half of a slot (prefix and tail): 32 rows of 256 bytes, row = key, the 16-byte chunk c of
   // row k at position c ^ (k & 15) (conflict-free fragment reads).  Load f of quarter h brings
   // rows k = h*16 + f*4 + lane/16: lane%16 is the position, so the chunk to fetch is
@@ -327,109 +347,134 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // V half of a prefix block: fragment order, straight out of the 8-key interleaved pool:
   // key halves 0 / 1 (2*D*8 elements apart) of d-blocks 2*h, 2*h+1 (32 channels * 8 apart).
   // V half of a tail tile: 32 rows of 256 bytes like K, chunk position c ^ 4*(bit 3 of k).
+  //
+  // A wave issues one instruction every few cycles at best, and a loader's requests are the
+  // stream: whatever it executes between two DMA instructions is time in which nothing is
+  // requested (measured: with ~150 scalar and vector instructions per four loads the issue of a
+  // block took longer than its transfer).  So everything that depends on the lane alone is
+  // computed once (byte offsets of its 16 bytes inside a block: ck, kq, vq, cv), the address of a
+  // load is a wave-uniform base plus such a 32-bit offset, and a block is 16 loads in a row.
+  uint32_t ck[4], kq[4], cv[2];
+#pragma unroll
+  for (int f = 0; f < 4; ++f) {
+    ck[f] = (uint32_t)((c16 ^ r4 ^ (4 * f)) << 4);   // chunk of row f*4 + r4 this lane fetches (K rows)
+    kq[f] = (uint32_t)(f * 1024 + r4 * 256) + ck[f];  // ... plus the row inside the quarter of a prefix block
+  }
+  cv[0] = (uint32_t)(c16 << 4);
+  cv[1] = (uint32_t)((c16 ^ 4) << 4);
+  const uint32_t vq = (uint32_t)((g2 * 128 + n) << 4);  // this lane's 16 bytes of a V fragment run
+  const char* const kpool = reinterpret_cast<const char*>(k_prefix) + (int64_t)hk * a.NP * (D * 2);
+  const char* const vpool = reinterpret_cast<const char*>(v_prefix) + (int64_t)hk * a.NP * (D * 2);
+  const char* const ktb = reinterpret_cast<const char*>(k_tail);
+  const char* const vtb = reinterpret_cast<const char*>(v_tail);
+  // 16 loads of a prefix block: K quarters 0, 1 (rows 0..15, 16..31), V quarters 2, 3
+#define HPD_PREFIX_BLOCK(GL)                                                                      \
+  GL(sK + kq[0], dst); GL(sK + kq[1], dst + 1024); GL(sK + kq[2], dst + 2048); GL(sK + kq[3], dst + 3072); \
+  GL(sK + 4096 + kq[0], dst + 4096); GL(sK + 4096 + kq[1], dst + 5120);                          \
+  GL(sK + 4096 + kq[2], dst + 6144); GL(sK + 4096 + kq[3], dst + 7168);                          \
+  GL(sV + vq, dst + 8192); GL(sV + 4096 + vq, dst + 9216); GL(sV + 512 + vq, dst + 10240);       \
+  GL(sV + 4608 + vq, dst + 11264);                                                               \
+  GL(sV + 1024 + vq, dst + 12288); GL(sV + 5120 + vq, dst + 13312); GL(sV + 1536 + vq, dst + 14336); \
+  GL(sV + 5632 + vq, dst + 15360)
   auto issue_block = [&](int32_t gb_raw, uint4* dst_slot) {
     // a slot past the last block re-loads the last block (never read): the count stays fixed
     const int32_t gb = min(gb_raw, NBT - 1);
-    int32_t slot0 = 0, tc = 0, tq = 0;
-    int32_t last4[4] = {0, 0, 0, 0};
-    const bool prefix = gb < NB;
-    if (prefix) {
+    char* const dst = reinterpret_cast<char*>(dst_slot);
+    if (gb < NB) {
+      int32_t slot0;
       if (PAPER) slot0 = gb < NBh ? hoff + gb * 32 : scalar_load(a.tb.pblk + 2 * (doff + gb - NBh));
       else if (PLIST) slot0 = gb < NBh ? scalar_load(a.tb.fblk + 2 * (hoff + gb)) : doff + (gb - NBh) * 32;
       else slot0 = gb < NBh ? hoff + gb * 32 : doff + (gb - NBh) * 32;
-    } else {
-      // tail tile: key k = position c*8 + k%8 of branch qd*4 + k/8; row k = h*16 + f*4 + lane/16
-      // is position (f&1)*4 + lane/16 of branch 2*h + f/2.  Branches and positions past the
-      // end repeat the last valid one (masked by the consumer).
-      const int32_t tt = gb - NB;
-      tc = tt / NQ;
-      tq = quad_of(tt - tc * NQ);
-      if (PAPER) {
-        // last position in memory of the quad's four key branches (one lookup per tile): a
-        // finished branch stops at its own length, the rows behind it were never written
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          last4[i] = min(a.step, scalar_load(a.tb.branch_len + pb0 + min(tq * 4 + i, kb_end - 1)) - 1);
+      const char* const sK = kpool + (int64_t)slot0 * (D * 2);
+      const char* const sV = vpool + (int64_t)slot0 * (D * 2);
+      // Document blocks - unless several row groups stream the same prefix - are read once per
+      // launch: ask the caches not to keep them (measured: 4-5 % on the memory-bound
+      // configurations).  The header is shared by the documents of its prompt and stays cacheable.
+      if (a.RG == 1 && gb >= NBh) {
+        HPD_PREFIX_BLOCK(HPD_GLL_NT);
+      } else {
+        HPD_PREFIX_BLOCK(HPD_GLL);
       }
+      return;
     }
+    const int32_t tt = gb - NB;
+    if (FMT && tt >= n_full_tiles) {
+      // a tile of the newest chunk in the format fmt_lg: row k = h*16 + f*4 + lane/16 of the
+      // slot is position k % NPOS of the tile's branch k / NPOS, a per-lane address from the
+      // table in LDS (the same row of the K and of the V pool).  Branches and positions past
+      // the end repeat the last valid one.
+      const int32_t tb0 = (tt - n_full_tiles) << (5 - fmt_lg);
+      const int32_t pmask = (1 << fmt_lg) - 1, last = newest - 1;
 #pragma nounroll
-    for (int32_t part = 0; part < 4; ++part) {
-      const bool is_k = part < 2;
-      const int32_t half = part & 1;
-      const int32_t e0 = is_k ? ((c16 ^ r4) << 3) : (c16 << 3);  // row-major loads: element in the row, load 0
-      const int32_t x1 = is_k ? 32 : 0, x2 = is_k ? 64 : 32;     // ... XORed with this for loads 1, 2 (3: both)
-      uint4* dst = dst_slot + part * 4 * 64;
-      const uint16_t *p0, *p1, *p2, *p3;
-      if (prefix) {
-        if (is_k) {
-          const uint16_t* rowp = kbase + (int64_t)(slot0 + half * 16 + r4) * D;
-          p0 = rowp + e0;
-          p1 = rowp + 4 * D + (e0 ^ x1);
-          p2 = rowp + 8 * D + (e0 ^ x2);
-          p3 = rowp + 12 * D + (e0 ^ x1 ^ x2);
-        } else {
-          p0 = vbase + (int64_t)(slot0 / 8) * D * 8 + (g2 * D + half * 64 + n) * 8;
-          p1 = p0 + 2 * D * 8;
-          p2 = p0 + 32 * 8;
-          p3 = p1 + 32 * 8;
+      for (int32_t half = 0; half < 2; ++half) {
+        char* const dk = dst + half * 4096;
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+          const int32_t k = half * 16 + f * 4 + r4;
+          const int32_t j = min(tb0 + (k >> fmt_lg), nbr_here - 1);
+          const int64_t row = (chunk_row[j] + min(k & pmask, last)) * (D * 2);
+          HPD_GLL_NT(ktb + row + ck[f], dk + f * 1024);
+          HPD_GLL_NT(vtb + row + cv[f >> 1], dk + 8192 + f * 1024);
         }
-      } else {
-        // the branch of a load is the same in all lanes: a scalar lookup
-        int32_t bA, bB, lastA = a.step, lastB = a.step;  // branch ids; last position in memory
-        if (PAPER) {
-          // key branches are consecutive ids from the prompt's first
-          bA = pb0 + min(tq * 4 + half * 2, kb_end - 1);
-          bB = pb0 + min(tq * 4 + half * 2 + 1, kb_end - 1);
-          lastA = half ? last4[2] : last4[0];
-          lastB = half ? last4[3] : last4[1];
-        } else {
-          const int32_t lbA = min(tq * 4 + half * 2, nbr_here - 1), lbB = min(tq * 4 + half * 2 + 1, nbr_here - 1);
-          const int32_t* ids = a.tb.live_branch + (a.live_base + row0_live + br0);
-          bA = ub0 >= 0 ? ub0 + br0 + lbA : scalar_load(ids + lbA);
-          bB = ub0 >= 0 ? ub0 + br0 + lbB : scalar_load(ids + lbB);
-        }
-        int32_t posA = min(tc * 8 + r4, lastA), posB = min(tc * 8 + 4 + r4, lastA);
-        int32_t posC = min(tc * 8 + r4, lastB), posD = min(tc * 8 + 4 + r4, lastB);
-        const uint16_t* pool = is_k ? k_tail : v_tail;
-        const uint16_t *rowA, *rowB;
-        if (PAGED || (PAPER && a.tb.tail_pages)) {
-          // a page holds a multiple of 8 steps, so the 8 positions of the tile (clamped to the
-          // newest row of the branch, which lies in or behind them) share one page per branch
-          const int32_t pmask = (1 << a.tb.page_shift) - 1;
-          const int32_t piA = min(tc * 8, lastA) >> a.tb.page_shift, piB = min(tc * 8, lastB) >> a.tb.page_shift;
-          int32_t pgA = scalar_load(a.tb.tail_pages + (int64_t)bA * a.tb.pages_per_branch + piA);
-          int32_t pgB = scalar_load(a.tb.tail_pages + (int64_t)bB * a.tb.pages_per_branch + piB);
-          pgA = min(max(pgA, 0), a.tb.n_pages - 1);
-          pgB = min(max(pgB, 0), a.tb.n_pages - 1);
-          rowA = pool + ((((int64_t)pgA * a.Hkv + hk)) << a.tb.page_shift) * D;
-          rowB = pool + ((((int64_t)pgB * a.Hkv + hk)) << a.tb.page_shift) * D;
-          posA &= pmask, posB &= pmask, posC &= pmask, posD &= pmask;
-        } else {
-          rowA = pool + ((int64_t)bA * a.Hkv + hk) * a.Tcap * D;
-          rowB = pool + ((int64_t)bB * a.Hkv + hk) * a.Tcap * D;
-        }
-        p0 = rowA + (int64_t)posA * D + e0;
-        p1 = rowA + (int64_t)posB * D + (e0 ^ x1);
-        p2 = rowB + (int64_t)posC * D + (e0 ^ x2);
-        p3 = rowB + (int64_t)posD * D + (e0 ^ x1 ^ x2);
       }
-      // Tail rows and - unless several row groups stream the same prefix - document blocks are
-      // read once per launch: ask the caches not to keep them (measured: 4-5 % on the
-      // memory-bound configurations).  The header is shared by the documents of its prompt and
-      // stays cacheable.
-      if (!prefix || (a.RG == 1 && gb >= NBh)) {
-        HPD_GLL_NT(p0, dst);
-        HPD_GLL_NT(p1, dst + 64);
-        HPD_GLL_NT(p2, dst + 128);
-        HPD_GLL_NT(p3, dst + 192);
+      return;
+    }
+    // tail tile: key k = position c*8 + k%8 of branch qd*4 + k/8; row k = h*16 + f*4 + lane/16
+    // is position (f&1)*4 + lane/16 of branch 2*h + f/2.  Branches and positions past the end
+    // repeat the last valid one (masked by the consumer).  The branch of a load is the same in
+    // all lanes: scalar lookups, once per tile.
+    const int32_t tc = tt / NQ;
+    const int32_t tq = quad_of(tt - tc * NQ);
+    const bool paged = PAGED || (PAPER && a.tb.tail_pages);
+    const int32_t pg_mask = paged ? (1 << a.tb.page_shift) - 1 : 0x7fffffff;
+    // first byte of the rows of the quad's i-th branch (of the page that holds the chunk) in both
+    // pools, and its last position in memory
+    auto branch_rows = [&](int32_t i, int64_t& rowb, int32_t& last) {
+      int32_t b;
+      last = a.step;
+      if (PAPER) {
+        // key branches are consecutive ids from the prompt's first; a finished branch stops at
+        // its own length, the rows behind it were never written
+        b = pb0 + min(tq * 4 + i, kb_end - 1);
+        last = min(a.step, scalar_load(a.tb.branch_len + b) - 1);
       } else {
-        HPD_GLL(p0, dst);
-        HPD_GLL(p1, dst + 64);
-        HPD_GLL(p2, dst + 128);
-        HPD_GLL(p3, dst + 192);
+        const int32_t lb = min(tq * 4 + i, nbr_here - 1);
+        b = ub0 >= 0 ? ub0 + br0 + lb : scalar_load(a.tb.live_branch + (a.live_base + row0_live + br0) + lb);
       }
+      if (paged) {
+        // a page holds a multiple of 8 steps, so the 8 positions of the tile (clamped to the
+        // newest row of the branch, which lies in or behind them) share one page per branch
+        int32_t pg = scalar_load(a.tb.tail_pages + (int64_t)b * a.tb.pages_per_branch +
+                                 (min(tc * 8, last) >> a.tb.page_shift));
+        pg = min(max(pg, 0), a.tb.n_pages - 1);
+        rowb = ((((int64_t)pg * a.Hkv + hk)) << a.tb.page_shift) * (D * 2);
+      } else {
+        rowb = ((int64_t)b * a.Hkv + hk) * a.Tcap * (D * 2);
+      }
+    };
+#pragma nounroll
+    for (int32_t half = 0; half < 2; ++half) {
+      int64_t rowA, rowB;
+      int32_t lastA, lastB;
+      branch_rows(2 * half, rowA, lastA);
+      branch_rows(2 * half + 1, rowB, lastB);
+      const uint32_t pA0 = (uint32_t)((min(tc * 8 + r4, lastA) & pg_mask) << 8);
+      const uint32_t pA1 = (uint32_t)((min(tc * 8 + 4 + r4, lastA) & pg_mask) << 8);
+      const uint32_t pB0 = (uint32_t)((min(tc * 8 + r4, lastB) & pg_mask) << 8);
+      const uint32_t pB1 = (uint32_t)((min(tc * 8 + 4 + r4, lastB) & pg_mask) << 8);
+      char* const dk = dst + half * 4096;
+      char* const dv = dst + 8192 + half * 4096;
+      HPD_GLL_NT(ktb + rowA + (pA0 + ck[0]), dk);
+      HPD_GLL_NT(ktb + rowA + (pA1 + ck[1]), dk + 1024);
+      HPD_GLL_NT(ktb + rowB + (pB0 + ck[2]), dk + 2048);
+      HPD_GLL_NT(ktb + rowB + (pB1 + ck[3]), dk + 3072);
+      HPD_GLL_NT(vtb + rowA + (pA0 + cv[0]), dv);
+      HPD_GLL_NT(vtb + rowA + (pA1 + cv[0]), dv + 1024);
+      HPD_GLL_NT(vtb + rowB + (pB0 + cv[1]), dv + 2048);
+      HPD_GLL_NT(vtb + rowB + (pB1 + cv[1]), dv + 3072);
     }
   };
+#undef HPD_PREFIX_BLOCK
   // ---- fused mode: the compute waves append the newest token of the row group's branches (the
   //      arithmetic of hpd_kv_append), 8 lanes per branch: channels c .. c+7 and 64+c .. 64+c+7.
   //      PAPER: the rows also see the newest token of every earlier live branch of the prompt,
@@ -473,9 +518,22 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // with a shorter prefix the append is completed before anything is loaded.
   const bool append_first = a.fused && NB < 4 * STAGE_BLOCKS;
   const int32_t r_pub = (a.fused && !append_first) ? 1 : -1;
-  if (append_first) {
-    if (!loader) append_from(ap_first + (tid >> 3));
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  // The table of the newest chunk's rows is written by the compute waves before the first of
+  // the two barriers of the query staging; the loaders request rounds 0 and 1 before that
+  // barrier.  If a tile of the newest chunk can be among them the table is written first.
+  auto fill_chunk_rows = [&]() {
+    if constexpr (FMT) {
+      for (int32_t j = tid; j < nbr_here; j += CWAVES * 64)
+        chunk_row[j] = hpd_tail_row(a.tb, branch_id(j), hk, a.Hkv, a.Tcap, (NC - 1) * 8);
+    }
+  };
+  const bool table_first = use_fmt && NB + n_full_tiles < 2 * STAGE_BLOCKS;
+  if (append_first || table_first) {
+    if (!loader) {
+      if (append_first) append_from(ap_first + (tid >> 3));
+      if (table_first) fill_chunk_rows();
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __syncthreads();
   }
 
@@ -549,6 +607,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       (row < STAGE_ROWS ? ring2 : ring3)[(row % STAGE_ROWS) * 16 + (c16 ^ (row & 15))] = qv[b];
   }
   if (upos >= 0 && wave == 0 && lane < 32) rope_q[lane] = rope_v;
+  if (use_fmt && !table_first) fill_chunk_rows();
   if constexpr (PAPER) {
     // tokens in memory of every key branch: min(step + 1, its length)
     for (int32_t i = tid; i < kb_end; i += CWAVES * 64) klen[i] = min(a.step + 1, a.tb.branch_len[pb0 + i]);
@@ -786,10 +845,20 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
           ok = first_bits(valid - g2 * 8) | (first_bits(valid - 16 - g2 * 8) << 8);
         } else {
           const int32_t tt = gb - NB;
-          const int32_t c = tt / NQ, qd = quad_of(tt - c * NQ);
           masked = true;
           tail = true;
-          if constexpr (PAPER) {
+          if (FMT && tt >= n_full_tiles) {
+            // a tile of the newest chunk: positions 0 .. newest-1 of the branches tb0 .. of the
+            // row group, NPOS keys apart; every row block that holds one of them works on it
+            const int32_t li = tt - n_full_tiles;
+            const int32_t tb0 = li << (5 - fmt_lg);
+            mine = rb * BPB < tb0 + (32 >> fmt_lg) && (rb + 1) * BPB > tb0 && li % KG == kg;
+            const int32_t k0 = (lb_row - tb0) << fmt_lg;  // this row's first key in the tile
+            const int32_t lo = k0 - g2 * 8, hi = lo + newest;
+            ok = (k0 >= 0 && k0 < 32) ? ((first_bits(hi) & ~first_bits(lo)) |
+                                         ((first_bits(hi - 16) & ~first_bits(lo - 16)) << 8)) : 0u;
+          } else if constexpr (PAPER) {
+            const int32_t c = tt / NQ, qd = quad_of(tt - c * NQ);
             // every row block that holds a branch not earlier than the quad's first works on
             // the tile; a row keeps the tokens in memory of the branches up to its own
             mine = qd * 4 <= kb_row_max && (c + qd) % KG == kg;
@@ -797,6 +866,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
             const int32_t cntA = kA < kb_end ? klen[kA] : 0, cntB = kB < kb_end ? klen[kB] : 0;
             ok = (kA <= kb_row ? first_bits(cntA - c * 8) : 0u) | (kB <= kb_row ? first_bits(cntB - c * 8) << 8 : 0u);
           } else {
+            const int32_t c = tt / NQ, qd = quad_of(tt - c * NQ);
             mine = qd / QPR == rb && (c * QPR + qd % QPR) % KG == kg;
             const uint32_t pm = first_bits(a.step + 1 - c * 8);
             ok = (qd * 4 + g2 == lb_row ? pm : 0u) | (qd * 4 + 2 + g2 == lb_row ? pm << 8 : 0u);
