@@ -17,7 +17,8 @@
 extern "C" {
 #endif
 
-/* reads `bytes` bytes of src once (16-byte loads, grid-stride); sink: 4 bytes, practically never written */
+/* reads `bytes` bytes of src once (16-byte loads, a contiguous share per workgroup; a remainder of less
+ * than 16 bytes per workgroup of the 32 x compute-unit grid is left out); sink: 4 bytes, practically never written */
 int hpd_peak_read(const void* src, size_t bytes, void* sink, void* stream);
 /* dst[i] = src[i] over `bytes` bytes (16-byte loads and stores) */
 int hpd_peak_copy(void* dst, const void* src, size_t bytes, void* stream);
