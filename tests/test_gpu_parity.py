@@ -93,6 +93,30 @@ def test_random_layout_sweep_stream_kernel(seed):
         H.check_all(wl, hip, label=f"sweep_{seed}_m{mode}")
 
 
+@pytest.mark.parametrize("mode", [3, 4])
+@pytest.mark.parametrize("case", ["tiny_prefix", "many_branches", "no_header_one_key"])
+def test_tail_tile_formats_of_the_newest_chunk(case, mode):
+    """The newest chunk of tail positions is cut into tiles of 1 x 32, 2 x 16, 4 x 8 or 8 x 4
+    (positions x branches) depending on how many positions it holds: every step 0..11 goes through
+    each format at least once, with full chunks behind it from step 8 on.  Cases: prefixes so short
+    that a tile of the newest chunk is among the first requests (its row table is then written
+    before the loaders start); documents with more branches than one tile or one row block holds
+    (tiles that span row blocks, ragged last tile); no header and a one-token document.  Every
+    group size; fused = two-call bit for bit; against the oracle."""
+    kw = dict(tiny_prefix=dict(p=3, j_range=(1, 3), n_range=(1, 40), h_range=(0, 20), l_range=(1, 40)),
+              many_branches=dict(p=2, j_range=(1, 2), n_range=(30, 70), h_range=(0, 70), l_range=(1, 300)),
+              no_header_one_key=dict(p=2, j_range=(1, 3), n_range=(1, 35), h_range=(0, 0), l_range=(1, 1)))[case]
+    for g in (1, 2, 4, 8):
+        _say(f"tile formats: {case} G={g} mode {mode}")
+        wl = W.random_workload(300 + g, dtype="bf16", hq=8, hkv=8 // g, d=128, base=500000.0, t=12, **kw)
+        a = H.run_hip(wl, kernel_mode=mode, fused=True)
+        rel = H.check_all(wl, a, label=f"fmt_{case}_g{g}_m{mode}")
+        b = H.run_hip(wl, inputs=a["inputs"], kernel_mode=mode, fused=False)
+        for x, y in zip(a["out"], b["out"]):
+            assert torch.equal(x, y)
+        _say(f"  worst err/rms {rel:.2e}")
+
+
 @pytest.mark.parametrize("g", [3, 5, 6, 7])
 def test_stream_kernel_group_sizes_that_are_not_powers_of_two(g):
     """Group sizes such as 40 query heads over 8 kv heads (5) run on the streaming kernel with
