@@ -139,6 +139,15 @@ __device__ __forceinline__ void unpack8(uint4 a, float out[8]) {
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// ds_read_b64_tr_b16: within each 16 lanes, lane i receives element i % 4 of the 8 bytes that the
+// lanes 4*j + i/4 (j = 0..3) address, in the order of j: a 4 x 16 transpose of 2-byte elements.
+typedef short short4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint2 lds_read_tr16(const char* p) {
+  const short4v v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) short4v*)(uintptr_t)p);
+  return __builtin_bit_cast(uint2, v);
+}
+
 // A 32-bit word at a wave-uniform address through the scalar data cache (read only).  The
 // loaders use it for table lookups: a vector load would have to wait for every DMA instruction
 // in front of it, because vector memory operations of a wave complete in order.
@@ -346,7 +355,9 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // (lane%16) ^ (f*4 + lane/16).
   // V half of a prefix block: fragment order, straight out of the 8-key interleaved pool:
   // key halves 0 / 1 (2*D*8 elements apart) of d-blocks 2*h, 2*h+1 (32 channels * 8 apart).
-  // V half of a tail tile: 32 rows of 256 bytes like K, chunk position c ^ 4*(bit 3 of k).
+  // V half of a tail tile: 32 rows of 256 bytes like K, chunk position c ^ 2*(k & 3): the
+  // transposing fragment read of the consumer takes 32 bytes of each of 4 consecutive rows per
+  // 16 lanes, which this spreads over all banks.
   //
   // A wave issues one instruction every few cycles at best, and a loader's requests are the
   // stream: whatever it executes between two DMA instructions is time in which nothing is
@@ -354,14 +365,13 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // block took longer than its transfer).  So everything that depends on the lane alone is
   // computed once (byte offsets of its 16 bytes inside a block: ck, kq, vq, cv), the address of a
   // load is a wave-uniform base plus such a 32-bit offset, and a block is 16 loads in a row.
-  uint32_t ck[4], kq[4], cv[2];
+  uint32_t ck[4], kq[4];
 #pragma unroll
   for (int f = 0; f < 4; ++f) {
     ck[f] = (uint32_t)((c16 ^ r4 ^ (4 * f)) << 4);   // chunk of row f*4 + r4 this lane fetches (K rows)
     kq[f] = (uint32_t)(f * 1024 + r4 * 256) + ck[f];  // ... plus the row inside the quarter of a prefix block
   }
-  cv[0] = (uint32_t)(c16 << 4);
-  cv[1] = (uint32_t)((c16 ^ 4) << 4);
+  const uint32_t cv = (uint32_t)((c16 ^ (2 * r4)) << 4);  // chunk of a V row of a tail tile (row % 4 = r4)
   const uint32_t vq = (uint32_t)((g2 * 128 + n) << 4);  // this lane's 16 bytes of a V fragment run
   const char* const kpool = reinterpret_cast<const char*>(k_prefix) + (int64_t)hk * a.NP * (D * 2);
   const char* const vpool = reinterpret_cast<const char*>(v_prefix) + (int64_t)hk * a.NP * (D * 2);
@@ -414,7 +424,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
           const int32_t j = min(tb0 + (k >> fmt_lg), nbr_here - 1);
           const int64_t row = (chunk_row[j] + min(k & pmask, last)) * (D * 2);
           HPD_GLL_NT(ktb + row + ck[f], dk + f * 1024);
-          HPD_GLL_NT(vtb + row + cv[f >> 1], dk + 8192 + f * 1024);
+          HPD_GLL_NT(vtb + row + cv, dk + 8192 + f * 1024);
         }
       }
       return;
@@ -468,10 +478,10 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       HPD_GLL_NT(ktb + rowA + (pA1 + ck[1]), dk + 1024);
       HPD_GLL_NT(ktb + rowB + (pB0 + ck[2]), dk + 2048);
       HPD_GLL_NT(ktb + rowB + (pB1 + ck[3]), dk + 3072);
-      HPD_GLL_NT(vtb + rowA + (pA0 + cv[0]), dv);
-      HPD_GLL_NT(vtb + rowA + (pA1 + cv[0]), dv + 1024);
-      HPD_GLL_NT(vtb + rowB + (pB0 + cv[1]), dv + 2048);
-      HPD_GLL_NT(vtb + rowB + (pB1 + cv[1]), dv + 3072);
+      HPD_GLL_NT(vtb + rowA + (pA0 + cv), dv);
+      HPD_GLL_NT(vtb + rowA + (pA1 + cv), dv + 1024);
+      HPD_GLL_NT(vtb + rowB + (pB0 + cv), dv + 2048);
+      HPD_GLL_NT(vtb + rowB + (pB1 + cv), dv + 3072);
     }
   };
 #undef HPD_PREFIX_BLOCK
@@ -707,19 +717,21 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 #pragma unroll
       for (int f = 0; f < 8; ++f) vf[f] = fr[(8 + f) * 64];
     } else {
-      // V half of a tail tile: row k at 256 * k bytes, chunk index swizzled by bit 3 of k.
+      // V half of a tail tile: row k at 256 * k bytes, 16-byte chunk c at position c ^ 2*(k & 3).
       // Fragment f = d-block * 2 + key half wants keys half*16 + g2*8 + 0..7 of channel
-      // d-block*32 + n: eight 2-byte reads, one per row.
-      const uint16_t* vrows = reinterpret_cast<const uint16_t*>(slot + 8 * 64);
+      // d-block*32 + n, a column of the tile: two transposing 8-byte reads.  In such a read each
+      // 16 lanes form a 4 x 4 arrangement, lane 4*j + r of them addresses 4 channels (quad r of
+      // the group's 16) of key j, and lane i receives channel i of keys 0..3.
+      const char* vrows = reinterpret_cast<const char*>(slot + 8 * 64);
+      const int tj = (lane >> 2) & 3, tr = lane & 3;
+      const int tx = ((lane >> 4) & 1) * 2 + (tr >> 1);  // chunk inside the d-block's four
+      const char* vlane = vrows + (g2 * 8 + tj) * 256 + (tr & 1) * 8;
 #pragma unroll
       for (int f = 0; f < 8; ++f) {
-        const int d = (f >> 1) * 32 + n;
-        const uint16_t* col = vrows + ((f & 1) * 16 + g2 * 8) * 128 + ((((d >> 3) ^ (g2 << 2)) << 3) | (d & 7));
-        uint32_t w[4];
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2)
-          w[e2] = (uint32_t)col[(2 * e2) * 128] | ((uint32_t)col[(2 * e2 + 1) * 128] << 16);
-        vf[f] = make_uint4(w[0], w[1], w[2], w[3]);
+        const int chunk = ((f >> 1) * 4 + tx) ^ (2 * tj);
+        const char* p = vlane + (f & 1) * 4096 + chunk * 16;
+        const uint2 k03 = lds_read_tr16(p), k47 = lds_read_tr16(p + 4 * 256);
+        vf[f] = make_uint4(k03.x, k03.y, k47.x, k47.y);
       }
     }
     float s[16];
