@@ -40,6 +40,13 @@
  *                                    HPD_MASK_PAPER - the attribute names of a prompt) occupies slots
  *                                    [seg_off, seg_off + seg_len); seg_off is a multiple
  *                                    of HPD_KEY_BLOCK.  K is stored already rotated.
+ *                                    HPD_BF16: a key element is the rotated key rounded to
+ *                                    bf16 (the precision of a bf16 cache), written in IEEE
+ *                                    half format - the same 2 bytes, exact for
+ *                                    2^-14 <= |k| <= 65504, within 2^-25 below, saturating
+ *                                    above - so that the score product can take the query
+ *                                    with 11 significant bits in one pass.  Both key pools;
+ *                                    the value pools hold the caller's bf16 bits.
  *   v_prefix : [Hkv][NP/8][D][8]     same slots; 8 consecutive keys are interleaved so
  *                                    that the P.V contraction reads 8 keys of one
  *                                    channel with one 16-byte load.

@@ -34,10 +34,13 @@
 //    get a latency-critical load through.  The two roles run different code paths and meet
 //    at barriers only.
 //  * Contraction (transposed):
-//        S^T[key,row] = K.Q^T   (A = K fragment, B = rotated, pre-scaled Q in registers as
-//                                bf16 hi + lo parts: two MFMA passes, Q rounding drops out)
-//        O^T[d,row]  += V^T.P^T (A = V fragment, B = P)
-//    with v_mfma_f32_32x32x16_bf16.  One query row lives in lanes n and n+32; softmax
+//        S^T[key,row] = K.Q^T   (A = K fragment, B = rotated, pre-scaled Q in registers;
+//                                v_mfma_f32_32x32x16_f16: the cache holds its bf16 keys in
+//                                half format, exactly, and the query keeps 11 significant
+//                                bits - with a bf16 query the error was 2.5e-2 x RMS, and a
+//                                bf16 hi + lo pair costs a second pass)
+//        O^T[d,row]  += V^T.P^T (A = V fragment, B = P; v_mfma_f32_32x32x16_bf16)
+//    One query row lives in lanes n and n+32; softmax
 //    statistics never leave them, and the fp32 scores of the first product become, after
 //    exponentiation and bf16 packing, the B operand of the second without any cross-lane
 //    movement.  The key order inside a block is permuted on the K side (an address, free) so
@@ -77,6 +80,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -137,7 +141,26 @@ __device__ __forceinline__ void unpack8(uint4 a, float out[8]) {
   out[4] = __uint_as_float(a.z << 16); out[5] = __uint_as_float(a.z & 0xffff0000u);
   out[6] = __uint_as_float(a.w << 16); out[7] = __uint_as_float(a.w & 0xffff0000u);
 }
+// 8 keys of the cache: rounded to bf16, written as halves
+__device__ __forceinline__ uint4 pack8_key(const float* v) {
+  float r[8];
+  unpack8(__builtin_bit_cast(uint4, pack8(v)), r);
+  return make_uint4(hpd::key_bits_pair(r[0], r[1]), hpd::key_bits_pair(r[2], r[3]),
+                    hpd::key_bits_pair(r[4], r[5]), hpd::key_bits_pair(r[6], r[7]));
+}
+// 8 query values as halves, rounded to nearest
+__device__ __forceinline__ f16x8 pack8_half(const float* v) {
+  f16x8 h;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) h[e] = (_Float16)v[e];
+  return h;
+}
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// c + the two bf16 values of w (v_dot2_f32_bf16 with a pair of ones)
+__device__ __forceinline__ float sum_bf16_pair(uint32_t w, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u), c, false);
+}
 
 // ds_read_b64_tr_b16: within each 16 lanes, lane i receives element i % 4 of the 8 bytes that the
 // lanes 4*j + i/4 (j = 0..3) address, in the order of j: a 4 x 16 transpose of 2-byte elements.
@@ -513,8 +536,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const int64_t trow = ((PAGED || PAPER) ? hpd_tail_row(a.tb, b, hk, a.Hkv, a.Tcap, a.step)
                                 : ((int64_t)b * a.Hkv + hk) * a.Tcap + a.step) * D;
     uint16_t* kd = k_tail + trow;
-    *reinterpret_cast<uint4*>(kd + ap_c) = __builtin_bit_cast(uint4, pack8(rl));
-    *reinterpret_cast<uint4*>(kd + 64 + ap_c) = __builtin_bit_cast(uint4, pack8(rh));
+    *reinterpret_cast<uint4*>(kd + ap_c) = pack8_key(rl);
+    *reinterpret_cast<uint4*>(kd + 64 + ap_c) = pack8_key(rh);
     uint16_t* vd = v_tail + trow;
     *reinterpret_cast<uint4*>(vd + ap_c) = r.vlo;
     *reinterpret_cast<uint4*>(vd + 64 + ap_c) = r.vhi;
@@ -641,9 +664,11 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave has its rows
   __builtin_amdgcn_s_barrier();        // stages 2 and 3 go back to the loaders
 
-  // ---- rotate the query: bf16 hi + lo MFMA B operands.  The softmax scale and the change to
-  //      base 2 ride on the query: scores come out of the MFMA ready for exp2.
-  bf16x8 Qh[8], Ql[8];
+  // ---- rotate the query: MFMA B operands in half precision (11 significant bits; the keys of
+  //      the cache hold bf16 values in half format, so one pass of the f16 matrix instruction
+  //      gives the score).  The softmax scale and the change to base 2 ride on the query:
+  //      scores come out of the MFMA ready for exp2.
+  f16x8 Qf[8];
   auto rotate_query = [&](auto cos_sin) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
@@ -658,15 +683,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
       }
 #pragma unroll
       for (int e = 0; e < 8; ++e) { rl[e] *= a.scale_log2; rh[e] *= a.scale_log2; }
-      Qh[kk] = pack8(rl);
-      Qh[kk + 4] = pack8(rh);
-      float hl[8], hh[8];
-      unpack8(__builtin_bit_cast(uint4, Qh[kk]), hl);
-      unpack8(__builtin_bit_cast(uint4, Qh[kk + 4]), hh);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { rl[e] -= hl[e]; rh[e] -= hh[e]; }
-      Ql[kk] = pack8(rl);
-      Ql[kk + 4] = pack8(rh);
+      Qf[kk] = pack8_half(rl);
+      Qf[kk + 4] = pack8_half(rh);
     }
   };
   if (upos >= 0) {
@@ -707,10 +725,9 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     for (int i = 0; i < 16; ++i) S[i] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 kf = __builtin_bit_cast(
-          bf16x8, *reinterpret_cast<const uint4*>(krows + (((kk * 2 + g2) ^ (krow & 15)) << 4)));
-      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Qh[kk], S, 0, 0, 0);
-      S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, Ql[kk], S, 0, 0, 0);
+      const f16x8 kf = __builtin_bit_cast(
+          f16x8, *reinterpret_cast<const uint4*>(krows + (((kk * 2 + g2) ^ (krow & 15)) << 4)));
+      S = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf, Qf[kk], S, 0, 0, 0);
     }
     uint4 vf[8];
     if (!tail) {
@@ -756,11 +773,18 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
         for (int i = 0; i < 16; ++i) acc[blk][i] *= alpha;
     }
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      s[i] = fast_exp2(s[i] - m_used);
-      l_lane += s[i];
-    }
+    for (int i = 0; i < 16; ++i) s[i] = fast_exp2(s[i] - m_used);
     const bf16x8 P0 = pack8(s), P1 = pack8(s + 8);
+    // the sum of the weights as the value product sees them (rounded to bf16): numerator and
+    // denominator of a row carry the same rounding
+    {
+      const uint4 w0 = __builtin_bit_cast(uint4, P0), w1 = __builtin_bit_cast(uint4, P1);
+      float la = sum_bf16_pair(w0.x, l_lane), lb = sum_bf16_pair(w1.x, 0.f);
+      la = sum_bf16_pair(w0.y, la); lb = sum_bf16_pair(w1.y, lb);
+      la = sum_bf16_pair(w0.z, la); lb = sum_bf16_pair(w1.z, lb);
+      la = sum_bf16_pair(w0.w, la); lb = sum_bf16_pair(w1.w, lb);
+      l_lane = la + lb;
+    }
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
       acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[blk * 2]), P0,

@@ -48,8 +48,8 @@ __global__ void prefix_fill_kernel(hpd_dev_tables tb, int32_t n_seg, int32_t P, 
   const int64_t kdst = ((int64_t)h * NP + slot) * D;
   float r1, r2;
   hpd::rope_pair(a, b, cs.x, cs.y, r1, r2);
-  k_prefix[kdst + i] = hpd::from_float<T>(r1);
-  k_prefix[kdst + i + half] = hpd::from_float<T>(r2);
+  k_prefix[kdst + i] = hpd::key_from_float<T>(r1);
+  k_prefix[kdst + i + half] = hpd::key_from_float<T>(r2);
   const int64_t vblk = ((int64_t)h * (NP / 8) + slot / 8) * D;
   v_prefix[(vblk + i) * 8 + (slot & 7)] = v_raw[src + i];
   v_prefix[(vblk + i + half) * 8 + (slot & 7)] = v_raw[src + i + half];
@@ -97,8 +97,10 @@ prefix_fill_bf16_128_kernel(hpd_dev_tables tb, int32_t n_seg, int32_t P, int32_t
                      c4.x, c4.y, a0, b0);
       hpd::rope_pair(hpd::bf16_bits_to_float(lo[e2] >> 16), hpd::bf16_bits_to_float(hi[e2] >> 16),
                      c4.z, c4.w, a1, b1);
-      olo[e2] = hpd::float_to_bf16_bits(a0) | (hpd::float_to_bf16_bits(a1) << 16);
-      ohi[e2] = hpd::float_to_bf16_bits(b0) | (hpd::float_to_bf16_bits(b1) << 16);
+      olo[e2] = hpd::key_bits_pair(hpd::bf16_bits_to_float(hpd::float_to_bf16_bits(a0)),
+                                   hpd::bf16_bits_to_float(hpd::float_to_bf16_bits(a1)));
+      ohi[e2] = hpd::key_bits_pair(hpd::bf16_bits_to_float(hpd::float_to_bf16_bits(b0)),
+                                   hpd::bf16_bits_to_float(hpd::float_to_bf16_bits(b1)));
     }
     uint16_t* kd = k_prefix + ((int64_t)h * NP + slot) * D;
     *reinterpret_cast<uint4*>(kd + cc * 8) = make_uint4(olo[0], olo[1], olo[2], olo[3]);
@@ -178,8 +180,8 @@ __global__ void append_kernel(hpd_dev_tables tb, int32_t step, int32_t n_live, i
   const int64_t slot = hpd_tail_row(tb, b, 0, 1, Tcap, step);
   float r1, r2;
   hpd::rope_pair(a, bb, cs.x, cs.y, r1, r2);
-  k_tail[dst + i] = hpd::from_float<T>(r1);
-  k_tail[dst + i + half] = hpd::from_float<T>(r2);
+  k_tail[dst + i] = hpd::key_from_float<T>(r1);
+  k_tail[dst + i + half] = hpd::key_from_float<T>(r2);
   v_tail[dst + i] = v_new[src + i];
   v_tail[dst + i + half] = v_new[src + i + half];
   if (slot_out && h == 0 && i == 0) slot_out[r] = slot;
@@ -488,7 +490,7 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
     float acc = 0.f;
     for (int32_t c = 0; c < D; c += 8) {
       float kv[8];
-      hpd::load8(kp + c, kv);
+      hpd::load8_key(kp + c, kv);
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc = fmaf(kv[e], q_rot[c + e], acc);
     }
