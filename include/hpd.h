@@ -40,18 +40,19 @@
  *                                    HPD_MASK_PAPER - the attribute names of a prompt) occupies slots
  *                                    [seg_off, seg_off + seg_len); seg_off is a multiple
  *                                    of HPD_KEY_BLOCK.  K is stored already rotated.
- *                                    HPD_BF16: a key element is the rotated key rounded to
- *                                    bf16 (the precision of a bf16 cache), written in IEEE
- *                                    half format - the same 2 bytes, exact for
- *                                    2^-14 <= |k| <= 65504, within 2^-25 below, saturating
- *                                    above - so that the score product can take the query
- *                                    with 11 significant bits in one pass.  Both key pools;
- *                                    the value pools hold the caller's bf16 bits.
+ *                                    (HPD_BF16: see "element format" below.)
  *   v_prefix : [Hkv][NP/8][D][8]     same slots; 8 consecutive keys are interleaved so
  *                                    that the P.V contraction reads 8 keys of one
  *                                    channel with one 16-byte load.
  *   k_tail   : [B][Hkv][T][D]        slot b*T + t holds the rotated key of branch b's
  *   v_tail   : [B][Hkv][T][D]        t-th value token (Algorithm 1's values[j,i,t]).
+ *   Element format of the four pools under HPD_BF16: an element holds a bf16 value - the
+ *   rotated key rounded to bf16 (the precision of a bf16 cache), the value as the caller gave
+ *   it - written in IEEE half format: the same 2 bytes, exact for 2^-14 <= |x| <= 65504,
+ *   within 2^-25 below, saturating above.  Both products of the attention then take their other
+ *   operand (query, softmax weights) with 11 significant bits in one pass of the
+ *   half-precision matrix instruction.  A scaled rotated query above 65504 in magnitude is not
+ *   supported (it would overflow the exponential as well).
  *   hpd_prefix_fill zeroes the V padding slots between a segment's end and the next
  *   multiple of HPD_KEY_BLOCK; K padding and unwritten tail slots may hold anything
  *   (including NaN patterns).  HPD_Q_POOL_BYTES reports the four sizes.

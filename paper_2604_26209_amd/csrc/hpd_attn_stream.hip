@@ -34,24 +34,25 @@
 //    get a latency-critical load through.  The two roles run different code paths and meet
 //    at barriers only.
 //  * Contraction (transposed):
-//        S^T[key,row] = K.Q^T   (A = K fragment, B = rotated, pre-scaled Q in registers;
-//                                v_mfma_f32_32x32x16_f16: the cache holds its bf16 keys in
-//                                half format, exactly, and the query keeps 11 significant
-//                                bits - with a bf16 query the error was 2.5e-2 x RMS, and a
-//                                bf16 hi + lo pair costs a second pass)
-//        O^T[d,row]  += V^T.P^T (A = V fragment, B = P; v_mfma_f32_32x32x16_bf16)
-//    One query row lives in lanes n and n+32; softmax
-//    statistics never leave them, and the fp32 scores of the first product become, after
-//    exponentiation and bf16 packing, the B operand of the second without any cross-lane
-//    movement.  The key order inside a block is permuted on the K side (an address, free) so
-//    that the 8 probabilities a lane holds for one MFMA belong to 8 consecutive keys, which
-//    is what the 8-key interleaved V pool delivers in 16 bytes.
-//  * Softmax.  Online max/sum in registers.  The running maximum is exact (the accumulators
-//    are rescaled whenever some row of the wave sees a larger score; the rescale is skipped,
-//    wave-uniformly, when no row does).  Exactness matters for accuracy: the dominant key of a
-//    row then has probability exactly 1.0, which bf16 represents without error; with a stale
-//    maximum the largest weight would carry a 2^-9 rounding error into P.V (measured: 3x
-//    larger max-abs error).
+//        S^T[key,row] = K.Q^T   (A = K fragment, B = rotated, pre-scaled Q in registers)
+//        O^T[d,row]  += V^T.P^T (A = V fragment, B = P)
+//    both with v_mfma_f32_32x32x16_f16: the pools hold their bf16 values in half format,
+//    exactly, and the query and the softmax weights keep 11 significant bits (with a bf16
+//    query the error was 2.5e-2 x RMS, and a bf16 hi + lo pair costs a second pass).  One query
+//    row lives in lanes n and n+32; softmax statistics never leave them, and the fp32 scores of
+//    the first product become, after exponentiation and packing, the B operand of the second
+//    without any cross-lane movement.  The key order inside a block is permuted on the K side
+//    (an address, free) so that the 8 probabilities a lane holds for one MFMA belong to 8
+//    consecutive keys, which is what the 8-key interleaved V pool delivers in 16 bytes.
+//  * Softmax.  Online max/sum in registers.  The reference point of a row's exponentials
+//    follows its running maximum within a factor of 2^8: the accumulators are rescaled, wave-
+//    uniformly, only when some row of the wave sees a score that exceeds its reference point
+//    by more - in the first blocks of a row, then hardly ever (with the exact maximum, most
+//    blocks of 32 keys raise the maximum of one of the wave's 32 rows, and the 64 multiplies
+//    of a rescale were a quarter of the vector instructions).  This rests on the weights being
+//    halves: with bf16 weights the largest weight of a row has to be exactly 1.0 - an exact
+//    maximum - or its 2^-9 rounding error shows in rows that one or two keys dominate
+//    (measured: 2.4e-2 x RMS against 0.9e-2).
 //  * Compute waves = (row block of 32 rows) x (key group), with as many key groups (at most
 //    4) as fit; key group kg takes the prefix blocks gb with gb % KG == kg, and the tail tiles
 //    of a row block go round its key groups.  At the end the groups are merged through LDS in
@@ -145,10 +146,15 @@ __device__ __forceinline__ void unpack8(uint4 a, float out[8]) {
 __device__ __forceinline__ uint4 pack8_key(const float* v) {
   float r[8];
   unpack8(__builtin_bit_cast(uint4, pack8(v)), r);
-  return make_uint4(hpd::key_bits_pair(r[0], r[1]), hpd::key_bits_pair(r[2], r[3]),
-                    hpd::key_bits_pair(r[4], r[5]), hpd::key_bits_pair(r[6], r[7]));
+  return make_uint4(hpd::cache_bits_pair(r[0], r[1]), hpd::cache_bits_pair(r[2], r[3]),
+                    hpd::cache_bits_pair(r[4], r[5]), hpd::cache_bits_pair(r[6], r[7]));
 }
-// 8 query values as halves, rounded to nearest
+// 8 bf16 values as cache elements
+__device__ __forceinline__ uint4 cache8(uint4 w) {
+  return make_uint4(hpd::cache_bits_from_bf16_pair(w.x), hpd::cache_bits_from_bf16_pair(w.y),
+                    hpd::cache_bits_from_bf16_pair(w.z), hpd::cache_bits_from_bf16_pair(w.w));
+}
+// 8 values (of the query, of the softmax weights) as halves, rounded to nearest
 __device__ __forceinline__ f16x8 pack8_half(const float* v) {
   f16x8 h;
 #pragma unroll
@@ -156,10 +162,12 @@ __device__ __forceinline__ f16x8 pack8_half(const float* v) {
   return h;
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+constexpr float MAX_SLACK = 8.f;  // log2 units: how far a score may exceed the reference point of its row
 
-// c + the two bf16 values of w (v_dot2_f32_bf16 with a pair of ones)
-__device__ __forceinline__ float sum_bf16_pair(uint32_t w, float c) {
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u), c, false);
+// c + the two halves of w (v_dot2_f32_f16 with a pair of ones)
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float sum_half_pair(uint32_t w, float c) {
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), __builtin_bit_cast(f16x2, 0x3c003c00u), c, false);
 }
 
 // ds_read_b64_tr_b16: within each 16 lanes, lane i receives element i % 4 of the 8 bytes that the
@@ -539,8 +547,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     *reinterpret_cast<uint4*>(kd + ap_c) = pack8_key(rl);
     *reinterpret_cast<uint4*>(kd + 64 + ap_c) = pack8_key(rh);
     uint16_t* vd = v_tail + trow;
-    *reinterpret_cast<uint4*>(vd + ap_c) = r.vlo;
-    *reinterpret_cast<uint4*>(vd + 64 + ap_c) = r.vhi;
+    *reinterpret_cast<uint4*>(vd + ap_c) = cache8(r.vlo);
+    *reinterpret_cast<uint4*>(vd + 64 + ap_c) = cache8(r.vhi);
   };
   auto append_from = [&](int32_t li0) {
     for (int32_t li = li0; li < ap_end; li += CWAVES * 8) append_store(li, append_load(li), false);
@@ -706,7 +714,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   }
 
   // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
-  float m_used = NEG_BIG;  // running maximum (log2 units), equal in lanes n and n+32
+  float m_used = NEG_BIG;  // reference point of the row's exponentials (log2 units), equal in lanes n and n+32
   float l_lane = 0.f;
   floatx16 acc[4];
 #pragma unroll
@@ -761,7 +769,12 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     float bm = NEG_BIG;
 #pragma unroll
     for (int i = 0; i < 16; ++i) bm = fmaxf(bm, s[i]);
-    if (__any(bm > m_used)) {
+    // The reference point of the exponentials follows the maximum of a row within 2^8: it
+    // moves (and the 64 accumulator values are rescaled) only when a score exceeds it by more,
+    // which after the first blocks of a row is rare.  The weights go into the value product as
+    // halves - 11 significant bits whatever their size, up to 2^8 - so the largest weight of a
+    // row need not be exactly 1 to be exact enough.
+    if (__any(bm > m_used + MAX_SLACK)) {
       bm = fmaxf(bm, __shfl_xor(bm, 32));
       const float m_new = fmaxf(m_used, bm);
       const float alpha = fast_exp2(m_used - m_new);
@@ -774,23 +787,23 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     }
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] = fast_exp2(s[i] - m_used);
-    const bf16x8 P0 = pack8(s), P1 = pack8(s + 8);
-    // the sum of the weights as the value product sees them (rounded to bf16): numerator and
+    const f16x8 P0 = pack8_half(s), P1 = pack8_half(s + 8);
+    // the sum of the weights as the value product sees them (rounded to half): numerator and
     // denominator of a row carry the same rounding
     {
       const uint4 w0 = __builtin_bit_cast(uint4, P0), w1 = __builtin_bit_cast(uint4, P1);
-      float la = sum_bf16_pair(w0.x, l_lane), lb = sum_bf16_pair(w1.x, 0.f);
-      la = sum_bf16_pair(w0.y, la); lb = sum_bf16_pair(w1.y, lb);
-      la = sum_bf16_pair(w0.z, la); lb = sum_bf16_pair(w1.z, lb);
-      la = sum_bf16_pair(w0.w, la); lb = sum_bf16_pair(w1.w, lb);
+      float la = sum_half_pair(w0.x, l_lane), lb = sum_half_pair(w1.x, 0.f);
+      la = sum_half_pair(w0.y, la); lb = sum_half_pair(w1.y, lb);
+      la = sum_half_pair(w0.z, la); lb = sum_half_pair(w1.z, lb);
+      la = sum_half_pair(w0.w, la); lb = sum_half_pair(w1.w, lb);
       l_lane = la + lb;
     }
 #pragma unroll
     for (int blk = 0; blk < 4; ++blk) {
-      acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[blk * 2]), P0,
-                                                         acc[blk], 0, 0, 0);
-      acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[blk * 2 + 1]), P1,
-                                                         acc[blk], 0, 0, 0);
+      acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, vf[blk * 2]), P0,
+                                                        acc[blk], 0, 0, 0);
+      acc[blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, vf[blk * 2 + 1]), P1,
+                                                        acc[blk], 0, 0, 0);
     }
   };
 

@@ -36,32 +36,37 @@ __device__ __forceinline__ bf16_t from_float<bf16_t>(float f) {
   return r;
 }
 
-// Keys of a bf16 cache.  The stored value is the rotated key rounded to bf16 (round to nearest
-// even: the precision of the cache), and it is written in IEEE half format: the same 2 bytes per
-// element, exact for 2^-14 <= |k| <= 65504 (bf16 has 8 significant bits, half has 11), within
-// 2^-25 absolute below that, saturating above.  The score product can then take the query as one
-// half operand (11 significant bits) instead of two bf16 operands (hi + lo).  Every kernel that
-// writes or reads a key goes through these.
-__device__ __forceinline__ uint32_t key_bits_pair(float a, float b) {
+// Elements of a bf16 cache.  The stored value is the bf16 value (a rotated key rounded to bf16,
+// round to nearest even: the precision of the cache; a value element as the caller gave it),
+// and it is written in IEEE half format: the same 2 bytes per element, exact for
+// 2^-14 <= |x| <= 65504 (bf16 has 8 significant bits, half has 11), within 2^-25 absolute below
+// that, saturating above.  Both products of the attention then run on the half-precision matrix
+// instruction, which takes the query and the softmax weights with 11 significant bits instead
+// of 8.  Every kernel that writes or reads a pool goes through these.
+__device__ __forceinline__ uint32_t cache_bits_pair(float a, float b) {
   // a, b hold bf16 values: the conversion towards zero is exact in the normal range of half
   // and saturates at the largest finite half
   return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(a, b));
 }
-__device__ __forceinline__ float key_bits_to_float(uint32_t bits) {
+__device__ __forceinline__ float cache_bits_to_float(uint32_t bits) {
   return (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
 }
 template <typename T>
-__device__ __forceinline__ T key_from_float(float f);
+__device__ __forceinline__ T cache_from_float(float f);
 template <>
-__device__ __forceinline__ float key_from_float<float>(float f) { return f; }
+__device__ __forceinline__ float cache_from_float<float>(float f) { return f; }
 template <>
-__device__ __forceinline__ bf16_t key_from_float<bf16_t>(float f) {
+__device__ __forceinline__ bf16_t cache_from_float<bf16_t>(float f) {
   bf16_t r;
-  r.bits = (uint16_t)key_bits_pair(bf16_bits_to_float(float_to_bf16_bits(f)), 0.f);
+  r.bits = (uint16_t)cache_bits_pair(bf16_bits_to_float(float_to_bf16_bits(f)), 0.f);
   return r;
 }
-__device__ __forceinline__ float key_to_float(float x) { return x; }
-__device__ __forceinline__ float key_to_float(bf16_t x) { return key_bits_to_float(x.bits); }
+__device__ __forceinline__ float cache_to_float(float x) { return x; }
+__device__ __forceinline__ float cache_to_float(bf16_t x) { return cache_bits_to_float(x.bits); }
+// two bf16 values (the halves of w) as cache elements
+__device__ __forceinline__ uint32_t cache_bits_from_bf16_pair(uint32_t w) {
+  return cache_bits_pair(__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u));
+}
 
 // Rotation of one (first-half, second-half) channel pair.  Every kernel that rotates a key
 // or a query uses this exact sequence so that all of them round identically.
@@ -84,14 +89,14 @@ __device__ __forceinline__ void load8(const bf16_t* p, float out[8]) {
   out[4] = bf16_bits_to_float(a.z & 0xffffu); out[5] = bf16_bits_to_float(a.z >> 16);
   out[6] = bf16_bits_to_float(a.w & 0xffffu); out[7] = bf16_bits_to_float(a.w >> 16);
 }
-// 8 consecutive keys of a pool
-__device__ __forceinline__ void load8_key(const float* p, float out[8]) { load8(p, out); }
-__device__ __forceinline__ void load8_key(const bf16_t* p, float out[8]) {
+// 8 consecutive elements of a pool
+__device__ __forceinline__ void load8_cache(const float* p, float out[8]) { load8(p, out); }
+__device__ __forceinline__ void load8_cache(const bf16_t* p, float out[8]) {
   const uint4 a = *reinterpret_cast<const uint4*>(p);
-  out[0] = key_bits_to_float(a.x & 0xffffu); out[1] = key_bits_to_float(a.x >> 16);
-  out[2] = key_bits_to_float(a.y & 0xffffu); out[3] = key_bits_to_float(a.y >> 16);
-  out[4] = key_bits_to_float(a.z & 0xffffu); out[5] = key_bits_to_float(a.z >> 16);
-  out[6] = key_bits_to_float(a.w & 0xffffu); out[7] = key_bits_to_float(a.w >> 16);
+  out[0] = cache_bits_to_float(a.x & 0xffffu); out[1] = cache_bits_to_float(a.x >> 16);
+  out[2] = cache_bits_to_float(a.y & 0xffffu); out[3] = cache_bits_to_float(a.y >> 16);
+  out[4] = cache_bits_to_float(a.z & 0xffffu); out[5] = cache_bits_to_float(a.z >> 16);
+  out[6] = cache_bits_to_float(a.w & 0xffffu); out[7] = cache_bits_to_float(a.w >> 16);
 }
 
 }  // namespace hpd

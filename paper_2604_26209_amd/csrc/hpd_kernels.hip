@@ -48,11 +48,11 @@ __global__ void prefix_fill_kernel(hpd_dev_tables tb, int32_t n_seg, int32_t P, 
   const int64_t kdst = ((int64_t)h * NP + slot) * D;
   float r1, r2;
   hpd::rope_pair(a, b, cs.x, cs.y, r1, r2);
-  k_prefix[kdst + i] = hpd::key_from_float<T>(r1);
-  k_prefix[kdst + i + half] = hpd::key_from_float<T>(r2);
+  k_prefix[kdst + i] = hpd::cache_from_float<T>(r1);
+  k_prefix[kdst + i + half] = hpd::cache_from_float<T>(r2);
   const int64_t vblk = ((int64_t)h * (NP / 8) + slot / 8) * D;
-  v_prefix[(vblk + i) * 8 + (slot & 7)] = v_raw[src + i];
-  v_prefix[(vblk + i + half) * 8 + (slot & 7)] = v_raw[src + i + half];
+  v_prefix[(vblk + i) * 8 + (slot & 7)] = hpd::cache_from_float<T>(hpd::to_float(v_raw[src + i]));
+  v_prefix[(vblk + i + half) * 8 + (slot & 7)] = hpd::cache_from_float<T>(hpd::to_float(v_raw[src + i + half]));
 }
 
 // The same for bf16 with 128 channels, the shape the streaming attention kernel serves: one
@@ -97,15 +97,19 @@ prefix_fill_bf16_128_kernel(hpd_dev_tables tb, int32_t n_seg, int32_t P, int32_t
                      c4.x, c4.y, a0, b0);
       hpd::rope_pair(hpd::bf16_bits_to_float(lo[e2] >> 16), hpd::bf16_bits_to_float(hi[e2] >> 16),
                      c4.z, c4.w, a1, b1);
-      olo[e2] = hpd::key_bits_pair(hpd::bf16_bits_to_float(hpd::float_to_bf16_bits(a0)),
+      olo[e2] = hpd::cache_bits_pair(hpd::bf16_bits_to_float(hpd::float_to_bf16_bits(a0)),
                                    hpd::bf16_bits_to_float(hpd::float_to_bf16_bits(a1)));
-      ohi[e2] = hpd::key_bits_pair(hpd::bf16_bits_to_float(hpd::float_to_bf16_bits(b0)),
+      ohi[e2] = hpd::cache_bits_pair(hpd::bf16_bits_to_float(hpd::float_to_bf16_bits(b0)),
                                    hpd::bf16_bits_to_float(hpd::float_to_bf16_bits(b1)));
     }
     uint16_t* kd = k_prefix + ((int64_t)h * NP + slot) * D;
     *reinterpret_cast<uint4*>(kd + cc * 8) = make_uint4(olo[0], olo[1], olo[2], olo[3]);
     *reinterpret_cast<uint4*>(kd + 64 + cc * 8) = make_uint4(ohi[0], ohi[1], ohi[2], ohi[3]);
   }
+  vlo = make_uint4(hpd::cache_bits_from_bf16_pair(vlo.x), hpd::cache_bits_from_bf16_pair(vlo.y),
+                   hpd::cache_bits_from_bf16_pair(vlo.z), hpd::cache_bits_from_bf16_pair(vlo.w));
+  vhi = make_uint4(hpd::cache_bits_from_bf16_pair(vhi.x), hpd::cache_bits_from_bf16_pair(vhi.y),
+                   hpd::cache_bits_from_bf16_pair(vhi.z), hpd::cache_bits_from_bf16_pair(vhi.w));
   *reinterpret_cast<uint4*>(&vt[wave][r][cc * 8]) = vlo;
   *reinterpret_cast<uint4*>(&vt[wave][r][64 + cc * 8]) = vhi;
   __syncthreads();
@@ -180,10 +184,10 @@ __global__ void append_kernel(hpd_dev_tables tb, int32_t step, int32_t n_live, i
   const int64_t slot = hpd_tail_row(tb, b, 0, 1, Tcap, step);
   float r1, r2;
   hpd::rope_pair(a, bb, cs.x, cs.y, r1, r2);
-  k_tail[dst + i] = hpd::key_from_float<T>(r1);
-  k_tail[dst + i + half] = hpd::key_from_float<T>(r2);
-  v_tail[dst + i] = v_new[src + i];
-  v_tail[dst + i + half] = v_new[src + i + half];
+  k_tail[dst + i] = hpd::cache_from_float<T>(r1);
+  k_tail[dst + i + half] = hpd::cache_from_float<T>(r2);
+  v_tail[dst + i] = hpd::cache_from_float<T>(hpd::to_float(v_new[src + i]));
+  v_tail[dst + i + half] = hpd::cache_from_float<T>(hpd::to_float(v_new[src + i + half]));
   if (slot_out && h == 0 && i == 0) slot_out[r] = slot;
 }
 
@@ -490,7 +494,7 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
     float acc = 0.f;
     for (int32_t c = 0; c < D; c += 8) {
       float kv[8];
-      hpd::load8_key(kp + c, kv);
+      hpd::load8_cache(kp + c, kv);
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc = fmaf(kv[e], q_rot[c + e], acc);
     }
@@ -516,11 +520,11 @@ attention_generic_kernel(hpd_dev_tables tb, int32_t step, int32_t Hq, int32_t Hk
       float vv;
       if (kk < Hlen + Llen) {
         const int64_t slot = (kk < Hlen) ? hoff + kk : doc_slot(kk);
-        vv = hpd::to_float(v_prefix[((vhead + slot / 8) * D + c) * 8 + (slot & 7)]);
+        vv = hpd::cache_to_float(v_prefix[((vhead + slot / 8) * D + c) * 8 + (slot & 7)]);
       } else {
         const int64_t row = tail_row(kk - Hlen - Llen);
         if (row < 0) continue;  // probability 0
-        vv = hpd::to_float(v_tail[row + c]);
+        vv = hpd::cache_to_float(v_tail[row + c]);
       }
       acc = fmaf(scores[kk], vv, acc);
     }

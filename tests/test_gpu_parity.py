@@ -780,8 +780,8 @@ def test_bf16_kv_pools_hold_the_rounded_rotated_keys(kernel_mode, fused):
     tail keys must be the bf16 rounding of the oracle's fp32-rotated keys - the same value, held
     in IEEE half format, which represents every bf16 value of the normal half range exactly -
     except where the kernels' fused multiply-add lands on the other side of a rounding tie: such
-    elements may differ by one bf16 ulp and must be rare -, values must be the input bits,
-    through the 8-key interleave of the prefix pool.  Covers the 128-channel fill kernel and
+    elements may differ by one bf16 ulp and must be rare -, values must be the input values in
+    the same format, through the 8-key interleave of the prefix pool.  Covers the 128-channel fill kernel and
     the fused append of the streaming kernel (mode 0), the two-call append kernel, and the
     element-wise fill kernel (mode 1)."""
     from paper_2604_26209_amd import binding as B
@@ -820,6 +820,15 @@ def test_bf16_kv_pools_hold_the_rounded_rotated_keys(kernel_mode, fused):
         n_keys += diff.size
         n_off += int((diff != 0).sum())
 
+    def check_v(got_half, want_f32):
+        # a value element is the caller's bf16 value in half format: the same value wherever it
+        # is a normal half, within 2^-24 below
+        want_f32 = np.ascontiguousarray(want_f32, dtype=np.float32)
+        got_f32 = np.ascontiguousarray(got_half).view(np.float16).astype(np.float32)
+        normal = np.abs(want_f32) >= 2.0 ** -13
+        assert np.array_equal(got_f32[normal], want_f32[normal])
+        assert np.all(np.abs(got_f32[~normal] - want_f32[~normal]) <= 2.0 ** -24)
+
     for p, po in orc.prompts.items():
         segs = [(p, 0, po.h)]
         run = po.h
@@ -830,7 +839,7 @@ def test_bf16_kv_pools_hold_the_rounded_rotated_keys(kernel_mode, fused):
             for i in range(n):
                 slot = seg_off[sid] + i
                 check_k(kp[:, slot, :], po.k[first + i])
-                assert np.array_equal(vp[:, slot // 8, :, slot % 8], as_bits(po.v[first + i]))
+                check_v(vp[:, slot // 8, :, slot % 8], po.v[first + i])
             # the V padding behind the segment is zero (masked keys must contribute 0 * V = 0)
             for slot in range(seg_off[sid] + n, -(-(seg_off[sid] + n) // 32) * 32):
                 assert not vp[:, slot // 8, :, slot % 8].any()
@@ -838,7 +847,7 @@ def test_bf16_kv_pools_hold_the_rounded_rotated_keys(kernel_mode, fused):
         for idx in range(po.n_prefix, len(po.kind)):
             b, t = b0 + po.branch[idx], po.step_of[idx]
             check_k(kt[b, :, t, :], po.k[idx])
-            assert np.array_equal(vt[b, :, t, :], as_bits(po.v[idx]))
+            check_v(vt[b, :, t, :], po.v[idx])
     print(f"bf16 pools: {n_off} of {n_keys} stored key elements one ulp from the rounded oracle key "
           f"({n_off / n_keys:.2e})")
     assert n_off <= 2e-3 * n_keys
