@@ -445,6 +445,10 @@ def measure_decode(args, k, steps, warmup, B, W, torch, np, min_timed_s=0.0):
                    "kv_footprint_mb": round(footprint / 1e6, 1), "out_dtype": "f32" if out_f32 else wl.dtype,
                    **({"tail_page_size": args.page_size} if args.page_size and not paper else {}),
                    "call": "hpd_kv_append+hpd_decode_attention" if args.two_call else "hpd_decode_step",
+                   **({"arithmetic": "inputs, cache values and outputs bf16; the pools hold the bf16 values in "
+                                     "IEEE half format and both products run on v_mfma_f32_32x32x16_f16 "
+                                     "(same dense peak as bf16), fp32 accumulation and softmax"}
+                      if stream_kernel else {}),
                    "parity_checked_on": ("fp32 outputs against the CPU oracle (tests/test_gpu_full_size.py, this "
                                          "configuration's full size and launch shape), and bf16 outputs == "
                                          "RNE(fp32 outputs) bit for bit for every row" if wl.dtype == "bf16" else

@@ -117,6 +117,41 @@ def test_tail_tile_formats_of_the_newest_chunk(case, mode):
         _say(f"  worst err/rms {rel:.2e}")
 
 
+@pytest.mark.parametrize("mode", [1, 3, 4])
+@pytest.mark.parametrize("case", ["peaked_x4", "argmax_x16", "flat_div16", "common_offset", "rising"])
+def test_score_ranges_of_the_online_softmax(case, mode):
+    """Inputs other than N(0,1): scores 4 and 16 times as wide (rows that one or two keys
+    dominate, up to an argmax), 16 times as narrow (a flat average), with a large common
+    component in queries and keys (every score near +16 in log2 units: the reference point of
+    the exponentials must follow), and with keys that grow along the document and the steps (the
+    maximum of a row keeps rising, block after block: the accumulators are rescaled again and
+    again).  Same tolerance as everywhere; generic kernel (mode 1) and both workgroup shapes."""
+    wl = W.random_workload(400, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=11, p=2,
+                           j_range=(1, 3), n_range=(1, 20), h_range=(0, 70), l_range=(40, 400))
+    from paper_2604_26209_amd import binding as B
+    lay = B.layout_from_workload(wl)
+    inp = H.Inputs(wl, lay.n_live(), "cuda", lay.counts()[B.HPD_C_N_PREFIX_TOKENS])
+    bf = lambda x: x.float().to(torch.bfloat16)
+    if case in ("peaked_x4", "argmax_x16", "flat_div16"):
+        f = dict(peaked_x4=4.0, argmax_x16=16.0, flat_div16=1.0 / 16)[case]
+        inp.q = [bf(x.float() * f) for x in inp.q]
+    elif case == "common_offset":
+        inp.q = [bf(x.float() + 1.0) for x in inp.q]
+        inp.k_raw = bf(inp.k_raw.float() + 1.0)
+        inp.k_new = [bf(x.float() + 1.0) for x in inp.k_new]
+    else:
+        # a component along which all queries point and the keys grow with their index
+        n = inp.k_raw.shape[0]
+        ramp = torch.arange(n, device="cuda", dtype=torch.float32)[:, None, None] * (4.0 / max(n, 1))
+        inp.k_raw = bf(inp.k_raw.float() + ramp)
+        inp.k_new = [bf(x.float() + 4.0 + 0.3 * t) for t, x in enumerate(inp.k_new)]
+        inp.q = [bf(x.float() * 0.5 + 1.0) for x in inp.q]
+    _say(f"score ranges: {case} mode {mode}")
+    a = H.run_hip(wl, inputs=inp, kernel_mode=mode, fused=mode != 1)
+    rel = H.check_all(wl, a, label=f"{case}_m{mode}")
+    _say(f"  worst err/rms {rel:.2e}")
+
+
 @pytest.mark.parametrize("g", [3, 5, 6, 7])
 def test_stream_kernel_group_sizes_that_are_not_powers_of_two(g):
     """Group sizes such as 40 query heads over 8 kv heads (5) run on the streaming kernel with
