@@ -104,11 +104,18 @@ struct Shape {
   static constexpr int WAVES = CW + LW;
   static constexpr int STAGE_U4 = SB * SLOT_U4;
   static constexpr int STAGE_ROWS = STAGE_U4 / 16;        // 256-byte rows a stage can hold
-  static constexpr int LOADS_PER_ROUND = SB * 16 / LW;    // DMA instructions per loader wave per round
+  static constexpr int LOADS_PER_ROUND = SB * 16 / (LW ? LW : CW);  // DMA instructions per loading wave per stage
   static constexpr int MAX_BLOCKS = CW;                   // row blocks per workgroup
 };
 using WideShape = Shape<6, 2, 2>;
 using NarrowShape = Shape<3, 1, 1>;
+//   dense   4 compute waves that also load (no loader waves), stages of one block, two
+//           workgroups per CU.  For the prefill attention, which is bound by the matrix and
+//           vector work of the compute waves: two compute waves on every SIMD (a wave overlaps
+//           its matrix and its vector instructions only with those of another wave on its
+//           SIMD), and the memory pipeline, far from saturated there, takes the 4 DMA
+//           instructions a wave issues per stage without holding it up.
+using DenseShape = Shape<4, 0, 1>;
 
 struct StreamArgs {
   hpd_dev_tables tb;
@@ -126,6 +133,16 @@ struct StreamArgs {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr),   \
                                    (__attribute__((address_space(3))) void*)(lptr), 16, 0, 2)
 
+// The same two instructions (M0 = LDS byte address of lane 0's 16 bytes, then the load) written
+// out, for waves that request blocks and also read them: the compiler makes every LDS read of a
+// wave wait for all loads-to-LDS the wave has in flight (it cannot tell the stage that is read
+// from the stages that are being filled), and the ring lives on loads that stay in flight across
+// the reads.  Which stage may be read is what the barriers of the rounds establish.
+__device__ __forceinline__ void dma16(const void* g, const void* l) {
+  const uint32_t la = (uint32_t)__builtin_amdgcn_readfirstlane(
+      (int32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)l));
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(la) : "memory", "m0");
+}
 __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
   floatx2 v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
@@ -240,6 +257,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   constexpr int BPB = 32 / G;              // branches (PREFILL: tokens) per row block
   constexpr int QPR = G >= 8 ? 1 : 8 / G;  // branch quads (tail tiles per 8 positions) per row block
   constexpr int CWAVES = SH::CW, LOADERS = SH::LW, STAGE_BLOCKS = SH::SB, STAGE_U4 = SH::STAGE_U4;
+  constexpr bool SELF = LOADERS == 0;  // the compute waves issue the loads themselves
+  static_assert(!SELF || (STAGE_BLOCKS * 4 == CWAVES), "one quarter of a block per wave and stage");
   constexpr int LOADS_PER_ROUND = SH::LOADS_PER_ROUND, STAGE_ROWS = SH::STAGE_ROWS;
   static_assert(2 * STAGE_ROWS >= CWAVES * 32, "stages 2 and 3 must hold the query rows of a row group");
   static_assert(3 * LOADS_PER_ROUND <= 63, "three rounds in flight must fit the vmcnt counter");
@@ -286,7 +305,10 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
 
   const int32_t R = nb * G;
   const int32_t nblk = (R + 31) >> 5;
-  const int32_t per_group = (nblk + a.RG - 1) / a.RG;  // <= MAX_BLOCKS by the host's choice of RG
+  // (decode: the row blocks of a unit are shared out evenly over its row groups; prefill, where
+  // the host sizes RG for the longest segment of the batch: full row groups one after the
+  // other, so that a short segment is not cut into many small ones)
+  const int32_t per_group = PREFILL ? CWAVES : (nblk + a.RG - 1) / a.RG;  // <= MAX_BLOCKS by the host's choice of RG
   const int32_t first_blk = rg * per_group;
   const int32_t nblk_here = min(per_group, nblk - first_blk);
   if (nblk_here <= 0) return;  // uniform over the workgroup
@@ -417,6 +439,32 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   GL(sV + 4608 + vq, dst + 11264);                                                               \
   GL(sV + 1024 + vq, dst + 12288); GL(sV + 5120 + vq, dst + 13312); GL(sV + 1536 + vq, dst + 14336); \
   GL(sV + 5632 + vq, dst + 15360)
+  // first byte of the rows of the quad's i-th branch (of the page that holds the chunk) in both
+  // pools, and its last position in memory
+  auto tile_branch_rows = [&](int32_t tc, int32_t tq, int32_t i, int64_t& rowb, int32_t& last) {
+    const bool paged = PAGED || (PAPER && a.tb.tail_pages);
+    int32_t b;
+    last = a.step;
+    if (PAPER) {
+      // key branches are consecutive ids from the prompt's first; a finished branch stops at
+      // its own length, the rows behind it were never written
+      b = pb0 + min(tq * 4 + i, kb_end - 1);
+      last = min(a.step, scalar_load(a.tb.branch_len + b) - 1);
+    } else {
+      const int32_t lb = min(tq * 4 + i, nbr_here - 1);
+      b = ub0 >= 0 ? ub0 + br0 + lb : scalar_load(a.tb.live_branch + (a.live_base + row0_live + br0) + lb);
+    }
+    if (paged) {
+      // a page holds a multiple of 8 steps, so the 8 positions of the tile (clamped to the
+      // newest row of the branch, which lies in or behind them) share one page per branch
+      int32_t pg = scalar_load(a.tb.tail_pages + (int64_t)b * a.tb.pages_per_branch +
+                               (min(tc * 8, last) >> a.tb.page_shift));
+      pg = min(max(pg, 0), a.tb.n_pages - 1);
+      rowb = ((((int64_t)pg * a.Hkv + hk)) << a.tb.page_shift) * (D * 2);
+    } else {
+      rowb = ((int64_t)b * a.Hkv + hk) * a.Tcap * (D * 2);
+    }
+  };
   auto issue_block = [&](int32_t gb_raw, uint4* dst_slot) {
     // a slot past the last block re-loads the last block (never read): the count stays fixed
     const int32_t gb = min(gb_raw, NBT - 1);
@@ -468,31 +516,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const int32_t tq = quad_of(tt - tc * NQ);
     const bool paged = PAGED || (PAPER && a.tb.tail_pages);
     const int32_t pg_mask = paged ? (1 << a.tb.page_shift) - 1 : 0x7fffffff;
-    // first byte of the rows of the quad's i-th branch (of the page that holds the chunk) in both
-    // pools, and its last position in memory
-    auto branch_rows = [&](int32_t i, int64_t& rowb, int32_t& last) {
-      int32_t b;
-      last = a.step;
-      if (PAPER) {
-        // key branches are consecutive ids from the prompt's first; a finished branch stops at
-        // its own length, the rows behind it were never written
-        b = pb0 + min(tq * 4 + i, kb_end - 1);
-        last = min(a.step, scalar_load(a.tb.branch_len + b) - 1);
-      } else {
-        const int32_t lb = min(tq * 4 + i, nbr_here - 1);
-        b = ub0 >= 0 ? ub0 + br0 + lb : scalar_load(a.tb.live_branch + (a.live_base + row0_live + br0) + lb);
-      }
-      if (paged) {
-        // a page holds a multiple of 8 steps, so the 8 positions of the tile (clamped to the
-        // newest row of the branch, which lies in or behind them) share one page per branch
-        int32_t pg = scalar_load(a.tb.tail_pages + (int64_t)b * a.tb.pages_per_branch +
-                                 (min(tc * 8, last) >> a.tb.page_shift));
-        pg = min(max(pg, 0), a.tb.n_pages - 1);
-        rowb = ((((int64_t)pg * a.Hkv + hk)) << a.tb.page_shift) * (D * 2);
-      } else {
-        rowb = ((int64_t)b * a.Hkv + hk) * a.Tcap * (D * 2);
-      }
-    };
+    auto branch_rows = [&](int32_t i, int64_t& rowb, int32_t& last) { tile_branch_rows(tc, tq, i, rowb, last); };
 #pragma nounroll
     for (int32_t half = 0; half < 2; ++half) {
       int64_t rowA, rowB;
@@ -558,7 +582,8 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // barrier of round 1, so a prefix of at least 8 blocks keeps every tail tile behind it;
   // with a shorter prefix the append is completed before anything is loaded.
   const bool append_first = a.fused && NB < 4 * STAGE_BLOCKS;
-  const int32_t r_pub = (a.fused && !append_first) ? 1 : -1;
+  // (the full shape waits for its appended rows before the barrier of round 0)
+  const int32_t r_pub = (a.fused && !append_first && !SELF) ? 1 : -1;
   // The table of the newest chunk's rows is written by the compute waves before the first of
   // the two barriers of the query staging; the loaders request rounds 0 and 1 before that
   // barrier.  If a tile of the newest chunk can be among them the table is written first.
@@ -569,6 +594,27 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     }
   };
   const bool table_first = use_fmt && NB + n_full_tiles < 2 * STAGE_BLOCKS;
+  // ---- the dense shape (prefill: prefix blocks only): wave w issues quarter w % 4 of block
+  //      w / 4 of a stage - the same loads as a loader's (quarters 0, 1: the K rows 0..15,
+  //      16..31; quarters 2, 3: the V half), 4 per wave and stage
+  auto issue_quarter = [&](int32_t pos, uint4* dst_slot, int32_t qt) {
+    static_assert(!SELF || PREFILL, "the compute waves load prefix blocks only");
+    const int32_t gb = min(pos, NBT - 1);
+    char* const dst = reinterpret_cast<char*>(dst_slot);
+    const int32_t half = qt & 1;
+    int32_t slot0;
+    if (PLIST) slot0 = gb < NBh ? scalar_load(a.tb.fblk + 2 * (hoff + gb)) : doff + (gb - NBh) * 32;
+    else slot0 = gb < NBh ? hoff + gb * 32 : doff + (gb - NBh) * 32;
+    if (qt < 2) {
+      const char* const sK = kpool + (int64_t)slot0 * (D * 2) + half * 4096;
+      char* const dk = dst + half * 4096;
+      dma16(sK + kq[0], dk); dma16(sK + kq[1], dk + 1024); dma16(sK + kq[2], dk + 2048); dma16(sK + kq[3], dk + 3072);
+    } else {
+      const char* const sV = vpool + (int64_t)slot0 * (D * 2) + half * 1024;
+      char* const dv = dst + 8192 + half * 4096;
+      dma16(sV + vq, dv); dma16(sV + 4096 + vq, dv + 1024); dma16(sV + 512 + vq, dv + 2048); dma16(sV + 4608 + vq, dv + 3072);
+    }
+  };
   if (append_first || table_first) {
     if (!loader) {
       if (append_first) append_from(ap_first + (tid >> 3));
@@ -624,6 +670,29 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   //      loaders leave alone until the second barrier): chunk c of row r at position
   //      c ^ (r & 15).  One wave fetches the (cos, sin) row of the shared position.  The new
   //      rows of the append are requested in the same breath.
+  // (full shape: the waves request their quarters of rounds 0 and 1 first, of rounds 2 and 3
+  // when the query staging has given stages 2 and 3 back, and of round r + 3 behind the barrier
+  // of round r; before that barrier a wave waits for its own loads of round r)
+  int32_t issued = 0;
+  auto issue_upto = [&](int32_t lim) {
+    if constexpr (SELF) {
+      for (; issued < min(NR, lim); ++issued) {
+        const int32_t x = issued & 3;
+        uint4* stage = x == 0 ? ring0 : (x == 1 ? ring1 : (x == 2 ? ring2 : ring3));
+        issue_quarter(issued * STAGE_BLOCKS + (wave >> 2), stage + (wave >> 2) * SLOT_U4, wave & 3);
+      }
+    }
+  };
+  auto own_loads_landed = [&](int32_t s1) {  // of the stages before s1
+    if constexpr (SELF) {
+      const int32_t newer = issued - s1;
+      if (newer >= 3) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(3 * LOADS_PER_ROUND) : "memory");
+      else if (newer == 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LOADS_PER_ROUND) : "memory");
+      else if (newer == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LOADS_PER_ROUND) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+  };
+  issue_upto(2);
   const bool append_late = a.fused && !append_first;
   const bool append_mine = append_late && ap_first + (tid >> 3) < ap_end;
   NewRows new_rows = {};
@@ -671,6 +740,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   }
   __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): this wave has its rows
   __builtin_amdgcn_s_barrier();        // stages 2 and 3 go back to the loaders
+  issue_upto(4);
 
   // ---- rotate the query: MFMA B operands in half precision (11 significant bits; the keys of
   //      the cache hold bf16 values in half format, so one pass of the f16 matrix instruction
@@ -711,6 +781,9 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   if (append_late) {
     if (append_mine) append_store(ap_first + (tid >> 3), new_rows, upos >= 0);
     append_from(ap_first + (tid >> 3) + CWAVES * 8);
+    // full shape: stores and loads of a wave do not complete in one order, so the counting of
+    // the loads starts from zero, with the appended rows in memory
+    if constexpr (SELF) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
 
   // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
@@ -835,8 +908,10 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
     const int32_t gb_h_part = (Hlen & 31) ? NBh - 1 : -1, gb_d_part = (Llen & 31) ? NB - 1 : -1;
     for (int32_t s0 = 0; s0 < s_tail; ++s0) {
       if (s0 == r_pub) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores of the append are complete
+      own_loads_landed(s0 + 1);
       __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS reads of the previous round are done
       __builtin_amdgcn_s_barrier();
+      issue_upto(s0 + 4);
       const int32_t st = s0 & 3;
       const uint4* stage = st == 0 ? ring0 : (st == 1 ? ring1 : (st == 2 ? ring2 : ring3));
 #pragma nounroll
@@ -859,8 +934,10 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   for (int32_t s0 = s_first; s0 < NR;) {
     const int32_t s1 = round_end(s0);
     if (s0 == r_pub) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores of the append are complete
+    own_loads_landed(s1);
     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): LDS reads of the previous round are done
     __builtin_amdgcn_s_barrier();
+    issue_upto(s0 + 4);
     if (active) {
 #pragma nounroll
       for (int32_t gb = s0 * STAGE_BLOCKS; gb < min(s1 * STAGE_BLOCKS, NBT); ++gb) {
@@ -1185,17 +1262,21 @@ hipError_t hpd_launch_prefill_stream(const hpd_layout* L, const void* q, const v
   const int32_t max_nblk = std::max(1, (L->fmax_rows * G + 31) / 32);
   // Every token is a query, so a segment has many row groups, and a row group streams only the
   // keys up to its last token: many short workgroups, whose starts and ends overlap better
-  // with two narrow workgroups per CU (measured: 3 % to 23 % faster than the wide shape on the
-  // four bf16 configurations).  kernel_mode 3 forces the wide shape.
-  const bool narrow = L->kernel_mode != 3;
-  a.RG = (max_nblk + (narrow ? NarrowShape::MAX_BLOCKS : WideShape::MAX_BLOCKS) - 1) /
-         (narrow ? NarrowShape::MAX_BLOCKS : WideShape::MAX_BLOCKS);
+  // with two workgroups per CU (the narrow shape measured 3 % to 23 % faster than the wide one
+  // on the four bf16 configurations), and whose time goes into the compute waves' matrix and
+  // vector work, not into memory: the dense shape (0 % to 5 % faster than the narrow one).
+  // kernel_mode 3 / 4 force the wide / the narrow shape.
+  const bool narrow = L->kernel_mode == 4, wide = L->kernel_mode == 3, dense = !narrow && !wide;
+  const int32_t shape_blocks = narrow ? NarrowShape::MAX_BLOCKS : dense ? DenseShape::MAX_BLOCKS : WideShape::MAX_BLOCKS;
+  a.RG = (max_nblk + shape_blocks - 1) / shape_blocks;
   a.n_groups = (int32_t)(n_units * a.Hkv);
   const int64_t items = ((int64_t)(a.n_groups + 7) / 8 * 8) * a.RG;
   if (items > 0x7fffffff) return hipErrorInvalidValue;
   const bool list = L->cfg.mask_mode == HPD_MASK_PAPER;
 #define HPD_LAUNCH_M(GG, PP)                                                                   \
   (narrow ? launch_g<GG, NarrowShape, PP>(a, items, q, k_prefix, v_prefix, nullptr, nullptr,  \
+                                          nullptr, nullptr, out, s)                           \
+   : dense ? launch_g<GG, DenseShape, PP>(a, items, q, k_prefix, v_prefix, nullptr, nullptr,  \
                                           nullptr, nullptr, out, s)                           \
           : launch_g<GG, WideShape, PP>(a, items, q, k_prefix, v_prefix, nullptr, nullptr,    \
                                         nullptr, nullptr, out, s))

@@ -79,7 +79,7 @@ def test_stream_kernel_fused_step_equals_two_calls(g, mode):
 def test_random_layout_sweep_stream_kernel(seed):
     """Random small batches through the step call: group size, head count, number of steps
     (up to four chunks of tail positions), ragged lengths, document and branch counts all
-    drawn from the seed; both workgroup shapes."""
+    drawn from the seed; all workgroup shapes."""
     rng = np.random.default_rng(seed)
     g = int(rng.choice([1, 2, 4, 8]))
     hkv = int(rng.choice([1, 2, 4]))
@@ -125,7 +125,7 @@ def test_score_ranges_of_the_online_softmax(case, mode):
     component in queries and keys (every score near +16 in log2 units: the reference point of
     the exponentials must follow), and with keys that grow along the document and the steps (the
     maximum of a row keeps rising, block after block: the accumulators are rescaled again and
-    again).  Same tolerance as everywhere; generic kernel (mode 1) and both workgroup shapes."""
+    again).  Same tolerance as everywhere; generic kernel (mode 1) and all workgroup shapes."""
     wl = W.random_workload(400, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=11, p=2,
                            j_range=(1, 3), n_range=(1, 20), h_range=(0, 70), l_range=(40, 400))
     from paper_2604_26209_amd import binding as B
@@ -156,7 +156,7 @@ def test_score_ranges_of_the_online_softmax(case, mode):
 def test_stream_kernel_group_sizes_that_are_not_powers_of_two(g):
     """Group sizes such as 40 query heads over 8 kv heads (5) run on the streaming kernel with
     the rows of a branch padded to the next power of two; padding rows are neither loaded nor
-    stored.  Decode (both masks, fused = two-call) and prefill, both workgroup shapes."""
+    stored.  Decode (both masks, fused = two-call) and prefill, all workgroup shapes."""
     rng = np.random.default_rng(190 + g)
     hkv = int(rng.choice([1, 2]))
     wl = W.random_workload(190 + g, dtype="bf16", hq=hkv * g, hkv=hkv, d=128, base=500000.0,
@@ -175,6 +175,7 @@ def test_stream_kernel_group_sizes_that_are_not_powers_of_two(g):
             for x, y in zip(a["out"], b["out"]):
                 assert torch.equal(x, y)
             _check_prefill(wl, mode, f"g{g}_prefill_m{mode}", attr_len=attr if paper else None)
+        _check_prefill(wl, 0, f"g{g}_prefill_m0", attr_len=attr if paper else None)
 
 
 @pytest.mark.parametrize("seed,kw", [(120, dict(hq=8, hkv=2, p=3, j_range=(1, 4), n_range=(1, 14), l_range=(1, 200))),
@@ -597,7 +598,7 @@ def test_paper_literal_mask_mode():
 
 @pytest.mark.parametrize("g", [1, 2, 4, 8])
 def test_paper_literal_mask_stream_kernel_shapes(g):
-    """The streaming kernel under HPD_MASK_PAPER: every group size, both workgroup shapes,
+    """The streaming kernel under HPD_MASK_PAPER: every group size, all workgroup shapes,
     prompts with more rows than one workgroup takes (several row groups, each appending the
     earlier groups' newest tokens itself in the step call), finished branches as keys, a tail
     of more than one chunk of 8 positions; the step call equals the two-call sequence bit for
@@ -677,11 +678,11 @@ def test_prefill_attention_fp32_generic():
 
 @pytest.mark.parametrize("g", [1, 2, 4, 8])
 def test_prefill_attention_bf16_all_kernels(g):
-    """Generic kernel and both shapes of the streaming kernel: segments shorter than a row
+    """Generic kernel and all shapes of the streaming kernel: segments shorter than a row
     block, segments of many row groups, empty headers, ragged ends."""
     wl = W.random_workload(92 + g, dtype="bf16", hq=8, hkv=8 // g, d=128, base=500000.0, t=2, p=3,
                            j_range=(1, 3), h_range=(0, 90), l_range=(1, 260 if g > 1 else 700))
-    for mode in (1, 3, 4):
+    for mode in (0, 1, 3, 4):  # 0: the default, the dense shape
         _say(f"prefill bf16 G={g} mode {mode}: {wl.n_prefix_tokens} tokens")
         rel = _check_prefill(wl, mode, f"prefill_bf16_g{g}_m{mode}")
         _say(f"  worst err/rms {rel:.2e}")
@@ -703,7 +704,7 @@ def test_prefill_attention_literal_mask_bf16_all_kernels(g):
     wl = W.random_workload(97 + g, dtype="bf16", hq=8, hkv=8 // g, d=128, base=500000.0, t=2, p=3,
                            j_range=(1, 4), n_range=(1, 30), h_range=(0, 90), l_range=(1, 200 if g > 1 else 500))
     attr = np.random.default_rng(97 + g).integers(1, 5, size=wl.n_branches).astype(np.int32)
-    for mode in (1, 3, 4):
+    for mode in (0, 1, 3, 4):
         _say(f"prefill literal bf16 G={g} mode {mode}: {wl.n_prefix_tokens} + {int(attr.sum())} tokens")
         rel = _check_prefill(wl, mode, f"prefill_literal_bf16_g{g}_m{mode}", attr_len=attr)
         _say(f"  worst err/rms {rel:.2e}")
