@@ -371,8 +371,9 @@ int hpd_finetune_mask(int32_t prompt_len, int32_t n_attr, const int32_t* attr_le
                       int64_t* s_out, void* stream);
 
 /* Selects the attention kernel: 0 = automatic, 1 = generic wave-reduction kernel for
- * everything, 2 = LDS-streaming MFMA kernel, workgroup shape chosen per launch, 3 / 4 = the
- * same with the wide / the narrow workgroup shape forced (2..4 return HPD_E_UNSUPPORTED if
+ * everything, 2 = LDS-streaming MFMA kernel, workgroup shape chosen per launch (decode: wide
+ * or narrow; hpd_prefill_attention: the dense shape), 3 / 4 = the same with the wide / the
+ * narrow workgroup shape forced for both calls (2..4 return HPD_E_UNSUPPORTED if
  * the shape does not allow the kernel: it needs bf16, head_dim 128 and a group size of 1,
  * 2, 4 or 8, and under HPD_MASK_PAPER at most 256 branches and 512 blocks of 32 keys per
  * prompt). */

@@ -16,8 +16,8 @@
 //    same 16-byte loads as a prefix block from the row-major tail pools.  Its K half looks
 //    like a prefix block's; its V half arrives as 32 rows of 256 bytes (the pool order: an
 //    append then is one coalesced row, where an 8-position interleave would cost a 2-byte
-//    scatter per channel) and is transposed by the consumer's LDS reads (2-byte reads,
-//    16-byte chunks XOR-swizzled at load time so that the two half-waves hit different banks).
+//    scatter per channel) and is transposed by the consumer's LDS reads (the transposing
+//    8-byte read of gfx950; rows swizzled at load time so that a read hits every bank once).
 //  * Loading.  Blocks travel HBM -> LDS with direct-to-LDS 16-byte loads
 //    (global_load_lds_dwordx4): no VGPRs are held by data in flight.  The V half of a prefix
 //    block is fetched in fragment order (a lane fetches exactly the 16 bytes that the same
@@ -32,7 +32,8 @@
 //    whatever a loading wave computes is time in which nothing is requested; and vector
 //    memory operations of a wave complete in order, so a wave with a deep DMA queue cannot
 //    get a latency-critical load through.  The two roles run different code paths and meet
-//    at barriers only.
+//    at barriers only.  (The prefill attention, which is bound by the compute waves and far
+//    from saturating the memory pipeline, runs a shape without loader waves: see DenseShape.)
 //  * Contraction (transposed):
 //        S^T[key,row] = K.Q^T   (A = K fragment, B = rotated, pre-scaled Q in registers)
 //        O^T[d,row]  += V^T.P^T (A = V fragment, B = P)
