@@ -152,6 +152,33 @@ def test_score_ranges_of_the_online_softmax(case, mode):
     _say(f"  worst err/rms {rel:.2e}")
 
 
+def test_values_beyond_the_half_range_saturate():
+    """The pools hold their bf16 values in half format, which ends at 65504: keys and values of
+    larger magnitude (bf16 can carry them) are stored as +-65504.  Nothing overflows - every output
+    stays finite, also in the rows that attend to such elements -, and the prompts without such
+    elements are unaffected (same tolerance against the oracle as ever)."""
+    wl = W.random_workload(410, dtype="bf16", hq=8, hkv=2, d=128, base=500000.0, t=6, p=3,
+                           j_range=(1, 3), n_range=(2, 12), h_range=(10, 70), l_range=(40, 200))
+    from paper_2604_26209_amd import binding as B
+    lay = B.layout_from_workload(wl)
+    inp = H.Inputs(wl, lay.n_live(), "cuda", lay.counts()[B.HPD_C_N_PREFIX_TOKENS])
+    # prompt 0 only: a few huge elements in its header, its first document and its new rows
+    h0 = int(wl.header_len[0])
+    big = torch.tensor(1.0e5, dtype=torch.bfloat16, device="cuda")
+    inp.k_raw[1, 0, 5] = big
+    inp.k_raw[h0 + 3, 1, 70] = -big
+    inp.v_raw[2, 0, 9] = big
+    inp.v_raw[h0 + 4, 1, 100] = -big
+    inp.k_new[0][0, 0, 17] = big
+    inp.v_new[1][0, 1, 3] = big
+    for mode in (3, 4):
+        _say(f"saturation mode {mode}")
+        a = H.run_hip(wl, inputs=inp, kernel_mode=mode, fused=True)
+        for o in a["out"]:
+            assert bool(torch.isfinite(o.float()).all())
+        H.check_all(wl, a, prompts=[1, 2], label=f"saturate_m{mode}")
+
+
 @pytest.mark.parametrize("g", [3, 5, 6, 7])
 def test_stream_kernel_group_sizes_that_are_not_powers_of_two(g):
     """Group sizes such as 40 query heads over 8 kv heads (5) run on the streaming kernel with
