@@ -583,8 +583,7 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   // barrier of round 1, so a prefix of at least 8 blocks keeps every tail tile behind it;
   // with a shorter prefix the append is completed before anything is loaded.
   const bool append_first = a.fused && NB < 4 * STAGE_BLOCKS;
-  // (the full shape waits for its appended rows before the barrier of round 0)
-  const int32_t r_pub = (a.fused && !append_first && !SELF) ? 1 : -1;
+  const int32_t r_pub = (a.fused && !append_first) ? 1 : -1;
   // The table of the newest chunk's rows is written by the compute waves before the first of
   // the two barriers of the query staging; the loaders request rounds 0 and 1 before that
   // barrier.  If a tile of the newest chunk can be among them the table is written first.
@@ -671,9 +670,11 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   //      loaders leave alone until the second barrier): chunk c of row r at position
   //      c ^ (r & 15).  One wave fetches the (cos, sin) row of the shared position.  The new
   //      rows of the append are requested in the same breath.
-  // (full shape: the waves request their quarters of rounds 0 and 1 first, of rounds 2 and 3
+  // (dense shape: the waves request their quarters of rounds 0 and 1 first, of rounds 2 and 3
   // when the query staging has given stages 2 and 3 back, and of round r + 3 behind the barrier
-  // of round r; before that barrier a wave waits for its own loads of round r)
+  // of round r; before that barrier a wave waits for its own loads of round r.  The shape serves
+  // the prefill only: nothing is appended, so loads are the only vector memory operations a wave
+  // has in flight during the rounds and their count says which have landed.)
   int32_t issued = 0;
   auto issue_upto = [&](int32_t lim) {
     if constexpr (SELF) {
@@ -782,9 +783,6 @@ attn_stream_kernel(StreamArgs a, const uint16_t* __restrict__ q, const uint16_t*
   if (append_late) {
     if (append_mine) append_store(ap_first + (tid >> 3), new_rows, upos >= 0);
     append_from(ap_first + (tid >> 3) + CWAVES * 8);
-    // full shape: stores and loads of a wave do not complete in one order, so the counting of
-    // the loads starts from zero, with the appended rows in memory
-    if constexpr (SELF) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
 
   // ---- online-softmax state: (max, this lane's share of the sum, O^T accumulators)
