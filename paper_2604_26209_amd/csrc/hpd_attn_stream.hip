@@ -142,7 +142,11 @@ struct StreamArgs {
 __device__ __forceinline__ void dma16(const void* g, const void* l) {
   const uint32_t la = (uint32_t)__builtin_amdgcn_readfirstlane(
       (int32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const void*)l));
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(la) : "memory", "m0");
+  uint32_t keep;  // M0 is the compiler's: put back what it held
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(keep)
+               : "v"(g), "s"(la)
+               : "memory");
 }
 __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi) {
   floatx2 v = {lo, hi};
